@@ -1,0 +1,311 @@
+/*
+ * CPU oracle for the SALAD attention-layer forward (sparse softmax attention in parallel
+ * with ReLU linear attention, combined by static and dynamic scaling).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition the GPU library is
+ * checked against.  It shares no code, header, table or helper with the HIP path, and
+ * nothing in the product may call it: only the tests, the smoke check and the benchmark's
+ * CPU-baseline leg do.
+ *
+ * Everything is evaluated in double precision on float32 input arrays (for bf16 workloads
+ * the arrays already hold bf16-representable values).  Each function writes the paper's
+ * definition out directly: two-pass softmax over exactly the kept keys, sums over all
+ * tokens for the linear state, no tiling, no online rescaling, no fusion.  OpenMP only
+ * distributes independent output rows over cores; it does not reorder any sum.
+ *
+ * Passages followed
+ *   sparse attention          Sec. 3 "Sparse Attention", Eq. (2); masked positions are excluded
+ *   token orders / ST-SWA     App. A.1.1 (default order: time slowest; temporal heads: tokens
+ *                             grouped by spatial location so that frames are consecutive)
+ *   ReLU linear attention     Sec. 3 "Linear Attention", Eq. (3)
+ *   static and dynamic scale  Alg. 1 (Level 1 / Level 2 / residual integration), Sec. 4.2
+ *
+ * Readings where the paper is silent (all listed in the design notes of the repository):
+ *   - the sliding window keeps a constant count of `kept` consecutive KV blocks per query
+ *     block, centred (extra block on the left for even counts) and shifted inward at the ends;
+ *   - sparsity rho maps to kept = clamp(floor((1-rho)*nb + 0.5), 1, nb);
+ *   - the linear-attention denominator is (phi(Q_i).Z + eps);
+ *   - the static projection is the per-layer scalar lambda times a per-head scalar a_h;
+ *   - the gate is Linear: D -> 1 without learned bias (a test-only scalar bias is accepted),
+ *     sigmoid per token, then the mean over tokens.
+ *
+ * Parity pins (tests/test_oracle_*.py): dense attention from a library routine, uniform
+ * weights for Q = 0, the quadratic form (phi(Q)phi(K)^T)V, closed forms for the gate and the
+ * combination, and structural invariants plus the stated densities for the mask.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define SO_OK 0
+#define SO_EINVAL 1
+
+/* ---- token order (App. A.1.1) ------------------------------------------------------ */
+
+/* Row index in the stored [N, d] layout (time slowest: n = t*Hh*W + y*W + x) of the token that
+ * sits at position p of a head's own order.  kind 0: default order, p = n.  kind 1: tokens
+ * grouped by spatial location, frames consecutive: p = (y*W + x)*T + t. */
+static int64_t row_of_position(int kind, int64_t p, int T, int64_t HW)
+{
+    if (kind == 0) return p;
+    int64_t loc = p / T;
+    int64_t t = p % T;
+    return t * HW + loc;
+}
+
+int64_t salad_oracle_row_of_position(int kind, int64_t p, int T, int Hh, int W)
+{
+    return row_of_position(kind, p, T, (int64_t)Hh * W);
+}
+
+int salad_oracle_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* ---- block mask (Sec. 3 sliding-window attention, App. A.1.1) ----------------------- */
+
+/* Number of KV blocks each query block keeps at sparsity rho ("proportion of computations
+ * reduced", Sec. 5.1), counted in block pairs. */
+int32_t salad_oracle_kept_from_sparsity(int32_t nb, double sparsity)
+{
+    double k = floor((1.0 - sparsity) * (double)nb + 0.5);
+    if (k < 1.0) k = 1.0;
+    if (k > (double)nb) k = (double)nb;
+    return (int32_t)k;
+}
+
+/* CSR of kept KV blocks.  Row h*nb + i lists, ascending, the kept blocks of query block i of
+ * head h; blocks are runs of `block` consecutive positions of that head's token order.
+ * row_ptr has H*nb + 1 entries; col_idx needs sum_h nb*kept[h] entries.  Returns nnz, or -1. */
+int64_t salad_oracle_block_mask(int T, int Hh, int W, int block, int H,
+                                const int32_t *kept, int32_t *row_ptr, int32_t *col_idx)
+{
+    int64_t N = (int64_t)T * Hh * W;
+    if (N <= 0 || block <= 0 || H <= 0) return -1;
+    int64_t nb = (N + block - 1) / block;
+    int64_t nnz = 0;
+    for (int h = 0; h < H; ++h) {
+        int64_t k = kept[h];
+        if (k < 1 || k > nb) return -1;
+        for (int64_t i = 0; i < nb; ++i) {
+            int64_t start = i - k / 2;
+            if (start < 0) start = 0;
+            if (start > nb - k) start = nb - k;
+            row_ptr[h * nb + i] = (int32_t)nnz;
+            for (int64_t j = start; j < start + k; ++j) col_idx[nnz++] = (int32_t)j;
+        }
+    }
+    row_ptr[(int64_t)H * nb] = (int32_t)nnz;
+    return nnz;
+}
+
+/* ---- sparse attention, Eq. (2) ------------------------------------------------------ */
+
+/* For the selected query blocks sel[0..nsel) of every (b, h): softmax over exactly the keys of
+ * the kept KV blocks (positions >= N do not exist), logits q.k*scale, two passes.
+ * q, k, v: float32 [B, H, N, d].  Output compact: out[((b*H + h)*nsel + s)*block + r][d]
+ * holds the row for position sel[s]*block + r of head h's order; rows_out (same leading shape)
+ * gets that token's stored row index n, or -1 when the position is >= N (output left zero). */
+int salad_oracle_sparse_attn(const float *q, const float *k, const float *v,
+                             int B, int H, int64_t N, int d,
+                             int T, int Hh, int W, int block,
+                             const uint8_t *head_kind,
+                             const int32_t *row_ptr, const int32_t *col_idx,
+                             double scale,
+                             const int32_t *sel, int nsel,
+                             double *out, int64_t *rows_out)
+{
+    if ((int64_t)T * Hh * W != N || block <= 0 || d <= 0) return SO_EINVAL;
+    const int64_t HW = (int64_t)Hh * W;
+    const int64_t nb = (N + block - 1) / block;
+    const int64_t total = (int64_t)B * H * nsel * block;
+    int bad = 0;
+#pragma omp parallel
+    {
+        double *logit = (double *)malloc(sizeof(double) * (size_t)(nb * block));
+        int64_t *krow = (int64_t *)malloc(sizeof(int64_t) * (size_t)(nb * block));
+#pragma omp for schedule(dynamic, 16)
+        for (int64_t idx = 0; idx < total; ++idx) {
+            int r = (int)(idx % block);
+            int64_t rest = idx / block;
+            int s = (int)(rest % nsel);
+            int64_t bh = rest / nsel;
+            int h = (int)(bh % H);
+            int64_t i = sel[s];
+            double *o = out + idx * d;
+            for (int c = 0; c < d; ++c) o[c] = 0.0;
+            int64_t p = i * block + r;
+            if (i < 0 || i >= nb) {
+#pragma omp atomic write
+                bad = 1;
+                rows_out[idx] = -1;
+                continue;
+            }
+            if (p >= N) { rows_out[idx] = -1; continue; }
+            int kind = head_kind[h];
+            int64_t n = row_of_position(kind, p, T, HW);
+            rows_out[idx] = n;
+            const float *qi = q + (bh * N + n) * d;
+            /* pass 1: logits over the kept set */
+            int64_t cnt = 0;
+            double m = -INFINITY;
+            for (int32_t e = row_ptr[h * nb + i]; e < row_ptr[h * nb + i + 1]; ++e) {
+                int64_t j = col_idx[e];
+                for (int c = 0; c < block; ++c) {
+                    int64_t pk = j * block + c;
+                    if (pk >= N) break;
+                    int64_t nk = row_of_position(kind, pk, T, HW);
+                    const float *kj = k + (bh * N + nk) * d;
+                    double acc = 0.0;
+                    for (int x = 0; x < d; ++x) acc += (double)qi[x] * (double)kj[x];
+                    acc *= scale;
+                    logit[cnt] = acc;
+                    krow[cnt] = nk;
+                    if (acc > m) m = acc;
+                    ++cnt;
+                }
+            }
+            if (cnt == 0) continue; /* empty row: defined as zero */
+            /* pass 2: weights and weighted sum of V */
+            double denom = 0.0;
+            for (int64_t t = 0; t < cnt; ++t) { logit[t] = exp(logit[t] - m); denom += logit[t]; }
+            for (int64_t t = 0; t < cnt; ++t) {
+                const float *vj = v + (bh * N + krow[t]) * d;
+                double wgt = logit[t] / denom;
+                for (int c = 0; c < d; ++c) o[c] += wgt * (double)vj[c];
+            }
+        }
+        free(logit);
+        free(krow);
+    }
+    return bad ? SO_EINVAL : SO_OK;
+}
+
+/* ---- ReLU linear attention, Eq. (3) ------------------------------------------------- */
+
+static inline double relu(double x) { return x > 0.0 ? x : 0.0; }
+
+/* State of one (b, h): Hs[a][c] = sum_j relu(K[j][a]) * V[j][c], Z[a] = sum_j relu(K[j][a]).
+ * k, v: [B, H, N, d]; Hs: [B, H, d, d]; Z: [B, H, d]. */
+int salad_oracle_linear_state(const float *k, const float *v, int B, int H, int64_t N, int d,
+                              double *Hs, double *Z)
+{
+    const int64_t BH = (int64_t)B * H;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int64_t bh = 0; bh < BH; ++bh) {
+        for (int a = 0; a < d; ++a) {
+            double *hrow = Hs + (bh * d + a) * d;
+            for (int c = 0; c < d; ++c) hrow[c] = 0.0;
+            double z = 0.0;
+            for (int64_t j = 0; j < N; ++j) {
+                double ka = relu((double)k[(bh * N + j) * d + a]);
+                const float *vj = v + (bh * N + j) * d;
+                for (int c = 0; c < d; ++c) hrow[c] += ka * (double)vj[c];
+                z += ka;
+            }
+            Z[bh * d + a] = z;
+        }
+    }
+    return SO_OK;
+}
+
+/* O_l[n] = relu(Q[n]) Hs / (relu(Q[n]).Z + eps) for the listed stored rows of every (b, h).
+ * rows: [B*H*nrows] stored row indices (entries < 0 are skipped, output zero);
+ * out: [B*H*nrows, d]. */
+int salad_oracle_linear_apply(const float *q, const double *Hs, const double *Z,
+                              int B, int H, int64_t N, int d, double eps,
+                              const int64_t *rows, int64_t nrows, double *out)
+{
+    const int64_t total = (int64_t)B * H * nrows;
+#pragma omp parallel for schedule(static)
+    for (int64_t idx = 0; idx < total; ++idx) {
+        int64_t bh = idx / nrows;
+        int64_t n = rows[idx];
+        double *o = out + idx * d;
+        for (int c = 0; c < d; ++c) o[c] = 0.0;
+        if (n < 0 || n >= N) continue;
+        const float *qi = q + (bh * N + n) * d;
+        double den = 0.0;
+        for (int a = 0; a < d; ++a) {
+            double qa = relu((double)qi[a]);
+            den += qa * Z[bh * d + a];
+            const double *hrow = Hs + (bh * d + a) * d;
+            for (int c = 0; c < d; ++c) o[c] += qa * hrow[c];
+        }
+        den += eps;
+        for (int c = 0; c < d; ++c) o[c] /= den;
+    }
+    return SO_OK;
+}
+
+/* The same quantity without reassociation: A = relu(Q) relu(K)^T (one row at a time),
+ * O_l[i] = (A_i V) / (A_i 1 + eps).  Quadratic in N: tiny inputs only.
+ * q, k, v: one head, [N, d]; out: [N, d]. */
+int salad_oracle_linear_attn_quadratic(const float *q, const float *k, const float *v,
+                                       int64_t N, int d, double eps, double *out)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < N; ++i) {
+        double *o = out + i * d;
+        for (int c = 0; c < d; ++c) o[c] = 0.0;
+        double rowsum = 0.0;
+        for (int64_t j = 0; j < N; ++j) {
+            double a = 0.0;
+            for (int x = 0; x < d; ++x)
+                a += relu((double)q[i * d + x]) * relu((double)k[j * d + x]);
+            rowsum += a;
+            for (int c = 0; c < d; ++c) o[c] += a * (double)v[j * d + c];
+        }
+        for (int c = 0; c < d; ++c) o[c] /= (rowsum + eps);
+    }
+    return SO_OK;
+}
+
+/* ---- dynamic scale, Alg. 1 "Level 2" ------------------------------------------------ */
+
+/* s[b] = (1/N) * sum_n sigmoid(x[b][n] . w + bias);  x: [B, N, D], w: [D]. */
+int salad_oracle_gate(const float *x, const float *w, double bias, int B, int64_t N, int D,
+                      double *s)
+{
+    double *sig = (double *)malloc(sizeof(double) * (size_t)N);
+    if (!sig) return SO_EINVAL;
+    for (int b = 0; b < B; ++b) {
+#pragma omp parallel for schedule(static)
+        for (int64_t n = 0; n < N; ++n) {
+            const float *xr = x + ((int64_t)b * N + n) * D;
+            double z = bias;
+            for (int c = 0; c < D; ++c) z += (double)xr[c] * (double)w[c];
+            sig[n] = 1.0 / (1.0 + exp(-z));
+        }
+        double total = 0.0;
+        for (int64_t n = 0; n < N; ++n) total += sig[n];
+        s[b] = total / (double)N;
+    }
+    free(sig);
+    return SO_OK;
+}
+
+/* ---- residual integration, Alg. 1 last block; Eq. (lambda scale), Sec. 4.2 ------------ */
+
+/* out = O_s + lambda * a[h] * s[b] * O_l on compact row sets of shape [B, H, nrows, d]. */
+int salad_oracle_combine(const double *o_s, const double *o_l, int B, int H, int64_t nrows, int d,
+                         double lambda, const float *head_scale, const double *s, double *out)
+{
+    for (int b = 0; b < B; ++b)
+        for (int h = 0; h < H; ++h) {
+            double a = head_scale ? (double)head_scale[h] : 1.0;
+            double coef = lambda * a * s[b];
+            int64_t base = ((int64_t)b * H + h) * nrows * d;
+            for (int64_t e = 0; e < nrows * d; ++e) out[base + e] = o_s[base + e] + coef * o_l[base + e];
+        }
+    return SO_OK;
+}

@@ -1,0 +1,273 @@
+"""Pins for the oracle's sparse branch, linear branch, gate and combination (no GPU).
+
+Each pin compares the oracle with something that is not the oracle: a library routine
+(torch's scaled_dot_product_attention in float64, scipy's expit), a different formulation of the
+same quantity (the quadratic form of linear attention), or a closed form that the definitions
+force (uniform weights for Q = 0, constant V, zero static scale).
+"""
+import numpy as np
+import pytest
+import torch
+from scipy.special import expit
+
+from paper_2601_16515_amd import workloads as wl
+
+
+def _qkv(seed, B, H, N, d, scale=1.0):
+    q = wl.normal(seed, "q", (B, H, N, d)) * scale
+    k = wl.normal(seed, "k", (B, H, N, d)) * scale
+    v = wl.normal(seed, "v", (B, H, N, d))
+    return q, k, v
+
+
+def _scatter(compact, rows, N):
+    """compact [B,H,R,d] + rows [B,H,R] -> stored layout [B,H,N,d]."""
+    B, H, R, d = compact.shape
+    out = np.full((B, H, N, d), np.nan)
+    for b in range(B):
+        for h in range(H):
+            ok = rows[b, h] >= 0
+            out[b, h, rows[b, h][ok]] = compact[b, h][ok]
+    assert not np.isnan(out).any()
+    return out
+
+
+def _token_mask(oracle, grid, block, kind, row_ptr, col_idx, h, nb):
+    T, Hh, W = grid
+    N = T * Hh * W
+    M = np.zeros((N, N), dtype=bool)
+    order = np.array([oracle.row_of_position(kind, p, T, Hh, W) for p in range(N)])
+    for i in range(nb):
+        qrows = order[i * block:min((i + 1) * block, N)]
+        for j in col_idx[row_ptr[h * nb + i]:row_ptr[h * nb + i + 1]]:
+            M[np.ix_(qrows, order[j * block:min((j + 1) * block, N)])] = True
+    return M
+
+
+# ---------------------------------------------------------------- sparse branch, Eq. (1)/(2)
+
+@pytest.mark.parametrize("grid,block,d", [((3, 5, 7), 16, 32), ((2, 8, 9), 64, 64)])
+def test_dense_window_equals_library_softmax_attention(oracle, grid, block, d):
+    """kept = nb (zero sparsity): Eq. (2) reduces to Eq. (1); compare with torch SDPA in float64.
+    Both head orders must give the same result (dense attention is permutation-equivariant)."""
+    T, Hh, W = grid
+    N = T * Hh * W
+    nb = (N + block - 1) // block
+    q, k, v = _qkv(11, 1, 2, N, d)
+    row_ptr, col_idx = oracle.block_mask(T, Hh, W, block, [nb, nb])
+    out, rows = oracle.sparse_attn(q, k, v, grid, block, [0, 1], row_ptr, col_idx)
+    got = _scatter(out, rows, N)
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(q).double(), torch.from_numpy(k).double(), torch.from_numpy(v).double()).numpy()
+    assert np.abs(got - ref).max() < 1e-12
+
+
+@pytest.mark.parametrize("grid,block,kept", [((3, 5, 7), 16, [2, 3]), ((4, 6, 5), 16, [1, 4]),
+                                              ((2, 9, 9), 64, [2, 1])])
+def test_sparse_equals_library_attention_with_token_mask(oracle, grid, block, kept):
+    """Eq. (2): masked softmax.  The token-level boolean mask is expanded from the CSR and handed
+    to torch SDPA (float64); ragged last block and both head orders included."""
+    T, Hh, W = grid
+    N = T * Hh * W
+    nb = (N + block - 1) // block
+    d = 32
+    q, k, v = _qkv(12, 1, 2, N, d, scale=1.5)
+    row_ptr, col_idx = oracle.block_mask(T, Hh, W, block, kept)
+    out, rows = oracle.sparse_attn(q, k, v, grid, block, [0, 1], row_ptr, col_idx)
+    got = _scatter(out, rows, N)
+    for h, kind in enumerate([0, 1]):
+        M = _token_mask(oracle, grid, block, kind, row_ptr, col_idx, h, nb)
+        ref = torch.nn.functional.scaled_dot_product_attention(
+            torch.from_numpy(q[:, h]).double(), torch.from_numpy(k[:, h]).double(),
+            torch.from_numpy(v[:, h]).double(), attn_mask=torch.from_numpy(M)[None]).numpy()
+        assert np.abs(got[:, h] - ref).max() < 1e-12
+
+
+def test_zero_queries_give_mean_of_kept_values(oracle):
+    """Q = 0 makes every kept weight equal, so O_s[p] is the arithmetic mean of V over exactly the
+    kept, existing tokens.  Pins the mask wiring, the tail and the permutation end to end."""
+    grid, block = (3, 7, 5), 16
+    T, Hh, W = grid
+    N = T * Hh * W
+    nb = (N + block - 1) // block
+    _, _, v = _qkv(13, 1, 2, N, 8)
+    q = np.zeros_like(v)
+    k = wl.normal(13, "k", v.shape)
+    kept = [3, 2]
+    row_ptr, col_idx = oracle.block_mask(T, Hh, W, block, kept)
+    out, rows = oracle.sparse_attn(q, k, v, grid, block, [0, 1], row_ptr, col_idx)
+    got = _scatter(out, rows, N)
+    for h, kind in enumerate([0, 1]):
+        M = _token_mask(oracle, grid, block, kind, row_ptr, col_idx, h, nb)
+        ref = (M.astype(np.float64) @ v[0, h].astype(np.float64)) / M.sum(1, keepdims=True)
+        assert np.abs(got[0, h] - ref).max() < 1e-13
+
+
+def test_constant_values_and_convexity(oracle):
+    grid, block = (2, 6, 7), 16
+    N = 2 * 6 * 7
+    q, k, v = _qkv(14, 1, 2, N, 16, scale=2.0)
+    row_ptr, col_idx = oracle.block_mask(*grid, block, [2, 3])
+    c = wl.normal(14, "const", (16,))
+    vc = np.broadcast_to(c, v.shape).copy()
+    out, rows = oracle.sparse_attn(q, k, vc, grid, block, [1, 0], row_ptr, col_idx)
+    ok = rows >= 0
+    assert np.abs(out[ok] - c).max() < 1e-14                 # softmax weights sum to one
+    out, rows = oracle.sparse_attn(q, k, v, grid, block, [1, 0], row_ptr, col_idx)
+    lo, hi = v.min(axis=2, keepdims=True), v.max(axis=2, keepdims=True)
+    assert np.all(out[ok] >= np.broadcast_to(lo, out.shape)[ok] - 1e-12)
+    assert np.all(out[ok] <= np.broadcast_to(hi, out.shape)[ok] + 1e-12)
+
+
+def test_selected_blocks_match_full_evaluation(oracle):
+    grid, block = (4, 5, 6), 16
+    N = 120
+    q, k, v = _qkv(15, 2, 2, N, 16)
+    row_ptr, col_idx = oracle.block_mask(*grid, block, [3, 3])
+    full, rows_full = oracle.sparse_attn(q, k, v, grid, block, [0, 1], row_ptr, col_idx)
+    sel = [0, 3, 7]
+    part, rows = oracle.sparse_attn(q, k, v, grid, block, [0, 1], row_ptr, col_idx, sel=sel)
+    for s, i in enumerate(sel):
+        assert np.array_equal(part[:, :, s * block:(s + 1) * block], full[:, :, i * block:(i + 1) * block])
+        assert np.array_equal(rows[:, :, s * block:(s + 1) * block], rows_full[:, :, i * block:(i + 1) * block])
+    assert (rows_full[:, :, -8:] == -1).all() and (rows_full[:, :, :-8] >= 0).all()   # 120 = 7*16 + 8
+
+
+def test_softmax_scale_argument(oracle):
+    grid, block = (1, 4, 8), 16
+    q, k, v = _qkv(16, 1, 1, 32, 16)
+    row_ptr, col_idx = oracle.block_mask(*grid, block, [2])
+    a, _ = oracle.sparse_attn(q, k, v, grid, block, [0], row_ptr, col_idx, scale=0.5)
+    b, _ = oracle.sparse_attn(2.0 * q, k, v, grid, block, [0], row_ptr, col_idx, scale=0.25)
+    assert np.abs(a - b).max() < 1e-13
+    dflt, _ = oracle.sparse_attn(q, k, v, grid, block, [0], row_ptr, col_idx)
+    c, _ = oracle.sparse_attn(q, k, v, grid, block, [0], row_ptr, col_idx, scale=0.25)   # 1/sqrt(16)
+    assert np.array_equal(dflt, c)
+
+
+# ---------------------------------------------------------------- linear branch, Eq. (3)
+
+def test_linear_state_form_equals_quadratic_form(oracle):
+    """Associativity (Sec. 3, Linear Attention): phi(Q)(phi(K)^T V) == (phi(Q)phi(K)^T)V."""
+    N, d, eps = 150, 24, 1e-6
+    q, k, v = _qkv(21, 1, 3, N, d)
+    Hs, Z = oracle.linear_state(k, v)
+    fast = oracle.linear_apply(q, Hs, Z, eps)
+    for h in range(3):
+        slow = oracle.linear_attn_quadratic(q[0, h], k[0, h], v[0, h], eps)
+        assert np.abs(fast[0, h] - slow).max() < 1e-11
+        # and against the formula written with numpy matmuls
+        A = np.maximum(q[0, h].astype(np.float64), 0) @ np.maximum(k[0, h].astype(np.float64), 0).T
+        ref = (A @ v[0, h].astype(np.float64)) / (A.sum(1, keepdims=True) + eps)
+        assert np.abs(slow - ref).max() < 1e-11
+
+
+def test_linear_state_values(oracle):
+    N, d = 70, 8
+    _, k, v = _qkv(22, 2, 2, N, d)
+    Hs, Z = oracle.linear_state(k, v)
+    kp = np.maximum(k.astype(np.float64), 0)
+    assert np.abs(Hs - np.einsum("bhna,bhnc->bhac", kp, v.astype(np.float64))).max() < 1e-11
+    assert np.abs(Z - kp.sum(2)).max() < 1e-11
+
+
+def test_linear_invariances(oracle):
+    N, d = 90, 16
+    q, k, v = _qkv(23, 1, 2, N, d)
+    Hs, Z = oracle.linear_state(k, v)
+    base = oracle.linear_apply(q, Hs, Z, 0.0)
+    # constant V -> that constant (weights are a convex combination when eps = 0)
+    c = wl.normal(23, "c", (d,))
+    Hc, Zc = oracle.linear_state(k, np.broadcast_to(c, v.shape).copy())
+    assert np.abs(oracle.linear_apply(q, Hc, Zc, 0.0) - c).max() < 1e-12
+    # jointly shuffling (K, V) rows changes nothing: the branch ignores token order
+    perm = np.argsort(wl.uniform(23, "perm", (N,)))
+    Hp, Zp = oracle.linear_state(k[:, :, perm], v[:, :, perm])
+    assert np.abs(oracle.linear_apply(q, Hp, Zp, 0.0) - base).max() < 1e-12
+    # positive rescaling of K cancels between numerator and denominator
+    Ha, Za = oracle.linear_state(4.0 * k, v)
+    assert np.abs(oracle.linear_apply(q, Ha, Za, 0.0) - base).max() < 1e-12
+    # a transposed state (H^T instead of H) must not pass
+    assert np.abs(oracle.linear_apply(q, Hs.transpose(0, 1, 3, 2).copy(), Z, 0.0) - base).max() > 1e-3
+    # rows argument picks stored rows
+    rows = np.array([[[5, -1, 17], [0, 89, 3]]], dtype=np.int64)
+    part = oracle.linear_apply(q, Hs, Z, 0.0, rows)
+    assert np.array_equal(part[0, 0, 0], base[0, 0, 5]) and np.array_equal(part[0, 1, 1], base[0, 1, 89])
+    assert np.all(part[0, 0, 1] == 0)
+
+
+def test_linear_eps_guards_empty_denominator(oracle):
+    N, d = 20, 8
+    q, k, v = _qkv(24, 1, 1, N, d)
+    q[0, 0, 3] = -np.abs(q[0, 0, 3])           # phi(Q_3) = 0
+    Hs, Z = oracle.linear_state(k, v)
+    out = oracle.linear_apply(q, Hs, Z, 1e-6)
+    assert np.all(out[0, 0, 3] == 0.0) and np.isfinite(out).all()
+
+
+# ---------------------------------------------------------------- gate, Alg. 1 Level 2
+
+def test_gate_closed_forms(oracle):
+    B, N, D = 2, 37, 24
+    x = wl.normal(31, "x", (B, N, D))
+    w = wl.normal(31, "w", (D,), std=0.5)
+    assert np.array_equal(oracle.gate(x, np.zeros(D, np.float32)), np.full(B, 0.5))
+    s = oracle.gate(x, w)
+    assert np.all((s > 0) & (s < 1))
+    ref = expit(x.astype(np.float64) @ w.astype(np.float64)).mean(axis=1)      # library sigmoid
+    assert np.abs(s - ref).max() < 1e-14
+    # identical tokens: the mean of equal sigmoids is that sigmoid
+    xc = np.broadcast_to(x[:, :1], x.shape).copy()
+    assert np.abs(oracle.gate(xc, w, 0.3) - expit(xc[:, 0].astype(np.float64) @ w.astype(np.float64) + 0.3)).max() < 1e-14
+    assert np.all(oracle.gate(x, w, 40.0) > 1 - 1e-9) and np.all(oracle.gate(x, w, -40.0) < 1e-9)
+    assert np.all(oracle.gate(x, w, 0.5) > oracle.gate(x, w, 0.0))
+    # sigmoid-then-mean, not mean-then-sigmoid
+    z = x.astype(np.float64) @ w.astype(np.float64)
+    assert np.abs(s - expit(z.mean(axis=1))).max() > 1e-4
+
+
+# ---------------------------------------------------------------- combination, Alg. 1 / Eq. (lambda)
+
+def test_combination_closed_forms(oracle):
+    w = wl.small("c", 2, 2, 16, 2, 6, 7, "f32", 0.5, seed=41, block=16)
+    inp = wl.make_inputs(w)
+    grid = (w.T, w.Hh, w.W)
+    kw = dict(grid=grid, block=w.block, head_kind=[0, 1], kept=[3, 3], eps=0.0)
+    r = oracle.salad_forward(inp["q"], inp["k"], inp["v"], inp["x_t"], inp["w_gate"], inp["head_scale"], lam=0.7, **kw)
+    ok = r["rows"] >= 0
+    # zero-initialised static scale: the layer is the sparse branch, bit for bit
+    z = oracle.salad_forward(inp["q"], inp["k"], inp["v"], inp["x_t"], inp["w_gate"], np.zeros(2, np.float32), lam=0.7, **kw)
+    assert np.array_equal(z["out"], z["o_sparse"])
+    z = oracle.salad_forward(inp["q"], inp["k"], inp["v"], inp["x_t"], inp["w_gate"], inp["head_scale"], lam=0.0, **kw)
+    assert np.array_equal(z["out"], z["o_sparse"])
+    # linear in lambda
+    r2 = oracle.salad_forward(inp["q"], inp["k"], inp["v"], inp["x_t"], inp["w_gate"], inp["head_scale"], lam=1.4, **kw)
+    assert np.abs((r2["out"] - r["o_sparse"]) - 2.0 * (r["out"] - r["o_sparse"])).max() < 1e-13
+    # constant V = c: both branches return c, so out = (1 + lambda a_h s_b) c
+    c = wl.normal(41, "c", (w.d,))
+    vc = np.broadcast_to(c, inp["v"].shape).copy()
+    rc = oracle.salad_forward(inp["q"], inp["k"], vc, inp["x_t"], inp["w_gate"], inp["head_scale"], lam=0.7, **kw)
+    for b in range(w.B):
+        for h in range(w.H):
+            coef = 1.0 + 0.7 * float(inp["head_scale"][h]) * rc["s"][b]
+            m = ok[b, h]
+            assert np.abs(rc["out"][b, h][m] - coef * c).max() < 1e-12
+    assert abs(rc["s"][0] - rc["s"][1]) > 1e-6          # the dynamic scale differs per sample
+    # the dynamic scale is the gate of x_t, one scalar per sample
+    assert np.abs(r["s"] - oracle.gate(inp["x_t"], inp["w_gate"])).max() == 0.0
+
+
+def test_tiny_config_runs_in_seconds(oracle):
+    """The smallest benchmark configuration end to end (B=1, H=2, d=64, grid 4x16x16)."""
+    import time
+    w = wl.TINY
+    inp = wl.make_inputs(w)
+    k = oracle.kept_from_sparsity(w.nb, w.sparsity)
+    t0 = time.time()
+    r = oracle.salad_forward(inp["q"], inp["k"], inp["v"], inp["x_t"], inp["w_gate"], inp["head_scale"],
+                             grid=(w.T, w.Hh, w.W), block=w.block, head_kind=wl.head_kinds(w), kept=[k] * w.H)
+    assert time.time() - t0 < 20
+    assert r["out"].shape == (1, 2, 1024, 64) and np.isfinite(r["out"]).all()
+    assert 0.45 < r["s"][0] < 0.55          # w_gate ~ N(0, 0.02^2): pre-activations are small
+    # the linear branch is smaller than the sparse one on N(0,1) inputs
+    assert np.abs(r["o_linear"]).mean() < 0.5 * np.abs(r["o_sparse"]).mean()
