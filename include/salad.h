@@ -1,0 +1,161 @@
+/*
+ * salad.h - C ABI of the MI355X (gfx950) library for the SALAD attention-layer forward:
+ * block-sparse softmax attention in parallel with ReLU linear attention, combined through
+ * static (per-layer, per-head) and dynamic (input-dependent) scaling.
+ *
+ * Conventions for every entry point
+ *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are
+ *     ordinary host memory read during the call only.  The library allocates no device memory
+ *     and keeps no pointer after a call returns.
+ *   - Work is enqueued on the given HIP stream (a hipStream_t passed as void*, NULL = the
+ *     default stream); no entry point synchronises with the host.
+ *   - All argument checks happen on the host before the first HIP call and return
+ *     SALAD_EINVAL / SALAD_ENOTSUP / SALAD_ENOSPC without touching the GPU.  HIP failures are
+ *     returned as SALAD_EHIP.  Nothing throws across this boundary.  salad_last_error() gives
+ *     the text for the calling thread's last non-OK status.
+ *   - Tensors are contiguous.  Q, K, V and the output are [B, H, N, d] with N = T*Hh*W tokens
+ *     stored time-slowest: n = t*Hh*W + y*W + x (the default flattening of App. A.1.1).
+ *   - block is 64 tokens; d is 64 or 128; H <= 64.
+ */
+#ifndef SALAD_H
+#define SALAD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SALAD_OK = 0,
+    SALAD_EINVAL = 1,  /* bad argument (null pointer, shape mismatch, out of range)            */
+    SALAD_ENOTSUP = 2, /* well-formed request outside the supported envelope                   */
+    SALAD_ENOSPC = 3,  /* a caller-provided buffer (col_idx, workspace) is too small           */
+    SALAD_EHIP = 4     /* a HIP runtime call failed                                            */
+} salad_status;
+
+typedef enum { SALAD_F32 = 0, SALAD_BF16 = 1 } salad_dtype;
+
+/* Token order of a head (App. A.1.1).  SPATIAL: the stored order, position p = n.
+ * TEMPORAL: tokens regrouped by spatial location so that the frames of one location are
+ * consecutive, p = (y*W + x)*T + t. */
+typedef enum { SALAD_HEAD_SPATIAL = 0, SALAD_HEAD_TEMPORAL = 1 } salad_head_kind;
+
+/* Feature map phi of the linear branch (Sec. 3, Linear Attention; Eq. (3) uses ReLU). */
+typedef enum { SALAD_PHI_RELU = 0 } salad_feature_map;
+
+/* Thread-local text describing the last non-OK status returned on this thread ("" if none). */
+const char *salad_last_error(void);
+
+/* ---- mask ---------------------------------------------------------------------------------- */
+
+/* Kept KV blocks per query block for a sparsity ("proportion of computations reduced by sparse
+ * attention", Sec. 5.1), counted in block pairs: clamp(floor((1-sparsity)*nb + 0.5), 1, nb).
+ * Pure host arithmetic.  Returns 0 if nb < 1. */
+int32_t salad_kept_from_sparsity(int32_t nb, double sparsity);
+
+/* Number of col_idx entries salad_block_mask will write: sum_h nb*kept[h].  -1 on bad input. */
+int64_t salad_block_mask_nnz(int32_t T, int32_t Hh, int32_t W, int32_t block, int32_t H,
+                             const int32_t *kept_host);
+
+/* Spatial-temporal sliding-window block mask (Sec. 3 "Sliding-window attention", App. A.1.1)
+ * as CSR over 64-token blocks of each head's own token order.  Row h*nb + i lists, ascending,
+ * the KV blocks query block i of head h keeps: kept[h] consecutive blocks centred on i (the
+ * extra one on the left for even counts), shifted inward at both sequence ends so that every
+ * row has exactly kept[h] entries.  The mask is static (it depends on no activation), so it is
+ * built once per (grid, kept) and reused by every layer and timestep.
+ *   T, Hh, W        latent grid, N = T*Hh*W, nb = ceil(N/block)
+ *   kept_host       host [H], each in 1..nb
+ *   row_ptr_dev     device int32 [H*nb + 1]  (written)
+ *   col_idx_dev     device int32 [col_capacity] (first nnz entries written)
+ * SALAD_ENOSPC if col_capacity < nnz. */
+salad_status salad_block_mask(int32_t T, int32_t Hh, int32_t W, int32_t block, int32_t H,
+                              const int32_t *kept_host,
+                              int32_t *row_ptr_dev, int32_t *col_idx_dev, int64_t col_capacity,
+                              void *hip_stream);
+
+/* ---- whole layer --------------------------------------------------------------------------- */
+
+typedef struct salad_fwd_params {
+    int32_t B, H, N, d;
+    int32_t dtype;            /* salad_dtype of q, k, v, out and x_t                              */
+    int32_t T, Hh, W, block;  /* latent grid (N == T*Hh*W) and block size (64)                    */
+    const void *q, *k, *v;    /* device [B,H,N,d]                                                 */
+    void *out;                /* device [B,H,N,d]; must not alias an input                        */
+    const int32_t *row_ptr;   /* device CSR from salad_block_mask, or any CSR with ascending      */
+    const int32_t *col_idx;   /*   unique block ids per row (rows h*nb + i, shared by all b)      */
+    const uint8_t *head_kind_host; /* host [H] salad_head_kind; NULL = all spatial               */
+    float softmax_scale;      /* 0 selects 1/sqrt(d) (Eq. (1))                                    */
+    int32_t phi;              /* salad_feature_map                                                */
+    float eps;                /* added to the linear branch's denominator phi(Q_i).Z              */
+    float lambda;             /* static per-layer scalar (Sec. 4.2, the lambda equation)          */
+    const float *head_scale;  /* device [H] static per-head scale a_h; NULL = 1                   */
+    const float *s_dev;       /* device [B] precomputed dynamic scale s, or NULL                  */
+    const void *x_t;          /* device [B,N,H*d], used when s_dev == NULL (Alg. 1 Level 2)       */
+    const float *w_gate;      /* device [H*d] gate weights, used when s_dev == NULL               */
+    float b_gate;             /* scalar added before the sigmoid (0 in the paper's layer)         */
+    float *s_out;             /* optional device [B]: the dynamic scale that was applied          */
+    float *o_sparse_dbg;      /* optional device fp32 [B,H,N,d]: sparse branch alone              */
+    float *o_linear_dbg;      /* optional device fp32 [B,H,N,d]: unscaled linear branch alone     */
+    void *workspace;          /* device, >= salad_fwd_workspace_bytes(), 256-byte aligned         */
+    size_t workspace_bytes;
+    int32_t flags;            /* SALAD_FLAG_* */
+    void *hip_stream;
+} salad_fwd_params;
+
+/* Run the linear apply and the scale-and-sum as a separate streaming kernel after the sparse
+ * kernel instead of inside its epilogue (same result up to rounding; bf16 only). */
+#define SALAD_FLAG_UNFUSED_EPILOGUE 1
+
+/* Device scratch the forward needs for these shapes (partial states, partial gate sums, the
+ * reduced state).  Reads only B, H, N, d, dtype.  0 on invalid shapes. */
+size_t salad_fwd_workspace_bytes(const salad_fwd_params *p);
+
+/* Alg. 1 from SparseAttn to the residual sum:
+ *   O_s = softmax over the kept KV blocks of (Q K^T * softmax_scale) V          (Eq. (2))
+ *   O_l = phi(Q) Hs / (phi(Q).Z + eps), Hs = sum_j phi(K_j)^T V_j, Z = sum_j phi(K_j)  (Eq. (3))
+ *   s_b = mean_n sigmoid(x_t[b,n,:].w_gate + b_gate)                             (Level 2)
+ *   out = O_s + lambda * a_h * s_b * O_l                (Level 1 in per-head form + residual)
+ * With lambda == 0 the linear branch is skipped and out is the sparse branch alone.
+ * bf16: MFMA kernels, fp32 accumulation, one round-to-nearest-even of the sum to bf16.
+ * fp32: plain fp32 kernels intended for small shapes. */
+salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p);
+
+/* ---- single steps (the same kernels the layer call launches) -------------------------------- */
+
+/* Eq. (3) sums: Hs [B,H,d,d] (Hs[a][c] = sum_j relu(K[j][a]) V[j][c]) and Z [B,H,d], fp32.
+ * workspace as for the layer call with the same B, H, N, d, dtype. */
+salad_status salad_linear_state_fwd(const void *k, const void *v, int32_t B, int32_t H, int32_t N,
+                                    int32_t d, int32_t dtype, float *Hs_out, float *Z_out,
+                                    void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Alg. 1 Level 2: s[b] = mean_n sigmoid(x_t[b,n,:].w_gate + b_gate); x_t [B,N,D], s fp32 [B]. */
+salad_status salad_gate_fwd(const void *x_t, const float *w_gate, float b_gate, int32_t B, int32_t N,
+                            int32_t D, int32_t dtype, float *s_out,
+                            void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* ---- per-kernel timing ----------------------------------------------------------------------- */
+
+typedef struct salad_kernel_times {
+    float gate_ms, state_ms, finalize_ms, attn_ms, epilogue_ms; /* summed over calls            */
+    int32_t calls;
+} salad_kernel_times;
+
+/* When enabled, the layer call brackets each of its kernels with HIP events on its stream. */
+salad_status salad_timing_enable(int32_t on);
+/* Waits for the recorded events, adds up the elapsed times since the last reset into *out and
+ * (if reset != 0) clears the record.  This one call does synchronise with the host. */
+salad_status salad_timing_read(salad_kernel_times *out, int32_t reset);
+
+/* ---- tuning ----------------------------------------------------------------------------------- */
+
+/* Launch-shape knobs for experiments; results do not depend on them beyond rounding order.
+ *   "state_wgs"  target workgroup count of the linear-state kernel (changes the workspace size:
+ *                query salad_fwd_workspace_bytes again after setting it). */
+salad_status salad_tune(const char *key, int32_t value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SALAD_H */

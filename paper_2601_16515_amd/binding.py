@@ -1,0 +1,282 @@
+"""Thin ctypes binding of libsalad (the C ABI declared in include/salad.h).
+
+Argument marshalling only: every step of the path runs in the library's HIP kernels.
+PyTorch is used for device memory and streams.  There is no CPU fallback: if the shared
+library has not been built, loading fails with an error that says how to build it.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import Optional, Sequence, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_CSRC = os.path.join(_HERE, "csrc")
+LIB_PATH = os.path.join(_HERE, "libsalad.so")
+SOURCES = ["salad_api.hip", "mask_gate_finalize.hip", "linear_state.hip", "sparse_attn.hip",
+           "linear_apply.hip"]
+
+SALAD_OK, SALAD_EINVAL, SALAD_ENOTSUP, SALAD_ENOSPC, SALAD_EHIP = range(5)
+SALAD_F32, SALAD_BF16 = 0, 1
+SALAD_HEAD_SPATIAL, SALAD_HEAD_TEMPORAL = 0, 1
+SALAD_PHI_RELU = 0
+SALAD_FLAG_UNFUSED_EPILOGUE = 1
+
+EXPORTS = ["salad_last_error", "salad_kept_from_sparsity", "salad_block_mask_nnz", "salad_block_mask",
+           "salad_fwd_workspace_bytes", "salad_sparse_linear_attn_fwd", "salad_linear_state_fwd",
+           "salad_gate_fwd", "salad_timing_enable", "salad_timing_read", "salad_tune"]
+
+
+class SaladError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"libsalad status {status}: {text}")
+        self.status = status
+
+
+class FwdParams(C.Structure):
+    _fields_ = [
+        ("B", C.c_int32), ("H", C.c_int32), ("N", C.c_int32), ("d", C.c_int32),
+        ("dtype", C.c_int32),
+        ("T", C.c_int32), ("Hh", C.c_int32), ("W", C.c_int32), ("block", C.c_int32),
+        ("q", C.c_void_p), ("k", C.c_void_p), ("v", C.c_void_p),
+        ("out", C.c_void_p),
+        ("row_ptr", C.c_void_p), ("col_idx", C.c_void_p),
+        ("head_kind_host", C.c_void_p),
+        ("softmax_scale", C.c_float),
+        ("phi", C.c_int32),
+        ("eps", C.c_float),
+        ("lam", C.c_float),
+        ("head_scale", C.c_void_p),
+        ("s_dev", C.c_void_p),
+        ("x_t", C.c_void_p),
+        ("w_gate", C.c_void_p),
+        ("b_gate", C.c_float),
+        ("s_out", C.c_void_p),
+        ("o_sparse_dbg", C.c_void_p),
+        ("o_linear_dbg", C.c_void_p),
+        ("workspace", C.c_void_p),
+        ("workspace_bytes", C.c_size_t),
+        ("flags", C.c_int32),
+        ("hip_stream", C.c_void_p),
+    ]
+
+
+class KernelTimes(C.Structure):
+    _fields_ = [("gate_ms", C.c_float), ("state_ms", C.c_float), ("finalize_ms", C.c_float),
+                ("attn_ms", C.c_float), ("epilogue_ms", C.c_float), ("calls", C.c_int32)]
+
+
+def build_library(verbose: bool = False) -> str:
+    """Compile csrc/*.hip for gfx950 into libsalad.so next to this file (hipcc cross-compiles
+    without a GPU)."""
+    cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-o", LIB_PATH] + [os.path.join(_CSRC, s) for s in SOURCES]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if verbose or r.returncode != 0:
+        print(r.stdout, r.stderr)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed building libsalad.so")
+    return LIB_PATH
+
+
+_lib: Optional[C.CDLL] = None
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                               "(or paper_2601_16515_amd.binding.build_library()) first; there is no fallback path")
+        L = C.CDLL(LIB_PATH)
+        L.salad_last_error.restype = C.c_char_p
+        L.salad_kept_from_sparsity.restype = C.c_int32
+        L.salad_kept_from_sparsity.argtypes = [C.c_int32, C.c_double]
+        L.salad_block_mask_nnz.restype = C.c_int64
+        L.salad_block_mask_nnz.argtypes = [C.c_int32] * 5 + [C.c_void_p]
+        L.salad_block_mask.restype = C.c_int
+        L.salad_block_mask.argtypes = [C.c_int32] * 5 + [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+        L.salad_fwd_workspace_bytes.restype = C.c_size_t
+        L.salad_fwd_workspace_bytes.argtypes = [C.POINTER(FwdParams)]
+        L.salad_sparse_linear_attn_fwd.restype = C.c_int
+        L.salad_sparse_linear_attn_fwd.argtypes = [C.POINTER(FwdParams)]
+        L.salad_linear_state_fwd.restype = C.c_int
+        L.salad_linear_state_fwd.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                             C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.salad_gate_fwd.restype = C.c_int
+        L.salad_gate_fwd.argtypes = [C.c_void_p, C.c_void_p, C.c_float, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                     C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.salad_timing_enable.restype = C.c_int
+        L.salad_timing_enable.argtypes = [C.c_int32]
+        L.salad_timing_read.restype = C.c_int
+        L.salad_timing_read.argtypes = [C.POINTER(KernelTimes), C.c_int32]
+        L.salad_tune.restype = C.c_int
+        L.salad_tune.argtypes = [C.c_char_p, C.c_int32]
+        _lib = L
+    return _lib
+
+
+def _check(st: int) -> None:
+    if st != SALAD_OK:
+        raise SaladError(st, lib().salad_last_error().decode())
+
+
+def _dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.bfloat16:
+        return SALAD_BF16
+    if t.dtype == torch.float32:
+        return SALAD_F32
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+# ---------------------------------------------------------------------------------------------
+# same names as the C entry points
+# ---------------------------------------------------------------------------------------------
+
+def salad_kept_from_sparsity(nb: int, sparsity: float) -> int:
+    return int(lib().salad_kept_from_sparsity(nb, sparsity))
+
+
+def salad_block_mask_nnz(T: int, Hh: int, W: int, block: int, kept: Sequence[int]) -> int:
+    arr = (C.c_int32 * len(kept))(*kept)
+    return int(lib().salad_block_mask_nnz(T, Hh, W, block, len(kept), arr))
+
+
+def salad_block_mask(T: int, Hh: int, W: int, block: int, kept: Sequence[int], device="cuda"):
+    """Returns (row_ptr, col_idx) int32 device tensors."""
+    import torch
+    H = len(kept)
+    arr = (C.c_int32 * H)(*kept)
+    nnz = lib().salad_block_mask_nnz(T, Hh, W, block, H, arr)
+    if nnz < 0:
+        raise SaladError(SALAD_EINVAL, "salad_block_mask_nnz rejected the arguments")
+    nb = (T * Hh * W + block - 1) // block
+    row_ptr = torch.empty(H * nb + 1, dtype=torch.int32, device=device)
+    col_idx = torch.empty(max(nnz, 1), dtype=torch.int32, device=device)
+    _check(lib().salad_block_mask(T, Hh, W, block, H, arr, row_ptr.data_ptr(), col_idx.data_ptr(), nnz, _stream()))
+    return row_ptr, col_idx[:nnz]
+
+
+def salad_fwd_workspace_bytes(B: int, H: int, N: int, d: int, dtype: int) -> int:
+    p = FwdParams()
+    p.B, p.H, p.N, p.d, p.dtype = B, H, N, d, dtype
+    return int(lib().salad_fwd_workspace_bytes(C.byref(p)))
+
+
+class Workspace:
+    """Caller-owned scratch for the layer call, sized by the library's query."""
+
+    def __init__(self, B: int, H: int, N: int, d: int, dtype: int, device="cuda"):
+        import torch
+        self.bytes = salad_fwd_workspace_bytes(B, H, N, d, dtype)
+        self.buf = torch.empty(max(self.bytes, 256) + 256, dtype=torch.uint8, device=device)
+        self.ptr = (self.buf.data_ptr() + 255) & ~255
+
+
+def make_fwd_params(q, k, v, out, grid: Tuple[int, int, int], row_ptr, col_idx, head_kind=None, *,
+                    lam: float = 1.0, head_scale=None, s=None, x_t=None, w_gate=None, b_gate: float = 0.0,
+                    eps: float = 1e-6, softmax_scale: float = 0.0, s_out=None, o_sparse_dbg=None,
+                    o_linear_dbg=None, workspace: Optional[Workspace] = None, flags: int = 0, block: int = 64):
+    """Fill a salad_fwd_params from torch tensors.  Returns (params, keepalive)."""
+    B, H, N, d = q.shape
+    p = FwdParams()
+    p.B, p.H, p.N, p.d = B, H, N, d
+    p.dtype = _dtype_code(q)
+    p.T, p.Hh, p.W = grid
+    p.block = block
+    p.q, p.k, p.v, p.out = q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr()
+    p.row_ptr, p.col_idx = row_ptr.data_ptr(), col_idx.data_ptr()
+    hk = None
+    if head_kind is not None:
+        hk = (C.c_uint8 * H)(*[int(x) for x in head_kind])
+        p.head_kind_host = C.cast(hk, C.c_void_p)
+    p.softmax_scale = softmax_scale
+    p.phi = SALAD_PHI_RELU
+    p.eps = eps
+    p.lam = lam
+    p.head_scale = _ptr(head_scale)
+    p.s_dev = _ptr(s)
+    p.x_t = _ptr(x_t)
+    p.w_gate = _ptr(w_gate)
+    p.b_gate = b_gate
+    p.s_out = _ptr(s_out)
+    p.o_sparse_dbg = _ptr(o_sparse_dbg)
+    p.o_linear_dbg = _ptr(o_linear_dbg)
+    if workspace is not None:
+        p.workspace = workspace.ptr
+        p.workspace_bytes = workspace.bytes
+    p.flags = flags
+    p.hip_stream = _stream()
+    return p, (hk, workspace)
+
+
+def salad_sparse_linear_attn_fwd(q, k, v, grid, row_ptr, col_idx, head_kind=None, *, out=None, **kw):
+    """Whole layer.  Allocates `out` (and a workspace unless one is passed) with torch, then makes
+    exactly one library call."""
+    import torch
+    B, H, N, d = q.shape
+    for t in (q, k, v):
+        assert t.is_cuda and t.is_contiguous() and t.shape == q.shape and t.dtype == q.dtype
+    if out is None:
+        out = torch.empty_like(q)
+    if kw.get("workspace") is None and kw.get("lam", 1.0) != 0.0:
+        kw["workspace"] = Workspace(B, H, N, d, _dtype_code(q), q.device)
+    p, keep = make_fwd_params(q, k, v, out, grid, row_ptr, col_idx, head_kind, **kw)
+    _check(lib().salad_sparse_linear_attn_fwd(C.byref(p)))
+    return out
+
+
+def salad_fwd_call(p: FwdParams) -> None:
+    """Re-issue a prepared call (benchmark loop: no allocation, no marshalling)."""
+    _check(lib().salad_sparse_linear_attn_fwd(C.byref(p)))
+
+
+def salad_linear_state_fwd(k, v, workspace: Optional[Workspace] = None):
+    import torch
+    B, H, N, d = k.shape
+    assert k.is_cuda and k.is_contiguous() and v.is_contiguous() and v.shape == k.shape
+    code = _dtype_code(k)
+    ws = workspace or Workspace(B, H, N, d, code, k.device)
+    Hs = torch.empty(B, H, d, d, dtype=torch.float32, device=k.device)
+    Z = torch.empty(B, H, d, dtype=torch.float32, device=k.device)
+    _check(lib().salad_linear_state_fwd(k.data_ptr(), v.data_ptr(), B, H, N, d, code, Hs.data_ptr(), Z.data_ptr(),
+                                        ws.ptr, ws.bytes, _stream()))
+    return Hs, Z
+
+
+def salad_gate_fwd(x_t, w_gate, b_gate: float = 0.0):
+    import torch
+    B, N, D = x_t.shape
+    assert x_t.is_cuda and x_t.is_contiguous() and w_gate.dtype == torch.float32 and w_gate.numel() == D
+    s = torch.empty(B, dtype=torch.float32, device=x_t.device)
+    ws = torch.empty(4 * B * 1024 + 1024, dtype=torch.uint8, device=x_t.device)
+    ptr = (ws.data_ptr() + 255) & ~255
+    _check(lib().salad_gate_fwd(x_t.data_ptr(), w_gate.data_ptr(), b_gate, B, N, D, _dtype_code(x_t), s.data_ptr(),
+                                ptr, ws.numel() - 256, _stream()))
+    return s
+
+
+def salad_timing_enable(on: bool) -> None:
+    _check(lib().salad_timing_enable(1 if on else 0))
+
+
+def salad_timing_read(reset: bool = True) -> KernelTimes:
+    kt = KernelTimes()
+    _check(lib().salad_timing_read(C.byref(kt), 1 if reset else 0))
+    return kt
+
+
+def salad_tune(key: str, value: int) -> None:
+    _check(lib().salad_tune(key.encode(), value))

@@ -1,0 +1,241 @@
+// Linear-attention state, Eq. (3):  Hs = sum_j relu(K_j)^T V_j  (d x d),  Z = sum_j relu(K_j).
+//
+// bf16 kernel.  HBM-bound: K and V are each read once (4*N*d bytes per head) for 2*N*d*d flops,
+// 64 flop/byte at d = 128 - below the MFMA ridge but above what plain FMAs sustain, so the outer
+// products run on bf16 MFMA with fp32 accumulators.  The contraction runs over tokens, which is
+// the row index of the stored [N, d] tensors, so both operands must be transposed on the way:
+// each thread loads a (TPT tokens x 8 features) patch with 16-byte loads, transposes it in
+// registers with byte permutes and writes token-contiguous vectors to LDS; MFMA operands are then
+// single 16-byte LDS reads.  The LDS tile is [feature][64 tokens + 8 pad] with the 8-token group
+// index XOR-ed by (feature / 16) so that both the 8-byte transposed writes and the 16-byte operand
+// reads spread over all banks.
+//
+// One workgroup (4 waves) owns one d x d accumulator: wave w holds the (w/2, w%2) quadrant.
+// The token range of a head is cut into chunks, one workgroup each; the fp32 partial states go to
+// the workspace and are added in chunk order by the finalize kernel (no float atomics, so results
+// are reproducible run to run).
+#include "salad_internal.h"
+
+namespace salad {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef short s16x2 __attribute__((ext_vector_type(2)));
+
+int g_state_target_wgs = 512;
+
+int state_tiles_per_chunk(int BH, int N)
+{
+    int tiles = (N + 63) / 64;
+    int want = g_state_target_wgs / (BH > 0 ? BH : 1);
+    if (want < 1) want = 1;
+    if (want > tiles) want = tiles;
+    return (tiles + want - 1) / want;
+}
+
+int state_num_chunks(int BH, int N)
+{
+    int tiles = (N + 63) / 64;
+    int tpc = state_tiles_per_chunk(BH, N);
+    return (tiles + tpc - 1) / tpc;
+}
+
+constexpr int XT_PITCH = 72;   // 64 tokens + 8 pad, in bf16 elements (144 bytes)
+
+// element offset of (row = feature, tok) in a transposed tile
+__device__ inline int xt_off(int row, int tok)
+{
+    return row * XT_PITCH + ((((tok >> 3) ^ (row >> 4)) & 7) << 3) + (tok & 7);
+}
+
+__device__ inline uint32_t relu_bf16x2(uint32_t x)
+{
+    s16x2 v = __builtin_bit_cast(s16x2, x);
+    s16x2 z = {0, 0};
+    v = __builtin_elementwise_max(v, z);   // negative bf16 (sign bit set) is a negative int16
+    return __builtin_bit_cast(uint32_t, v);
+}
+
+template <int D>
+__global__ __launch_bounds__(256, 2) void state_partial_kernel(const u16 *__restrict__ k,
+                                                               const u16 *__restrict__ v, int N,
+                                                               int tiles_per_chunk, int P,
+                                                               float *__restrict__ partial)
+{
+    constexpr int CH = D / 8;          // 16-byte chunks per row
+    constexpr int TPT = D / 32;        // tokens per thread per tile (4 for d=128, 2 for d=64)
+    constexpr int QT = D / 64;         // 32x32 tiles per side of a wave's quadrant
+    __shared__ __attribute__((aligned(16))) u16 KT[D * XT_PITCH];
+    __shared__ __attribute__((aligned(16))) u16 VT[D * XT_PITCH];
+    __shared__ float zred[4][D];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, hh = lane >> 5;
+    const int bh = blockIdx.y, chunk = blockIdx.x;
+    const int fg = tid % CH, tq = tid / CH;   // feature group (8 features), token group (TPT tokens)
+    const u16 *kb = k + (size_t)bh * N * D;
+    const u16 *vb = v + (size_t)bh * N * D;
+    const int tile0 = chunk * tiles_per_chunk;
+    int tile1 = tile0 + tiles_per_chunk;
+    const int tiles = (N + 63) / 64;
+    if (tile1 > tiles) tile1 = tiles;
+
+    f32x16 acc[QT][QT];
+#pragma unroll
+    for (int i = 0; i < QT; ++i)
+#pragma unroll
+        for (int j = 0; j < QT; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    float zacc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) zacc[e] = 0.f;
+
+    uint4 kreg[TPT], vreg[TPT];
+    auto gload = [&](int tile) {
+#pragma unroll
+        for (int i = 0; i < TPT; ++i) {
+            int n = tile * 64 + tq * TPT + i;
+            if (n < N) {
+                kreg[i] = *reinterpret_cast<const uint4 *>(kb + (size_t)n * D + fg * 8);
+                vreg[i] = *reinterpret_cast<const uint4 *>(vb + (size_t)n * D + fg * 8);
+            } else {
+                kreg[i] = make_uint4(0, 0, 0, 0);
+                vreg[i] = make_uint4(0, 0, 0, 0);
+            }
+        }
+    };
+    // transposed store of a (TPT x 8) patch: for feature f, TPT consecutive tokens
+    auto tstore = [&](u16 *dst, const uint4 (&r)[TPT]) {
+        uint32_t w[TPT][4];
+#pragma unroll
+        for (int i = 0; i < TPT; ++i) { w[i][0] = r[i].x; w[i][1] = r[i].y; w[i][2] = r[i].z; w[i][3] = r[i].w; }
+#pragma unroll
+        for (int f = 0; f < 8; ++f) {
+            const uint32_t sel = (f & 1) ? 0x07060302u : 0x05040100u;
+            int off = xt_off(fg * 8 + f, tq * TPT);
+            if (TPT == 4) {
+                uint2 o;
+                o.x = __builtin_amdgcn_perm(w[1][f >> 1], w[0][f >> 1], sel);
+                o.y = __builtin_amdgcn_perm(w[3][f >> 1], w[2][f >> 1], sel);
+                *reinterpret_cast<uint2 *>(dst + off) = o;
+            } else {
+                uint32_t o = __builtin_amdgcn_perm(w[1][f >> 1], w[0][f >> 1], sel);
+                *reinterpret_cast<uint32_t *>(dst + off) = o;
+            }
+        }
+    };
+
+    const int wa = wave >> 1, wc = wave & 1;
+    if (tile0 < tile1) gload(tile0);
+    for (int tile = tile0; tile < tile1; ++tile) {
+        // ReLU on K, running sums for Z
+#pragma unroll
+        for (int i = 0; i < TPT; ++i) {
+            kreg[i].x = relu_bf16x2(kreg[i].x); kreg[i].y = relu_bf16x2(kreg[i].y);
+            kreg[i].z = relu_bf16x2(kreg[i].z); kreg[i].w = relu_bf16x2(kreg[i].w);
+            uint32_t w4[4] = {kreg[i].x, kreg[i].y, kreg[i].z, kreg[i].w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                zacc[2 * j] += __uint_as_float(w4[j] << 16);
+                zacc[2 * j + 1] += __uint_as_float(w4[j] & 0xffff0000u);
+            }
+        }
+        tstore(KT, kreg);
+        tstore(VT, vreg);
+        __syncthreads();
+        if (tile + 1 < tile1) gload(tile + 1);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {   // 16 tokens per MFMA
+            bf16x8 af[QT], bfr[QT];
+#pragma unroll
+            for (int i = 0; i < QT; ++i) {
+                int ra = (wa * QT + i) * 32 + l32;
+                int rc = (wc * QT + i) * 32 + l32;
+                af[i] = *reinterpret_cast<const bf16x8 *>(KT + xt_off(ra, s * 16 + hh * 8));
+                bfr[i] = *reinterpret_cast<const bf16x8 *>(VT + xt_off(rc, s * 16 + hh * 8));
+            }
+#pragma unroll
+            for (int i = 0; i < QT; ++i)
+#pragma unroll
+                for (int j = 0; j < QT; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+
+    // partial Hs: accumulator register r of lane (l32, hh) is row a = 8*(r/4) + 4*hh + r%4, col c = l32
+    const int per = D * D + D;
+    float *out = partial + ((size_t)bh * P + chunk) * per;
+#pragma unroll
+    for (int i = 0; i < QT; ++i)
+#pragma unroll
+        for (int j = 0; j < QT; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                int a = (wa * QT + i) * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
+                int c = (wc * QT + j) * 32 + l32;
+                out[a * D + c] = acc[i][j][r];
+            }
+    // partial Z: threads with the same fg hold sums over different tokens.  Within a wave the lanes
+    // with equal fg are CH apart; across waves go through LDS in wave order.
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        float zz = zacc[e];
+        for (int o = CH; o < 64; o <<= 1) zz += __shfl_xor(zz, o);
+        zacc[e] = zz;
+    }
+    if (lane < CH) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) zred[wave][lane * 8 + e] = zacc[e];
+    }
+    __syncthreads();
+    if (tid < D) out[D * D + tid] = (zred[0][tid] + zred[1][tid]) + (zred[2][tid] + zred[3][tid]);
+}
+
+hipError_t launch_state_partial_bf16(const u16 *k, const u16 *v, int BH, int N, int D,
+                                     float *partial, hipStream_t st)
+{
+    int tpc = state_tiles_per_chunk(BH, N);
+    int P = state_num_chunks(BH, N);
+    dim3 grid(P, BH), block(256);
+    if (D == 128)
+        hipLaunchKernelGGL(state_partial_kernel<128>, grid, block, 0, st, k, v, N, tpc, P, partial);
+    else
+        hipLaunchKernelGGL(state_partial_kernel<64>, grid, block, 0, st, k, v, N, tpc, P, partial);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// fp32 state for small shapes: one thread per element of Hs, one extra row of threads for Z.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void state_f32_kernel(const float *__restrict__ k, const float *__restrict__ v,
+                                                        int N, int D, float *__restrict__ Hs, float *__restrict__ Z)
+{
+    int bh = blockIdx.y;
+    int e = blockIdx.x * 256 + threadIdx.x;
+    if (e >= D * D + D) return;
+    const float *kb = k + (size_t)bh * N * D;
+    const float *vb = v + (size_t)bh * N * D;
+    if (e < D * D) {
+        int a = e / D, c = e - a * D;
+        float s = 0.f;
+        for (int n = 0; n < N; ++n) s = fmaf(fmaxf(kb[(size_t)n * D + a], 0.f), vb[(size_t)n * D + c], s);
+        Hs[(size_t)bh * D * D + e] = s;
+    } else {
+        int a = e - D * D;
+        float s = 0.f;
+        for (int n = 0; n < N; ++n) s += fmaxf(kb[(size_t)n * D + a], 0.f);
+        Z[(size_t)bh * D + a] = s;
+    }
+}
+
+hipError_t launch_state_f32(const float *k, const float *v, int BH, int N, int D, float *Hs, float *Z,
+                            hipStream_t st)
+{
+    dim3 grid((D * D + D + 255) / 256, BH), block(256);
+    hipLaunchKernelGGL(state_f32_kernel, grid, block, 0, st, k, v, N, D, Hs, Z);
+    return hipGetLastError();
+}
+
+}  // namespace salad

@@ -1,0 +1,381 @@
+// Host side of libsalad: argument checks, workspace layout, launch order, error text, timing.
+// Every check runs before the first HIP call so that bad arguments are reported without a GPU.
+#include <hip/hip_runtime.h>
+
+#include <array>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <vector>
+
+#include "../../include/salad.h"
+#include "salad_internal.h"
+
+using namespace salad;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+salad_status fail(salad_status st, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+salad_status hip_fail(hipError_t e, const char *what)
+{
+    return fail(SALAD_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct WsLayout {
+    size_t gate_partial, state_partial, Hs, Z, hfrag, s, coef, total;
+    int nparts, P;
+};
+
+WsLayout ws_layout(int B, int H, int N, int d, int dtype)
+{
+    WsLayout w{};
+    const size_t BH = (size_t)B * H;
+    w.nparts = gate_num_parts(N);
+    w.P = dtype == SALAD_BF16 ? state_num_chunks((int)BH, N) : 0;
+    size_t off = 0;
+    w.gate_partial = off; off = align256(off + sizeof(float) * (size_t)B * w.nparts);
+    w.state_partial = off; off = align256(off + sizeof(float) * BH * (size_t)w.P * ((size_t)d * d + d));
+    w.Hs = off; off = align256(off + sizeof(float) * BH * d * d);
+    w.Z = off; off = align256(off + sizeof(float) * BH * d);
+    w.hfrag = off; off = align256(off + (dtype == SALAD_BF16 ? sizeof(u16) * BH * 2 * d * d : 0));
+    w.s = off; off = align256(off + sizeof(float) * B);
+    w.coef = off; off = align256(off + sizeof(float) * BH);
+    w.total = off;
+    return w;
+}
+
+bool shape_ok(int B, int H, int N, int d, int dtype)
+{
+    if (B < 1 || H < 1 || N < 1) return false;
+    if (dtype != SALAD_BF16 && dtype != SALAD_F32) return false;
+    if (d != 64 && d != 128) return false;
+    if ((long long)B * H * N * d > (1ll << 40)) return false;
+    return true;
+}
+
+// ---- timing -----------------------------------------------------------------------------------
+std::mutex g_tmu;
+bool g_timing = false;
+struct CallEvents { hipEvent_t e[6]; bool has_epilogue, has_linear; };
+std::vector<CallEvents> g_calls;
+std::vector<hipEvent_t> g_free_events;
+
+hipEvent_t get_event()
+{
+    if (!g_free_events.empty()) {
+        hipEvent_t e = g_free_events.back();
+        g_free_events.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *salad_last_error(void) { return g_err; }
+
+int32_t salad_kept_from_sparsity(int32_t nb, double sparsity)
+{
+    if (nb < 1) return 0;
+    double k = std::floor((1.0 - sparsity) * (double)nb + 0.5);
+    if (!(k >= 1.0)) k = 1.0;
+    if (k > (double)nb) k = (double)nb;
+    return (int32_t)k;
+}
+
+int64_t salad_block_mask_nnz(int32_t T, int32_t Hh, int32_t W, int32_t block, int32_t H, const int32_t *kept_host)
+{
+    if (T < 1 || Hh < 1 || W < 1 || block < 1 || H < 1 || !kept_host) return -1;
+    const int64_t N = (int64_t)T * Hh * W;
+    const int64_t nb = (N + block - 1) / block;
+    int64_t nnz = 0;
+    for (int h = 0; h < H; ++h) {
+        if (kept_host[h] < 1 || kept_host[h] > nb) return -1;
+        nnz += nb * kept_host[h];
+    }
+    return nnz;
+}
+
+salad_status salad_block_mask(int32_t T, int32_t Hh, int32_t W, int32_t block, int32_t H,
+                              const int32_t *kept_host, int32_t *row_ptr_dev, int32_t *col_idx_dev,
+                              int64_t col_capacity, void *hip_stream)
+{
+    if (T < 1 || Hh < 1 || W < 1) return fail(SALAD_EINVAL, "salad_block_mask: grid (%d,%d,%d) must be positive", T, Hh, W);
+    if (block != 64) return fail(SALAD_ENOTSUP, "salad_block_mask: block %d not supported (64 only)", block);
+    if (H < 1 || H > 64) return fail(SALAD_ENOTSUP, "salad_block_mask: H=%d outside 1..64", H);
+    if (!kept_host || !row_ptr_dev || !col_idx_dev) return fail(SALAD_EINVAL, "salad_block_mask: null pointer");
+    const int64_t N = (int64_t)T * Hh * W;
+    if (N > (1ll << 30)) return fail(SALAD_EINVAL, "salad_block_mask: N=%lld too large", (long long)N);
+    const int64_t nnz = salad_block_mask_nnz(T, Hh, W, block, H, kept_host);
+    if (nnz < 0) return fail(SALAD_EINVAL, "salad_block_mask: kept[h] must lie in 1..nb");
+    if (nnz > 0x7fffffffll) return fail(SALAD_ENOTSUP, "salad_block_mask: nnz=%lld exceeds int32", (long long)nnz);
+    if (col_capacity < nnz) return fail(SALAD_ENOSPC, "salad_block_mask: col_capacity %lld < nnz %lld", (long long)col_capacity, (long long)nnz);
+    MaskArgs a{};
+    a.nb = (int32_t)((N + block - 1) / block);
+    a.H = H;
+    int64_t base = 0;
+    for (int h = 0; h < H; ++h) {
+        a.kept[h] = kept_host[h];
+        a.base[h] = base;
+        base += (int64_t)a.nb * kept_host[h];
+    }
+    a.row_ptr = row_ptr_dev;
+    a.col_idx = col_idx_dev;
+    hipError_t e = launch_block_mask(a, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return hip_fail(e, "salad_block_mask launch");
+    return SALAD_OK;
+}
+
+size_t salad_fwd_workspace_bytes(const salad_fwd_params *p)
+{
+    if (!p || !shape_ok(p->B, p->H, p->N, p->d, p->dtype)) return 0;
+    return ws_layout(p->B, p->H, p->N, p->d, p->dtype).total;
+}
+
+salad_status salad_linear_state_fwd(const void *k, const void *v, int32_t B, int32_t H, int32_t N, int32_t d,
+                                    int32_t dtype, float *Hs_out, float *Z_out, void *workspace,
+                                    size_t workspace_bytes, void *hip_stream)
+{
+    if (!k || !v || !Hs_out || !Z_out) return fail(SALAD_EINVAL, "salad_linear_state_fwd: null pointer");
+    if (!shape_ok(B, H, N, d, dtype)) return fail(SALAD_EINVAL, "salad_linear_state_fwd: unsupported shape B=%d H=%d N=%d d=%d dtype=%d", B, H, N, d, dtype);
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (dtype == SALAD_F32) {
+        hipError_t e = launch_state_f32((const float *)k, (const float *)v, B * H, N, d, Hs_out, Z_out, st);
+        if (e != hipSuccess) return hip_fail(e, "state_f32 launch");
+        return SALAD_OK;
+    }
+    WsLayout w = ws_layout(B, H, N, d, dtype);
+    if (!workspace || ((uintptr_t)workspace & 255)) return fail(SALAD_EINVAL, "salad_linear_state_fwd: workspace null or not 256-byte aligned");
+    if (workspace_bytes < w.total) return fail(SALAD_ENOSPC, "salad_linear_state_fwd: workspace %zu < %zu bytes", workspace_bytes, w.total);
+    char *ws = (char *)workspace;
+    hipError_t e = launch_state_partial_bf16((const u16 *)k, (const u16 *)v, B * H, N, d, (float *)(ws + w.state_partial), st);
+    if (e != hipSuccess) return hip_fail(e, "state_partial launch");
+    FinalizeArgs f{};
+    f.B = B; f.H = H; f.D = d;
+    f.state_partial = (const float *)(ws + w.state_partial); f.P = w.P;
+    f.Hs = Hs_out; f.Z = Z_out; f.hfrag = nullptr;
+    f.nparts = 0; f.N = N; f.do_gate = 0;
+    e = launch_finalize(f, st);
+    if (e != hipSuccess) return hip_fail(e, "finalize launch");
+    return SALAD_OK;
+}
+
+salad_status salad_gate_fwd(const void *x_t, const float *w_gate, float b_gate, int32_t B, int32_t N, int32_t D,
+                            int32_t dtype, float *s_out, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!x_t || !w_gate || !s_out) return fail(SALAD_EINVAL, "salad_gate_fwd: null pointer");
+    if (B < 1 || N < 1 || D < 8 || (D & 7)) return fail(SALAD_EINVAL, "salad_gate_fwd: need B,N >= 1 and D a positive multiple of 8 (got %d,%d,%d)", B, N, D);
+    if (D > 5120) return fail(SALAD_ENOTSUP, "salad_gate_fwd: D=%d above 5120", D);
+    if (dtype != SALAD_BF16 && dtype != SALAD_F32) return fail(SALAD_EINVAL, "salad_gate_fwd: dtype %d", dtype);
+    const int nparts = gate_num_parts(N);
+    const size_t need = align256(sizeof(float) * (size_t)B * nparts) + align256(sizeof(float) * B);
+    if (!workspace || ((uintptr_t)workspace & 255)) return fail(SALAD_EINVAL, "salad_gate_fwd: workspace null or not 256-byte aligned");
+    if (workspace_bytes < need) return fail(SALAD_ENOSPC, "salad_gate_fwd: workspace %zu < %zu bytes", workspace_bytes, need);
+    hipStream_t st = (hipStream_t)hip_stream;
+    float *partial = (float *)workspace;
+    hipError_t e = launch_gate_partial(x_t, w_gate, b_gate, B, N, D, dtype == SALAD_BF16, partial, nparts, st);
+    if (e != hipSuccess) return hip_fail(e, "gate launch");
+    FinalizeArgs f{};
+    f.B = B; f.H = 1; f.D = 64; f.P = 0;
+    f.gate_partial = partial; f.nparts = nparts; f.N = N;
+    f.s_out = s_out; f.s_ws = (float *)((char *)workspace + align256(sizeof(float) * (size_t)B * nparts));
+    f.coef = nullptr; f.do_gate = 1;
+    e = launch_finalize(f, st);
+    if (e != hipSuccess) return hip_fail(e, "finalize launch");
+    return SALAD_OK;
+}
+
+salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
+{
+    if (!p) return fail(SALAD_EINVAL, "salad_sparse_linear_attn_fwd: null params");
+    if (p->B < 1 || p->H < 1 || p->N < 1) return fail(SALAD_EINVAL, "fwd: B=%d H=%d N=%d must be positive", p->B, p->H, p->N);
+    if (p->dtype != SALAD_BF16 && p->dtype != SALAD_F32) return fail(SALAD_EINVAL, "fwd: dtype %d", p->dtype);
+    if (p->d != 64 && p->d != 128) return fail(SALAD_ENOTSUP, "fwd: d=%d not supported (64 or 128)", p->d);
+    if (p->block != 64) return fail(SALAD_ENOTSUP, "fwd: block=%d not supported (64 only)", p->block);
+    if (p->H > 64) return fail(SALAD_ENOTSUP, "fwd: H=%d above 64", p->H);
+    if (p->T < 1 || p->Hh < 1 || p->W < 1 || (long long)p->T * p->Hh * p->W != p->N)
+        return fail(SALAD_EINVAL, "fwd: N=%d is not T*Hh*W = %d*%d*%d", p->N, p->T, p->Hh, p->W);
+    if (!shape_ok(p->B, p->H, p->N, p->d, p->dtype)) return fail(SALAD_EINVAL, "fwd: tensor too large");
+    if (!p->q || !p->k || !p->v || !p->out) return fail(SALAD_EINVAL, "fwd: q, k, v, out must be non-null");
+    if (p->out == p->q || p->out == p->k || p->out == p->v) return fail(SALAD_EINVAL, "fwd: out aliases an input");
+    if (!p->row_ptr || !p->col_idx) return fail(SALAD_EINVAL, "fwd: CSR pointers must be non-null");
+    if (p->phi != SALAD_PHI_RELU) return fail(SALAD_ENOTSUP, "fwd: feature map %d not supported (ReLU only)", p->phi);
+    if (!(p->eps >= 0.f)) return fail(SALAD_EINVAL, "fwd: eps must be >= 0");
+    if (!(p->softmax_scale >= 0.f) || !std::isfinite(p->softmax_scale)) return fail(SALAD_EINVAL, "fwd: softmax_scale must be finite and >= 0");
+    if (!std::isfinite(p->lambda)) return fail(SALAD_EINVAL, "fwd: lambda must be finite");
+    const bool use_linear = p->lambda != 0.f;
+    const bool need_gate = use_linear && !p->s_dev;
+    const int Dm = p->H * p->d;
+    if (need_gate) {
+        if (!p->x_t || !p->w_gate) return fail(SALAD_EINVAL, "fwd: lambda != 0 needs s_dev, or x_t and w_gate");
+        if (Dm > 5120) return fail(SALAD_ENOTSUP, "fwd: gate over D=H*d=%d above 5120; pass s_dev", Dm);
+    }
+    const bool unfused = (p->flags & SALAD_FLAG_UNFUSED_EPILOGUE) != 0;
+    if (unfused && p->dtype != SALAD_BF16) return fail(SALAD_ENOTSUP, "fwd: unfused epilogue is bf16 only");
+    if (p->flags & ~SALAD_FLAG_UNFUSED_EPILOGUE) return fail(SALAD_EINVAL, "fwd: unknown flags 0x%x", p->flags);
+    const WsLayout w = ws_layout(p->B, p->H, p->N, p->d, p->dtype);
+    if (use_linear) {
+        if (!p->workspace || ((uintptr_t)p->workspace & 255)) return fail(SALAD_EINVAL, "fwd: workspace null or not 256-byte aligned");
+        if (p->workspace_bytes < w.total) return fail(SALAD_ENOSPC, "fwd: workspace %zu < %zu bytes", p->workspace_bytes, w.total);
+    }
+    uint64_t kind_mask = 0;
+    if (p->head_kind_host)
+        for (int h = 0; h < p->H; ++h) {
+            if (p->head_kind_host[h] > 1) return fail(SALAD_EINVAL, "fwd: head_kind[%d]=%d", h, (int)p->head_kind_host[h]);
+            if (p->head_kind_host[h] == SALAD_HEAD_TEMPORAL) kind_mask |= 1ull << h;
+        }
+
+    hipStream_t st = (hipStream_t)p->hip_stream;
+    char *ws = (char *)p->workspace;
+    const int BH = p->B * p->H;
+    const bool bf16 = p->dtype == SALAD_BF16;
+    hipError_t e;
+
+    CallEvents ev{};
+    bool timing;
+    {
+        std::lock_guard<std::mutex> lk(g_tmu);
+        timing = g_timing;
+        if (timing)
+            for (auto &x : ev.e) {
+                x = get_event();
+                if (!x) return fail(SALAD_EHIP, "fwd: hipEventCreate failed");
+            }
+    }
+    ev.has_linear = use_linear;
+    ev.has_epilogue = unfused && use_linear;
+    auto mark = [&](int i) { if (timing) (void)hipEventRecord(ev.e[i], st); };
+
+    mark(0);
+    if (use_linear) {
+        if (need_gate) {
+            e = launch_gate_partial(p->x_t, p->w_gate, p->b_gate, p->B, p->N, Dm, bf16, (float *)(ws + w.gate_partial), w.nparts, st);
+            if (e != hipSuccess) return hip_fail(e, "gate launch");
+        }
+        mark(1);
+        if (bf16)
+            e = launch_state_partial_bf16((const u16 *)p->k, (const u16 *)p->v, BH, p->N, p->d, (float *)(ws + w.state_partial), st);
+        else
+            e = launch_state_f32((const float *)p->k, (const float *)p->v, BH, p->N, p->d, (float *)(ws + w.Hs), (float *)(ws + w.Z), st);
+        if (e != hipSuccess) return hip_fail(e, "state launch");
+        mark(2);
+        FinalizeArgs f{};
+        f.B = p->B; f.H = p->H; f.D = p->d;
+        f.state_partial = (const float *)(ws + w.state_partial); f.P = w.P;
+        f.Hs = (float *)(ws + w.Hs); f.Z = (float *)(ws + w.Z);
+        f.hfrag = bf16 ? (u16 *)(ws + w.hfrag) : nullptr;
+        f.gate_partial = (const float *)(ws + w.gate_partial); f.nparts = need_gate ? w.nparts : 0; f.N = p->N;
+        f.s_dev = p->s_dev; f.lambda = p->lambda; f.head_scale = p->head_scale;
+        f.s_out = p->s_out; f.s_ws = (float *)(ws + w.s); f.coef = (float *)(ws + w.coef); f.do_gate = 1;
+        e = launch_finalize(f, st);
+        if (e != hipSuccess) return hip_fail(e, "finalize launch");
+    } else {
+        mark(1);
+        mark(2);
+    }
+    mark(3);
+
+    AttnArgs a{};
+    a.q = p->q; a.k = p->k; a.v = p->v; a.out = p->out;
+    a.row_ptr = p->row_ptr; a.col_idx = p->col_idx;
+    a.B = p->B; a.H = p->H; a.N = p->N; a.nb = (p->N + 63) / 64; a.T = p->T; a.HW = p->Hh * p->W; a.D = p->d;
+    a.kind_mask = kind_mask;
+    a.scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / std::sqrt((float)p->d);
+    a.use_linear = use_linear;
+    a.hfrag = use_linear && bf16 ? (const u16 *)(ws + w.hfrag) : nullptr;
+    a.Hs = use_linear ? (const float *)(ws + w.Hs) : nullptr;
+    a.Z = use_linear ? (const float *)(ws + w.Z) : nullptr;
+    a.coef = use_linear ? (const float *)(ws + w.coef) : nullptr;
+    a.eps = p->eps;
+    a.o_sparse_dbg = p->o_sparse_dbg; a.o_linear_dbg = unfused ? nullptr : p->o_linear_dbg;
+    a.write_sparse_only = unfused;
+    e = bf16 ? launch_sparse_attn_bf16(a, st) : launch_sparse_attn_f32(a, st);
+    if (e != hipSuccess) return hip_fail(e, "sparse attention launch");
+    mark(4);
+    if (unfused && use_linear) {
+        ApplyArgs ap{};
+        ap.q = (const u16 *)p->q; ap.out = (u16 *)p->out; ap.BH = BH; ap.N = p->N; ap.D = p->d;
+        ap.hfrag = (const u16 *)(ws + w.hfrag); ap.Z = (const float *)(ws + w.Z); ap.coef = (const float *)(ws + w.coef);
+        ap.eps = p->eps; ap.o_linear_dbg = p->o_linear_dbg;
+        e = launch_linear_apply_bf16(ap, st);
+        if (e != hipSuccess) return hip_fail(e, "linear apply launch");
+    }
+    mark(5);
+    if (timing) {
+        std::lock_guard<std::mutex> lk(g_tmu);
+        g_calls.push_back(ev);
+    }
+    return SALAD_OK;
+}
+
+salad_status salad_timing_enable(int32_t on)
+{
+    std::lock_guard<std::mutex> lk(g_tmu);
+    g_timing = on != 0;
+    return SALAD_OK;
+}
+
+salad_status salad_timing_read(salad_kernel_times *out, int32_t reset)
+{
+    if (!out) return fail(SALAD_EINVAL, "salad_timing_read: null output");
+    std::lock_guard<std::mutex> lk(g_tmu);
+    std::memset(out, 0, sizeof(*out));
+    for (auto &c : g_calls) {
+        hipError_t e = hipEventSynchronize(c.e[5]);
+        if (e != hipSuccess) return hip_fail(e, "hipEventSynchronize");
+        float ms[5] = {0, 0, 0, 0, 0};
+        for (int i = 0; i < 5; ++i) {
+            e = hipEventElapsedTime(&ms[i], c.e[i], c.e[i + 1]);
+            if (e != hipSuccess) return hip_fail(e, "hipEventElapsedTime");
+        }
+        out->gate_ms += ms[0];
+        out->state_ms += ms[1];
+        out->finalize_ms += ms[2];
+        out->attn_ms += ms[3];
+        out->epilogue_ms += ms[4];
+        out->calls += 1;
+    }
+    if (reset) {
+        for (auto &c : g_calls)
+            for (auto &x : c.e) g_free_events.push_back(x);
+        g_calls.clear();
+    }
+    return SALAD_OK;
+}
+
+/* Tuning knobs for experiments; not part of the documented layer semantics.
+ * "state_wgs": target number of workgroups of the linear-state kernel (changes the workspace size). */
+salad_status salad_tune(const char *key, int32_t value)
+{
+    if (!key) return fail(SALAD_EINVAL, "salad_tune: null key");
+    if (!std::strcmp(key, "state_wgs")) {
+        if (value < 1 || value > 65536) return fail(SALAD_EINVAL, "salad_tune: state_wgs out of range");
+        g_state_target_wgs = value;
+        return SALAD_OK;
+    }
+    if (!std::strcmp(key, "attn_variant")) {
+        g_attn_variant = value;
+        return SALAD_OK;
+    }
+    return fail(SALAD_EINVAL, "salad_tune: unknown key %s", key);
+}
+
+}  // extern "C"

@@ -1,0 +1,87 @@
+// Internal declarations shared by the host API file and the kernel files of libsalad.
+// Not installed; the public interface is include/salad.h.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace salad {
+
+typedef unsigned short u16;
+
+// ---- block mask -------------------------------------------------------------------------------
+struct MaskArgs {
+    int32_t nb, H;
+    int32_t kept[64];
+    int64_t base[64];   // first col_idx entry of head h
+    int32_t *row_ptr, *col_idx;
+};
+hipError_t launch_block_mask(const MaskArgs &a, hipStream_t st);
+
+// ---- gate (Alg. 1 Level 2) ----------------------------------------------------------------------
+// Pass 1: per-workgroup partial sums of sigmoid(x.w + b) -> partial[b * nparts + part].
+hipError_t launch_gate_partial(const void *x_t, const float *w, float bias, int B, int N, int D,
+                               int is_bf16, float *partial, int nparts, hipStream_t st);
+int gate_num_parts(int N);
+
+// ---- linear state (Eq. (3) sums) ----------------------------------------------------------------
+// bf16: partial states over token chunks, MFMA.  partial[(bh*P + c)][D*D + D] fp32.
+int state_tiles_per_chunk(int BH, int N);
+int state_num_chunks(int BH, int N);
+hipError_t launch_state_partial_bf16(const u16 *k, const u16 *v, int BH, int N, int D,
+                                     float *partial, hipStream_t st);
+// fp32: direct evaluation, one thread per state element (small shapes).
+hipError_t launch_state_f32(const float *k, const float *v, int BH, int N, int D,
+                            float *Hs, float *Z, hipStream_t st);
+
+// ---- finalize: reduce partials, dynamic scale, coefficients ---------------------------------------
+struct FinalizeArgs {
+    int B, H, D;
+    // state (bf16 path only; P == 0 skips the state part)
+    const float *state_partial; int P;
+    float *Hs, *Z;       // [BH, D, D], [BH, D] fp32
+    u16 *hfrag;          // [BH][2][D*D] bf16 hi / lo parts of Hs in MFMA A-operand order (may be null)
+    // gate
+    const float *gate_partial; int nparts; int N;   // nparts == 0: take s from s_dev
+    const float *s_dev;
+    float lambda; const float *head_scale;
+    float *s_out;        // [B] (may be null)
+    float *s_ws;         // [B]
+    float *coef;         // [BH] lambda * a_h * s_b (may be null)
+    int do_gate;         // 0: state part only
+};
+hipError_t launch_finalize(const FinalizeArgs &a, hipStream_t st);
+
+// ---- sparse attention + fused linear apply / scale / sum -------------------------------------------
+struct AttnArgs {
+    const void *q, *k, *v;
+    void *out;
+    const int32_t *row_ptr, *col_idx;
+    int B, H, N, nb, T, HW, D;
+    unsigned long long kind_mask;   // bit h set: head h uses the temporal token order
+    float scale;                    // softmax scale (natural-log domain)
+    int use_linear;                 // 0: out = O_s
+    const u16 *hfrag;               // bf16 path
+    const float *Hs;                // fp32 path
+    const float *Z;
+    const float *coef;              // [BH]
+    float eps;
+    float *o_sparse_dbg, *o_linear_dbg;
+    int write_sparse_only;          // bf16: store O_s (rounded) to out and skip the linear part
+};
+hipError_t launch_sparse_attn_bf16(const AttnArgs &a, hipStream_t st);
+hipError_t launch_sparse_attn_f32(const AttnArgs &a, hipStream_t st);
+
+// ---- unfused linear apply + scale + sum (bf16): out = out + coef * phi(Q) Hs / (phi(Q).Z + eps) ----
+struct ApplyArgs {
+    const u16 *q; u16 *out;     // out holds O_s on entry
+    int BH, N, D;
+    const u16 *hfrag; const float *Z; const float *coef; float eps;
+    float *o_linear_dbg;
+};
+hipError_t launch_linear_apply_bf16(const ApplyArgs &a, hipStream_t st);
+
+// tuning knobs (salad_tune)
+extern int g_state_target_wgs;
+extern int g_attn_variant;
+
+}  // namespace salad

@@ -14,7 +14,9 @@ never shifts another.
 """
 from __future__ import annotations
 
+import concurrent.futures
 import dataclasses
+import os
 from typing import Dict, List, Optional, Tuple
 
 import numpy as np
@@ -55,16 +57,26 @@ def uniform(seed: int, tag: str, shape, lo: float = 0.0, hi: float = 1.0) -> np.
     return (lo + (hi - lo) * u).reshape(shape)
 
 
-def normal(seed: int, tag: str, shape, std: float = 1.0, chunk: int = 1 << 22) -> np.ndarray:
-    """N(0, std^2) float32 array; element i uses counters 2i and 2i+1 (Box-Muller, cosine branch)."""
+def _normal_chunk(key: np.uint64, std: float, out: np.ndarray, s: int, c: int) -> None:
+    u = _uniform01(key, 2 * s, 2 * c)
+    r = np.sqrt(-2.0 * np.log(u[0::2]))
+    out[s:s + c] = (std * r * np.cos(2.0 * np.pi * u[1::2])).astype(np.float32)
+
+
+def normal(seed: int, tag: str, shape, std: float = 1.0, chunk: int = 1 << 20) -> np.ndarray:
+    """N(0, std^2) float32 array; element i uses counters 2i and 2i+1 (Box-Muller, cosine branch).
+    Chunks are filled by a small thread pool; the values do not depend on the chunking."""
     n = int(np.prod(shape))
     out = np.empty(n, dtype=np.float32)
     key = _key(seed, tag)
-    for s in range(0, n, chunk):
-        c = min(chunk, n - s)
-        u = _uniform01(key, 2 * s, 2 * c)
-        r = np.sqrt(-2.0 * np.log(u[0::2]))
-        out[s:s + c] = (std * r * np.cos(2.0 * np.pi * u[1::2])).astype(np.float32)
+    starts = list(range(0, n, chunk))
+    if len(starts) <= 1:
+        for s in starts:
+            _normal_chunk(key, std, out, s, min(chunk, n - s))
+    else:
+        workers = max(1, min(16, os.cpu_count() or 1))
+        with concurrent.futures.ThreadPoolExecutor(workers) as ex:
+            list(ex.map(lambda s: _normal_chunk(key, std, out, s, min(chunk, n - s)), starts))
     return out.reshape(shape)
 
 

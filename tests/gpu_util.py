@@ -1,0 +1,94 @@
+"""Helpers for the GPU parity tests: upload seeded inputs, run the library through its binding,
+evaluate the oracle on the same numbers, compare with the stated tolerances."""
+import sys
+
+import numpy as np
+import torch
+
+from paper_2601_16515_amd import binding as sb
+from paper_2601_16515_amd import workloads as wl
+
+# spec tolerances for bf16 inputs with fp32 accumulation
+MAX_ABS = 2e-2
+REL_L2 = 5e-3
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def to_dev(a, dtype):
+    t = torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    return t.to(torch.bfloat16) if dtype == "bf16" else t
+
+
+def upload(w, inp):
+    d = {t: to_dev(inp[t], w.dtype) for t in ("q", "k", "v")}
+    if "x_t" in inp:
+        d["x_t"] = to_dev(inp["x_t"], w.dtype)
+    d["w_gate"] = torch.from_numpy(inp["w_gate"]).cuda()
+    d["head_scale"] = torch.from_numpy(inp["head_scale"]).cuda()
+    return d
+
+
+def errors(got, ref):
+    """max-abs and relative L2 of got against ref (float64 arrays of equal shape)."""
+    diff = got - ref
+    den = float(np.sqrt((ref ** 2).sum()))
+    return float(np.abs(diff).max()), float(np.sqrt((diff ** 2).sum()) / max(den, 1e-300))
+
+
+def gather_rows(full, rows):
+    """full [B,H,N,d] numpy, rows [B,H,R] (stored row or -1) -> ([B,H,R,d], mask [B,H,R])."""
+    B, H, R = rows.shape
+    ok = rows >= 0
+    idx = np.where(ok, rows, 0)
+    out = np.take_along_axis(full, idx[..., None], axis=2)
+    return out, ok
+
+
+def run_layer(w, inp, dev, kept, kinds, *, lam=None, dbg=True, flags=0, s=None, head_scale="default",
+              b_gate=0.0, csr=None, softmax_scale=0.0, eps=None):
+    """One layer call; returns dict of numpy float64 arrays (out, o_sparse, o_linear, s)."""
+    grid = (w.T, w.Hh, w.W)
+    if csr is None:
+        row_ptr, col_idx = sb.salad_block_mask(w.T, w.Hh, w.W, w.block, kept)
+    else:
+        row_ptr, col_idx = (torch.from_numpy(np.ascontiguousarray(x, dtype=np.int32)).cuda() for x in csr)
+    q = dev["q"]
+    o_s = torch.full(q.shape, float("nan"), dtype=torch.float32, device="cuda") if dbg else None
+    o_l = torch.full(q.shape, float("nan"), dtype=torch.float32, device="cuda") if dbg else None
+    s_out = torch.zeros(w.B, dtype=torch.float32, device="cuda")
+    hs = dev["head_scale"] if isinstance(head_scale, str) else head_scale
+    out = sb.salad_sparse_linear_attn_fwd(
+        q, dev["k"], dev["v"], grid, row_ptr, col_idx, kinds,
+        lam=w.lam if lam is None else lam, head_scale=hs, s=s,
+        x_t=None if s is not None else dev.get("x_t"), w_gate=None if s is not None else dev["w_gate"],
+        b_gate=b_gate, eps=w.eps if eps is None else eps, softmax_scale=softmax_scale, s_out=s_out,
+        o_sparse_dbg=o_s, o_linear_dbg=o_l, flags=flags)
+    torch.cuda.synchronize()
+    res = {"out": out.float().cpu().numpy().astype(np.float64), "s": s_out.cpu().numpy().astype(np.float64),
+           "row_ptr": row_ptr.cpu().numpy(), "col_idx": col_idx.cpu().numpy(), "out_t": out}
+    if dbg:
+        res["o_sparse"] = o_s.cpu().numpy().astype(np.float64)
+        res["o_linear"] = o_l.cpu().numpy().astype(np.float64)
+    return res
+
+
+def compare_layer(res, ref, *, check_linear=True, tol_abs=MAX_ABS, tol_rel=REL_L2, label=""):
+    """Compare a run_layer result with an oracle salad_forward result on the oracle's row set."""
+    rows = ref["rows"]
+    report = {}
+    for name in ("out", "o_sparse", "o_linear"):
+        if name not in res or (name == "o_linear" and not check_linear):
+            continue
+        got, ok = gather_rows(res[name], rows)
+        assert np.isfinite(got[ok]).all(), f"{label}{name}: non-finite values on valid rows"
+        report[name] = errors(got[ok], ref[name][ok])
+    say(f"  {label} " + " ".join(f"{k}: max_abs={a:.3e} rel_l2={r:.3e}" for k, (a, r) in report.items()))
+    for name, (a, r) in report.items():
+        assert r <= tol_rel, f"{label}{name}: rel_l2 {r:.3e} > {tol_rel}"
+        if name == "out":
+            assert a <= tol_abs, f"{label}{name}: max_abs {a:.3e} > {tol_abs}"
+    return report

@@ -1,0 +1,155 @@
+"""C-ABI checks that need no GPU: the library loads, exports every declared symbol, and rejects
+bad arguments on the host before any HIP call."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2601_16515_amd import binding as sb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(sb.LIB_PATH):
+        sb.build_library()
+    return sb.lib()
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "salad.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(salad_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_symbols()
+    assert set(names) == set(sb.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_kept_from_sparsity_host_arithmetic(lib, oracle):
+    for nb in (1, 2, 16, 195, 512, 1182):
+        for rho in (0.0, 0.5, 0.75, 0.9, 0.95, 1.0, 0.333):
+            assert sb.salad_kept_from_sparsity(nb, rho) == oracle.kept_from_sparsity(nb, rho)
+    assert sb.salad_kept_from_sparsity(0, 0.5) == 0
+    assert sb.salad_kept_from_sparsity(512, 0.9) == 51
+
+
+def test_mask_nnz(lib):
+    assert sb.salad_block_mask_nnz(21, 30, 52, 64, [51] * 12) == 313344
+    assert sb.salad_block_mask_nnz(4, 16, 16, 64, [4, 4]) == 128
+    assert sb.salad_block_mask_nnz(4, 16, 16, 64, [4, 17]) == -1
+    assert sb.salad_block_mask_nnz(4, 16, 16, 64, [0, 4]) == -1
+    assert sb.salad_block_mask_nnz(0, 16, 16, 64, [1]) == -1
+
+
+def _err(lib):
+    return lib.salad_last_error().decode()
+
+
+def test_block_mask_argument_errors(lib):
+    kept = (C.c_int32 * 2)(4, 4)
+    fake = 0x1000   # never dereferenced: every check happens before the first HIP call
+    assert lib.salad_block_mask(4, 16, 16, 64, 2, kept, None, fake, 128, None) == sb.SALAD_EINVAL
+    assert "null" in _err(lib)
+    assert lib.salad_block_mask(4, 16, 16, 32, 2, kept, fake, fake, 128, None) == sb.SALAD_ENOTSUP
+    assert lib.salad_block_mask(4, 16, 16, 64, 2, kept, fake, fake, 127, None) == sb.SALAD_ENOSPC
+    assert "127" in _err(lib)
+    assert lib.salad_block_mask(4, 0, 16, 64, 2, kept, fake, fake, 128, None) == sb.SALAD_EINVAL
+    bad = (C.c_int32 * 2)(4, 99)
+    assert lib.salad_block_mask(4, 16, 16, 64, 2, bad, fake, fake, 1 << 20, None) == sb.SALAD_EINVAL
+    many = (C.c_int32 * 65)(*([1] * 65))
+    assert lib.salad_block_mask(4, 16, 16, 64, 65, many, fake, fake, 1 << 20, None) == sb.SALAD_ENOTSUP
+
+
+def _params(**over):
+    p = sb.FwdParams()
+    p.B, p.H, p.N, p.d, p.dtype = 1, 2, 1024, 64, sb.SALAD_BF16
+    p.T, p.Hh, p.W, p.block = 4, 16, 16, 64
+    for f in ("q", "k", "v", "row_ptr", "col_idx", "x_t", "w_gate"):
+        setattr(p, f, 0x1000)
+    p.out = 0x2000
+    p.workspace = 0x4000
+    p.workspace_bytes = 1 << 30
+    p.lam = 1.0
+    p.eps = 1e-6
+    for k, v in over.items():
+        setattr(p, k, v)
+    return p
+
+
+@pytest.mark.parametrize("over,status,needle", [
+    (dict(d=96), sb.SALAD_ENOTSUP, "d=96"),
+    (dict(block=128), sb.SALAD_ENOTSUP, "block"),
+    (dict(N=1000), sb.SALAD_EINVAL, "T*Hh*W"),
+    (dict(q=None), sb.SALAD_EINVAL, "non-null"),
+    (dict(out=0x1000), sb.SALAD_EINVAL, "alias"),
+    (dict(row_ptr=None), sb.SALAD_EINVAL, "CSR"),
+    (dict(phi=3), sb.SALAD_ENOTSUP, "feature map"),
+    (dict(dtype=7), sb.SALAD_EINVAL, "dtype"),
+    (dict(B=0), sb.SALAD_EINVAL, "positive"),
+    (dict(H=65), sb.SALAD_ENOTSUP, "H=65"),
+    (dict(eps=-1.0), sb.SALAD_EINVAL, "eps"),
+    (dict(x_t=None), sb.SALAD_EINVAL, "s_dev"),
+    (dict(workspace=None), sb.SALAD_EINVAL, "workspace"),
+    (dict(workspace=0x4001), sb.SALAD_EINVAL, "aligned"),
+    (dict(workspace_bytes=16), sb.SALAD_ENOSPC, "workspace"),
+    (dict(flags=8), sb.SALAD_EINVAL, "flags"),
+    (dict(flags=1, dtype=sb.SALAD_F32), sb.SALAD_ENOTSUP, "bf16"),
+    (dict(lam=float("nan")), sb.SALAD_EINVAL, "lambda"),
+])
+def test_fwd_argument_errors(lib, over, status, needle):
+    p = _params(**over)
+    assert lib.salad_sparse_linear_attn_fwd(C.byref(p)) == status
+    assert needle in _err(lib)
+
+
+def test_fwd_null_params_and_head_kind(lib):
+    assert lib.salad_sparse_linear_attn_fwd(None) == sb.SALAD_EINVAL
+    hk = (C.c_uint8 * 2)(0, 5)
+    p = _params(head_kind_host=C.cast(hk, C.c_void_p))
+    assert lib.salad_sparse_linear_attn_fwd(C.byref(p)) == sb.SALAD_EINVAL
+    assert "head_kind" in _err(lib)
+
+
+def test_workspace_query(lib):
+    assert sb.salad_fwd_workspace_bytes(1, 12, 32760, 128, sb.SALAD_BF16) > 12 * (128 * 128 + 128) * 4
+    assert sb.salad_fwd_workspace_bytes(1, 2, 1024, 64, sb.SALAD_F32) > 0
+    assert sb.salad_fwd_workspace_bytes(1, 2, 1024, 96, sb.SALAD_BF16) == 0
+    assert sb.salad_fwd_workspace_bytes(1, 2, 1024, 64, sb.SALAD_BF16) % 256 == 0
+
+
+def test_step_entry_points_reject_bad_arguments(lib):
+    fake = 0x1000
+    assert lib.salad_linear_state_fwd(None, fake, 1, 2, 64, 64, sb.SALAD_BF16, fake, fake, fake, 1 << 30, None) == sb.SALAD_EINVAL
+    assert lib.salad_linear_state_fwd(fake, fake, 1, 2, 64, 48, sb.SALAD_BF16, fake, fake, 0x4000, 1 << 30, None) == sb.SALAD_EINVAL
+    assert lib.salad_linear_state_fwd(fake, fake, 1, 2, 64, 64, sb.SALAD_BF16, fake, fake, 0x4000, 8, None) == sb.SALAD_ENOSPC
+    assert lib.salad_gate_fwd(fake, fake, 0.0, 1, 64, 12, sb.SALAD_BF16, fake, 0x4000, 1 << 20, None) == sb.SALAD_EINVAL
+    assert lib.salad_gate_fwd(fake, fake, 0.0, 1, 64, 8192, sb.SALAD_BF16, fake, 0x4000, 1 << 20, None) == sb.SALAD_ENOTSUP
+    assert lib.salad_gate_fwd(fake, None, 0.0, 1, 64, 128, sb.SALAD_BF16, fake, 0x4000, 1 << 20, None) == sb.SALAD_EINVAL
+    assert lib.salad_timing_read(None, 0) == sb.SALAD_EINVAL
+    assert lib.salad_tune(b"no_such_knob", 1) == sb.SALAD_EINVAL
+
+
+def test_binding_refuses_to_run_without_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(sb, "_lib", None)
+    monkeypatch.setattr(sb, "LIB_PATH", str(tmp_path / "missing.so"))
+    with pytest.raises(RuntimeError, match="no fallback"):
+        sb.lib()
+
+
+def test_product_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2601_16515_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "salad_oracle" not in text and "from oracle" not in text and "import oracle" not in text, f
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c")):
+            text = open(os.path.join(ROOT, "oracle", f)).read()
+            assert "paper_2601_16515_amd" not in text and "libsalad.so" not in text, f

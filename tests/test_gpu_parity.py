@@ -1,0 +1,305 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Integer work (the mask) must match bit for bit; floating point within max-abs 2e-2 and
+relative L2 5e-3 (bf16 inputs, fp32 accumulation), per branch and combined."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2601_16515_amd import binding as sb
+from paper_2601_16515_amd import workloads as wl
+from tests.gpu_util import MAX_ABS, REL_L2, compare_layer, errors, gather_rows, run_layer, say, to_dev, upload
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    sb.lib()   # fails loudly if libsalad.so is missing
+
+
+# --------------------------------------------------------------------------------------------- mask
+
+@pytest.mark.parametrize("grid,kept", [
+    ((4, 16, 16), [4, 4]), ((5, 6, 9), [1, 5, 3]), ((8, 30, 52), [49] * 12), ((21, 30, 52), [51] * 12),
+    ((21, 30, 52), [512, 1, 26, 256]), ((1, 1, 1), [1]), ((21, 45, 80), [118] * 40),
+])
+def test_block_mask_bit_exact(oracle, grid, kept):
+    say(f"mask grid={grid} kept[0]={kept[0]} H={len(kept)}")
+    row_ptr, col_idx = sb.salad_block_mask(*grid, 64, kept)
+    torch.cuda.synchronize()
+    rp, ci = oracle.block_mask(*grid, 64, kept)
+    assert np.array_equal(row_ptr.cpu().numpy(), rp)
+    assert np.array_equal(col_idx.cpu().numpy(), ci)
+
+
+# --------------------------------------------------------------------------------------------- gate
+
+@pytest.mark.parametrize("B,N,D,dtype", [(1, 1024, 128, "f32"), (2, 270, 1536, "bf16"), (1, 4099, 5120, "bf16"),
+                                         (3, 7, 64, "bf16"), (1, 1, 8, "f32"), (1, 12480, 1536, "bf16")])
+def test_gate_parity(oracle, B, N, D, dtype):
+    say(f"gate B={B} N={N} D={D} {dtype}")
+    x = wl.normal(50, "x", (B, N, D))
+    if dtype == "bf16":
+        x = wl.round_to_bf16(x)
+    wg = wl.normal(50, "w", (D,), std=0.05)
+    for bias in (0.0, 0.7):
+        s = sb.salad_gate_fwd(to_dev(x, dtype), torch.from_numpy(wg).cuda(), bias)
+        torch.cuda.synchronize()
+        ref = oracle.gate(x, wg, bias)
+        assert np.abs(s.cpu().numpy().astype(np.float64) - ref).max() < 2e-6
+
+
+# ------------------------------------------------------------------------------------- linear state
+
+@pytest.mark.parametrize("B,H,N,d,dtype", [(1, 2, 270, 128, "bf16"), (2, 3, 1000, 128, "bf16"), (1, 2, 777, 64, "bf16"),
+                                           (1, 1, 64, 128, "bf16"), (1, 1, 5, 64, "bf16"), (1, 2, 300, 64, "f32"),
+                                           (1, 12, 12480, 128, "bf16")])
+def test_linear_state_parity(oracle, B, H, N, d, dtype):
+    say(f"state B={B} H={H} N={N} d={d} {dtype}")
+    k = wl.normal(60, "k", (B, H, N, d))
+    v = wl.normal(60, "v", (B, H, N, d))
+    if dtype == "bf16":
+        k, v = wl.round_to_bf16(k), wl.round_to_bf16(v)
+    Hs, Z = sb.salad_linear_state_fwd(to_dev(k, dtype), to_dev(v, dtype))
+    torch.cuda.synchronize()
+    rH, rZ = oracle.linear_state(k, v)
+    aH, eH = errors(Hs.cpu().numpy().astype(np.float64), rH)
+    aZ, eZ = errors(Z.cpu().numpy().astype(np.float64), rZ)
+    say(f"  Hs rel_l2={eH:.3e} Z rel_l2={eZ:.3e}")
+    assert eH < 2e-6 and eZ < 2e-6          # exact bf16 products, fp32 accumulation
+
+
+def test_linear_state_chunking_does_not_change_result(oracle):
+    """Different numbers of token chunks (workgroups) only change the fp32 summation order."""
+    k = wl.round_to_bf16(wl.normal(61, "k", (1, 2, 2000, 128)))
+    v = wl.round_to_bf16(wl.normal(61, "v", (1, 2, 2000, 128)))
+    rH, rZ = oracle.linear_state(k, v)
+    try:
+        for wgs in (2, 7, 64, 4096):
+            sb.salad_tune("state_wgs", wgs)
+            Hs, Z = sb.salad_linear_state_fwd(to_dev(k, "bf16"), to_dev(v, "bf16"))
+            torch.cuda.synchronize()
+            assert errors(Hs.cpu().numpy().astype(np.float64), rH)[1] < 2e-6
+            assert errors(Z.cpu().numpy().astype(np.float64), rZ)[1] < 2e-6
+    finally:
+        sb.salad_tune("state_wgs", 512)
+
+
+# -------------------------------------------------------------------------------------- whole layer
+
+def _oracle_layer(oracle, w, inp, kept, kinds, sel=None, **kw):
+    return oracle.salad_forward(inp["q"], inp["k"], inp["v"], inp["x_t"], inp["w_gate"], inp["head_scale"],
+                                grid=(w.T, w.Hh, w.W), block=w.block, head_kind=kinds, kept=kept,
+                                lam=kw.pop("lam", w.lam), eps=kw.pop("eps", w.eps), sel=sel, **kw)
+
+
+SMALL = [
+    wl.small("tail14-d128", 1, 2, 128, 5, 6, 9, "bf16", 0.5, seed=101),      # N=270: 5 blocks, 14-token tail
+    wl.small("odd-blocks-d128", 2, 3, 128, 7, 9, 11, "bf16", 0.6, seed=102),  # N=693: 11 blocks, tail 53, B=2
+    wl.small("d64", 1, 4, 64, 6, 10, 10, "bf16", 0.7, seed=103),              # N=600: 10 blocks, tail 24
+    wl.small("one-block", 1, 2, 128, 2, 3, 5, "bf16", 0.0, seed=104),         # N=30 < one block
+    wl.small("exact-blocks", 1, 2, 128, 4, 8, 16, "bf16", 0.75, seed=105),    # N=512, no tail
+    wl.small("T-gt-block", 1, 2, 128, 70, 3, 2, "bf16", 0.5, seed=106),       # T=70 > 64: a location spans blocks
+]
+
+
+@pytest.mark.parametrize("w", SMALL, ids=lambda w: w.name)
+def test_layer_parity_small_bf16(oracle, w):
+    say(f"layer {w.name} N={w.N} nb={w.nb}")
+    inp = wl.make_inputs(w)
+    dev = upload(w, inp)
+    kinds = wl.head_kinds(w)
+    k = sb.salad_kept_from_sparsity(w.nb, w.sparsity)
+    kept = [max(1, min(w.nb, k + (h % 2))) for h in range(w.H)]      # heads differ in window size
+    res = run_layer(w, inp, dev, kept, kinds)
+    ref = _oracle_layer(oracle, w, inp, kept, kinds)
+    assert np.array_equal(res["row_ptr"], ref["row_ptr"]) and np.array_equal(res["col_idx"], ref["col_idx"])
+    assert np.abs(res["s"] - ref["s"]).max() < 2e-6
+    compare_layer(res, ref, label=w.name)
+
+
+def test_layer_parity_tiny_config_fp32(oracle):
+    w = wl.TINY
+    say(f"layer {w.name} (fp32) N={w.N}")
+    inp = wl.make_inputs(w)
+    dev = upload(w, inp)
+    kinds = wl.head_kinds(w)
+    kept = [sb.salad_kept_from_sparsity(w.nb, w.sparsity)] * w.H
+    assert kept == [4, 4]
+    res = run_layer(w, inp, dev, kept, kinds)
+    ref = _oracle_layer(oracle, w, inp, kept, kinds)
+    assert np.array_equal(res["col_idx"], ref["col_idx"])
+    compare_layer(res, ref, tol_abs=1e-4, tol_rel=1e-5, label="tiny-f32")
+
+
+def test_fp32_path_ragged_d128(oracle):
+    w = wl.small("f32-d128", 1, 2, 128, 3, 7, 9, "f32", 0.4, seed=107)       # N=189
+    inp = wl.make_inputs(w)
+    dev = upload(w, inp)
+    kinds = wl.head_kinds(w)
+    kept = [2, 3]
+    res = run_layer(w, inp, dev, kept, kinds)
+    compare_layer(res, _oracle_layer(oracle, w, inp, kept, kinds), tol_abs=1e-4, tol_rel=1e-5, label="f32-d128")
+
+
+def test_zero_static_scale_gives_sparse_branch_exactly(oracle):
+    """Zero-initialised static scale (Sec. 4.2): the layer output is the sparse branch alone; the
+    three ways of switching the linear branch off agree bit for bit."""
+    w = SMALL[1]
+    inp = wl.make_inputs(w)
+    dev = upload(w, inp)
+    kinds = wl.head_kinds(w)
+    kept = [4] * w.H
+    r0 = run_layer(w, inp, dev, kept, kinds, lam=0.0, dbg=False)
+    r1 = run_layer(w, inp, dev, kept, kinds, head_scale=torch.zeros(w.H, device="cuda"), dbg=False)
+    r2 = run_layer(w, inp, dev, kept, kinds, s=torch.zeros(w.B, device="cuda"), dbg=False)
+    assert torch.equal(r0["out_t"], r1["out_t"]) and torch.equal(r0["out_t"], r2["out_t"])
+    ref = _oracle_layer(oracle, w, inp, kept, kinds, lam=0.0)
+    assert np.array_equal(ref["out"], ref["o_sparse"])
+    compare_layer(r0, ref, label="lambda=0")
+
+
+def test_linear_dominant_case(oracle):
+    """On N(0,1) inputs the linear term is below the bf16 spacing of O_s, so a large static scale
+    makes the combined output sensitive to the linear branch."""
+    w = SMALL[0]
+    inp = wl.make_inputs(w)
+    dev = upload(w, inp)
+    kinds = wl.head_kinds(w)
+    kept = [3, 2]
+    res = run_layer(w, inp, dev, kept, kinds, lam=100.0)
+    ref = _oracle_layer(oracle, w, inp, kept, kinds, lam=100.0)
+    got, ok = gather_rows(res["out"], ref["rows"])
+    lin_share = np.abs(ref["out"] - ref["o_sparse"])[ok].mean() / np.abs(ref["out"])[ok].mean()
+    assert lin_share > 0.5
+    a, r = errors(got[ok], ref["out"][ok])
+    say(f"  linear-dominant: share={lin_share:.2f} max_abs={a:.3e} rel_l2={r:.3e}")
+    assert r <= REL_L2
+
+
+def test_precomputed_s_and_bias_and_scale_arguments(oracle):
+    w = SMALL[2]
+    inp = wl.make_inputs(w)
+    dev = upload(w, inp)
+    kinds = wl.head_kinds(w)
+    kept = [3] * w.H
+    s = torch.tensor([0.31], device="cuda")
+    res = run_layer(w, inp, dev, kept, kinds, s=s, softmax_scale=0.2, eps=1e-3)
+    ref = _oracle_layer(oracle, w, inp, kept, kinds, s_override=[0.31], scale=0.2, eps=1e-3)
+    assert abs(res["s"][0] - 0.31) < 1e-7
+    compare_layer(res, ref, label="s_dev")
+    res = run_layer(w, inp, dev, kept, kinds, b_gate=-1.5)
+    ref = _oracle_layer(oracle, w, inp, kept, kinds, b_gate=-1.5)
+    assert np.abs(res["s"] - ref["s"]).max() < 2e-6 and ref["s"][0] < 0.25
+    compare_layer(res, ref, label="b_gate")
+
+
+def test_zero_queries_average_the_kept_values(oracle):
+    """Q = 0: O_s is the plain mean of V over the kept, existing tokens (pins mask wiring, tail and
+    token orders on the GPU without the oracle's softmax)."""
+    w = SMALL[1]
+    inp = wl.make_inputs(w)
+    inp["q"] = np.zeros_like(inp["q"])
+    dev = upload(w, inp)
+    kinds = wl.head_kinds(w)
+    kept = [3, 4, 2]
+    res = run_layer(w, inp, dev, kept, kinds, lam=0.0)
+    rp, ci = oracle.block_mask(w.T, w.Hh, w.W, 64, kept)
+    for h in range(w.H):
+        order = np.array([oracle.row_of_position(int(kinds[h]), p, w.T, w.Hh, w.W) for p in range(w.N)])
+        for i in range(w.nb):
+            cols = ci[rp[h * w.nb + i]:rp[h * w.nb + i + 1]]
+            krows = np.concatenate([order[j * 64:min((j + 1) * 64, w.N)] for j in cols])
+            mean = inp["v"][:, h][:, krows].astype(np.float64).mean(axis=1)          # [B, d]
+            qrows = order[i * 64:min((i + 1) * 64, w.N)]
+            got = res["o_sparse"][:, h][:, qrows]                                      # [B, rows, d]
+            assert np.abs(got - mean[:, None, :]).max() < 3e-3
+
+
+def test_arbitrary_csr(oracle):
+    """Any CSR with ascending unique block ids per row is accepted (e.g. a Top-K selection): rows
+    of different lengths, non-contiguous ids, neighbouring query blocks with disjoint lists."""
+    w = wl.small("csr", 1, 2, 128, 4, 10, 16, "bf16", 0.5, seed=108)    # N=640, nb=10
+    inp = wl.make_inputs(w)
+    dev = upload(w, inp)
+    kinds = wl.head_kinds(w)
+    u = wl.uniform(108, "pick", (w.H * w.nb, w.nb))
+    row_ptr, col_idx = [0], []
+    for r in range(w.H * w.nb):
+        cnt = 1 + (r * 7) % 5
+        cols = sorted(np.argsort(u[r])[:cnt].tolist())
+        col_idx += cols
+        row_ptr.append(len(col_idx))
+    csr = (np.array(row_ptr, np.int32), np.array(col_idx, np.int32))
+    res = run_layer(w, inp, dev, None, kinds, csr=csr)
+    o_s, rows = oracle.sparse_attn(inp["q"], inp["k"], inp["v"], (w.T, w.Hh, w.W), 64, kinds, *csr)
+    got, ok = gather_rows(res["o_sparse"], rows)
+    a, r = errors(got[ok], o_s[ok])
+    say(f"  arbitrary CSR: o_sparse max_abs={a:.3e} rel_l2={r:.3e}")
+    assert r <= REL_L2
+
+
+def test_unfused_epilogue_matches(oracle):
+    w = SMALL[1]
+    inp = wl.make_inputs(w)
+    dev = upload(w, inp)
+    kinds = wl.head_kinds(w)
+    kept = [4] * w.H
+    ref = _oracle_layer(oracle, w, inp, kept, kinds, lam=30.0)
+    res = run_layer(w, inp, dev, kept, kinds, lam=30.0, flags=sb.SALAD_FLAG_UNFUSED_EPILOGUE)
+    compare_layer(res, ref, label="unfused")
+
+
+def test_run_to_run_bit_reproducible():
+    w = SMALL[1]
+    inp = wl.make_inputs(w)
+    dev = upload(w, inp)
+    kinds = wl.head_kinds(w)
+    outs = [run_layer(w, inp, dev, [4] * w.H, kinds, dbg=False)["out_t"] for _ in range(3)]
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+
+
+# ------------------------------------------------------------------- benchmark configurations
+
+def _sampled_parity(oracle, w, nsel, label):
+    say(f"{label}: generating inputs N={w.N} H={w.H}")
+    inp = wl.make_inputs(w)
+    dev = upload(w, inp)
+    kinds = wl.head_kinds(w)
+    kept = [sb.salad_kept_from_sparsity(w.nb, w.sparsity)] * w.H
+    say(f"{label}: GPU call, kept={kept[0]} of {w.nb}")
+    res = run_layer(w, inp, dev, kept, kinds)
+    sel = wl.sample_blocks(w.nb, nsel, w.seed)
+    say(f"{label}: oracle on {len(sel)} query blocks per head")
+    ref = _oracle_layer(oracle, w, inp, kept, kinds, sel=sel)
+    assert np.array_equal(res["row_ptr"], ref["row_ptr"]) and np.array_equal(res["col_idx"], ref["col_idx"])
+    assert np.abs(res["s"] - ref["s"]).max() < 2e-6
+    compare_layer(res, ref, label=label)
+    # properties that hold at any size: finite everywhere, every row written
+    assert np.isfinite(res["out"]).all() and np.isfinite(res["o_sparse"]).all() and np.isfinite(res["o_linear"]).all()
+    return res, ref, inp, dev, kinds, kept
+
+
+def test_mid_config_sampled(oracle):
+    _sampled_parity(oracle, wl.MID, 12, "mid")
+
+
+def test_wan13_480p_90_sampled(oracle):
+    """The headline configuration at full size, in the launch configuration the benchmark times;
+    the oracle evaluates sampled query blocks (first, last = 56-token tail, middle, seeded picks)
+    of every head, plus the full linear state and gate."""
+    res, ref, inp, dev, kinds, kept = _sampled_parity(oracle, wl.WAN13_480P, 6, "480p-90")
+    Hs, Z = sb.salad_linear_state_fwd(dev["k"], dev["v"])
+    torch.cuda.synchronize()
+    assert errors(Hs.cpu().numpy().astype(np.float64), ref["Hs"])[1] < 2e-6
+    assert errors(Z.cpu().numpy().astype(np.float64), ref["Z"])[1] < 2e-6
+    # benchmark launch: no debug outputs -> identical bits to the debug-instrumented call
+    fast = run_layer(wl.WAN13_480P, inp, dev, kept, kinds, dbg=False)
+    assert np.array_equal(fast["out"], res["out"])
+
+
+@pytest.mark.parametrize("rho", [0.0, 0.95])
+def test_wan13_480p_sweep_ends_sampled(oracle, rho):
+    w = wl.WAN13_480P.with_sparsity(rho)
+    _sampled_parity(oracle, w, 4 if rho == 0.0 else 8, f"480p-{rho:g}")
