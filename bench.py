@@ -1,0 +1,158 @@
+#!/usr/bin/env python3
+"""Benchmark of the SALAD attention-layer forward on one MI355X.
+
+One step = one call of salad_sparse_linear_attn_fwd (gate, linear state, finalize, block-sparse
+attention with the fused linear apply and scale-and-sum) on the Wan-1.3B-shaped 480p workload at
+90 % sparsity (B=1, H=12, d=128, grid 21x30x52, N=32760, bf16), inputs resident in HBM.  The
+metric is effective TFLOP/s counting only the FLOPs of kept block pairs; ms/call is ms_per_step.
+Prints one JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, published
+
+
+def kept_flops(row_ptr, col_idx, H, N, d, block, B):
+    """4*d*rows_i*cols_j summed over kept block pairs with exact token counts (QK^T and PV)."""
+    import numpy as np
+    nb = (N + block - 1) // block
+    size = np.full(nb, block, dtype=np.int64)
+    size[-1] = N - (nb - 1) * block
+    rows = np.repeat(np.tile(size, H), np.diff(row_ptr))
+    return int(4 * d * B * (rows * size[col_idx]).sum())
+
+
+def cpu_baseline(w, inp, kinds, kept, every):
+    """The oracle as it stands, timed on a bounded sample: every `every`-th query block of every
+    head for the sparse branch (the rest of the layer is a fraction of a percent of its work)."""
+    import numpy as np
+    from oracle import salad_oracle as so
+    rp, ci = so.block_mask(w.T, w.Hh, w.W, w.block, kept)
+    sel = np.arange(0, w.nb, every, dtype=np.int32)
+    t0 = time.time()
+    so.sparse_attn(inp["q"], inp["k"], inp["v"], (w.T, w.Hh, w.W), w.block, kinds, rp, ci, sel=sel)
+    dt = time.time() - t0
+    size = np.full(w.nb, w.block, dtype=np.int64)
+    size[-1] = w.N - (w.nb - 1) * w.block
+    fl = 0
+    for h in range(w.H):
+        for i in sel:
+            cols = ci[rp[h * w.nb + i]:rp[h * w.nb + i + 1]]
+            fl += 4 * w.d * size[i] * size[cols].sum()
+    fl *= w.B
+    return {"value": fl / dt * 1e-12, "unit": "TFLOP/s", "cores": so.threads(), "kind": "oracle",
+            "sample": f"fp64 oracle sparse branch on every {every}th query block of all {w.H} heads "
+                      f"({len(sel)} of {w.nb} blocks, {fl * 1e-9:.1f} GFLOP of kept-block work) in {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--sparsity", type=float, default=None, help="override the workload's sparsity")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense-control", action="store_true")
+    ap.add_argument("--cpu-sample-every", type=int, default=4)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2601_16515_amd import binding as sb, workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    torch.cuda.set_device(0)
+    w = wl.WAN13_480P if args.sparsity is None else wl.WAN13_480P.with_sparsity(args.sparsity)
+    inp = wl.make_inputs(w)
+    kinds = wl.head_kinds(w)
+    kept = [sb.salad_kept_from_sparsity(w.nb, w.sparsity)] * w.H
+    grid = (w.T, w.Hh, w.W)
+    dev = torch.device("cuda:0")
+    q, k, v, x = (torch.from_numpy(inp[t]).to(dev).to(torch.bfloat16) for t in ("q", "k", "v", "x_t"))
+    wg = torch.from_numpy(inp["w_gate"]).to(dev)
+    hs = torch.from_numpy(inp["head_scale"]).to(dev)
+    out = torch.empty_like(q)
+    row_ptr, col_idx = sb.salad_block_mask(*grid, w.block, kept)
+    ws = sb.Workspace(w.B, w.H, w.N, w.d, sb.SALAD_BF16, dev)
+    flops = kept_flops(row_ptr.cpu().numpy(), col_idx.cpu().numpy(), w.H, w.N, w.d, w.block, w.B)
+
+    def timed(params, steps, warmup):
+        for _ in range(warmup):
+            sb.salad_fwd_call(params)
+        torch.cuda.synchronize()
+        sb.salad_timing_read(reset=True)
+        sb.salad_timing_enable(True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            sb.salad_fwd_call(params)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        sb.salad_timing_enable(False)
+        kt = sb.salad_timing_read(reset=True)
+        return dt / steps * 1e3, kt
+
+    p, keep = sb.make_fwd_params(q, k, v, out, grid, row_ptr, col_idx, kinds, lam=w.lam, head_scale=hs, x_t=x,
+                                 w_gate=wg, eps=w.eps, workspace=ws)
+    ms, kt = timed(p, args.steps, args.warmup)
+    n = max(kt.calls, 1)
+    attn_ms, state_ms, gate_ms, fin_ms = kt.attn_ms / n, kt.state_ms / n, kt.gate_ms / n, kt.finalize_ms / n
+    esz = 2
+    kv_bytes = 2 * w.B * w.H * w.N * w.d * esz
+    x_bytes = w.B * w.N * w.D * esz
+    result = {
+        "metric": "effective TFLOP/s on kept blocks (fused sparse + linear attention forward); ms/call = ms_per_step",
+        "value": flops / (ms * 1e-3) * 1e-12, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "H": w.H, "N": w.N, "d": w.d, "grid": list(grid), "block": w.block,
+                   "sparsity": w.sparsity, "kept_blocks_per_query_block": kept[0], "nnz_block_pairs": int(col_idx.numel()),
+                   "kept_gflop": flops * 1e-9, "head_orders": "even heads spatial, odd heads temporal"},
+        "roofline": {"bound": "mfma", "achieved": flops / (attn_ms * 1e-3) * 1e-12, "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": flops / (attn_ms * 1e-3) * 1e-12 / PEAK_BF16_TFLOPS, "traffic": None,
+                     "kernel": "sparse_attn_bf16_kernel<128>", "kernel_ms": attn_ms},
+        "kernels_ms": {"gate": gate_ms, "linear_state": state_ms, "finalize": fin_ms, "sparse_attn_fused": attn_ms},
+        "hbm_kernels": {
+            "linear_state": {"bytes": kv_bytes, "GB/s": kv_bytes / (state_ms * 1e-3) * 1e-9, "frac_of_8TB/s": kv_bytes / (state_ms * 1e-3) * 1e-9 / PEAK_HBM_GBS},
+            "gate": {"bytes": x_bytes, "GB/s": x_bytes / (gate_ms * 1e-3) * 1e-9, "frac_of_8TB/s": x_bytes / (gate_ms * 1e-3) * 1e-9 / PEAK_HBM_GBS},
+        },
+    }
+
+    # unfused epilogue: separate streaming kernel (reads Q and O_s, writes O)
+    pu, keep_u = sb.make_fwd_params(q, k, v, out, grid, row_ptr, col_idx, kinds, lam=w.lam, head_scale=hs, x_t=x,
+                                    w_gate=wg, eps=w.eps, workspace=ws, flags=sb.SALAD_FLAG_UNFUSED_EPILOGUE)
+    ms_u, kt_u = timed(pu, max(5, args.steps // 5), 2)
+    epi_ms = kt_u.epilogue_ms / max(kt_u.calls, 1)
+    epi_bytes = 3 * w.B * w.H * w.N * w.d * esz
+    result["hbm_kernels"]["linear_apply_epilogue_unfused"] = {
+        "bytes": epi_bytes, "GB/s": epi_bytes / (epi_ms * 1e-3) * 1e-9,
+        "frac_of_8TB/s": epi_bytes / (epi_ms * 1e-3) * 1e-9 / PEAK_HBM_GBS, "ms": epi_ms, "unfused_call_ms": ms_u}
+
+    if not args.no_dense_control and w.sparsity > 0:
+        kept_d = [w.nb] * w.H
+        rp_d, ci_d = sb.salad_block_mask(*grid, w.block, kept_d)
+        fl_d = kept_flops(rp_d.cpu().numpy(), ci_d.cpu().numpy(), w.H, w.N, w.d, w.block, w.B)
+        pd, keep_d = sb.make_fwd_params(q, k, v, out, grid, rp_d, ci_d, kinds, lam=w.lam, head_scale=hs, x_t=x,
+                                        w_gate=wg, eps=w.eps, workspace=ws)
+        ms_d, _ = timed(pd, 3, 1)
+        result["dense_control"] = {"ms_per_call": ms_d, "TFLOP/s": fl_d / (ms_d * 1e-3) * 1e-12,
+                                   "speedup_sparse_vs_dense": ms_d / ms,
+                                   "paper_end_to_end_speedup_context": "1.52-2.03x over full attention, GPU model not stated in the paper"}
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, inp, kinds, kept, args.cpu_sample_every)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
