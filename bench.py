@@ -61,7 +61,7 @@ def main():
     ap.add_argument("--sparsity", type=float, default=None, help="override the workload's sparsity")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense-control", action="store_true")
-    ap.add_argument("--cpu-sample-every", type=int, default=4)
+    ap.add_argument("--cpu-sample-every", type=int, default=1)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
