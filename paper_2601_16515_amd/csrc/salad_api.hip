@@ -307,6 +307,7 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
     a.eps = p->eps;
     a.o_sparse_dbg = p->o_sparse_dbg; a.o_linear_dbg = unfused ? nullptr : p->o_linear_dbg;
     a.write_sparse_only = unfused;
+    a.t_magic = ((uint64_t)p->N * (uint64_t)p->T < (1ull << 32) && p->T > 1) ? (unsigned)((1ull << 32) / (uint64_t)p->T + 1) : 0u;
     e = bf16 ? launch_sparse_attn_bf16(a, st) : launch_sparse_attn_f32(a, st);
     if (e != hipSuccess) return hip_fail(e, "sparse attention launch");
     mark(4);

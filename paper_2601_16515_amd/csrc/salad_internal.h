@@ -67,9 +67,11 @@ struct AttnArgs {
     float eps;
     float *o_sparse_dbg, *o_linear_dbg;
     int write_sparse_only;          // bf16: store O_s (rounded) to out and skip the linear part
+    unsigned t_magic;               // floor(2^32 / T) + 1 when N * T < 2^32, else 0
 };
 hipError_t launch_sparse_attn_bf16(const AttnArgs &a, hipStream_t st);
 hipError_t launch_sparse_attn_f32(const AttnArgs &a, hipStream_t st);
+hipError_t launch_sparse_attn_v2(const AttnArgs &a, hipStream_t st);   // d = 128 only
 
 // ---- unfused linear apply + scale + sum (bf16): out = out + coef * phi(Q) Hs / (phi(Q).Z + eps) ----
 struct ApplyArgs {

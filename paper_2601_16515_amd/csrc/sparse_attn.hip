@@ -317,6 +317,7 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_kernel(AttnArgs a, in
 
 hipError_t launch_sparse_attn_bf16(const AttnArgs &a, hipStream_t st)
 {
+    if (a.D == 128 && g_attn_variant == 1) return launch_sparse_attn_v2(a, st);
     const int ntiles = (a.nb + 1) / 2;
     const int total = a.B * a.H * ntiles;
     const int per_xcd = (total + 7) / 8;
