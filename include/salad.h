@@ -98,7 +98,7 @@ typedef struct salad_fwd_params {
     float *s_out;             /* optional device [B]: the dynamic scale that was applied          */
     float *o_sparse_dbg;      /* optional device fp32 [B,H,N,d]: sparse branch alone              */
     float *o_linear_dbg;      /* optional device fp32 [B,H,N,d]: unscaled linear branch alone     */
-    void *workspace;          /* device, >= salad_fwd_workspace_bytes(), 256-byte aligned         */
+    void *workspace;          /* device, >= salad_fwd_workspace_bytes(), 256-byte aligned; always needed */
     size_t workspace_bytes;
     int32_t flags;            /* SALAD_FLAG_* */
     void *hip_stream;
@@ -109,7 +109,7 @@ typedef struct salad_fwd_params {
 #define SALAD_FLAG_UNFUSED_EPILOGUE 1
 
 /* Device scratch the forward needs for these shapes (partial states, partial gate sums, the
- * reduced state).  Reads only B, H, N, d, dtype.  0 on invalid shapes. */
+ * reduced state, per-tile block lists).  Reads only B, H, N, d, dtype.  0 on invalid shapes. */
 size_t salad_fwd_workspace_bytes(const salad_fwd_params *p);
 
 /* Alg. 1 from SparseAttn to the residual sum:

@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(_HERE, "libsalad.so")
 SOURCES = ["salad_api.hip", "mask_gate_finalize.hip", "linear_state.hip", "sparse_attn.hip",
-           "sparse_attn_v2.hip", "linear_apply.hip"]
+           "sparse_attn_v2.hip", "sparse_attn_v5.hip", "linear_apply.hip"]
 
 SALAD_OK, SALAD_EINVAL, SALAD_ENOTSUP, SALAD_ENOSPC, SALAD_EHIP = range(5)
 SALAD_F32, SALAD_BF16 = 0, 1
@@ -231,7 +231,7 @@ def salad_sparse_linear_attn_fwd(q, k, v, grid, row_ptr, col_idx, head_kind=None
         assert t.is_cuda and t.is_contiguous() and t.shape == q.shape and t.dtype == q.dtype
     if out is None:
         out = torch.empty_like(q)
-    if kw.get("workspace") is None and kw.get("lam", 1.0) != 0.0:
+    if kw.get("workspace") is None:
         kw["workspace"] = Workspace(B, H, N, d, _dtype_code(q), q.device)
     p, keep = make_fwd_params(q, k, v, out, grid, row_ptr, col_idx, head_kind, **kw)
     _check(lib().salad_sparse_linear_attn_fwd(C.byref(p)))

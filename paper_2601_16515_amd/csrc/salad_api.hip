@@ -36,7 +36,7 @@ salad_status hip_fail(hipError_t e, const char *what)
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct WsLayout {
-    size_t gate_partial, state_partial, Hs, Z, hfrag, s, coef, total;
+    size_t gate_partial, state_partial, Hs, Z, hfrag, s, coef, tile_lists, tile_counts, total;
     int nparts, P;
 };
 
@@ -54,6 +54,12 @@ WsLayout ws_layout(int B, int H, int N, int d, int dtype)
     w.hfrag = off; off = align256(off + (dtype == SALAD_BF16 ? sizeof(u16) * BH * 2 * d * d : 0));
     w.s = off; off = align256(off + sizeof(float) * B);
     w.coef = off; off = align256(off + sizeof(float) * BH);
+    {   // union lists per (head, 4-block tile) for the large-tile attention kernel
+        const int nb = (N + 63) / 64, ntiles = (nb + 3) / 4;
+        const bool need = dtype == SALAD_BF16 && d == 128 && (size_t)tile_list_cap(nb) * 4 <= 24 * 1024;
+        w.tile_lists = off; off = align256(off + (need ? sizeof(uint32_t) * (size_t)H * ntiles * tile_list_cap(nb) : 0));
+        w.tile_counts = off; off = align256(off + (need ? sizeof(int32_t) * (size_t)H * ntiles : 0));
+    }
     w.total = off;
     return w;
 }
@@ -232,7 +238,8 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
     if (unfused && p->dtype != SALAD_BF16) return fail(SALAD_ENOTSUP, "fwd: unfused epilogue is bf16 only");
     if (p->flags & ~SALAD_FLAG_UNFUSED_EPILOGUE) return fail(SALAD_EINVAL, "fwd: unknown flags 0x%x", p->flags);
     const WsLayout w = ws_layout(p->B, p->H, p->N, p->d, p->dtype);
-    if (use_linear) {
+    const bool need_lists = p->dtype == SALAD_BF16 && p->d == 128 && (size_t)tile_list_cap((p->N + 63) / 64) * 4 <= 24 * 1024;
+    if (use_linear || need_lists) {
         if (!p->workspace || ((uintptr_t)p->workspace & 255)) return fail(SALAD_EINVAL, "fwd: workspace null or not 256-byte aligned");
         if (p->workspace_bytes < w.total) return fail(SALAD_ENOSPC, "fwd: workspace %zu < %zu bytes", p->workspace_bytes, w.total);
     }
@@ -307,6 +314,13 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
     a.eps = p->eps;
     a.o_sparse_dbg = p->o_sparse_dbg; a.o_linear_dbg = unfused ? nullptr : p->o_linear_dbg;
     a.write_sparse_only = unfused;
+    if (need_lists) {
+        a.tile_lists = (const uint32_t *)(ws + w.tile_lists);
+        a.tile_counts = (const int32_t *)(ws + w.tile_counts);
+        a.list_cap = tile_list_cap(a.nb);
+        e = launch_tile_lists(p->row_ptr, p->col_idx, p->H, a.nb, (uint32_t *)(ws + w.tile_lists), (int32_t *)(ws + w.tile_counts), st);
+        if (e != hipSuccess) return hip_fail(e, "tile list launch");
+    }
     a.t_magic = ((uint64_t)p->N * (uint64_t)p->T < (1ull << 32) && p->T > 1) ? (unsigned)((1ull << 32) / (uint64_t)p->T + 1) : 0u;
     e = bf16 ? launch_sparse_attn_bf16(a, st) : launch_sparse_attn_f32(a, st);
     if (e != hipSuccess) return hip_fail(e, "sparse attention launch");
@@ -360,6 +374,13 @@ salad_status salad_timing_read(salad_kernel_times *out, int32_t reset)
         g_calls.clear();
     }
     return SALAD_OK;
+}
+
+/* Development aid, not declared in the public header: timestamps of one workgroup's phases. */
+void salad_debug_set_trace(void *ptr, int block)
+{
+    g_trace_ptr = (long long *)ptr;
+    g_trace_block = block;
 }
 
 /* Tuning knobs for experiments; not part of the documented layer semantics.

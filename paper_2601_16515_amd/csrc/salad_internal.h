@@ -68,10 +68,19 @@ struct AttnArgs {
     float *o_sparse_dbg, *o_linear_dbg;
     int write_sparse_only;          // bf16: store O_s (rounded) to out and skip the linear part
     unsigned t_magic;               // floor(2^32 / T) + 1 when N * T < 2^32, else 0
+    // per (head, 4-query-block tile): ascending union of the 4 CSR rows, entry = block | keep-mask << 24
+    const uint32_t *tile_lists;     // [H * ntiles4][list_cap]
+    const int32_t *tile_counts;     // [H * ntiles4]
+    int list_cap;
 };
 hipError_t launch_sparse_attn_bf16(const AttnArgs &a, hipStream_t st);
+// union lists of the CSR rows of every 4-query-block tile (input of the large-tile attention kernel)
+int tile_list_cap(int nb);
+hipError_t launch_tile_lists(const int32_t *row_ptr, const int32_t *col_idx, int H, int nb, uint32_t *lists,
+                             int32_t *counts, hipStream_t st);
 hipError_t launch_sparse_attn_f32(const AttnArgs &a, hipStream_t st);
 hipError_t launch_sparse_attn_v2(const AttnArgs &a, hipStream_t st);   // d = 128 only
+hipError_t launch_sparse_attn_v5(const AttnArgs &a, hipStream_t st);   // d = 128 only
 
 // ---- unfused linear apply + scale + sum (bf16): out = out + coef * phi(Q) Hs / (phi(Q).Z + eps) ----
 struct ApplyArgs {
@@ -85,5 +94,7 @@ hipError_t launch_linear_apply_bf16(const ApplyArgs &a, hipStream_t st);
 // tuning knobs (salad_tune)
 extern int g_state_target_wgs;
 extern int g_attn_variant;
+extern long long *g_trace_ptr;   // development: per-phase timestamps of one workgroup
+extern int g_trace_block;
 
 }  // namespace salad

@@ -33,6 +33,8 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef short s16x2 __attribute__((ext_vector_type(2)));
 
 int g_attn_variant = 0;
+long long *g_trace_ptr = nullptr;
+int g_trace_block = 0;
 
 constexpr int XT_PITCH = 72;
 __device__ inline int vt_off(int row, int tok)
@@ -317,7 +319,14 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_kernel(AttnArgs a, in
 
 hipError_t launch_sparse_attn_bf16(const AttnArgs &a, hipStream_t st)
 {
-    if (a.D == 128 && g_attn_variant == 1) return launch_sparse_attn_v2(a, st);
+    // d = 128: the large-tile ping-pong kernel unless its block list does not fit in LDS or a variant is
+    // forced (attn_variant & 15: 0 = automatic, 1 = double-buffered 128-row kernel, 2 = first-generation kernel)
+    const int variant = g_attn_variant & 15;
+    if (a.D == 128 && variant != 2) {
+        const bool fits = (size_t)tile_list_cap(a.nb) * 4 <= 24 * 1024;
+        if ((variant == 0 || variant == 5) && fits && a.tile_lists) return launch_sparse_attn_v5(a, st);
+        return launch_sparse_attn_v2(a, st);
+    }
     const int ntiles = (a.nb + 1) / 2;
     const int total = a.B * a.H * ntiles;
     const int per_xcd = (total + 7) / 8;

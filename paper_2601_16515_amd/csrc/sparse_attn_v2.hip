@@ -159,18 +159,31 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_v2_kernel(AttnArgs a, int 
         const int cur_blk = blk, cur_flags = flags;
         more = next_block(blk, flags);
         if (more) issue(blk, buf ^ 1);
+        // the refilled list entries are scalar loads; retire them here so that the waits on LDS
+        // data below can be counted instead of waiting for everything
+        asm volatile("" ::"s"(ca1), "s"(cb1));
         if ((cur_flags & mybit) && qblk < nb) {
             const u16 *Kt = Kb + buf * TILE;
             const u16 *Vt = Vb + buf * TILE;
             f32x16 s[2];
+            {
+                // all 16 K fragments are requested before the first product so that LDS latency is
+                // paid once per block instead of once per MFMA
+                bf16x8 kf[2][NS];
 #pragma unroll
-            for (int kt = 0; kt < 2; ++kt) {
+                for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) s[kt][r] = 0.f;
+                    for (int st = 0; st < NS; ++st)
+                        kf[kt][st] = *reinterpret_cast<const bf16x8 *>(Kt + kt * 32 * D + koff[st]);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) s[kt][r] = 0.f;
 #pragma unroll
                 for (int st = 0; st < NS; ++st) {
-                    bf16x8 kf = *reinterpret_cast<const bf16x8 *>(Kt + kt * 32 * D + koff[st]);
-                    s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[st].v, s[kt], 0, 0, 0);
+                    s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0][st], qf[st].v, s[0], 0, 0, 0);
+                    s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[1][st], qf[st].v, s[1], 0, 0, 0);
                 }
             }
             const int kbase = cur_blk * 64 + hh * 8;
@@ -209,15 +222,27 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_v2_kernel(AttnArgs a, int 
                     pf[kt * 2 + (r >> 3)].w[(r & 7) >> 1] = pack2(p0, p1);
                 }
             l_run += psum;
+            {
+                // V^T fragments are requested a full 16-key group (4 fragments) ahead of their use
+                Frag vf[2][NDT];
+                auto vread = [&](int c16, Frag (&f)[NDT]) {
 #pragma unroll
-            for (int c16 = 0; c16 < 4; ++c16) {
+                    for (int dt = 0; dt < NDT; ++dt) {
+                        const u16 *vp = Vt + c16 * 16 * D + voff[dt];
+                        f[dt].h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)LDS_PTR(vp));
+                        f[dt].h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)LDS_PTR(vp + 4 * D));
+                    }
+                };
+                vread(0, vf[0]);
+                vread(1, vf[1]);
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int dt = 0; dt < NDT; ++dt) {
-                    Frag vf;
-                    const u16 *vp = Vt + c16 * 16 * D + voff[dt];
-                    vf.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)LDS_PTR(vp));
-                    vf.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)LDS_PTR(vp + 4 * D));
-                    o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf[c16].v, o[dt], 0, 0, 0);
+                for (int c16 = 0; c16 < 4; ++c16) {
+#pragma unroll
+                    for (int dt = 0; dt < NDT; ++dt)
+                        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[c16 & 1][dt].v, pf[c16].v, o[dt], 0, 0, 0);
+                    if (c16 + 2 < 4) vread(c16 + 2, vf[c16 & 1]);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
         }

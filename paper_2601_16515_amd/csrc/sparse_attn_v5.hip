@@ -1,0 +1,531 @@
+// Block-sparse softmax attention (Eq. (2)) with the fused linear apply / scale / sum epilogue,
+// d = 128.  Large tile, deep LDS prefetch, ping-pong wave groups.
+//
+//   * One workgroup = 8 waves = 256 query positions = 4 CSR rows of one (batch, head); one workgroup
+//     per CU (LDS: up to 10 K/V tiles of 16 KB plus the block list).
+//   * The ascending union of the 4 rows' kept-block lists is built once per workgroup in LDS (bitmap +
+//     ballot compaction), each entry carrying a 4-bit "kept by query block i" mask.  The main loop
+//     reads one entry per iteration from LDS; no global or scalar load sits on its critical path.
+//   * K and V tiles go straight from global memory into a ring of LDS slots PD blocks ahead of their
+//     use (global_load_lds_dwordx4, bank swizzle applied on the global side).  The wait before the
+//     per-block barrier is counted (s_waitcnt vmcnt(n)), so PD blocks of loads stay in flight and
+//     L2 / fabric latency is covered without a second resident workgroup.
+//   * Ping-pong: waves 0-3 (group 0) and 4-7 (group 1) share the 4 SIMDs pairwise.  Each KV block is
+//     handled in two barrier-separated phases; in phase A group 0 runs its matrix work (O += V^T P of
+//     the previous block, S = K Q^T of the current one) while group 1 runs its vector work (softmax);
+//     in phase B they swap.  A SIMD issues VALU instructions under a running MFMA, so both pipes stay
+//     busy although each wave's own code is sequential.
+//   * V^T operands come from ds_read_b64_tr_b16, K rows are read through the kappa permutation so
+//     that P never moves between lanes, the reference maximum is raised lazily (threshold 2^8).
+//   * Epilogue: the hi/lo bf16 fragments of the linear state are staged once per workgroup in LDS.
+#include "salad_internal.h"
+
+namespace salad {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef short s16x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+#define LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
+#define GLB_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
+#define TR_READ(p) __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)LDS_PTR(p))
+#define INL __attribute__((always_inline))
+// s_waitcnt with only vmcnt constrained (gfx9 encoding: vmcnt[3:0] | expcnt 7 << 4 | lgkmcnt 15 << 8)
+#define WAIT_VM(n) __builtin_amdgcn_s_waitcnt(0x0F70 | (n))
+
+namespace {
+
+__device__ inline int row_of_position5(int kind, int p, int T, int HW, unsigned magic)
+{
+    if (!kind) return p;
+    int loc = magic ? (int)__umulhi((unsigned)p, magic) : p / T;
+    return (p - loc * T) * HW + loc;
+}
+
+__device__ inline uint32_t pack2e(float a, float b)
+{
+    f32x2 x = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
+}
+
+__device__ inline uint32_t relu2e(uint32_t x)
+{
+    s16x2 v = __builtin_bit_cast(s16x2, x);
+    s16x2 z = {0, 0};
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(v, z));
+}
+
+// One 16-byte-per-lane global -> LDS load (lane i lands at lds_addr + 16 i).  Issued through inline
+// assembly so that the compiler's automatic "wait for every pending LDS load before any LDS read"
+// does not apply: which loads must have landed is known exactly and waited for with WAIT_VM below.
+__device__ inline void lds_dma16(const void *gptr, unsigned lds_addr_uniform)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :
+                 : "s"(lds_addr_uniform), "v"(gptr)
+                 : "memory", "m0");
+}
+
+__device__ inline unsigned lds_addr_of(const void *p)
+{
+    return __builtin_amdgcn_readfirstlane((unsigned)(size_t)LDS_PTR(p));
+}
+
+// max of a value with its copy in the other 32-lane half, on the VALU (v_permlane32_swap): the LDS
+// unit, which a cross-lane shuffle would go through, is saturated by the other group's operand reads.
+__device__ inline float max_with_other_half(float x)
+{
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+union Frag5 {
+    bf16x8 v;
+    uint4 u;
+    uint32_t w[4];
+    s16x4 h[2];
+};
+
+}  // namespace
+
+// Pre-pass: for every (head, tile of 4 query blocks) the ascending union of the 4 CSR rows' kept blocks,
+// each entry tagged with which of the 4 rows keep it.  One wave per tile: bitmap in LDS, then ordered
+// compaction with ballots.  The mask is static, but the layer call accepts any CSR, so this runs per call
+// (a few microseconds).
+__global__ __launch_bounds__(64) void tile_lists_kernel(const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
+                                                        int nb, int ntiles, int cap, uint32_t *__restrict__ lists,
+                                                        int32_t *__restrict__ counts)
+{
+    extern __shared__ uint32_t bm[];
+    const int h = blockIdx.y, tile = blockIdx.x, lane = threadIdx.x;
+    for (int i = lane; i < nb; i += 64) bm[i] = 0u;
+    __syncthreads();
+    for (int i = 0; i < 4; ++i) {
+        const int r = tile * 4 + i;
+        if (r < nb) {
+            const int b0 = row_ptr[h * nb + r], b1 = row_ptr[h * nb + r + 1];
+            for (int e = b0 + lane; e < b1; e += 64) {
+                const int c = col_idx[e];
+                if (c >= 0 && c < nb) atomicOr(&bm[c], 1u << (24 + i));
+            }
+        }
+    }
+    __syncthreads();
+    uint32_t *out = lists + ((size_t)h * ntiles + tile) * cap;
+    int count = 0;
+    for (int base = 0; base < nb; base += 64) {
+        const int b = base + lane;
+        const uint32_t f = b < nb ? bm[b] : 0u;
+        const unsigned long long bal = __ballot(f != 0u);
+        const int pos = count + __popcll(bal & ((1ull << lane) - 1ull));
+        if (f) out[pos] = (uint32_t)b | f;
+        count += __popcll(bal);
+    }
+    if (lane == 0) counts[h * ntiles + tile] = count;
+}
+
+int tile_list_cap(int nb) { return (nb + 63) & ~63; }
+
+hipError_t launch_tile_lists(const int32_t *row_ptr, const int32_t *col_idx, int H, int nb, uint32_t *lists,
+                             int32_t *counts, hipStream_t st)
+{
+    const int ntiles = (nb + 3) / 4;
+    const int cap = tile_list_cap(nb);
+    hipLaunchKernelGGL(tile_lists_kernel, dim3(ntiles, H), dim3(64), (size_t)cap * 4, st, row_ptr, col_idx, nb, ntiles, cap, lists, counts);
+    return hipGetLastError();
+}
+
+// PD: prefetch distance in KV blocks; NSLOT = PD + 2 ring slots for K and for V.
+template <int PD, bool DBG, bool DIAG>
+__global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int ntiles, int total, int per_xcd, int list_cap, int skip_arg, long long *trace, int trace_block)
+{
+    const int skip = DIAG ? skip_arg : 0;   // diagnostics (stage skipping, timestamps) only in the DIAG build
+    constexpr int D = 128, NS = 8, NDT = 4;
+    constexpr int TILE = 64 * D;                 // elements
+    constexpr int NSLOT = PD + 2;
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    u16 *Kb = reinterpret_cast<u16 *>(smem);                       // NSLOT tiles
+    u16 *Vb = Kb + NSLOT * TILE;                                    // NSLOT tiles
+    uint32_t *blist = reinterpret_cast<uint32_t *>(Vb + NSLOT * TILE);   // [list_cap] union list: blk | mask << 24
+
+    const int g = blockIdx.x;
+    const int L = (g & 7) * per_xcd + (g >> 3);
+    if (L >= total) return;
+    const int bh = L / ntiles, tile = L - bh * ntiles;
+    const int h = bh % a.H;
+    const int kind = (int)((a.kind_mask >> h) & 1ull);
+    const int N = a.N, T = a.T, HW = a.HW, nb = a.nb;
+    const unsigned magic = a.t_magic;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, hh = lane >> 5;
+    const int group = wave >> 2;
+    const bool tr = DIAG && trace != nullptr && (int)blockIdx.x == trace_block && lane == 0;
+    long long *trw = trace + wave * 1024;
+    int trn = 0;
+#define TRACE() do { if (DIAG && tr && trn < 1024) trw[trn++] = clock64(); } while (0)
+    TRACE();
+    const u16 *qb = reinterpret_cast<const u16 *>(a.q) + (size_t)bh * N * D;
+    const u16 *kb = reinterpret_cast<const u16 *>(a.k) + (size_t)bh * N * D;
+    const u16 *vb = reinterpret_cast<const u16 *>(a.v) + (size_t)bh * N * D;
+
+    const int qsub = wave >> 1;
+    const int qblk = tile * 4 + qsub;
+    const unsigned mybit = qblk < nb ? (1u << (24 + qsub)) : 0u;
+    const int qpos = qblk * 64 + (wave & 1) * 32 + l32;
+    const bool qvalid = (qblk < nb) && (qpos < N);
+    const int qrow = row_of_position5(kind, qvalid ? qpos : N - 1, T, HW, magic);
+
+    Frag5 qf[NS];
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+        qf[s].u = *reinterpret_cast<const uint4 *>(qb + (size_t)qrow * D + s * 16 + hh * 8);
+
+    // ---- this tile's union list (built by the pre-pass): one coalesced round trip into LDS
+    const int n = a.tile_counts[h * ntiles + tile];
+    {
+        const uint32_t *src = a.tile_lists + ((size_t)h * ntiles + tile) * list_cap;
+        for (int i = tid; i < n; i += 512) blist[i] = src[i];
+    }
+    __syncthreads();
+    TRACE();
+    // Retire the Q loads here: inside the loop the only vector-memory operations in flight must be the
+    // K/V prefetches, whose completion is tracked by hand.
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+        asm volatile("" : "+v"(qf[s].w[0]), "+v"(qf[s].w[1]), "+v"(qf[s].w[2]), "+v"(qf[s].w[3]));
+
+    // ---- global -> LDS: thread owns LDS slots (row 32 i + tid/16, chunk tid%16), i = 0, 1, of a tile
+    const int lr = tid >> 4, pc = tid & 15;
+    const int kchunk = (pc ^ (lr & 15)) * 8;
+    const int vchunk = (pc ^ ((lr & 3) << 2)) * 8;
+    auto fetch = [&](int blk, int slot) INL {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            int p = blk * 64 + i * 32 + lr;
+            p = p < N ? p : N - 1;
+            const size_t off = (size_t)(unsigned)(row_of_position5(kind, p, T, HW, magic) * D);
+            lds_dma16(kb + off + kchunk, lds_addr_of(Kb + slot * TILE + (i * 512 + wave * 64) * 8));
+            lds_dma16(vb + off + vchunk, lds_addr_of(Vb + slot * TILE + (i * 512 + wave * 64) * 8));
+        }
+    };
+
+    // ---- LDS operand addresses (element offsets inside a tile)
+    const int kappa = (l32 & 0x13) | ((l32 & 4) << 1) | ((l32 & 8) >> 1);
+    int koff[NS];
+#pragma unroll
+    for (int st = 0; st < NS; ++st) koff[st] = kappa * D + (((2 * st + hh) ^ (kappa & 15)) << 3);
+    const int vr = 8 * hh + ((l32 >> 2) & 3);
+    int voff[NDT];
+#pragma unroll
+    for (int dt = 0; dt < NDT; ++dt) {
+        int chunk = 4 * dt + 2 * (l32 >> 4) + ((l32 & 3) >> 1);
+        voff[dt] = vr * D + ((chunk ^ ((vr & 3) << 2)) << 3) + 4 * (l32 & 1);
+    }
+
+    f32x16 o[NDT];
+#pragma unroll
+    for (int i = 0; i < NDT; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[i][r] = 0.f;
+    float m_run = -1e30f, l_run = 0.f;
+    const float c2 = a.scale * 1.44269504088896340736f;
+    f32x16 s[2];
+    Frag5 pf[4];
+
+    // V^T fragments of 16-key groups 0 and 1 are requested at the end of the softmax that produces P
+    // (the V tile of that block is already in LDS), so the next matrix phase starts without waiting.
+    Frag5 vf[2][NDT];
+    auto vread = [&](const u16 *Vt, int c16, Frag5 (&f)[NDT]) INL {
+#pragma unroll
+        for (int dt = 0; dt < NDT; ++dt) {
+            const u16 *vp = Vt + c16 * 16 * D + voff[dt];
+            f[dt].h[0] = TR_READ(vp);
+            f[dt].h[1] = TR_READ(vp + 4 * D);
+        }
+    };
+    auto preload_V = [&](const u16 *Vt) INL {
+        vread(Vt, 0, vf[0]);
+    };
+    auto pv_group = [&](int c16) INL {
+#pragma unroll
+        for (int dt = 0; dt < NDT; ++dt)
+            o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[c16 & 1][dt].v, pf[c16].v, o[dt], 0, 0, 0);
+    };
+    auto stage_PV = [&](const u16 *Vt) INL {       // vf[0] (16-key group 0) already requested
+        vread(Vt, 1, vf[1]);
+        __builtin_amdgcn_sched_barrier(0);
+        pv_group(0); vread(Vt, 2, vf[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        pv_group(1); vread(Vt, 3, vf[1]);
+        __builtin_amdgcn_sched_barrier(0);
+        pv_group(2);
+        pv_group(3);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto stage_S = [&](const u16 *Kt) INL {
+        bf16x8 kf[2][NS];
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+            for (int st = 0; st < NS; ++st)
+                kf[kt][st] = *reinterpret_cast<const bf16x8 *>(Kt + kt * 32 * D + koff[st]);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[kt][r] = 0.f;
+#pragma unroll
+        for (int st = 0; st < NS; ++st) {
+            s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0][st], qf[st].v, s[0], 0, 0, 0);
+            s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[1][st], qf[st].v, s[1], 0, 0, 0);
+        }
+    };
+    // both products of one matrix phase, K fragments requested under the running PV MFMAs
+    auto stage_PV_S = [&](const u16 *Vt, const u16 *Kt) INL {
+        bf16x8 kf[2][NS];
+        vread(Vt, 1, vf[1]);
+        __builtin_amdgcn_sched_barrier(0);
+        pv_group(0); vread(Vt, 2, vf[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        pv_group(1); vread(Vt, 3, vf[1]);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int st = 0; st < NS; ++st) kf[0][st] = *reinterpret_cast<const bf16x8 *>(Kt + koff[st]);
+        pv_group(2);
+        __builtin_amdgcn_sched_barrier(0);
+        pv_group(3);
+#pragma unroll
+        for (int st = 0; st < NS; ++st) kf[1][st] = *reinterpret_cast<const bf16x8 *>(Kt + 32 * D + koff[st]);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[kt][r] = 0.f;
+#pragma unroll
+        for (int st = 0; st < NS; ++st) {
+            s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0][st], qf[st].v, s[0], 0, 0, 0);
+            s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[1][st], qf[st].v, s[1], 0, 0, 0);
+        }
+    };
+    auto stage_softmax = [&](int blk) INL {
+        if (blk * 64 + 64 > N) {
+            const int kbase = blk * 64 + hh * 8;
+#pragma unroll
+            for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (kbase + kt * 32 + 16 * (r >> 3) + (r & 7) >= N) s[kt][r] = -INFINITY;
+        }
+        float mx = s[0][0];
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kt][r]);
+        mx = max_with_other_half(mx) * c2;
+        if (__any(mx > m_run + 8.0f)) {
+            const float m_new = fmaxf(m_run, mx);
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+            m_run = m_new;
+            l_run *= alpha;
+#pragma unroll
+            for (int i = 0; i < NDT; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o[i][r] *= alpha;
+        }
+        float psum = 0.f;
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+            for (int r = 0; r < 16; r += 2) {
+                float p0 = __builtin_amdgcn_exp2f(fmaf(s[kt][r], c2, -m_run));
+                float p1 = __builtin_amdgcn_exp2f(fmaf(s[kt][r + 1], c2, -m_run));
+                psum += p0 + p1;
+                pf[kt * 2 + (r >> 3)].w[(r & 7) >> 1] = pack2e(p0, p1);
+            }
+        l_run += psum;
+    };
+
+    const bool lin = a.use_linear && !a.write_sparse_only;
+    const u16 *hf = a.hfrag + (size_t)bh * 2 * D * D;
+    // 64 KB of linear-state fragments (hi, lo) for the epilogue, staged into the K ring once it is idle
+    auto stage_state = [&]() INL {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) lds_dma16(hf + (size_t)(i * 512 + tid) * 8, lds_addr_of(Kb + (i * 512 + wave * 64) * 8));
+    };
+
+    // ---- main loop over the union list.  Iteration j: S(j) and softmax(j), PV(j-1); fetch block j+PD.
+    // Block b lives in ring slot b % NSLOT of both rings (K(b) is read in iteration b, V(b) in b+1).
+    if (n > 0) {
+#pragma unroll
+        for (int b = 0; b < PD; ++b)
+            if (b < n && !(skip & 8)) fetch((int)(blist[b] & 0xffffffu), b);
+        uint32_t e_prev = 0u, e_cur = blist[0];
+        int slot_cur = 0;                         // j % NSLOT
+        for (int j = 0; j < n; ++j) {
+            // all fetches up to block j must have landed; newer ones may stay in flight
+            {
+                const int last = (j + PD - 1 < n - 1) ? j + PD - 1 : n - 1;
+                int newer = last - j;
+                if (skip & 8) newer = 0;
+                if (newer >= 3) WAIT_VM(12);
+                else if (newer == 2) WAIT_VM(8);
+                else if (newer == 1) WAIT_VM(4);
+                else WAIT_VM(0);
+            }
+            TRACE();
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            TRACE();
+            const uint32_t e_nxt = (j + 1 < n) ? blist[j + 1] : 0u;
+            int slot_f = slot_cur + PD; if (slot_f >= NSLOT) slot_f -= NSLOT;
+            if (j + PD < n && !(skip & 8)) fetch((int)(blist[j + PD] & 0xffffffu), slot_f);
+            int slot_prev = slot_cur - 1; if (slot_prev < 0) slot_prev += NSLOT;
+            const bool kS = (e_cur & mybit) != 0, kP = (j >= 1) && (e_prev & mybit);
+            const bool dS = kS && !(skip & 2), dP = kP && !(skip & 4), dM0 = kS && !(skip & 1), dM1 = kP && !(skip & 1);
+            const u16 *Kt = Kb + slot_cur * TILE;
+            const u16 *Vt = Vb + slot_prev * TILE;
+            const u16 *Vc = Vb + slot_cur * TILE;      // V tile of block j (already landed with K(j))
+            if (group == 0) {
+                if (dP && dS) stage_PV_S(Vt, Kt);
+                else { if (dP) stage_PV(Vt); if (dS) stage_S(Kt); }
+                TRACE();
+                if (!(skip & 16)) __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+                if (dM0) stage_softmax((int)(e_cur & 0xffffffu));
+                if (dS) preload_V(Vc);                  // for PV(j) in the next iteration
+                TRACE();
+            } else {
+                if (dM1) stage_softmax((int)(e_prev & 0xffffffu));
+                if (dP) preload_V(Vt);                  // for PV(j-1) right after the barrier
+                TRACE();
+                if (!(skip & 16)) __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+                if (dP && dS) stage_PV_S(Vt, Kt);
+                else { if (dP) stage_PV(Vt); if (dS) stage_S(Kt); }
+                TRACE();
+            }
+            e_prev = e_cur; e_cur = e_nxt;
+            ++slot_cur; if (slot_cur >= NSLOT) slot_cur = 0;
+        }
+        // tail: the PV product of the last block (group 1 still owes its softmax).  The K ring is idle
+        // from here on, so the epilogue's state fragments are fetched into it under these MFMAs.
+        WAIT_VM(0);
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        if (lin) stage_state();
+        {
+            int slot_prev = slot_cur - 1; if (slot_prev < 0) slot_prev += NSLOT;
+            const u16 *Vt = Vb + slot_prev * TILE;
+            const bool kP = (e_prev & mybit) != 0;
+            if (group == 1 && kP && !(skip & 1)) { stage_softmax((int)(e_prev & 0xffffffu)); preload_V(Vt); }
+            if (kP && !(skip & 4)) stage_PV(Vt);
+        }
+    }
+
+    TRACE();
+    // ---- epilogue ---------------------------------------------------------------------------------
+    float l_tot = l_run + __shfl_xor(l_run, 32);
+    const float inv_l = l_tot > 0.f ? 1.f / l_tot : 0.f;
+    f32x16 num[NDT];
+    float lin_scale = 0.f, inv_den = 0.f;
+    if (lin) {
+        if (n == 0) stage_state();
+        float dpart = 0.f;
+        const float *Zh = a.Z + (size_t)bh * D;
+#pragma unroll
+        for (int st = 0; st < NS; ++st) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                uint32_t w = relu2e(qf[st].w[j]);
+                qf[st].w[j] = w;
+                dpart = fmaf(__uint_as_float(w << 16), Zh[st * 16 + hh * 8 + 2 * j], dpart);
+                dpart = fmaf(__uint_as_float(w & 0xffff0000u), Zh[st * 16 + hh * 8 + 2 * j + 1], dpart);
+            }
+        }
+        const float den = dpart + __shfl_xor(dpart, 32) + a.eps;
+        inv_den = 1.f / den;
+        lin_scale = a.coef[bh] * inv_den;
+        WAIT_VM(0);
+        __syncthreads();   // the staged fragments have landed in every wave's view
+#pragma unroll
+        for (int dt = 0; dt < NDT; ++dt) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) num[dt][r] = 0.f;
+#pragma unroll
+            for (int st = 0; st < NS; ++st) {
+                const int idx = ((dt * NS + st) * 64 + lane) * 8;
+                bf16x8 hi = *reinterpret_cast<const bf16x8 *>(Kb + idx);
+                bf16x8 lo = *reinterpret_cast<const bf16x8 *>(Kb + D * D + idx);
+                num[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo, qf[st].v, num[dt], 0, 0, 0);
+                num[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hi, qf[st].v, num[dt], 0, 0, 0);
+            }
+        }
+    }
+    TRACE();
+    if (!qvalid) return;
+    const size_t obase = ((size_t)bh * N + qrow) * D;
+    u16 *outp = reinterpret_cast<u16 *>(a.out) + obase;
+#pragma unroll
+    for (int dt = 0; dt < NDT; ++dt) {
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+            const int col = dt * 32 + 8 * g4 + 4 * hh;
+            float os[4], ol[4], ov[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                os[t] = o[dt][g4 * 4 + t] * inv_l;
+                ol[t] = lin ? num[dt][g4 * 4 + t] : 0.f;
+                ov[t] = lin ? fmaf(ol[t], lin_scale, os[t]) : os[t];
+            }
+            uint2 pk;
+            pk.x = pack2e(ov[0], ov[1]);
+            pk.y = pack2e(ov[2], ov[3]);
+            *reinterpret_cast<uint2 *>(outp + col) = pk;
+            if (DBG) {
+                if (a.o_sparse_dbg)
+                    *reinterpret_cast<float4 *>(a.o_sparse_dbg + obase + col) = make_float4(os[0], os[1], os[2], os[3]);
+                if (a.o_linear_dbg && lin)
+                    *reinterpret_cast<float4 *>(a.o_linear_dbg + obase + col) =
+                        make_float4(ol[0] * inv_den, ol[1] * inv_den, ol[2] * inv_den, ol[3] * inv_den);
+            }
+        }
+    }
+    TRACE();
+    if (DIAG && tr) trw[1023] = trn;
+#undef TRACE
+}
+
+template <int PD, bool DBG, bool DIAG>
+static hipError_t launch_v5(const AttnArgs &a, hipStream_t st)
+{
+    const int ntiles = (a.nb + 3) / 4;
+    const int total = a.B * a.H * ntiles;
+    const int per_xcd = (total + 7) / 8;
+    const int list_cap = (a.nb + 63) & ~63;
+    const size_t lds = (size_t)(PD + 2) * 2 * 64 * 128 * 2 + (size_t)list_cap * 4;
+    constexpr int kMaxDyn = 160 * 1024 - 2048;   // the static part is rounded up to its 1 KB alignment
+    if (lds > (size_t)kMaxDyn) return hipErrorInvalidValue;
+    auto kern = sparse_attn_v5_kernel<PD, DBG, DIAG>;
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDyn);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(512), lds, st, a, ntiles, total, per_xcd, list_cap, g_attn_variant >> 4, g_trace_ptr, g_trace_block);
+    return hipGetLastError();
+}
+
+hipError_t launch_sparse_attn_v5(const AttnArgs &a, hipStream_t st)
+{
+    const bool dbg = a.o_sparse_dbg || a.o_linear_dbg;
+    const bool diag = (g_attn_variant >> 4) != 0 || g_trace_ptr != nullptr;
+    if (diag) return launch_v5<2, false, true>(a, st);
+    return dbg ? launch_v5<2, true, false>(a, st) : launch_v5<2, false, false>(a, st);
+}
+
+}  // namespace salad
