@@ -261,7 +261,7 @@ def salad_gate_fwd(x_t, w_gate, b_gate: float = 0.0):
     B, N, D = x_t.shape
     assert x_t.is_cuda and x_t.is_contiguous() and w_gate.dtype == torch.float32 and w_gate.numel() == D
     s = torch.empty(B, dtype=torch.float32, device=x_t.device)
-    ws = torch.empty(4 * B * 1024 + 1024, dtype=torch.uint8, device=x_t.device)
+    ws = torch.empty(4 * B * 2048 + 1024, dtype=torch.uint8, device=x_t.device)
     ptr = (ws.data_ptr() + 255) & ~255
     _check(lib().salad_gate_fwd(x_t.data_ptr(), w_gate.data_ptr(), b_gate, B, N, D, _dtype_code(x_t), s.data_ptr(),
                                 ptr, ws.numel() - 256, _stream()))

@@ -46,26 +46,49 @@ hipError_t launch_block_mask(const MaskArgs &a, hipStream_t st)
 // ------------------------------------------------------------------------------------------------
 constexpr int GATE_MAX_CHUNKS = 10;   // D <= 8*64*10 = 5120
 
-template <bool BF16>
-__device__ inline void load8(const void *row, int chunk, float (&f)[8])
-{
-    if (BF16) {
-        uint4 u = *reinterpret_cast<const uint4 *>(reinterpret_cast<const u16 *>(row) + chunk * 8);
-        uint32_t w[4] = {u.x, u.y, u.z, u.w};
+// Raw 8-element chunk of a row: 16 bytes (bf16) or 32 bytes (fp32) per lane.
+template <bool BF16> struct Chunk8;
+template <> struct Chunk8<true> {
+    uint4 u;
+    __device__ inline void load(const void *row, int chunk) { u = *reinterpret_cast<const uint4 *>(reinterpret_cast<const u16 *>(row) + chunk * 8); }
+    __device__ inline void zero() { u = make_uint4(0, 0, 0, 0); }
+    __device__ inline float dot(const float (&w)[8], float acc) const
+    {
+        const uint32_t v[4] = {u.x, u.y, u.z, u.w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            f[2 * i] = __uint_as_float(w[i] << 16);
-            f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+            acc = fmaf(__uint_as_float(v[i] << 16), w[2 * i], acc);
+            acc = fmaf(__uint_as_float(v[i] & 0xffff0000u), w[2 * i + 1], acc);
         }
-    } else {
-        const float4 *p = reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(row) + chunk * 8);
-        float4 a = p[0], b = p[1];
-        f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w;
-        f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
+        return acc;
     }
-}
+};
+template <> struct Chunk8<false> {
+    float v[8];
+    __device__ inline void load(const void *row, int chunk)
+    {
+        const float4 *p = reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(row) + chunk * 8);
+        const float4 a = p[0], b = p[1];
+        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    }
+    __device__ inline void zero()
+    {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = 0.f;
+    }
+    __device__ inline float dot(const float (&w)[8], float acc) const
+    {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc = fmaf(v[i], w[i], acc);
+        return acc;
+    }
+};
 
-template <bool BF16>
+// NCH: 8-element chunks per lane (D <= 512 * NCH); TOK: tokens a wave handles per step.  The loads of the
+// next step are issued before the current step is reduced (two register buffers), so a wave always has
+// TOK*NCH 16-byte loads per lane in flight while it runs the dot products, the wave reduction and the
+// sigmoid of the previous tokens.
+template <bool BF16, int NCH, int TOK>
 __global__ __launch_bounds__(256) void gate_partial_kernel(const void *x_t, const float *__restrict__ w,
                                                            float bias, int N, int D,
                                                            float *__restrict__ partial, int nparts)
@@ -74,33 +97,57 @@ __global__ __launch_bounds__(256) void gate_partial_kernel(const void *x_t, cons
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int b = blockIdx.y;
     const int nch = D >> 3;
-    float wr[GATE_MAX_CHUNKS][8];
+    float wr[NCH][8];
 #pragma unroll
-    for (int j = 0; j < GATE_MAX_CHUNKS; ++j) {
+    for (int j = 0; j < NCH; ++j) {
         int c = lane + 64 * j;
 #pragma unroll
         for (int e = 0; e < 8; ++e) wr[j][e] = (c < nch) ? w[c * 8 + e] : 0.f;
     }
     const size_t esz = BF16 ? 2 : 4;
     const char *xb = reinterpret_cast<const char *>(x_t) + (size_t)b * N * D * esz;
+    const int stride = nparts * 4 * TOK;
     float acc = 0.f;
-    for (int n = blockIdx.x * 4 + wave; n < N; n += nparts * 4) {
-        const void *row = xb + (size_t)n * D * esz;
-        float dot = 0.f;
+    Chunk8<BF16> bufA[TOK][NCH], bufB[TOK][NCH];
+    auto issue = [&](Chunk8<BF16> (&buf)[TOK][NCH], int n0) __attribute__((always_inline)) {
 #pragma unroll
-        for (int j = 0; j < GATE_MAX_CHUNKS; ++j) {
-            int c = lane + 64 * j;
-            if (c < nch) {
-                float f[8];
-                load8<BF16>(row, c, f);
+        for (int t = 0; t < TOK; ++t) {
+            const int n = n0 + t < N ? n0 + t : N - 1;
+            const void *row = xb + (size_t)n * D * esz;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) dot = fmaf(f[e], wr[j][e], dot);
+            for (int j = 0; j < NCH; ++j) {
+                const int c = lane + 64 * j;
+                if (c < nch) buf[t][j].load(row, c);
+                else buf[t][j].zero();
             }
         }
+    };
+    auto consume = [&](const Chunk8<BF16> (&buf)[TOK][NCH], int n0) __attribute__((always_inline)) {
+        float dot[TOK];
 #pragma unroll
-        for (int o = 32; o > 0; o >>= 1) dot += __shfl_xor(dot, o);
-        float z = dot + bias;
-        acc += 1.f / (1.f + __expf(-z));   // identical in every lane
+        for (int t = 0; t < TOK; ++t) {
+            dot[t] = 0.f;
+#pragma unroll
+            for (int j = 0; j < NCH; ++j) dot[t] = buf[t][j].dot(wr[j], dot[t]);
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1)
+#pragma unroll
+            for (int t = 0; t < TOK; ++t) dot[t] += __shfl_xor(dot[t], o);
+#pragma unroll
+        for (int t = 0; t < TOK; ++t)
+            if (n0 + t < N) acc += 1.f / (1.f + __expf(-(dot[t] + bias)));   // identical in every lane
+    };
+    int n0 = (blockIdx.x * 4 + wave) * TOK;
+    if (n0 < N) issue(bufA, n0);
+    while (n0 < N) {
+        if (n0 + stride < N) issue(bufB, n0 + stride);
+        consume(bufA, n0);
+        n0 += stride;
+        if (n0 >= N) break;
+        if (n0 + stride < N) issue(bufA, n0 + stride);
+        consume(bufB, n0);
+        n0 += stride;
     }
     if (lane == 0) wave_sum[wave] = acc;
     __syncthreads();
@@ -108,25 +155,48 @@ __global__ __launch_bounds__(256) void gate_partial_kernel(const void *x_t, cons
         partial[(size_t)b * nparts + blockIdx.x] = (wave_sum[0] + wave_sum[1]) + (wave_sum[2] + wave_sum[3]);
 }
 
+int g_gate_parts = 512, g_gate_tok = 2;
+
 int gate_num_parts(int N)
 {
-    int parts = (N + 3) / 4;            // at most one token per wave
-    return parts < 1024 ? (parts < 1 ? 1 : parts) : 1024;
+    int parts = (N + 15) / 16;          // a workgroup step covers 16 tokens (4 waves x up to 4 tokens)
+    return parts < g_gate_parts ? (parts < 1 ? 1 : parts) : g_gate_parts;
+}
+
+static void gate_dispatch_bf16(dim3 grid, dim3 block, hipStream_t st, const void *x_t, const float *w, float bias, int N, int D,
+                               float *partial, int nparts)
+{
+    const int nch = (D / 8 + 63) / 64;
+    if (nch <= 1) hipLaunchKernelGGL((gate_partial_kernel<true, 1, 4>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
+    else if (nch <= 2) hipLaunchKernelGGL((gate_partial_kernel<true, 2, 4>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
+    else if (nch <= 3 && g_gate_tok == 1) hipLaunchKernelGGL((gate_partial_kernel<true, 3, 1>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
+    else if (nch <= 3 && g_gate_tok == 4) hipLaunchKernelGGL((gate_partial_kernel<true, 3, 4>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
+    else if (nch <= 3) hipLaunchKernelGGL((gate_partial_kernel<true, 3, 2>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
+    else if (nch <= 5) hipLaunchKernelGGL((gate_partial_kernel<true, 5, 2>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
+    else hipLaunchKernelGGL((gate_partial_kernel<true, GATE_MAX_CHUNKS, 1>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
+}
+
+// fp32 inputs are the small-shape path: one token per wave step
+static void gate_dispatch_f32(dim3 grid, dim3 block, hipStream_t st, const void *x_t, const float *w, float bias, int N, int D,
+                              float *partial, int nparts)
+{
+    const int nch = (D / 8 + 63) / 64;
+    if (nch <= 2) hipLaunchKernelGGL((gate_partial_kernel<false, 2, 1>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
+    else if (nch <= 5) hipLaunchKernelGGL((gate_partial_kernel<false, 5, 1>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
+    else hipLaunchKernelGGL((gate_partial_kernel<false, GATE_MAX_CHUNKS, 1>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
 }
 
 hipError_t launch_gate_partial(const void *x_t, const float *w, float bias, int B, int N, int D,
                                int is_bf16, float *partial, int nparts, hipStream_t st)
 {
     dim3 grid(nparts, B), block(256);
-    if (is_bf16)
-        hipLaunchKernelGGL(gate_partial_kernel<true>, grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
-    else
-        hipLaunchKernelGGL(gate_partial_kernel<false>, grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
+    if (is_bf16) gate_dispatch_bf16(grid, block, st, x_t, w, bias, N, D, partial, nparts);
+    else gate_dispatch_f32(grid, block, st, x_t, w, bias, N, D, partial, nparts);
     return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------------------
-// Finalize.  Workgroups [0, BH*ceil((D*D+D)/256)) add up the P partial states of one head in chunk
+// Finalize.  Workgroups [0, BH*ceil((D*D+D)/64)) add up the P partial states of one head in chunk
 // order (fp32) and emit Hs, Z and the bf16 hi/lo split of Hs laid out as MFMA A-operand fragments
 // of Hs^T:  element (a, c) -> ((c/32 * (D/16) + a/16) * 64 + ((a%16)/8)*32 + c%32) * 8 + a%8.
 // The last workgroup reduces the gate partial sums (or takes the caller's s), writes s and the
@@ -142,14 +212,24 @@ __device__ inline u16 f32_to_bf16_rne(float f)
 __global__ __launch_bounds__(256) void finalize_kernel(FinalizeArgs a, int state_blocks, int blocks_per_head)
 {
     const int D = a.D;
+    __shared__ float part[4][64];
     if ((int)blockIdx.x < state_blocks) {
-        int bh = blockIdx.x / blocks_per_head;
-        int e = (blockIdx.x - bh * blocks_per_head) * 256 + threadIdx.x;
-        int per = D * D + D;
-        if (e >= per) return;
-        const float *p = a.state_partial + (size_t)bh * a.P * per + e;
+        // 64 state elements per workgroup; the P partials are split over 4 thread groups (more loads in
+        // flight), each group adds its share in chunk order, the 4 sums are added in group order
+        const int bh = blockIdx.x / blocks_per_head;
+        const int le = threadIdx.x & 63, grp = threadIdx.x >> 6;
+        const int e = (blockIdx.x - bh * blocks_per_head) * 64 + le;
+        const int per = D * D + D;
         float s = 0.f;
-        for (int c = 0; c < a.P; ++c) s += p[(size_t)c * per];
+        if (e < per) {
+            const float *p = a.state_partial + (size_t)bh * a.P * per + e;
+            const int c0 = (a.P * grp) / 4, c1 = (a.P * (grp + 1)) / 4;
+            for (int c = c0; c < c1; ++c) s += p[(size_t)c * per];
+        }
+        part[grp][le] = s;
+        __syncthreads();
+        if (grp != 0 || e >= per) return;
+        s = (part[0][le] + part[1][le]) + (part[2][le] + part[3][le]);
         if (e < D * D) {
             a.Hs[(size_t)bh * D * D + e] = s;
             if (a.hfrag) {
@@ -200,7 +280,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(FinalizeArgs a, int state
 hipError_t launch_finalize(const FinalizeArgs &a, hipStream_t st)
 {
     int per = a.D * a.D + a.D;
-    int blocks_per_head = (per + 255) / 256;
+    int blocks_per_head = (per + 63) / 64;
     int state_blocks = a.P > 0 ? a.B * a.H * blocks_per_head : 0;
     hipLaunchKernelGGL(finalize_kernel, dim3(state_blocks + (a.do_gate ? 1 : 0)), dim3(256), 0, st, a, state_blocks, blocks_per_head);
     return hipGetLastError();

@@ -393,6 +393,8 @@ salad_status salad_tune(const char *key, int32_t value)
         g_state_target_wgs = value;
         return SALAD_OK;
     }
+    if (!std::strcmp(key, "gate_parts")) { if (value < 1 || value > 2048) return fail(SALAD_EINVAL, "salad_tune: gate_parts out of range"); g_gate_parts = value; return SALAD_OK; }
+    if (!std::strcmp(key, "gate_tok")) { g_gate_tok = value; return SALAD_OK; }
     if (!std::strcmp(key, "attn_variant")) {
         g_attn_variant = value;
         return SALAD_OK;

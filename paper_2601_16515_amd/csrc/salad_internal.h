@@ -93,6 +93,7 @@ hipError_t launch_linear_apply_bf16(const ApplyArgs &a, hipStream_t st);
 
 // tuning knobs (salad_tune)
 extern int g_state_target_wgs;
+extern int g_gate_parts, g_gate_tok;
 extern int g_attn_variant;
 extern long long *g_trace_ptr;   // development: per-phase timestamps of one workgroup
 extern int g_trace_block;
