@@ -91,22 +91,23 @@ __global__ __launch_bounds__(256, 2) void state_partial_kernel(const u16 *__rest
 #pragma unroll
     for (int e = 0; e < 8; ++e) zacc[e] = 0.f;
 
-    uint4 kreg[TPT], vreg[TPT];
-    auto gload = [&](int tile) {
+    // two tiles of global loads are kept in flight per thread (register buffers 0 and 1)
+    uint4 kreg[2][TPT], vreg[2][TPT];
+    auto gload = [&](uint4 (&kr)[TPT], uint4 (&vr)[TPT], int tile) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < TPT; ++i) {
             int n = tile * 64 + tq * TPT + i;
             if (n < N) {
-                kreg[i] = *reinterpret_cast<const uint4 *>(kb + (size_t)n * D + fg * 8);
-                vreg[i] = *reinterpret_cast<const uint4 *>(vb + (size_t)n * D + fg * 8);
+                kr[i] = *reinterpret_cast<const uint4 *>(kb + (size_t)n * D + fg * 8);
+                vr[i] = *reinterpret_cast<const uint4 *>(vb + (size_t)n * D + fg * 8);
             } else {
-                kreg[i] = make_uint4(0, 0, 0, 0);
-                vreg[i] = make_uint4(0, 0, 0, 0);
+                kr[i] = make_uint4(0, 0, 0, 0);
+                vr[i] = make_uint4(0, 0, 0, 0);
             }
         }
     };
     // transposed store of a (TPT x 8) patch: for feature f, TPT consecutive tokens
-    auto tstore = [&](u16 *dst, const uint4 (&r)[TPT]) {
+    auto tstore = [&](u16 *dst, const uint4 (&r)[TPT]) __attribute__((always_inline)) {
         uint32_t w[TPT][4];
 #pragma unroll
         for (int i = 0; i < TPT; ++i) { w[i][0] = r[i].x; w[i][1] = r[i].y; w[i][2] = r[i].z; w[i][3] = r[i].w; }
@@ -127,24 +128,23 @@ __global__ __launch_bounds__(256, 2) void state_partial_kernel(const u16 *__rest
     };
 
     const int wa = wave >> 1, wc = wave & 1;
-    if (tile0 < tile1) gload(tile0);
-    for (int tile = tile0; tile < tile1; ++tile) {
+    auto step = [&](uint4 (&kr)[TPT], uint4 (&vr)[TPT], int tile) __attribute__((always_inline)) {
         // ReLU on K, running sums for Z
 #pragma unroll
         for (int i = 0; i < TPT; ++i) {
-            kreg[i].x = relu_bf16x2(kreg[i].x); kreg[i].y = relu_bf16x2(kreg[i].y);
-            kreg[i].z = relu_bf16x2(kreg[i].z); kreg[i].w = relu_bf16x2(kreg[i].w);
-            uint32_t w4[4] = {kreg[i].x, kreg[i].y, kreg[i].z, kreg[i].w};
+            kr[i].x = relu_bf16x2(kr[i].x); kr[i].y = relu_bf16x2(kr[i].y);
+            kr[i].z = relu_bf16x2(kr[i].z); kr[i].w = relu_bf16x2(kr[i].w);
+            uint32_t w4[4] = {kr[i].x, kr[i].y, kr[i].z, kr[i].w};
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 zacc[2 * j] += __uint_as_float(w4[j] << 16);
                 zacc[2 * j + 1] += __uint_as_float(w4[j] & 0xffff0000u);
             }
         }
-        tstore(KT, kreg);
-        tstore(VT, vreg);
+        tstore(KT, kr);
+        tstore(VT, vr);
         __syncthreads();
-        if (tile + 1 < tile1) gload(tile + 1);
+        if (tile + 2 < tile1) gload(kr, vr, tile + 2);
 #pragma unroll
         for (int s = 0; s < 4; ++s) {   // 16 tokens per MFMA
             bf16x8 af[QT], bfr[QT];
@@ -162,6 +162,12 @@ __global__ __launch_bounds__(256, 2) void state_partial_kernel(const u16 *__rest
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
         }
         __syncthreads();
+    };
+    if (tile0 < tile1) gload(kreg[0], vreg[0], tile0);
+    if (tile0 + 1 < tile1) gload(kreg[1], vreg[1], tile0 + 1);
+    for (int tile = tile0; tile < tile1; tile += 2) {
+        step(kreg[0], vreg[0], tile);
+        if (tile + 1 < tile1) step(kreg[1], vreg[1], tile + 1);
     }
 
     // partial Hs: accumulator register r of lane (l32, hh) is row a = 8*(r/4) + 4*hh + r%4, col c = l32
