@@ -30,6 +30,19 @@ def kept_flops(row_ptr, col_idx, H, N, d, block, B):
     return int(4 * d * B * (rows * size[col_idx]).sum())
 
 
+def measured_attn_traffic():
+    """HBM-side bytes per launch of the attention kernel from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE and WRITE_SIZE runs, calibrated against a plain copy); None if the file is absent."""
+    path = os.path.join(ROOT, "profiles", "bench_wan13_480p90_hbm_traffic.md")
+    try:
+        for line in open(path):
+            if line.startswith("attn_traffic_bytes_per_launch:"):
+                return int(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(w, inp, kinds, kept, every):
     """The oracle as it stands, timed on a bounded sample: every `every`-th query block of every
     head for the sparse branch (the rest of the layer is a fraction of a percent of its work)."""
@@ -120,8 +133,9 @@ def main():
                    "sparsity": w.sparsity, "kept_blocks_per_query_block": kept[0], "nnz_block_pairs": int(col_idx.numel()),
                    "kept_gflop": flops * 1e-9, "head_orders": "even heads spatial, odd heads temporal"},
         "roofline": {"bound": "mfma", "achieved": flops / (attn_ms * 1e-3) * 1e-12, "peak": PEAK_BF16_TFLOPS,
-                     "unit": "TFLOP/s", "frac": flops / (attn_ms * 1e-3) * 1e-12 / PEAK_BF16_TFLOPS, "traffic": None,
-                     "kernel": "sparse_attn_bf16_kernel<128>", "kernel_ms": attn_ms},
+                     "unit": "TFLOP/s", "frac": flops / (attn_ms * 1e-3) * 1e-12 / PEAK_BF16_TFLOPS,
+                     "traffic": measured_attn_traffic() if args.sparsity is None else None,
+                     "kernel": "sparse_attn_v5_kernel<2> (+ tile_lists_kernel pre-pass)", "kernel_ms": attn_ms},
         "kernels_ms": {"gate": gate_ms, "linear_state": state_ms, "finalize": fin_ms, "sparse_attn_fused": attn_ms},
         "hbm_kernels": {
             "linear_state": {"bytes": kv_bytes, "GB/s": kv_bytes / (state_ms * 1e-3) * 1e-9, "frac_of_8TB/s": kv_bytes / (state_ms * 1e-3) * 1e-9 / PEAK_HBM_GBS},
