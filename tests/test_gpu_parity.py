@@ -101,6 +101,9 @@ SMALL = [
     wl.small("one-block", 1, 2, 128, 2, 3, 5, "bf16", 0.0, seed=104),         # N=30 < one block
     wl.small("exact-blocks", 1, 2, 128, 4, 8, 16, "bf16", 0.75, seed=105),    # N=512, no tail
     wl.small("T-gt-block", 1, 2, 128, 70, 3, 2, "bf16", 0.5, seed=106),       # T=70 > 64: a location spans blocks
+    wl.small("single-token", 1, 1, 128, 1, 1, 1, "bf16", 0.0, seed=109),      # N=1
+    wl.small("five-tiles-d128", 1, 3, 128, 9, 10, 13, "bf16", 0.8, seed=110), # N=1170: 19 blocks = 5 tiles of 4, tail 18
+    wl.small("d64-ragged", 2, 2, 64, 3, 11, 13, "bf16", 0.5, seed=111),       # N=429, d=64, B=2
 ]
 
 
@@ -227,7 +230,7 @@ def test_arbitrary_csr(oracle):
     u = wl.uniform(108, "pick", (w.H * w.nb, w.nb))
     row_ptr, col_idx = [0], []
     for r in range(w.H * w.nb):
-        cnt = 1 + (r * 7) % 5
+        cnt = (1 + (r * 7) % 5) if r != 3 else 0          # one empty row: its sparse output is defined as zero
         cols = sorted(np.argsort(u[r])[:cnt].tolist())
         col_idx += cols
         row_ptr.append(len(col_idx))
@@ -299,7 +302,14 @@ def test_wan13_480p_90_sampled(oracle):
     assert np.array_equal(fast["out"], res["out"])
 
 
-@pytest.mark.parametrize("rho", [0.0, 0.95])
-def test_wan13_480p_sweep_ends_sampled(oracle, rho):
+@pytest.mark.parametrize("rho", [0.0, 0.5, 0.75, 0.95])
+def test_wan13_480p_sweep_sampled(oracle, rho):
+    """The other points of the sparsity sweep at the 480p shape (same seeded inputs)."""
     w = wl.WAN13_480P.with_sparsity(rho)
-    _sampled_parity(oracle, w, 4 if rho == 0.0 else 8, f"480p-{rho:g}")
+    _sampled_parity(oracle, w, 4 if rho < 0.7 else 8, f"480p-{rho:g}")
+
+
+@pytest.mark.timeout(900)
+def test_wan14_720p_90_sampled(oracle):
+    """Wan-14B-shaped 720p configuration: H=40, N=75600 (16-token tail), gate over D=5120."""
+    _sampled_parity(oracle, wl.WAN14_720P, 4, "720p-90")
