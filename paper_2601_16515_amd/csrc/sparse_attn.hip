@@ -323,7 +323,11 @@ hipError_t launch_sparse_attn_bf16(const AttnArgs &a, hipStream_t st)
     // forced (attn_variant & 15: 0 = automatic, 1 = double-buffered 128-row kernel, 2 = first-generation kernel)
     const int variant = g_attn_variant & 15;
     if (a.D == 128 && variant != 2) {
-        const bool fits = (size_t)tile_list_cap(a.nb) * 4 <= 24 * 1024;
+        // the large-tile kernel addresses rows with 32-bit byte offsets and divides by T with a
+        // multiply (t_magic); a T = 1 grid makes the temporal order the identity
+        const bool temporal = a.kind_mask != 0 && a.T > 1;
+        const bool fits = (size_t)tile_list_cap(a.nb) * 4 <= 24 * 1024 && (unsigned long long)a.N * 256ull < (1ull << 32) &&
+                          (!temporal || a.t_magic != 0);
         if ((variant == 0 || variant == 5) && fits && a.tile_lists) return launch_sparse_attn_v5(a, st);
         return launch_sparse_attn_v2(a, st);
     }

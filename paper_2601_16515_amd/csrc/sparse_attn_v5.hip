@@ -10,13 +10,18 @@
 //     use (global_load_lds_dwordx4, bank swizzle applied on the global side).  The wait before the
 //     per-block barrier is counted (s_waitcnt vmcnt(n)), so PD blocks of loads stay in flight and
 //     L2 / fabric latency is covered without a second resident workgroup.
-//   * Ping-pong: waves 0-3 (group 0) and 4-7 (group 1) share the 4 SIMDs pairwise.  Each KV block is
-//     handled in two barrier-separated phases; in phase A group 0 runs its matrix work (O += V^T P of
-//     the previous block, S = K Q^T of the current one) while group 1 runs its vector work (softmax);
-//     in phase B they swap.  A SIMD issues VALU instructions under a running MFMA, so both pipes stay
-//     busy although each wave's own code is sequential.
+//   * Ping-pong: waves 0-3 (group 0) and 4-7 (group 1) share the 4 SIMDs pairwise.  Per KV block a wave
+//     has a matrix part (O += V^T P of the previous block, S = K Q^T of the current one: 32 MFMAs) and a
+//     vector part (softmax of S, then the address arithmetic and issue of the next prefetch).  Group 0
+//     runs matrix then vector, group 1 vector then matrix, so that one wave of a SIMD feeds the matrix
+//     pipe while the other uses the vector ALU.  One barrier per KV block (it also protects the ring).
 //   * V^T operands come from ds_read_b64_tr_b16, K rows are read through the kappa permutation so
-//     that P never moves between lanes, the reference maximum is raised lazily (threshold 2^8).
+//     that P never moves between lanes.  LDS operand reads are spread evenly between the MFMAs through a
+//     small ring of fragment registers.
+//   * Softmax with few vector instructions: logits live in the log2 domain (one fma and one v_exp_f32 per
+//     element); row sums are taken from the bf16-rounded probabilities with v_dot2c_f32_bf16; the block
+//     maximum is not computed unless a block's sums show that some logit exceeds the running reference
+//     by more than 13 binades (the reference then moves to the true maximum and the block is redone).
 //   * Epilogue: the hi/lo bf16 fragments of the linear state are staged once per workgroup in LDS.
 #include "salad_internal.h"
 
@@ -41,7 +46,7 @@ namespace {
 __device__ inline int row_of_position5(int kind, int p, int T, int HW, unsigned magic)
 {
     if (!kind) return p;
-    int loc = magic ? (int)__umulhi((unsigned)p, magic) : p / T;
+    const int loc = (int)__umulhi((unsigned)p, magic);   // exact p / T (the host checks the range)
     return (p - loc * T) * HW + loc;
 }
 
@@ -69,6 +74,16 @@ __device__ inline void lds_dma16(const void *gptr, unsigned lds_addr_uniform)
                  : "memory", "m0");
 }
 
+// Same, addressed as (wave-uniform 64-bit base) + (per-lane unsigned 32-bit byte offset): no 64-bit
+// vector arithmetic per load.
+__device__ inline void lds_dma16_base(const void *base_uniform, unsigned byte_off, unsigned lds_addr_uniform)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_addr_uniform), "v"(byte_off), "s"(base_uniform)
+                 : "memory", "m0");
+}
+
 __device__ inline unsigned lds_addr_of(const void *p)
 {
     return __builtin_amdgcn_readfirstlane((unsigned)(size_t)LDS_PTR(p));
@@ -80,6 +95,15 @@ __device__ inline float max_with_other_half(float x)
 {
     auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
     return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+// acc + lo(w) + hi(w) for a packed pair of bf16 (dot product with (1, 1), fp32 accumulate).  Chains of these
+// on one accumulator need no wait; any other instruction reading the result needs four idle slots first
+// (see the s_nop where the sums are consumed).
+__device__ inline float add_bf16_pair(float acc, uint32_t w)
+{
+    asm("v_dot2c_f32_bf16 %0, %1, %2" : "+v"(acc) : "v"(w), "v"(0x3f803f80u));
+    return acc;
 }
 
 union Frag5 {
@@ -139,10 +163,14 @@ hipError_t launch_tile_lists(const int32_t *row_ptr, const int32_t *col_idx, int
 }
 
 // PD: prefetch distance in KV blocks; NSLOT = PD + 2 ring slots for K and for V.
-template <int PD, bool DBG, bool DIAG>
-__global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int ntiles, int total, int per_xcd, int list_cap, int skip_arg, long long *trace, int trace_block)
+// SKIP (development builds only, -DSALAD_DIAG): bit 0 drops the softmax stage, 1 the S product, 2 the PV
+// product, 3 the K/V loads; 4 adds a barrier between the two phases of an iteration, 5 records timestamps, 6 raises the
+// priority of the vector phase, 7 of the matrix phase, 8 recomputes the row maximum for every block.
+template <int PD, bool DBG, int SKIP>
+__global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int ntiles, int total, int per_xcd, int list_cap, long long *trace, int trace_block)
 {
-    const int skip = DIAG ? skip_arg : 0;   // diagnostics (stage skipping, timestamps) only in the DIAG build
+    constexpr int skip = SKIP;
+    constexpr bool DIAG = (SKIP & 32) != 0;
     constexpr int D = 128, NS = 8, NDT = 4;
     constexpr int TILE = 64 * D;                 // elements
     constexpr int NSLOT = PD + 2;
@@ -156,18 +184,20 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
     if (L >= total) return;
     const int bh = L / ntiles, tile = L - bh * ntiles;
     const int h = bh % a.H;
-    const int kind = (int)((a.kind_mask >> h) & 1ull);
     const int N = a.N, T = a.T, HW = a.HW, nb = a.nb;
+    const int kind = T > 1 ? (int)((a.kind_mask >> h) & 1ull) : 0;
     const unsigned magic = a.t_magic;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hh = lane >> 5;
     const int group = wave >> 2;
-    const bool tr = DIAG && trace != nullptr && (int)blockIdx.x == trace_block && lane == 0;
-    long long *trw = trace + wave * 1024;
-    int trn = 0;
-#define TRACE() do { if (DIAG && tr && trn < 1024) trw[trn++] = clock64(); } while (0)
-    TRACE();
+    long long stamp[4] = {0, 0, 0, 0};
+    const long long real0 = DIAG ? (long long)__builtin_amdgcn_s_memrealtime() : 0;   // 100 MHz
+#define STAMP(i) do { if (DIAG) stamp[i] = clock64(); } while (0)
+    uint32_t tv[4] = {0u, 0u, 0u, 0u};   // per-iteration timestamps, one lane per iteration (development builds)
+#define TSTAMP(k) do { if (DIAG) { const uint32_t t_ = (uint32_t)__builtin_amdgcn_s_memtime(); \
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tv_writelane_b32 %0, %1, m0" : "+v"(tv[k]) : "s"(t_), "s"(j & 63) : "m0"); } } while (0)
+    STAMP(0);
     const u16 *qb = reinterpret_cast<const u16 *>(a.q) + (size_t)bh * N * D;
     const u16 *kb = reinterpret_cast<const u16 *>(a.k) + (size_t)bh * N * D;
     const u16 *vb = reinterpret_cast<const u16 *>(a.v) + (size_t)bh * N * D;
@@ -184,34 +214,46 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
     for (int s = 0; s < NS; ++s)
         qf[s].u = *reinterpret_cast<const uint4 *>(qb + (size_t)qrow * D + s * 16 + hh * 8);
 
-    // ---- this tile's union list (built by the pre-pass): one coalesced round trip into LDS
+    // ---- this tile's union list (built by the pre-pass): the whole row of list_cap slots is copied, so
+    // the copy does not wait for the count (slots past the count hold stale words that are never used)
     const int n = a.tile_counts[h * ntiles + tile];
     {
         const uint32_t *src = a.tile_lists + ((size_t)h * ntiles + tile) * list_cap;
-        for (int i = tid; i < n; i += 512) blist[i] = src[i];
+        for (int i = tid; i < list_cap; i += 512) blist[i] = src[i];
     }
     __syncthreads();
-    TRACE();
     // Retire the Q loads here: inside the loop the only vector-memory operations in flight must be the
     // K/V prefetches, whose completion is tracked by hand.
 #pragma unroll
     for (int s = 0; s < NS; ++s)
         asm volatile("" : "+v"(qf[s].w[0]), "+v"(qf[s].w[1]), "+v"(qf[s].w[2]), "+v"(qf[s].w[3]));
 
-    // ---- global -> LDS: thread owns LDS slots (row 32 i + tid/16, chunk tid%16), i = 0, 1, of a tile
+    const float c2 = a.scale * 1.44269504088896340736f;   // logits are handled in the log2 domain
+
+    // ---- global -> LDS: thread owns LDS slots (row 32 i + tid/16, chunk tid%16), i = 0, 1, of a tile.
+    // LDS destinations are wave-uniform scalars; global sources are a uniform base plus a 32-bit offset.
     const int lr = tid >> 4, pc = tid & 15;
-    const int kchunk = (pc ^ (lr & 15)) * 8;
-    const int vchunk = (pc ^ ((lr & 3) << 2)) * 8;
+    const unsigned kchunk_b = (unsigned)((pc ^ (lr & 15)) * 16);
+    const unsigned vchunk_b = (unsigned)((pc ^ ((lr & 3) << 2)) * 16);
+    const unsigned wave_u = (unsigned)__builtin_amdgcn_readfirstlane(wave);
+    const unsigned k_lds0 = lds_addr_of(Kb) + wave_u * 1024u;
+    const unsigned v_lds0 = lds_addr_of(Vb) + wave_u * 1024u;
     auto fetch = [&](int blk, int slot) INL {
+        const unsigned kl = k_lds0 + (unsigned)slot * (unsigned)(TILE * 2);
+        const unsigned vl = v_lds0 + (unsigned)slot * (unsigned)(TILE * 2);
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             int p = blk * 64 + i * 32 + lr;
             p = p < N ? p : N - 1;
-            const size_t off = (size_t)(unsigned)(row_of_position5(kind, p, T, HW, magic) * D);
-            lds_dma16(kb + off + kchunk, lds_addr_of(Kb + slot * TILE + (i * 512 + wave * 64) * 8));
-            lds_dma16(vb + off + vchunk, lds_addr_of(Vb + slot * TILE + (i * 512 + wave * 64) * 8));
+            const unsigned row_b = (unsigned)row_of_position5(kind, p, T, HW, magic) * (unsigned)(D * 2);
+            lds_dma16_base(kb, row_b + kchunk_b, kl + i * 8192u);
+            lds_dma16_base(vb, row_b + vchunk_b, vl + i * 8192u);
         }
     };
+    // list entries travel in a vector register (lane l holds entry 64 c + l of the current 64-entry
+    // chunk c) and are picked with v_readlane: no LDS round trip per iteration
+    uint32_t ev = blist[lane];
+    auto entry = [&](int idx) INL -> uint32_t { return (uint32_t)__builtin_amdgcn_readlane((int)ev, idx & 63); };
 
     // ---- LDS operand addresses (element offsets inside a tile)
     const int kappa = (l32 & 0x13) | ((l32 & 4) << 1) | ((l32 & 8) >> 1);
@@ -231,87 +273,73 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
     for (int i = 0; i < NDT; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[i][r] = 0.f;
-    float m_run = -1e30f, l_run = 0.f;
-    const float c2 = a.scale * 1.44269504088896340736f;
+    float m_run = 0.f, l_run = 0.f;
+    bool have_ref = false;                 // wave-uniform: m_run has been set from a block's true maximum
     f32x16 s[2];
     Frag5 pf[4];
 
-    // V^T fragments of 16-key groups 0 and 1 are requested at the end of the softmax that produces P
-    // (the V tile of that block is already in LDS), so the next matrix phase starts without waiting.
-    Frag5 vf[2][NDT];
-    auto vread = [&](const u16 *Vt, int c16, Frag5 (&f)[NDT]) INL {
-#pragma unroll
-        for (int dt = 0; dt < NDT; ++dt) {
-            const u16 *vp = Vt + c16 * 16 * D + voff[dt];
-            f[dt].h[0] = TR_READ(vp);
-            f[dt].h[1] = TR_READ(vp + 4 * D);
+    // Matrix phase = 32 MFMAs per wave: 16 for O^T += V^T P^T (A = V^T fragment: two transposing 8-byte reads),
+    // then 16 for S^T = K Q^T (A = K fragment: one 16-byte read).  Operand fragments move through a ring of
+    // RING register quads: MFMA i takes ring[i % RING] and the read of fragment i + RING is issued right after
+    // it, so LDS requests are spread evenly over the phase (the LDS has to deliver 1 KB per MFMA per wave,
+    // about three quarters of what it can sustain, and bursts of reads stall the matrix pipe) and at most
+    // 2 RING <= 15 of them are in flight.  The first RING fragments are requested in the preceding vector
+    // phase, once the V tile they come from is known to have landed.
+    constexpr int RING = 7;
+    Frag5 ring[RING];
+    auto read_frag = [&](int i, const u16 *Vt, const u16 *Kt, Frag5 &f) INL {
+        if (i < 16) {
+            const u16 *vp = Vt + (i >> 2) * 16 * D + voff[i & 3];
+            f.h[0] = TR_READ(vp);
+            f.h[1] = TR_READ(vp + 4 * D);
+        } else {
+            const int t = i - 16;
+            f.v = *reinterpret_cast<const bf16x8 *>(Kt + (t & 1) * 32 * D + koff[t >> 1]);
         }
     };
-    auto preload_V = [&](const u16 *Vt) INL {
-        vread(Vt, 0, vf[0]);
-    };
-    auto pv_group = [&](int c16) INL {
+    auto mfma_step = [&](int i, const Frag5 &f) INL {
+        if (i < 16) {
+            o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.v, pf[i >> 2].v, o[i & 3], 0, 0, 0);
+        } else {
+            const int t = i - 16, kt = t & 1, st = t >> 1;
+            if (st == 0) {
+                f32x16 z;
 #pragma unroll
-        for (int dt = 0; dt < NDT; ++dt)
-            o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[c16 & 1][dt].v, pf[c16].v, o[dt], 0, 0, 0);
-    };
-    auto stage_PV = [&](const u16 *Vt) INL {       // vf[0] (16-key group 0) already requested
-        vread(Vt, 1, vf[1]);
-        __builtin_amdgcn_sched_barrier(0);
-        pv_group(0); vread(Vt, 2, vf[0]);
-        __builtin_amdgcn_sched_barrier(0);
-        pv_group(1); vread(Vt, 3, vf[1]);
-        __builtin_amdgcn_sched_barrier(0);
-        pv_group(2);
-        pv_group(3);
-        __builtin_amdgcn_sched_barrier(0);
-    };
-    auto stage_S = [&](const u16 *Kt) INL {
-        bf16x8 kf[2][NS];
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-            for (int st = 0; st < NS; ++st)
-                kf[kt][st] = *reinterpret_cast<const bf16x8 *>(Kt + kt * 32 * D + koff[st]);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s[kt][r] = 0.f;
-#pragma unroll
-        for (int st = 0; st < NS; ++st) {
-            s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0][st], qf[st].v, s[0], 0, 0, 0);
-            s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[1][st], qf[st].v, s[1], 0, 0, 0);
+                for (int r = 0; r < 16; ++r) z[r] = 0.f;
+                s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.v, qf[st].v, z, 0, 0, 0);
+            } else {
+                s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.v, qf[st].v, s[kt], 0, 0, 0);
+            }
         }
     };
-    // both products of one matrix phase, K fragments requested under the running PV MFMAs
-    auto stage_PV_S = [&](const u16 *Vt, const u16 *Kt) INL {
-        bf16x8 kf[2][NS];
-        vread(Vt, 1, vf[1]);
-        __builtin_amdgcn_sched_barrier(0);
-        pv_group(0); vread(Vt, 2, vf[0]);
-        __builtin_amdgcn_sched_barrier(0);
-        pv_group(1); vread(Vt, 3, vf[1]);
-        __builtin_amdgcn_sched_barrier(0);
+    auto preload_V = [&](const u16 *Vt) INL {      // fragments 0 .. RING-1 (all of them V^T fragments)
 #pragma unroll
-        for (int st = 0; st < NS; ++st) kf[0][st] = *reinterpret_cast<const bf16x8 *>(Kt + koff[st]);
-        pv_group(2);
-        __builtin_amdgcn_sched_barrier(0);
-        pv_group(3);
+        for (int i = 0; i < RING; ++i) read_frag(i, Vt, nullptr, ring[i]);
+    };
+    // steps FIRST .. LAST-1 of the sequence; ring[(FIRST + k) % RING], k < RING, already requested
+    auto run_steps = [&](const u16 *Vt, const u16 *Kt, int first, int last) INL {
 #pragma unroll
-        for (int st = 0; st < NS; ++st) kf[1][st] = *reinterpret_cast<const bf16x8 *>(Kt + 32 * D + koff[st]);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s[kt][r] = 0.f;
-#pragma unroll
-        for (int st = 0; st < NS; ++st) {
-            s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0][st], qf[st].v, s[0], 0, 0, 0);
-            s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[1][st], qf[st].v, s[1], 0, 0, 0);
+        for (int i = first; i < last; ++i) {
+            mfma_step(i, ring[i % RING]);
+            if (i + RING < last) read_frag(i + RING, Vt, Kt, ring[i % RING]);
+            __builtin_amdgcn_sched_barrier(0);
         }
+    };
+    auto stage_PV_S = [&](const u16 *Vt, const u16 *Kt) INL { run_steps(Vt, Kt, 0, 32); };
+    auto stage_PV = [&](const u16 *Vt) INL { run_steps(Vt, nullptr, 0, 16); };
+    auto stage_S = [&](const u16 *Kt) INL {          // rare (first block of a row, blocks another row's mask drops)
+#pragma unroll
+        for (int i = 0; i < RING; ++i) read_frag(16 + i, nullptr, Kt, ring[(16 + i) % RING]);
+        run_steps(nullptr, Kt, 16, 32);
     };
     auto stage_softmax = [&](int blk) INL {
+        if (skip & 1) {   // development: keep S alive and P defined without doing the work
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int k = 0; k < 4; ++k) asm volatile("" : "+v"(pf[i].w[k]) : "v"(s[0]), "v"(s[1]));
+            return;
+        }
         if (blk * 64 + 64 > N) {
             const int kbase = blk * 64 + hh * 8;
 #pragma unroll
@@ -320,32 +348,52 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
                 for (int r = 0; r < 16; ++r)
                     if (kbase + kt * 32 + 16 * (r >> 3) + (r & 7) >= N) s[kt][r] = -INFINITY;
         }
-        float mx = s[0][0];
+        // P = 2^(S c2 - m) rounded to bf16; returns the lane's sum of the rounded values (what the PV product sees)
+        auto exp_pack = [&]() INL -> float {
+            float ps0 = 0.f, ps1 = 0.f;
 #pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
+            for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kt][r]);
-        mx = max_with_other_half(mx) * c2;
-        if (__any(mx > m_run + 8.0f)) {
-            const float m_new = fmaxf(m_run, mx);
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-            m_run = m_new;
-            l_run *= alpha;
-#pragma unroll
-            for (int i = 0; i < NDT; ++i)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) o[i][r] *= alpha;
-        }
+                for (int r = 0; r < 16; r += 2) {
+                    const uint32_t w = pack2e(__builtin_amdgcn_exp2f(fmaf(s[kt][r], c2, -m_run)),
+                                              __builtin_amdgcn_exp2f(fmaf(s[kt][r + 1], c2, -m_run)));
+                    pf[kt * 2 + (r >> 3)].w[(r & 7) >> 1] = w;
+                    if (r & 2) ps1 = add_bf16_pair(ps1, w); else ps0 = add_bf16_pair(ps0, w);
+                }
+            // the dot instructions come from inline assembly, so the compiler does not know that another
+            // vector instruction must not read their result in the next four issue slots
+            asm volatile("s_nop 4" : "+v"(ps0), "+v"(ps1));
+            return ps0 + ps1;
+        };
+        // The reference only has to keep 2^S in range, so the block maximum is not computed unless the
+        // sums say that some logit rose more than 13 binades above the reference (or no reference exists
+        // yet): then the reference moves to the true maximum and the block is redone.
         float psum = 0.f;
+        bool redo = !have_ref || (skip & 256);
+        if (have_ref && !(skip & 256)) {
+            psum = exp_pack();
+            redo = __any(!(psum <= 8192.f));
+        }
+        if (redo) {
+            float mx = s[0][0];
 #pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
+            for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-            for (int r = 0; r < 16; r += 2) {
-                float p0 = __builtin_amdgcn_exp2f(fmaf(s[kt][r], c2, -m_run));
-                float p1 = __builtin_amdgcn_exp2f(fmaf(s[kt][r + 1], c2, -m_run));
-                psum += p0 + p1;
-                pf[kt * 2 + (r >> 3)].w[(r & 7) >> 1] = pack2e(p0, p1);
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kt][r]);
+            mx = fmaf(fmaxf(max_with_other_half(mx), -1e30f), c2, -m_run);   // block maximum minus reference
+            const float shift = have_ref ? fmaxf(mx, 0.f) : mx;                // new reference minus old reference
+            if (have_ref) {
+                const float alpha = __builtin_amdgcn_exp2f(-shift);
+                l_run *= alpha;
+#pragma unroll
+                for (int i = 0; i < NDT; ++i)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) o[i][r] *= alpha;
             }
+            m_run += shift;
+            have_ref = true;
+            psum = exp_pack();
+        }
         l_run += psum;
     };
 
@@ -359,56 +407,82 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
 
     // ---- main loop over the union list.  Iteration j: S(j) and softmax(j), PV(j-1); fetch block j+PD.
     // Block b lives in ring slot b % NSLOT of both rings (K(b) is read in iteration b, V(b) in b+1).
+    // The fetch of block j+PD is issued from each group's vector phase, where its address arithmetic
+    // runs under the other group's MFMAs; slot (j+PD) % NSLOT was last read in iteration j-1.
+    STAMP(1);
     if (n > 0) {
 #pragma unroll
         for (int b = 0; b < PD; ++b)
-            if (b < n && !(skip & 8)) fetch((int)(blist[b] & 0xffffffu), b);
-        uint32_t e_prev = 0u, e_cur = blist[0];
+            if (b < n && !(skip & 8)) fetch((int)(entry(b) & 0xffffffu), b);
+        uint32_t e_prev = 0u;
+        uint32_t eq[PD];                          // eq[i] = entry j + i
+#pragma unroll
+        for (int b = 0; b < PD; ++b) eq[b] = b < n ? entry(b) : 0u;
         int slot_cur = 0;                         // j % NSLOT
         for (int j = 0; j < n; ++j) {
             // all fetches up to block j must have landed; newer ones may stay in flight
             {
-                const int last = (j + PD - 1 < n - 1) ? j + PD - 1 : n - 1;
-                int newer = last - j;
+                int newer = n - 1 - j;
+                if (newer > PD - 1) newer = PD - 1;
                 if (skip & 8) newer = 0;
                 if (newer >= 3) WAIT_VM(12);
                 else if (newer == 2) WAIT_VM(8);
                 else if (newer == 1) WAIT_VM(4);
                 else WAIT_VM(0);
             }
-            TRACE();
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
-            TRACE();
-            const uint32_t e_nxt = (j + 1 < n) ? blist[j + 1] : 0u;
+            TSTAMP(0);
+            const int jf = j + PD;
+            uint32_t e_f = 0u;
+            if (jf < n) {
+                if ((jf & 63) == 0) ev = blist[jf + lane];
+                e_f = entry(jf);
+            }
+            const bool do_fetch = jf < n && !(skip & 8);
             int slot_f = slot_cur + PD; if (slot_f >= NSLOT) slot_f -= NSLOT;
-            if (j + PD < n && !(skip & 8)) fetch((int)(blist[j + PD] & 0xffffffu), slot_f);
             int slot_prev = slot_cur - 1; if (slot_prev < 0) slot_prev += NSLOT;
+            const uint32_t e_cur = eq[0];
             const bool kS = (e_cur & mybit) != 0, kP = (j >= 1) && (e_prev & mybit);
-            const bool dS = kS && !(skip & 2), dP = kP && !(skip & 4), dM0 = kS && !(skip & 1), dM1 = kP && !(skip & 1);
+            const bool dS = kS && !(skip & 2), dP = kP && !(skip & 4), dM0 = kS, dM1 = kP;
             const u16 *Kt = Kb + slot_cur * TILE;
             const u16 *Vt = Vb + slot_prev * TILE;
             const u16 *Vc = Vb + slot_cur * TILE;      // V tile of block j (already landed with K(j))
             if (group == 0) {
+                if (skip & 128) __builtin_amdgcn_s_setprio(2);
                 if (dP && dS) stage_PV_S(Vt, Kt);
                 else { if (dP) stage_PV(Vt); if (dS) stage_S(Kt); }
-                TRACE();
-                if (!(skip & 16)) __builtin_amdgcn_s_barrier();
+                if (skip & 128) __builtin_amdgcn_s_setprio(0);
+                TSTAMP(1);
+                if (skip & 16) __builtin_amdgcn_s_barrier();
                 asm volatile("" ::: "memory");
+                TSTAMP(2);
+                if (skip & 64) __builtin_amdgcn_s_setprio(3);
+                if (dS) preload_V(Vc);                  // for PV(j) in the next iteration; lands under the softmax
                 if (dM0) stage_softmax((int)(e_cur & 0xffffffu));
-                if (dS) preload_V(Vc);                  // for PV(j) in the next iteration
-                TRACE();
+                TSTAMP(3);
+                if (do_fetch) fetch((int)(e_f & 0xffffffu), slot_f);
+                if (skip & 64) __builtin_amdgcn_s_setprio(0);
             } else {
+                if (skip & 64) __builtin_amdgcn_s_setprio(3);
+                if (dP) preload_V(Vt);                  // for PV(j-1) right after the barrier; lands under the softmax
                 if (dM1) stage_softmax((int)(e_prev & 0xffffffu));
-                if (dP) preload_V(Vt);                  // for PV(j-1) right after the barrier
-                TRACE();
-                if (!(skip & 16)) __builtin_amdgcn_s_barrier();
+                TSTAMP(1);
+                if (do_fetch) fetch((int)(e_f & 0xffffffu), slot_f);
+                if (skip & 64) __builtin_amdgcn_s_setprio(0);
+                if (skip & 16) __builtin_amdgcn_s_barrier();
                 asm volatile("" ::: "memory");
+                TSTAMP(2);
+                if (skip & 128) __builtin_amdgcn_s_setprio(2);
                 if (dP && dS) stage_PV_S(Vt, Kt);
                 else { if (dP) stage_PV(Vt); if (dS) stage_S(Kt); }
-                TRACE();
+                if (skip & 128) __builtin_amdgcn_s_setprio(0);
+                TSTAMP(3);
             }
-            e_prev = e_cur; e_cur = e_nxt;
+            e_prev = e_cur;
+#pragma unroll
+            for (int b = 0; b + 1 < PD; ++b) eq[b] = eq[b + 1];
+            eq[PD - 1] = e_f;
             ++slot_cur; if (slot_cur >= NSLOT) slot_cur = 0;
         }
         // tail: the PV product of the last block (group 1 still owes its softmax).  The K ring is idle
@@ -421,12 +495,12 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
             int slot_prev = slot_cur - 1; if (slot_prev < 0) slot_prev += NSLOT;
             const u16 *Vt = Vb + slot_prev * TILE;
             const bool kP = (e_prev & mybit) != 0;
-            if (group == 1 && kP && !(skip & 1)) { stage_softmax((int)(e_prev & 0xffffffu)); preload_V(Vt); }
+            if (group == 1 && kP) { preload_V(Vt); stage_softmax((int)(e_prev & 0xffffffu)); }
             if (kP && !(skip & 4)) stage_PV(Vt);
         }
     }
 
-    TRACE();
+    STAMP(2);
     // ---- epilogue ---------------------------------------------------------------------------------
     float l_tot = l_run + __shfl_xor(l_run, 32);
     const float inv_l = l_tot > 0.f ? 1.f / l_tot : 0.f;
@@ -465,7 +539,6 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
             }
         }
     }
-    TRACE();
     if (!qvalid) return;
     const size_t obase = ((size_t)bh * N + qrow) * D;
     u16 *outp = reinterpret_cast<u16 *>(a.out) + obase;
@@ -494,12 +567,22 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
             }
         }
     }
-    TRACE();
-    if (DIAG && tr) trw[1023] = trn;
-#undef TRACE
+    if (DIAG && trace != nullptr && (int)blockIdx.x == trace_block) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) trace[64 + (wave * 4 + i) * 64 + lane] = tv[i];
+    }
+    if (DIAG && trace != nullptr && (int)blockIdx.x == trace_block && lane == 0) {
+        STAMP(3);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) trace[wave * 4 + i] = stamp[i];
+        trace[40 + wave] = (long long)__builtin_amdgcn_s_memrealtime() - real0;
+        trace[32 + wave] = __builtin_amdgcn_s_getreg((16 - 1) << 11 | 0 << 6 | 4);   // HW_ID[15:0]: wave, SIMD, pipe, CU, SH, SE
+    }
+#undef STAMP
+#undef TSTAMP
 }
 
-template <int PD, bool DBG, bool DIAG>
+template <int PD, bool DBG, int SKIP>
 static hipError_t launch_v5(const AttnArgs &a, hipStream_t st)
 {
     const int ntiles = (a.nb + 3) / 4;
@@ -509,23 +592,31 @@ static hipError_t launch_v5(const AttnArgs &a, hipStream_t st)
     const size_t lds = (size_t)(PD + 2) * 2 * 64 * 128 * 2 + (size_t)list_cap * 4;
     constexpr int kMaxDyn = 160 * 1024 - 2048;   // the static part is rounded up to its 1 KB alignment
     if (lds > (size_t)kMaxDyn) return hipErrorInvalidValue;
-    auto kern = sparse_attn_v5_kernel<PD, DBG, DIAG>;
+    auto kern = sparse_attn_v5_kernel<PD, DBG, SKIP>;
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDyn);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(512), lds, st, a, ntiles, total, per_xcd, list_cap, g_attn_variant >> 4, g_trace_ptr, g_trace_block);
+    hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(512), lds, st, a, ntiles, total, per_xcd, list_cap, g_trace_ptr, g_trace_block);
     return hipGetLastError();
 }
 
 hipError_t launch_sparse_attn_v5(const AttnArgs &a, hipStream_t st)
 {
     const bool dbg = a.o_sparse_dbg || a.o_linear_dbg;
-    const bool diag = (g_attn_variant >> 4) != 0 || g_trace_ptr != nullptr;
-    if (diag) return launch_v5<2, false, true>(a, st);
-    return dbg ? launch_v5<2, true, false>(a, st) : launch_v5<2, false, false>(a, st);
+#ifdef SALAD_DIAG
+    switch (g_attn_variant >> 4) {
+    case 0: break;
+#define SALAD_DIAG_CASE(k) case k: return launch_v5<2, false, k>(a, st);
+    SALAD_DIAG_CASE(1) SALAD_DIAG_CASE(6) SALAD_DIAG_CASE(7) SALAD_DIAG_CASE(8) SALAD_DIAG_CASE(9) SALAD_DIAG_CASE(14)
+    SALAD_DIAG_CASE(15) SALAD_DIAG_CASE(16) SALAD_DIAG_CASE(32) SALAD_DIAG_CASE(33) SALAD_DIAG_CASE(47) SALAD_DIAG_CASE(64) SALAD_DIAG_CASE(96) SALAD_DIAG_CASE(192) SALAD_DIAG_CASE(224) SALAD_DIAG_CASE(256) SALAD_DIAG_CASE(80)
+#undef SALAD_DIAG_CASE
+    default: return hipErrorInvalidValue;
+    }
+#endif
+    return dbg ? launch_v5<2, true, 0>(a, st) : launch_v5<2, false, 0>(a, st);
 }
 
 }  // namespace salad
