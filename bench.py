@@ -75,6 +75,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense-control", action="store_true")
     ap.add_argument("--cpu-sample-every", type=int, default=1)
+    ap.add_argument("--traffic-calibration", action="store_true",
+                    help="also run three plain device copies of Q (a kernel of known size) so that a "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run of this command can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -163,6 +166,12 @@ def main():
         result["dense_control"] = {"ms_per_call": ms_d, "TFLOP/s": fl_d / (ms_d * 1e-3) * 1e-12,
                                    "speedup_sparse_vs_dense": ms_d / ms,
                                    "paper_end_to_end_speedup_context": "1.52-2.03x over full attention, GPU model not stated in the paper"}
+    if args.traffic_calibration:
+        scratch = torch.empty_like(q)
+        for _ in range(3):
+            scratch.copy_(q)
+        torch.cuda.synchronize()
+        result["traffic_calibration"] = {"kernel": "device copy of Q, 3 launches", "bytes_read": q.numel() * esz, "bytes_written": q.numel() * esz}
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, inp, kinds, kept, args.cpu_sample_every)
     print(json.dumps(result))

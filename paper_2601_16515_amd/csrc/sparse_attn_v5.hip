@@ -115,17 +115,23 @@ union Frag5 {
 
 }  // namespace
 
-// Pre-pass: for every (head, tile of 4 query blocks) the ascending union of the 4 CSR rows' kept blocks,
-// each entry tagged with which of the 4 rows keep it.  One wave per tile: bitmap in LDS, then ordered
-// compaction with ballots.  The mask is static, but the layer call accepts any CSR, so this runs per call
-// (a few microseconds).
+// Pre-pass: for every (head, tile of 4 query blocks) the union of the 4 CSR rows' kept blocks, each entry
+// tagged with which of the 4 rows keep it.  One wave per tile: bitmap in LDS, ordered compaction with
+// ballots, then the ascending list is rotated so that it starts at the entry whose block id is smallest
+// modulo the list length.  Softmax does not care about the order, and with sliding windows the rotation makes
+// neighbouring tiles (which run at the same time on one XCD and whose windows overlap) reach a given KV
+// block at about the same iteration, so the block is fetched into that XCD's L2 once instead of once per
+// tile.  The mask is static, but the layer call accepts any CSR, so this runs per call (a few microseconds).
 __global__ __launch_bounds__(64) void tile_lists_kernel(const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
                                                         int nb, int ntiles, int cap, uint32_t *__restrict__ lists,
                                                         int32_t *__restrict__ counts)
 {
-    extern __shared__ uint32_t bm[];
+    extern __shared__ uint32_t bm[];          // [cap] bitmap, then [cap] compacted list
+    uint32_t *lst = bm + cap;
+    __shared__ uint32_t best;
     const int h = blockIdx.y, tile = blockIdx.x, lane = threadIdx.x;
     for (int i = lane; i < nb; i += 64) bm[i] = 0u;
+    if (lane == 0) best = 0xffffffffu;
     __syncthreads();
     for (int i = 0; i < 4; ++i) {
         const int r = tile * 4 + i;
@@ -138,15 +144,29 @@ __global__ __launch_bounds__(64) void tile_lists_kernel(const int32_t *__restric
         }
     }
     __syncthreads();
-    uint32_t *out = lists + ((size_t)h * ntiles + tile) * cap;
     int count = 0;
     for (int base = 0; base < nb; base += 64) {
         const int b = base + lane;
         const uint32_t f = b < nb ? bm[b] : 0u;
         const unsigned long long bal = __ballot(f != 0u);
         const int pos = count + __popcll(bal & ((1ull << lane) - 1ull));
-        if (f) out[pos] = (uint32_t)b | f;
+        if (f) lst[pos] = (uint32_t)b | f;
         count += __popcll(bal);
+    }
+    __syncthreads();
+    // rotation point: the entry with the smallest (block id mod count); ties cannot occur within count
+    // consecutive ids, and for any other list the lowest position wins
+    for (int i = lane; i < count; i += 64) {
+        const uint32_t key = (lst[i] & 0xffffffu) % (uint32_t)count;
+        atomicMin(&best, (key << 13) | (uint32_t)i);      // at most 6144 entries (list size limit checked on the host)
+    }
+    __syncthreads();
+    const int rot = count > 0 ? (int)(best & 0x1fffu) : 0;
+    uint32_t *out = lists + ((size_t)h * ntiles + tile) * cap;
+    for (int i = lane; i < count; i += 64) {
+        int src = i + rot;
+        if (src >= count) src -= count;
+        out[i] = lst[src];
     }
     if (lane == 0) counts[h * ntiles + tile] = count;
 }
@@ -158,7 +178,7 @@ hipError_t launch_tile_lists(const int32_t *row_ptr, const int32_t *col_idx, int
 {
     const int ntiles = (nb + 3) / 4;
     const int cap = tile_list_cap(nb);
-    hipLaunchKernelGGL(tile_lists_kernel, dim3(ntiles, H), dim3(64), (size_t)cap * 4, st, row_ptr, col_idx, nb, ntiles, cap, lists, counts);
+    hipLaunchKernelGGL(tile_lists_kernel, dim3(ntiles, H), dim3(64), (size_t)cap * 8, st, row_ptr, col_idx, nb, ntiles, cap, lists, counts);
     return hipGetLastError();
 }
 
@@ -239,6 +259,7 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
     const unsigned k_lds0 = lds_addr_of(Kb) + wave_u * 1024u;
     const unsigned v_lds0 = lds_addr_of(Vb) + wave_u * 1024u;
     auto fetch = [&](int blk, int slot) INL {
+        if (skip & 1024) blk = 0;      // development: always the same (cached) block
         const unsigned kl = k_lds0 + (unsigned)slot * (unsigned)(TILE * 2);
         const unsigned vl = v_lds0 + (unsigned)slot * (unsigned)(TILE * 2);
 #pragma unroll
@@ -430,7 +451,7 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
                 else if (newer == 1) WAIT_VM(4);
                 else WAIT_VM(0);
             }
-            __builtin_amdgcn_s_barrier();
+            if (!(skip & 512)) __builtin_amdgcn_s_barrier();   // (timing experiment only: results are wrong without it)
             asm volatile("" ::: "memory");
             TSTAMP(0);
             const int jf = j + PD;
@@ -611,7 +632,7 @@ hipError_t launch_sparse_attn_v5(const AttnArgs &a, hipStream_t st)
     case 0: break;
 #define SALAD_DIAG_CASE(k) case k: return launch_v5<2, false, k>(a, st);
     SALAD_DIAG_CASE(1) SALAD_DIAG_CASE(6) SALAD_DIAG_CASE(7) SALAD_DIAG_CASE(8) SALAD_DIAG_CASE(9) SALAD_DIAG_CASE(14)
-    SALAD_DIAG_CASE(15) SALAD_DIAG_CASE(16) SALAD_DIAG_CASE(32) SALAD_DIAG_CASE(33) SALAD_DIAG_CASE(47) SALAD_DIAG_CASE(64) SALAD_DIAG_CASE(96) SALAD_DIAG_CASE(192) SALAD_DIAG_CASE(224) SALAD_DIAG_CASE(256) SALAD_DIAG_CASE(80)
+    SALAD_DIAG_CASE(15) SALAD_DIAG_CASE(16) SALAD_DIAG_CASE(32) SALAD_DIAG_CASE(33) SALAD_DIAG_CASE(47) SALAD_DIAG_CASE(64) SALAD_DIAG_CASE(96) SALAD_DIAG_CASE(192) SALAD_DIAG_CASE(224) SALAD_DIAG_CASE(256) SALAD_DIAG_CASE(80) SALAD_DIAG_CASE(512) SALAD_DIAG_CASE(520) SALAD_DIAG_CASE(513) SALAD_DIAG_CASE(1024)
 #undef SALAD_DIAG_CASE
     default: return hipErrorInvalidValue;
     }
