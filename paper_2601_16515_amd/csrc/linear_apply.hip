@@ -3,6 +3,9 @@
 // where `out` holds the sparse branch (bf16) on entry.  HBM-bound: reads Q and O_s, writes O
 // (6*N*d bytes per head); the d x d product runs on bf16 MFMA with Hs split into hi + lo parts.
 // One wave owns 32 stored rows at a time; the state fragments are staged in LDS once per workgroup.
+// d = 128 (linear_apply128_kernel): every global access is a full 128-byte line segment (8 rows x 128 bytes
+// per wave instruction); rows change between that layout and the MFMA operand / accumulator layouts
+// through a wave-private 8 KB LDS buffer.  d = 64 keeps the direct-access kernel.
 #include "salad_internal.h"
 
 namespace salad {
@@ -72,6 +75,7 @@ __global__ __launch_bounds__(256) void linear_apply_kernel(ApplyArgs a, int rows
                 dpart = fmaf(__uint_as_float(w & 0xffff0000u), zr[st][2 * j + 1], dpart);
             }
         }
+        asm volatile("" ::: "memory");   // the wave's LDS operations execute in order; as above
         const float inv_den = 1.f / (dpart + __shfl_xor(dpart, 32) + a.eps);
         const float sc = coef * inv_den;
 #pragma unroll
@@ -111,16 +115,169 @@ __global__ __launch_bounds__(256) void linear_apply_kernel(ApplyArgs a, int rows
     }
 }
 
+// d = 128.  Per wave and 32-row block: Q rows -> LDS -> B-operand fragments; relu, denominator; for each
+// half of the 128 output columns 32 MFMAs against the hi + lo state fragments, scaled results (fp32) -> LDS ->
+// row layout, added to O_s in fp32, one rounding to bf16, stored.
+template <bool DBG>
+__global__ __launch_bounds__(512) void linear_apply128_kernel(ApplyArgs a, int rows_per_wg)
+{
+    constexpr int D = 128, NS = 8;
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    u16 *hf_lds = reinterpret_cast<u16 *>(smem);                                  // [2][D*D] hi, lo fragments
+    float *z_lds = reinterpret_cast<float *>(smem + 2 * D * D * 2);               // [D]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    unsigned char *stage = smem + 2 * D * D * 2 + 1024 + wave * 8192;             // wave-private, 8 KB
+    const int l32 = lane & 31, hh = lane >> 5;
+    const int bh = blockIdx.y;
+    {   // fragments are lane-linear in memory: copy as is (16 bytes per lane per load)
+        const u16 *hf = a.hfrag + (size_t)bh * 2 * D * D;
+#pragma unroll
+        for (int i = 0; i < 2 * D * D / 8 / 512; ++i)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(hf + (size_t)(i * 512 + tid) * 8),
+                                             (__attribute__((address_space(3))) void *)(hf_lds + (i * 512 + wave * 64) * 8), 16, 0, 0);
+        if (tid < D) z_lds[tid] = a.Z[(size_t)bh * D + tid];
+    }
+    const float coef = a.coef[bh];
+    __syncthreads();
+    const int N = a.N;
+    const u16 *qh = a.q + (size_t)bh * N * D;
+    u16 *oh = a.out + (size_t)bh * N * D;
+    const int r8 = lane >> 3, c8 = lane & 7;          // row layout of a half: 8 rows x 8 chunks of 16 bytes per instruction
+    const int r4 = lane >> 4, c16 = lane & 15;        // row layout of full rows: 4 rows x 16 chunks
+    const int row_end = min(N, (int)(blockIdx.x + 1) * rows_per_wg);
+    for (int rb = blockIdx.x * rows_per_wg + wave * 32; rb < row_end; rb += 256) {
+        // ---- Q: 8 coalesced loads, swizzled into LDS (chunk ^ (row & 15)), read back as B-operand fragments
+        uint4 qc[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int row = min(rb + 4 * i + r4, N - 1);
+            qc[i] = *reinterpret_cast<const uint4 *>(qh + (size_t)row * D + c16 * 8);
+        }
+        // O_s in the half-row layout (half h, rows 8k + r8): issued now, consumed at the end
+        uint4 os[2][4];
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int row = min(rb + 8 * k + r8, N - 1);
+                os[h][k] = *reinterpret_cast<const uint4 *>(oh + (size_t)row * D + h * 64 + c8 * 8);
+            }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int lrow = 4 * i + r4;
+            *reinterpret_cast<uint4 *>(stage + lrow * 256 + ((c16 ^ (lrow & 15)) << 4)) = qc[i];
+        }
+        asm volatile("" ::: "memory");   // the wave's LDS operations execute in order; keep the compiler from reordering them
+        Frag8a qf[NS];
+        float dpart = 0.f;
+#pragma unroll
+        for (int st = 0; st < NS; ++st) {
+            qf[st].u = *reinterpret_cast<const uint4 *>(stage + l32 * 256 + (((2 * st + hh) ^ (l32 & 15)) << 4));
+            const float4 z0 = *reinterpret_cast<const float4 *>(z_lds + st * 16 + hh * 8);
+            const float4 z1 = *reinterpret_cast<const float4 *>(z_lds + st * 16 + hh * 8 + 4);
+            const float zz[8] = {z0.x, z0.y, z0.z, z0.w, z1.x, z1.y, z1.z, z1.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                s16x2 v = __builtin_bit_cast(s16x2, qf[st].w[j]);
+                s16x2 z = {0, 0};
+                uint32_t w = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(v, z));
+                qf[st].w[j] = w;
+                dpart = fmaf(__uint_as_float(w << 16), zz[2 * j], dpart);
+                dpart = fmaf(__uint_as_float(w & 0xffff0000u), zz[2 * j + 1], dpart);
+            }
+        }
+        asm volatile("" ::: "memory");   // the wave's LDS operations execute in order; as above
+        const float inv_den = 1.f / (dpart + __shfl_xor(dpart, 32) + a.eps);
+        const float sc = coef * inv_den;
+        const bool rvalid = rb + l32 < N;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            f32x16 num[2];
+#pragma unroll
+            for (int dl = 0; dl < 2; ++dl) {
+                const int dt = 2 * h + dl;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) num[dl][r] = 0.f;
+#pragma unroll
+                for (int st = 0; st < NS; ++st) {
+                    const int idx = ((dt * NS + st) * 64 + lane) * 8;
+                    bf16x8 hi = *reinterpret_cast<const bf16x8 *>(hf_lds + idx);
+                    bf16x8 lo = *reinterpret_cast<const bf16x8 *>(hf_lds + D * D + idx);
+                    num[dl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo, qf[st].v, num[dl], 0, 0, 0);
+                    num[dl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hi, qf[st].v, num[dl], 0, 0, 0);
+                }
+            }
+            // accumulator layout (lane = row l32; registers 4 g4 + t = column 32 dl + 8 g4 + 4 hh + t) -> LDS, fp32,
+            // rows of 64 columns = 16 chunks of 16 bytes, chunk ^ (row & 15)
+#pragma unroll
+            for (int dl = 0; dl < 2; ++dl)
+#pragma unroll
+                for (int g4 = 0; g4 < 4; ++g4) {
+                    const int chunk = dl * 8 + 2 * g4 + hh;
+                    *reinterpret_cast<float4 *>(stage + l32 * 256 + ((chunk ^ (l32 & 15)) << 4)) =
+                        make_float4(num[dl][g4 * 4 + 0] * sc, num[dl][g4 * 4 + 1] * sc, num[dl][g4 * 4 + 2] * sc, num[dl][g4 * 4 + 3] * sc);
+                    if (DBG) {
+                        if (a.o_linear_dbg && rvalid)
+                            *reinterpret_cast<float4 *>(a.o_linear_dbg + ((size_t)bh * N + rb + l32) * D + (2 * h + dl) * 32 + 8 * g4 + 4 * hh) =
+                                make_float4(num[dl][g4 * 4 + 0] * inv_den, num[dl][g4 * 4 + 1] * inv_den,
+                                            num[dl][g4 * 4 + 2] * inv_den, num[dl][g4 * 4 + 3] * inv_den);
+                    }
+                }
+            asm volatile("" ::: "memory");
+            // row layout: 8 rows x 8 chunks of 8 columns per instruction; out = O_s + scaled numerator, one rounding
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int lrow = 8 * k + r8;
+                const float4 n0 = *reinterpret_cast<const float4 *>(stage + lrow * 256 + (((2 * c8) ^ (lrow & 15)) << 4));
+                const float4 n1 = *reinterpret_cast<const float4 *>(stage + lrow * 256 + (((2 * c8 + 1) ^ (lrow & 15)) << 4));
+                const uint4 o4 = os[h][k];
+                uint4 pk;
+                {
+                    f32x2 x0 = {__uint_as_float(o4.x << 16) + n0.x, __uint_as_float(o4.x & 0xffff0000u) + n0.y};
+                    f32x2 x1 = {__uint_as_float(o4.y << 16) + n0.z, __uint_as_float(o4.y & 0xffff0000u) + n0.w};
+                    f32x2 x2 = {__uint_as_float(o4.z << 16) + n1.x, __uint_as_float(o4.z & 0xffff0000u) + n1.y};
+                    f32x2 x3 = {__uint_as_float(o4.w << 16) + n1.z, __uint_as_float(o4.w & 0xffff0000u) + n1.w};
+                    pk.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(x0, bf16x2));
+                    pk.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(x1, bf16x2));
+                    pk.z = __builtin_bit_cast(uint32_t, __builtin_convertvector(x2, bf16x2));
+                    pk.w = __builtin_bit_cast(uint32_t, __builtin_convertvector(x3, bf16x2));
+                }
+                const int row = rb + lrow;
+                if (row < N) *reinterpret_cast<uint4 *>(oh + (size_t)row * D + h * 64 + c8 * 8) = pk;
+            }
+            asm volatile("" ::: "memory");
+        }
+    }
+}
+
 hipError_t launch_linear_apply_bf16(const ApplyArgs &a, hipStream_t st)
 {
+    if (a.D == 128) {
+        // one workgroup of 8 waves per CU (64 KB of state fragments + 8 x 8 KB of staging), about two
+        // workgroup-sized row ranges per CU; 256 rows per pass of a workgroup
+        long long rows = ((long long)a.N * a.BH + 511) / 512;
+        int rows_per_wg = (int)((rows + 255) / 256) * 256;
+        if (rows_per_wg < 256) rows_per_wg = 256;
+        dim3 grid((a.N + rows_per_wg - 1) / rows_per_wg, a.BH), block(512);
+        constexpr int lds = 2 * 128 * 128 * 2 + 1024 + 8 * 8192;
+        static bool attr_done = false;
+        if (!attr_done) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(linear_apply128_kernel<false>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+            if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void *>(linear_apply128_kernel<true>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+            if (e != hipSuccess) return e;
+            attr_done = true;
+        }
+        if (a.o_linear_dbg) hipLaunchKernelGGL(linear_apply128_kernel<true>, grid, block, lds, st, a, rows_per_wg);
+        else hipLaunchKernelGGL(linear_apply128_kernel<false>, grid, block, lds, st, a, rows_per_wg);
+        return hipGetLastError();
+    }
     // rows per workgroup (a multiple of 128): about two workgroups per CU, so that the 2*d*d*2 bytes of
     // state fragments staged in LDS are reused over many rows
     long long rows = ((long long)a.N * a.BH + 511) / 512;
     int rows_per_wg = (int)((rows + 127) / 128) * 128;
     if (rows_per_wg < 128) rows_per_wg = 128;
     dim3 grid((a.N + rows_per_wg - 1) / rows_per_wg, a.BH), block(256);
-    if (a.D == 128) hipLaunchKernelGGL(linear_apply_kernel<128>, grid, block, 0, st, a, rows_per_wg);
-    else hipLaunchKernelGGL(linear_apply_kernel<64>, grid, block, 0, st, a, rows_per_wg);
+    hipLaunchKernelGGL(linear_apply_kernel<64>, grid, block, 0, st, a, rows_per_wg);
     return hipGetLastError();
 }
 
