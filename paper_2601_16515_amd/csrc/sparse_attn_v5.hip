@@ -2,13 +2,13 @@
 // d = 128.  Large tile, deep LDS prefetch, ping-pong wave groups.
 //
 //   * One workgroup = 8 waves = 256 query positions = 4 CSR rows of one (batch, head); one workgroup
-//     per CU (LDS: up to 10 K/V tiles of 16 KB plus the block list).
+//     per CU (LDS: 4 K + 5 V tiles of 16 KB plus the block list).
 //   * The ascending union of the 4 rows' kept-block lists is built once per workgroup in LDS (bitmap +
 //     ballot compaction), each entry carrying a 4-bit "kept by query block i" mask.  The main loop
 //     reads one entry per iteration from LDS; no global or scalar load sits on its critical path.
 //   * K and V tiles go straight from global memory into a ring of LDS slots PD blocks ahead of their
-//     use (global_load_lds_dwordx4, bank swizzle applied on the global side).  The wait before the
-//     per-block barrier is counted (s_waitcnt vmcnt(n)), so PD blocks of loads stay in flight and
+//     use, PD = 3 (global_load_lds_dwordx4, bank swizzle applied on the global side).  The wait before the
+//     per-block barrier is counted (s_waitcnt vmcnt(n)), so PD - 1 blocks of loads stay in flight and
 //     L2 / fabric latency is covered without a second resident workgroup.
 //   * Ping-pong: waves 0-3 (group 0) and 4-7 (group 1) share the 4 SIMDs pairwise.  Per KV block a wave
 //     has a matrix part (O += V^T P of the previous block, S = K Q^T of the current one: 32 MFMAs) and a
@@ -182,10 +182,13 @@ hipError_t launch_tile_lists(const int32_t *row_ptr, const int32_t *col_idx, int
     return hipGetLastError();
 }
 
-// PD: prefetch distance in KV blocks; NSLOT = PD + 2 ring slots for K and for V.
+// PD: prefetch distance in KV blocks.  K(b) is read in iteration b only, V(b) also in iteration b+1: the K ring
+// has PD + 1 slots, the V ring PD + 2.
 // SKIP (development builds only, -DSALAD_DIAG): bit 0 drops the softmax stage, 1 the S product, 2 the PV
 // product, 3 the K/V loads; 4 adds a barrier between the two phases of an iteration, 5 records timestamps, 6 raises the
-// priority of the vector phase, 7 of the matrix phase, 8 recomputes the row maximum for every block.
+// priority of the vector phase, 7 of the matrix phase, 8 recomputes the row maximum for every block, 9 drops
+// the per-block barrier (timing only: results are wrong), 10 always fetches block 0, 11 keeps the prefetch's
+// address arithmetic but not its loads.
 template <int PD, bool DBG, int SKIP>
 __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int ntiles, int total, int per_xcd, int list_cap, long long *trace, int trace_block)
 {
@@ -193,11 +196,11 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
     constexpr bool DIAG = (SKIP & 32) != 0;
     constexpr int D = 128, NS = 8, NDT = 4;
     constexpr int TILE = 64 * D;                 // elements
-    constexpr int NSLOT = PD + 2;
+    constexpr int NK = PD + 1, NV = PD + 2;
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
-    u16 *Kb = reinterpret_cast<u16 *>(smem);                       // NSLOT tiles
-    u16 *Vb = Kb + NSLOT * TILE;                                    // NSLOT tiles
-    uint32_t *blist = reinterpret_cast<uint32_t *>(Vb + NSLOT * TILE);   // [list_cap] union list: blk | mask << 24
+    u16 *Kb = reinterpret_cast<u16 *>(smem);                       // NK tiles
+    u16 *Vb = Kb + NK * TILE;                                       // NV tiles
+    uint32_t *blist = reinterpret_cast<uint32_t *>(Vb + NV * TILE);      // [list_cap] union list: blk | mask << 24
 
     const int g = blockIdx.x;
     const int L = (g & 7) * per_xcd + (g >> 3);
@@ -258,17 +261,21 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
     const unsigned wave_u = (unsigned)__builtin_amdgcn_readfirstlane(wave);
     const unsigned k_lds0 = lds_addr_of(Kb) + wave_u * 1024u;
     const unsigned v_lds0 = lds_addr_of(Vb) + wave_u * 1024u;
-    auto fetch = [&](int blk, int slot) INL {
+    auto fetch = [&](int blk, int kslot, int vslot) INL {
         if (skip & 1024) blk = 0;      // development: always the same (cached) block
-        const unsigned kl = k_lds0 + (unsigned)slot * (unsigned)(TILE * 2);
-        const unsigned vl = v_lds0 + (unsigned)slot * (unsigned)(TILE * 2);
+        const unsigned kl = k_lds0 + (unsigned)kslot * (unsigned)(TILE * 2);
+        const unsigned vl = v_lds0 + (unsigned)vslot * (unsigned)(TILE * 2);
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             int p = blk * 64 + i * 32 + lr;
             p = p < N ? p : N - 1;
             const unsigned row_b = (unsigned)row_of_position5(kind, p, T, HW, magic) * (unsigned)(D * 2);
-            lds_dma16_base(kb, row_b + kchunk_b, kl + i * 8192u);
-            lds_dma16_base(vb, row_b + vchunk_b, vl + i * 8192u);
+            if (skip & 2048) {       // development: the address arithmetic without the loads
+                asm volatile("" : : "v"(row_b + kchunk_b), "s"(kl + i * 8192u), "v"(row_b + vchunk_b), "s"(vl + i * 8192u));
+            } else {
+                lds_dma16_base(kb, row_b + kchunk_b, kl + i * 8192u);
+                lds_dma16_base(vb, row_b + vchunk_b, vl + i * 8192u);
+            }
         }
     };
     // list entries travel in a vector register (lane l holds entry 64 c + l of the current 64-entry
@@ -427,19 +434,19 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
     };
 
     // ---- main loop over the union list.  Iteration j: S(j) and softmax(j), PV(j-1); fetch block j+PD.
-    // Block b lives in ring slot b % NSLOT of both rings (K(b) is read in iteration b, V(b) in b+1).
+    // Block b lives in slot b % NK of the K ring and b % NV of the V ring.
     // The fetch of block j+PD is issued from each group's vector phase, where its address arithmetic
-    // runs under the other group's MFMAs; slot (j+PD) % NSLOT was last read in iteration j-1.
+    // runs under the other group's MFMAs; the slots it goes to were last read in iteration j-1.
     STAMP(1);
     if (n > 0) {
 #pragma unroll
         for (int b = 0; b < PD; ++b)
-            if (b < n && !(skip & 8)) fetch((int)(entry(b) & 0xffffffu), b);
+            if (b < n && !(skip & 8)) fetch((int)(entry(b) & 0xffffffu), b, b);
         uint32_t e_prev = 0u;
         uint32_t eq[PD];                          // eq[i] = entry j + i
 #pragma unroll
         for (int b = 0; b < PD; ++b) eq[b] = b < n ? entry(b) : 0u;
-        int slot_cur = 0;                         // j % NSLOT
+        int kslot = 0, vslot = 0;                 // j % NK, j % NV
         for (int j = 0; j < n; ++j) {
             // all fetches up to block j must have landed; newer ones may stay in flight
             {
@@ -461,14 +468,15 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
                 e_f = entry(jf);
             }
             const bool do_fetch = jf < n && !(skip & 8);
-            int slot_f = slot_cur + PD; if (slot_f >= NSLOT) slot_f -= NSLOT;
-            int slot_prev = slot_cur - 1; if (slot_prev < 0) slot_prev += NSLOT;
+            int kslot_f = kslot + PD; if (kslot_f >= NK) kslot_f -= NK;
+            int vslot_f = vslot + PD; if (vslot_f >= NV) vslot_f -= NV;
+            int vslot_prev = vslot - 1; if (vslot_prev < 0) vslot_prev += NV;
             const uint32_t e_cur = eq[0];
             const bool kS = (e_cur & mybit) != 0, kP = (j >= 1) && (e_prev & mybit);
             const bool dS = kS && !(skip & 2), dP = kP && !(skip & 4), dM0 = kS, dM1 = kP;
-            const u16 *Kt = Kb + slot_cur * TILE;
-            const u16 *Vt = Vb + slot_prev * TILE;
-            const u16 *Vc = Vb + slot_cur * TILE;      // V tile of block j (already landed with K(j))
+            const u16 *Kt = Kb + kslot * TILE;
+            const u16 *Vt = Vb + vslot_prev * TILE;
+            const u16 *Vc = Vb + vslot * TILE;         // V tile of block j (already landed with K(j))
             if (group == 0) {
                 if (skip & 128) __builtin_amdgcn_s_setprio(2);
                 if (dP && dS) stage_PV_S(Vt, Kt);
@@ -482,14 +490,14 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
                 if (dS) preload_V(Vc);                  // for PV(j) in the next iteration; lands under the softmax
                 if (dM0) stage_softmax((int)(e_cur & 0xffffffu));
                 TSTAMP(3);
-                if (do_fetch) fetch((int)(e_f & 0xffffffu), slot_f);
+                if (do_fetch) fetch((int)(e_f & 0xffffffu), kslot_f, vslot_f);
                 if (skip & 64) __builtin_amdgcn_s_setprio(0);
             } else {
                 if (skip & 64) __builtin_amdgcn_s_setprio(3);
                 if (dP) preload_V(Vt);                  // for PV(j-1) right after the barrier; lands under the softmax
                 if (dM1) stage_softmax((int)(e_prev & 0xffffffu));
                 TSTAMP(1);
-                if (do_fetch) fetch((int)(e_f & 0xffffffu), slot_f);
+                if (do_fetch) fetch((int)(e_f & 0xffffffu), kslot_f, vslot_f);
                 if (skip & 64) __builtin_amdgcn_s_setprio(0);
                 if (skip & 16) __builtin_amdgcn_s_barrier();
                 asm volatile("" ::: "memory");
@@ -504,7 +512,8 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
 #pragma unroll
             for (int b = 0; b + 1 < PD; ++b) eq[b] = eq[b + 1];
             eq[PD - 1] = e_f;
-            ++slot_cur; if (slot_cur >= NSLOT) slot_cur = 0;
+            ++kslot; if (kslot >= NK) kslot = 0;
+            ++vslot; if (vslot >= NV) vslot = 0;
         }
         // tail: the PV product of the last block (group 1 still owes its softmax).  The K ring is idle
         // from here on, so the epilogue's state fragments are fetched into it under these MFMAs.
@@ -513,8 +522,8 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
         asm volatile("" ::: "memory");
         if (lin) stage_state();
         {
-            int slot_prev = slot_cur - 1; if (slot_prev < 0) slot_prev += NSLOT;
-            const u16 *Vt = Vb + slot_prev * TILE;
+            int vslot_prev = vslot - 1; if (vslot_prev < 0) vslot_prev += NV;
+            const u16 *Vt = Vb + vslot_prev * TILE;
             const bool kP = (e_prev & mybit) != 0;
             if (group == 1 && kP) { preload_V(Vt); stage_softmax((int)(e_prev & 0xffffffu)); }
             if (kP && !(skip & 4)) stage_PV(Vt);
@@ -610,7 +619,8 @@ static hipError_t launch_v5(const AttnArgs &a, hipStream_t st)
     const int total = a.B * a.H * ntiles;
     const int per_xcd = (total + 7) / 8;
     const int list_cap = (a.nb + 63) & ~63;
-    const size_t lds = (size_t)(PD + 2) * 2 * 64 * 128 * 2 + (size_t)list_cap * 4;
+    const size_t lds = (size_t)(2 * PD + 3) * 64 * 128 * 2 + (size_t)list_cap * 4;
+    static_assert(PD + 1 >= 4, "the epilogue stages 64 KB of state fragments in the K ring");
     constexpr int kMaxDyn = 160 * 1024 - 2048;   // the static part is rounded up to its 1 KB alignment
     if (lds > (size_t)kMaxDyn) return hipErrorInvalidValue;
     auto kern = sparse_attn_v5_kernel<PD, DBG, SKIP>;
@@ -630,14 +640,14 @@ hipError_t launch_sparse_attn_v5(const AttnArgs &a, hipStream_t st)
 #ifdef SALAD_DIAG
     switch (g_attn_variant >> 4) {
     case 0: break;
-#define SALAD_DIAG_CASE(k) case k: return launch_v5<2, false, k>(a, st);
+#define SALAD_DIAG_CASE(k) case k: return launch_v5<3, false, k>(a, st);
     SALAD_DIAG_CASE(1) SALAD_DIAG_CASE(6) SALAD_DIAG_CASE(7) SALAD_DIAG_CASE(8) SALAD_DIAG_CASE(9) SALAD_DIAG_CASE(14)
-    SALAD_DIAG_CASE(15) SALAD_DIAG_CASE(16) SALAD_DIAG_CASE(32) SALAD_DIAG_CASE(33) SALAD_DIAG_CASE(47) SALAD_DIAG_CASE(64) SALAD_DIAG_CASE(96) SALAD_DIAG_CASE(192) SALAD_DIAG_CASE(224) SALAD_DIAG_CASE(256) SALAD_DIAG_CASE(80) SALAD_DIAG_CASE(512) SALAD_DIAG_CASE(520) SALAD_DIAG_CASE(513) SALAD_DIAG_CASE(1024)
+    SALAD_DIAG_CASE(15) SALAD_DIAG_CASE(16) SALAD_DIAG_CASE(32) SALAD_DIAG_CASE(33) SALAD_DIAG_CASE(47) SALAD_DIAG_CASE(64) SALAD_DIAG_CASE(96) SALAD_DIAG_CASE(192) SALAD_DIAG_CASE(224) SALAD_DIAG_CASE(256) SALAD_DIAG_CASE(80) SALAD_DIAG_CASE(512) SALAD_DIAG_CASE(520) SALAD_DIAG_CASE(513) SALAD_DIAG_CASE(1024) SALAD_DIAG_CASE(2048)
 #undef SALAD_DIAG_CASE
     default: return hipErrorInvalidValue;
     }
 #endif
-    return dbg ? launch_v5<2, true, 0>(a, st) : launch_v5<2, false, 0>(a, st);
+    return dbg ? launch_v5<3, true, 0>(a, st) : launch_v5<3, false, 0>(a, st);
 }
 
 }  // namespace salad
