@@ -138,7 +138,7 @@ def main():
         "roofline": {"bound": "mfma", "achieved": flops / (attn_ms * 1e-3) * 1e-12, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": flops / (attn_ms * 1e-3) * 1e-12 / PEAK_BF16_TFLOPS,
                      "traffic": measured_attn_traffic() if args.sparsity is None else None,
-                     "kernel": "sparse_attn_v5_kernel<2> (+ tile_lists_kernel pre-pass)", "kernel_ms": attn_ms},
+                     "kernel": "sparse_attn_v5_kernel<3> (+ tile_lists_kernel pre-pass)", "kernel_ms": attn_ms},
         "kernels_ms": {"gate": gate_ms, "linear_state": state_ms, "finalize": fin_ms, "sparse_attn_fused": attn_ms},
         "hbm_kernels": {
             "linear_state": {"bytes": kv_bytes, "GB/s": kv_bytes / (state_ms * 1e-3) * 1e-9, "frac_of_8TB/s": kv_bytes / (state_ms * 1e-3) * 1e-9 / PEAK_HBM_GBS},

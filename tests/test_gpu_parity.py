@@ -254,6 +254,24 @@ def test_unfused_epilogue_matches(oracle):
     compare_layer(res, ref, label="unfused")
 
 
+@pytest.mark.parametrize("variant", [1, 2], ids=["128-row-fallback", "first-generation"])
+def test_fallback_attention_kernels(oracle, variant):
+    """The d=128 kernels that serve as fallbacks (block list too long for LDS, huge N, inexact division)
+    produce the same layer within the same tolerances; selected here through the tuning knob."""
+    w = SMALL[7]                                      # five tiles of 4 query blocks, ragged tail, 3 heads
+    inp = wl.make_inputs(w)
+    dev = upload(w, inp)
+    kinds = wl.head_kinds(w)
+    kept = [4, 5, 4]
+    ref = _oracle_layer(oracle, w, inp, kept, kinds)
+    sb.salad_tune("attn_variant", variant)
+    try:
+        res = run_layer(w, inp, dev, kept, kinds)
+    finally:
+        sb.salad_tune("attn_variant", 0)
+    compare_layer(res, ref, label=f"variant{variant}")
+
+
 def test_run_to_run_bit_reproducible():
     w = SMALL[1]
     inp = wl.make_inputs(w)
