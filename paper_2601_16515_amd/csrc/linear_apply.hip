@@ -260,13 +260,10 @@ hipError_t launch_linear_apply_bf16(const ApplyArgs &a, hipStream_t st)
         if (rows_per_wg < 256) rows_per_wg = 256;
         dim3 grid((a.N + rows_per_wg - 1) / rows_per_wg, a.BH), block(512);
         constexpr int lds = 2 * 128 * 128 * 2 + 1024 + 8 * 8192;
-        static bool attr_done = false;
-        if (!attr_done) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(linear_apply128_kernel<false>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-            if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void *>(linear_apply128_kernel<true>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-            if (e != hipSuccess) return e;
-            attr_done = true;
-        }
+        static bool done_plain[16] = {}, done_dbg[16] = {};
+        hipError_t e = a.o_linear_dbg ? dyn_lds_attr_once(reinterpret_cast<const void *>(linear_apply128_kernel<true>), lds, done_dbg)
+                                      : dyn_lds_attr_once(reinterpret_cast<const void *>(linear_apply128_kernel<false>), lds, done_plain);
+        if (e != hipSuccess) return e;
         if (a.o_linear_dbg) hipLaunchKernelGGL(linear_apply128_kernel<true>, grid, block, lds, st, a, rows_per_wg);
         else hipLaunchKernelGGL(linear_apply128_kernel<false>, grid, block, lds, st, a, rows_per_wg);
         return hipGetLastError();

@@ -376,12 +376,14 @@ salad_status salad_timing_read(salad_kernel_times *out, int32_t reset)
     return SALAD_OK;
 }
 
-/* Development aid, not declared in the public header: timestamps of one workgroup's phases. */
+#ifdef SALAD_DIAG
+/* Development builds only, not declared in the public header: timestamps of one workgroup's phases. */
 void salad_debug_set_trace(void *ptr, int block)
 {
     g_trace_ptr = (long long *)ptr;
     g_trace_block = block;
 }
+#endif
 
 /* Tuning knobs for experiments; not part of the documented layer semantics.
  * "state_wgs": target number of workgroups of the linear-state kernel (changes the workspace size). */

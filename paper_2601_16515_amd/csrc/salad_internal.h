@@ -91,6 +91,19 @@ struct ApplyArgs {
 };
 hipError_t launch_linear_apply_bf16(const ApplyArgs &a, hipStream_t st);
 
+// Raises a kernel's dynamic-LDS limit once per device (`done` is the caller's per-kernel flag array).
+inline hipError_t dyn_lds_attr_once(const void *kernel, int bytes, bool (&done)[16])
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 16) return hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (done[dev]) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess) done[dev] = true;
+    return e;
+}
+
 // tuning knobs (salad_tune)
 extern int g_state_target_wgs;
 extern int g_gate_parts, g_gate_tok;

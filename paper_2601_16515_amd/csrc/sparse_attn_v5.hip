@@ -624,12 +624,8 @@ static hipError_t launch_v5(const AttnArgs &a, hipStream_t st)
     constexpr int kMaxDyn = 160 * 1024 - 2048;   // the static part is rounded up to its 1 KB alignment
     if (lds > (size_t)kMaxDyn) return hipErrorInvalidValue;
     auto kern = sparse_attn_v5_kernel<PD, DBG, SKIP>;
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDyn);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    static bool attr_done[16] = {};
+    if (hipError_t e = dyn_lds_attr_once(reinterpret_cast<const void *>(kern), kMaxDyn, attr_done); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(512), lds, st, a, ntiles, total, per_xcd, list_cap, g_trace_ptr, g_trace_block);
     return hipGetLastError();
 }
