@@ -281,6 +281,34 @@ def test_run_to_run_bit_reproducible():
     assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
 
 
+def test_layer_call_under_graph_capture():
+    """The layer call allocates nothing and never synchronises, so it can be captured into a HIP graph.
+    Replays (with eager work and synchronisation in between) give the bits of the eager call."""
+    w = SMALL[7]
+    inp = wl.make_inputs(w)
+    dev = upload(w, inp)
+    kinds = wl.head_kinds(w)
+    kept = [4, 5, 4]
+    eager = run_layer(w, inp, dev, kept, kinds, dbg=False)["out_t"].clone()
+    grid = (w.T, w.Hh, w.W)
+    row_ptr, col_idx = sb.salad_block_mask(*grid, w.block, kept)
+    q, k, v = dev["q"], dev["k"], dev["v"]
+    out = torch.zeros_like(q)
+    ws = sb.Workspace(w.B, w.H, w.N, w.d, sb.SALAD_BF16, q.device)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        p, keep = sb.make_fwd_params(q, k, v, out, grid, row_ptr, col_idx, kinds, lam=w.lam, head_scale=dev["head_scale"],
+                                     x_t=dev["x_t"], w_gate=dev["w_gate"], eps=w.eps, workspace=ws)
+        sb.salad_fwd_call(p)
+    for rep in range(3):
+        out.fill_(float("nan"))                      # eager work between replays
+        (dev["x_t"].float().sum()).item()            # ... and a synchronisation
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), f"replay {rep} differs from the eager call"
+
+
 # ------------------------------------------------------------------- benchmark configurations
 
 def _sampled_parity(oracle, w, nsel, label):
