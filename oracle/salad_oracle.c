@@ -19,6 +19,8 @@
  *                             grouped by spatial location so that frames are consecutive)
  *   ReLU linear attention     Sec. 3 "Linear Attention", Eq. (3)
  *   static and dynamic scale  Alg. 1 (Level 1 / Level 2 / residual integration), Sec. 4.2
+ *   branch dropping           Sec. 4.3, App. A.3 (the linear branch of a sample is pruned when its
+ *                             dynamic scale lies below the threshold)
  *
  * Readings where the paper is silent (all listed in the design notes of the repository):
  *   - the sliding window keeps a constant count of `kept` consecutive KV blocks per query
@@ -27,7 +29,9 @@
  *   - the linear-attention denominator is (phi(Q_i).Z + eps);
  *   - the static projection is the per-layer scalar lambda times a per-head scalar a_h;
  *   - the gate is Linear: D -> 1 without learned bias (a test-only scalar bias is accepted),
- *     sigmoid per token, then the mean over tokens.
+ *     sigmoid per token, then the mean over tokens;
+ *   - "below the threshold" is the strict inequality s_b < tau; a dropped branch contributes
+ *     exactly nothing (out = O_s), and tau <= 0 never drops since s_b > 0.
  *
  * Parity pins (tests/test_oracle_*.py): dense attention from a library routine, uniform
  * weights for Q = 0, the quadratic form (phi(Q)phi(K)^T)V, closed forms for the gate and the
@@ -295,6 +299,14 @@ int salad_oracle_gate(const float *x, const float *w, double bias, int B, int64_
 }
 
 /* ---- residual integration, Alg. 1 last block; Eq. (lambda scale), Sec. 4.2 ------------ */
+
+/* Post-tuning branch dropping, Sec. 4.3: dropped[b] = 1 when the sample's dynamic scale is below the
+ * threshold.  The comparison is made on the float32 value of s, the precision the device holds it in. */
+int salad_oracle_branch_drop(const double *s, int B, double tau, int *dropped)
+{
+    for (int b = 0; b < B; ++b) dropped[b] = ((float)s[b] < (float)tau) ? 1 : 0;
+    return SO_OK;
+}
 
 /* out = O_s + lambda * a[h] * s[b] * O_l on compact row sets of shape [B, H, nrows, d]. */
 int salad_oracle_combine(const double *o_s, const double *o_l, int B, int H, int64_t nrows, int d,

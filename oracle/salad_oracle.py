@@ -162,8 +162,16 @@ def combine(o_s, o_l, lam: float, head_scale, s) -> np.ndarray:
     return out
 
 
+def branch_drop(s, tau: float) -> np.ndarray:
+    """Sec. 4.3: which samples' linear branches are pruned (dynamic scale below the threshold)."""
+    s = np.ascontiguousarray(s, dtype=np.float64)
+    dropped = np.zeros(s.shape[0], dtype=np.int32)
+    _load().salad_oracle_branch_drop(_p(s), C.c_int(s.shape[0]), C.c_double(tau), _p(dropped))
+    return dropped
+
+
 def salad_forward(q, k, v, x_t, w_gate, head_scale, grid, block, head_kind, kept, lam=1.0, eps=1e-6,
-                  b_gate=0.0, scale=None, sel=None, s_override=None) -> Dict[str, np.ndarray]:
+                  b_gate=0.0, scale=None, sel=None, s_override=None, drop_threshold=0.0) -> Dict[str, np.ndarray]:
     """Whole layer (Alg. 1 from SparseAttn to the residual sum) on the selected query blocks.
 
     Returns compact row sets [B,H,nsel*block,d] for o_sparse, o_linear and out, the stored row
@@ -174,6 +182,8 @@ def salad_forward(q, k, v, x_t, w_gate, head_scale, grid, block, head_kind, kept
     Hs, Z = linear_state(k, v)
     o_l = linear_apply(q, Hs, Z, eps, rows)
     s = gate(x_t, w_gate, b_gate) if s_override is None else np.asarray(s_override, dtype=np.float64)
-    out = combine(o_s, o_l, lam, head_scale, s)
+    dropped = branch_drop(s, drop_threshold)
+    # a pruned branch contributes exactly nothing: its samples are combined with a zero dynamic scale
+    out = combine(o_s, o_l, lam, head_scale, np.where(dropped != 0, 0.0, s))
     return {"o_sparse": o_s, "o_linear": o_l, "out": out, "rows": rows, "Hs": Hs, "Z": Z, "s": s,
-            "row_ptr": row_ptr, "col_idx": col_idx}
+            "row_ptr": row_ptr, "col_idx": col_idx, "dropped": dropped}

@@ -257,6 +257,43 @@ def test_combination_closed_forms(oracle):
     assert np.abs(r["s"] - oracle.gate(inp["x_t"], inp["w_gate"])).max() == 0.0
 
 
+# ---------------------------------------------------------------- branch dropping, Sec. 4.3
+
+def test_branch_dropping(oracle):
+    """A sample whose dynamic scale lies below the threshold loses its linear branch entirely; the others
+    are untouched.  Strict inequality; a threshold of 0 never drops (the scale is a mean of sigmoids > 0)."""
+    w = wl.small("drop", 3, 2, 16, 2, 6, 7, "f32", 0.5, seed=43, block=16)
+    inp = wl.make_inputs(w)
+    # per-sample offsets push the three gates apart
+    x = inp["x_t"].copy()
+    wg = inp["w_gate"]
+    x[0] += 40.0 * wg / np.dot(wg, wg) * 0.05
+    x[2] -= 40.0 * wg / np.dot(wg, wg) * 0.05
+    kw = dict(grid=(w.T, w.Hh, w.W), block=w.block, head_kind=[0, 1], kept=[3, 3], lam=0.9)
+    args = (inp["q"], inp["k"], inp["v"], x, wg, inp["head_scale"])
+    base = oracle.salad_forward(*args, **kw)
+    s = base["s"]
+    assert s[2] < s[1] < s[0] and s[0] - s[2] > 0.05
+    assert not base["dropped"].any() and np.array_equal(oracle.salad_forward(*args, drop_threshold=0.0, **kw)["out"], base["out"])
+    # threshold between the two smallest scales: only sample 2 is pruned
+    tau = 0.5 * (s[1] + s[2])
+    r = oracle.salad_forward(*args, drop_threshold=tau, **kw)
+    assert r["dropped"].tolist() == [0, 0, 1]
+    assert np.array_equal(r["out"][2], r["o_sparse"][2])                    # exactly the sparse branch
+    assert np.array_equal(r["out"][:2], base["out"][:2])                    # the others unchanged
+    assert np.abs(base["out"][2] - base["o_sparse"][2]).max() > 1e-3        # and the branch did matter
+    # above every scale: all pruned; the reported scale itself is not altered
+    r = oracle.salad_forward(*args, drop_threshold=1.5, **kw)
+    assert r["dropped"].all() and np.array_equal(r["out"], r["o_sparse"]) and np.array_equal(r["s"], s)
+    # strict inequality, decided on the float32 value of the scale
+    s32 = float(np.float32(s[1]))
+    assert oracle.branch_drop(s, s32).tolist() == [0, 0, 1]
+    assert oracle.branch_drop(s, float(np.nextafter(np.float32(s32), np.float32(2.0)))).tolist() == [0, 1, 1]
+    # monotone in the threshold
+    counts = [int(oracle.branch_drop(s, t).sum()) for t in np.linspace(0.0, 1.0, 21)]
+    assert counts == sorted(counts) and counts[0] == 0 and counts[-1] == 3
+
+
 def test_tiny_config_runs_in_seconds(oracle):
     """The smallest benchmark configuration end to end (B=1, H=2, d=64, grid 4x16x16)."""
     import time
