@@ -102,6 +102,9 @@ typedef struct salad_fwd_params {
     size_t workspace_bytes;
     int32_t flags;            /* SALAD_FLAG_* */
     void *hip_stream;
+    float drop_threshold;     /* post-tuning branch dropping (Sec. 4.3): tau_t; <= 0 disables         */
+    int32_t *dropped_out;     /* optional device int32 [B]: 1 where the linear branch was pruned, else 0;
+                                 written only when dropping is active (lambda != 0, drop_threshold > 0)  */
 } salad_fwd_params;
 
 /* Run the linear apply and the scale-and-sum as a separate streaming kernel after the sparse
@@ -118,6 +121,10 @@ size_t salad_fwd_workspace_bytes(const salad_fwd_params *p);
  *   s_b = mean_n sigmoid(x_t[b,n,:].w_gate + b_gate)                             (Level 2)
  *   out = O_s + lambda * a_h * s_b * O_l                (Level 1 in per-head form + residual)
  * With lambda == 0 the linear branch is skipped and out is the sparse branch alone.
+ * Post-tuning branch dropping (Sec. 4.3, App. A.3): with drop_threshold = tau > 0, a sample whose dynamic
+ * scale s_b < tau (strict, compared in fp32) loses its linear branch: out[b] = O_s[b], exactly as with
+ * lambda == 0.  The decision is taken on the device (no host synchronisation): the gate is reduced first,
+ * and the state, reduce and apply kernels skip the pruned samples, so their K, V are not read again.
  * bf16: MFMA kernels, fp32 accumulation, one round-to-nearest-even of the sum to bf16.
  * fp32: plain fp32 kernels intended for small shapes. */
 salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p);

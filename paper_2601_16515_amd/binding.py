@@ -59,6 +59,8 @@ class FwdParams(C.Structure):
         ("workspace_bytes", C.c_size_t),
         ("flags", C.c_int32),
         ("hip_stream", C.c_void_p),
+        ("drop_threshold", C.c_float),
+        ("dropped_out", C.c_void_p),
     ]
 
 
@@ -188,7 +190,8 @@ class Workspace:
 def make_fwd_params(q, k, v, out, grid: Tuple[int, int, int], row_ptr, col_idx, head_kind=None, *,
                     lam: float = 1.0, head_scale=None, s=None, x_t=None, w_gate=None, b_gate: float = 0.0,
                     eps: float = 1e-6, softmax_scale: float = 0.0, s_out=None, o_sparse_dbg=None,
-                    o_linear_dbg=None, workspace: Optional[Workspace] = None, flags: int = 0, block: int = 64):
+                    o_linear_dbg=None, workspace: Optional[Workspace] = None, flags: int = 0, block: int = 64,
+                    drop_threshold: float = 0.0, dropped_out=None):
     """Fill a salad_fwd_params from torch tensors.  Returns (params, keepalive)."""
     B, H, N, d = q.shape
     p = FwdParams()
@@ -219,6 +222,8 @@ def make_fwd_params(q, k, v, out, grid: Tuple[int, int, int], row_ptr, col_idx, 
         p.workspace_bytes = workspace.bytes
     p.flags = flags
     p.hip_stream = _stream()
+    p.drop_threshold = drop_threshold
+    p.dropped_out = _ptr(dropped_out)
     return p, (hk, workspace)
 
 

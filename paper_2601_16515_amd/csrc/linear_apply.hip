@@ -31,6 +31,7 @@ __global__ __launch_bounds__(256) void linear_apply_kernel(ApplyArgs a, int rows
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hh = lane >> 5;
     const int bh = blockIdx.y;
+    if (a.drop && a.drop[bh / a.H]) return;            // pruned sample (Sec. 4.3): out already holds O_s
     {   // fragments are lane-linear in memory: copy as is (16 bytes per lane per load)
         const u16 *hf = a.hfrag + (size_t)bh * 2 * D * D;
         constexpr int LOADS = 2 * D * D / 8 / 256;
@@ -129,6 +130,7 @@ __global__ __launch_bounds__(512) void linear_apply128_kernel(ApplyArgs a, int r
     unsigned char *stage = smem + 2 * D * D * 2 + 1024 + wave * 8192;             // wave-private, 8 KB
     const int l32 = lane & 31, hh = lane >> 5;
     const int bh = blockIdx.y;
+    if (a.drop && a.drop[bh / a.H]) return;            // pruned sample (Sec. 4.3): out already holds O_s
     {   // fragments are lane-linear in memory: copy as is (16 bytes per lane per load)
         const u16 *hf = a.hfrag + (size_t)bh * 2 * D * D;
 #pragma unroll

@@ -60,8 +60,10 @@ template <int D>
 __global__ __launch_bounds__(256, 2) void state_partial_kernel(const u16 *__restrict__ k,
                                                                const u16 *__restrict__ v, int N,
                                                                int tiles_per_chunk, int P,
-                                                               float *__restrict__ partial)
+                                                               float *__restrict__ partial,
+                                                               const int32_t *__restrict__ drop, int H)
 {
+    if (drop && drop[blockIdx.y / H]) return;          // pruned sample (Sec. 4.3): K, V are not read
     constexpr int CH = D / 8;          // 16-byte chunks per row
     constexpr int TPT = D / 32;        // tokens per thread per tile (4 for d=128, 2 for d=64)
     constexpr int QT = D / 64;         // 32x32 tiles per side of a wave's quadrant
@@ -200,15 +202,15 @@ __global__ __launch_bounds__(256, 2) void state_partial_kernel(const u16 *__rest
 }
 
 hipError_t launch_state_partial_bf16(const u16 *k, const u16 *v, int BH, int N, int D,
-                                     float *partial, hipStream_t st)
+                                     float *partial, const int32_t *drop, int H, hipStream_t st)
 {
     int tpc = state_tiles_per_chunk(BH, N);
     int P = state_num_chunks(BH, N);
     dim3 grid(P, BH), block(256);
     if (D == 128)
-        hipLaunchKernelGGL(state_partial_kernel<128>, grid, block, 0, st, k, v, N, tpc, P, partial);
+        hipLaunchKernelGGL(state_partial_kernel<128>, grid, block, 0, st, k, v, N, tpc, P, partial, drop, H);
     else
-        hipLaunchKernelGGL(state_partial_kernel<64>, grid, block, 0, st, k, v, N, tpc, P, partial);
+        hipLaunchKernelGGL(state_partial_kernel<64>, grid, block, 0, st, k, v, N, tpc, P, partial, drop, H);
     return hipGetLastError();
 }
 
@@ -216,9 +218,11 @@ hipError_t launch_state_partial_bf16(const u16 *k, const u16 *v, int BH, int N, 
 // fp32 state for small shapes: one thread per element of Hs, one extra row of threads for Z.
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void state_f32_kernel(const float *__restrict__ k, const float *__restrict__ v,
-                                                        int N, int D, float *__restrict__ Hs, float *__restrict__ Z)
+                                                        int N, int D, float *__restrict__ Hs, float *__restrict__ Z,
+                                                        const int32_t *__restrict__ drop, int H)
 {
     int bh = blockIdx.y;
+    if (drop && drop[bh / H]) return;                  // pruned sample (Sec. 4.3)
     int e = blockIdx.x * 256 + threadIdx.x;
     if (e >= D * D + D) return;
     const float *kb = k + (size_t)bh * N * D;
@@ -237,10 +241,10 @@ __global__ __launch_bounds__(256) void state_f32_kernel(const float *__restrict_
 }
 
 hipError_t launch_state_f32(const float *k, const float *v, int BH, int N, int D, float *Hs, float *Z,
-                            hipStream_t st)
+                            const int32_t *drop, int H, hipStream_t st)
 {
     dim3 grid((D * D + D + 255) / 256, BH), block(256);
-    hipLaunchKernelGGL(state_f32_kernel, grid, block, 0, st, k, v, N, D, Hs, Z);
+    hipLaunchKernelGGL(state_f32_kernel, grid, block, 0, st, k, v, N, D, Hs, Z, drop, H);
     return hipGetLastError();
 }
 

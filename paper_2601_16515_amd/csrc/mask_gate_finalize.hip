@@ -217,6 +217,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(FinalizeArgs a, int state
         // 64 state elements per workgroup; the P partials are split over 4 thread groups (more loads in
         // flight), each group adds its share in chunk order, the 4 sums are added in group order
         const int bh = blockIdx.x / blocks_per_head;
+        if (a.drop && a.drop[bh / a.H]) return;        // pruned sample: its partial states were not computed
         const int le = threadIdx.x & 63, grp = threadIdx.x >> 6;
         const int e = (blockIdx.x - bh * blocks_per_head) * 64 + le;
         const int per = D * D + D;
@@ -267,13 +268,16 @@ __global__ __launch_bounds__(256) void finalize_kernel(FinalizeArgs a, int state
         } else {
             s = a.s_dev[b];
         }
+        const bool dropped = a.drop != nullptr && s < a.tau;      // Sec. 4.3: scale below the threshold
         if (threadIdx.x == 0) {
             a.s_ws[b] = s;
             if (a.s_out) a.s_out[b] = s;
+            if (a.drop) a.drop[b] = dropped ? 1 : 0;
+            if (a.dropped_out) a.dropped_out[b] = dropped ? 1 : 0;
         }
         if (a.coef)
             for (int h = threadIdx.x; h < a.H; h += 256)
-                a.coef[b * a.H + h] = a.lambda * (a.head_scale ? a.head_scale[h] : 1.f) * s;
+                a.coef[b * a.H + h] = dropped ? 0.f : a.lambda * (a.head_scale ? a.head_scale[h] : 1.f) * s;
     }
 }
 

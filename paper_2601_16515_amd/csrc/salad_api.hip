@@ -36,7 +36,7 @@ salad_status hip_fail(hipError_t e, const char *what)
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct WsLayout {
-    size_t gate_partial, state_partial, Hs, Z, hfrag, s, coef, tile_lists, tile_counts, total;
+    size_t gate_partial, state_partial, Hs, Z, hfrag, s, coef, drop, tile_lists, tile_counts, total;
     int nparts, P;
 };
 
@@ -54,6 +54,7 @@ WsLayout ws_layout(int B, int H, int N, int d, int dtype)
     w.hfrag = off; off = align256(off + (dtype == SALAD_BF16 ? sizeof(u16) * BH * 2 * d * d : 0));
     w.s = off; off = align256(off + sizeof(float) * B);
     w.coef = off; off = align256(off + sizeof(float) * BH);
+    w.drop = off; off = align256(off + sizeof(int32_t) * B);
     {   // union lists per (head, 4-block tile) for the large-tile attention kernel
         const int nb = (N + 63) / 64, ntiles = (nb + 3) / 4;
         const bool need = dtype == SALAD_BF16 && d == 128 && (size_t)tile_list_cap(nb) * 4 <= 24 * 1024;
@@ -164,7 +165,7 @@ salad_status salad_linear_state_fwd(const void *k, const void *v, int32_t B, int
     if (!shape_ok(B, H, N, d, dtype)) return fail(SALAD_EINVAL, "salad_linear_state_fwd: unsupported shape B=%d H=%d N=%d d=%d dtype=%d", B, H, N, d, dtype);
     hipStream_t st = (hipStream_t)hip_stream;
     if (dtype == SALAD_F32) {
-        hipError_t e = launch_state_f32((const float *)k, (const float *)v, B * H, N, d, Hs_out, Z_out, st);
+        hipError_t e = launch_state_f32((const float *)k, (const float *)v, B * H, N, d, Hs_out, Z_out, nullptr, H, st);
         if (e != hipSuccess) return hip_fail(e, "state_f32 launch");
         return SALAD_OK;
     }
@@ -172,7 +173,7 @@ salad_status salad_linear_state_fwd(const void *k, const void *v, int32_t B, int
     if (!workspace || ((uintptr_t)workspace & 255)) return fail(SALAD_EINVAL, "salad_linear_state_fwd: workspace null or not 256-byte aligned");
     if (workspace_bytes < w.total) return fail(SALAD_ENOSPC, "salad_linear_state_fwd: workspace %zu < %zu bytes", workspace_bytes, w.total);
     char *ws = (char *)workspace;
-    hipError_t e = launch_state_partial_bf16((const u16 *)k, (const u16 *)v, B * H, N, d, (float *)(ws + w.state_partial), st);
+    hipError_t e = launch_state_partial_bf16((const u16 *)k, (const u16 *)v, B * H, N, d, (float *)(ws + w.state_partial), nullptr, H, st);
     if (e != hipSuccess) return hip_fail(e, "state_partial launch");
     FinalizeArgs f{};
     f.B = B; f.H = H; f.D = d;
@@ -227,6 +228,7 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
     if (!(p->eps >= 0.f)) return fail(SALAD_EINVAL, "fwd: eps must be >= 0");
     if (!(p->softmax_scale >= 0.f) || !std::isfinite(p->softmax_scale)) return fail(SALAD_EINVAL, "fwd: softmax_scale must be finite and >= 0");
     if (!std::isfinite(p->lambda)) return fail(SALAD_EINVAL, "fwd: lambda must be finite");
+    if (std::isnan(p->drop_threshold)) return fail(SALAD_EINVAL, "fwd: drop_threshold must not be NaN");
     const bool use_linear = p->lambda != 0.f;
     const bool need_gate = use_linear && !p->s_dev;
     const int Dm = p->H * p->d;
@@ -271,19 +273,16 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
     ev.has_epilogue = unfused && use_linear;
     auto mark = [&](int i) { if (timing) (void)hipEventRecord(ev.e[i], st); };
 
+    // Post-tuning branch dropping (Sec. 4.3): the dynamic scale has to be known before the state kernel, so the
+    // gate is reduced first (finalize in gate-only form) and the later kernels skip the pruned samples.
+    const bool dropping = use_linear && p->drop_threshold > 0.f;
+    int32_t *drop = dropping ? (int32_t *)(ws + w.drop) : nullptr;
     mark(0);
     if (use_linear) {
         if (need_gate) {
             e = launch_gate_partial(p->x_t, p->w_gate, p->b_gate, p->B, p->N, Dm, bf16, (float *)(ws + w.gate_partial), w.nparts, st);
             if (e != hipSuccess) return hip_fail(e, "gate launch");
         }
-        mark(1);
-        if (bf16)
-            e = launch_state_partial_bf16((const u16 *)p->k, (const u16 *)p->v, BH, p->N, p->d, (float *)(ws + w.state_partial), st);
-        else
-            e = launch_state_f32((const float *)p->k, (const float *)p->v, BH, p->N, p->d, (float *)(ws + w.Hs), (float *)(ws + w.Z), st);
-        if (e != hipSuccess) return hip_fail(e, "state launch");
-        mark(2);
         FinalizeArgs f{};
         f.B = p->B; f.H = p->H; f.D = p->d;
         f.state_partial = (const float *)(ws + w.state_partial); f.P = w.P;
@@ -292,8 +291,25 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
         f.gate_partial = (const float *)(ws + w.gate_partial); f.nparts = need_gate ? w.nparts : 0; f.N = p->N;
         f.s_dev = p->s_dev; f.lambda = p->lambda; f.head_scale = p->head_scale;
         f.s_out = p->s_out; f.s_ws = (float *)(ws + w.s); f.coef = (float *)(ws + w.coef); f.do_gate = 1;
-        e = launch_finalize(f, st);
-        if (e != hipSuccess) return hip_fail(e, "finalize launch");
+        f.tau = p->drop_threshold; f.drop = drop; f.dropped_out = dropping ? p->dropped_out : nullptr;
+        if (dropping) {
+            FinalizeArgs g = f;
+            g.P = 0;                                   // gate part only: s, coefficients, drop flags
+            e = launch_finalize(g, st);
+            if (e != hipSuccess) return hip_fail(e, "gate reduce launch");
+            f.do_gate = 0;
+        }
+        mark(1);
+        if (bf16)
+            e = launch_state_partial_bf16((const u16 *)p->k, (const u16 *)p->v, BH, p->N, p->d, (float *)(ws + w.state_partial), drop, p->H, st);
+        else
+            e = launch_state_f32((const float *)p->k, (const float *)p->v, BH, p->N, p->d, (float *)(ws + w.Hs), (float *)(ws + w.Z), drop, p->H, st);
+        if (e != hipSuccess) return hip_fail(e, "state launch");
+        mark(2);
+        if (bf16 || f.do_gate) {                       // fp32: the state kernel wrote Hs, Z directly
+            e = launch_finalize(f, st);
+            if (e != hipSuccess) return hip_fail(e, "finalize launch");
+        }
     } else {
         mark(1);
         mark(2);
@@ -314,6 +330,7 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
     a.eps = p->eps;
     a.o_sparse_dbg = p->o_sparse_dbg; a.o_linear_dbg = unfused ? nullptr : p->o_linear_dbg;
     a.write_sparse_only = unfused;
+    a.drop = drop;
     if (need_lists) {
         a.tile_lists = (const uint32_t *)(ws + w.tile_lists);
         a.tile_counts = (const int32_t *)(ws + w.tile_counts);
@@ -330,6 +347,7 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
         ap.q = (const u16 *)p->q; ap.out = (u16 *)p->out; ap.BH = BH; ap.N = p->N; ap.D = p->d;
         ap.hfrag = (const u16 *)(ws + w.hfrag); ap.Z = (const float *)(ws + w.Z); ap.coef = (const float *)(ws + w.coef);
         ap.eps = p->eps; ap.o_linear_dbg = p->o_linear_dbg;
+        ap.drop = drop; ap.H = p->H;
         e = launch_linear_apply_bf16(ap, st);
         if (e != hipSuccess) return hip_fail(e, "linear apply launch");
     }

@@ -27,11 +27,12 @@ int gate_num_parts(int N);
 // bf16: partial states over token chunks, MFMA.  partial[(bh*P + c)][D*D + D] fp32.
 int state_tiles_per_chunk(int BH, int N);
 int state_num_chunks(int BH, int N);
+// drop (may be null): int32 [B], workgroups of a sample with drop[b] != 0 return at once (H heads per sample)
 hipError_t launch_state_partial_bf16(const u16 *k, const u16 *v, int BH, int N, int D,
-                                     float *partial, hipStream_t st);
+                                     float *partial, const int32_t *drop, int H, hipStream_t st);
 // fp32: direct evaluation, one thread per state element (small shapes).
 hipError_t launch_state_f32(const float *k, const float *v, int BH, int N, int D,
-                            float *Hs, float *Z, hipStream_t st);
+                            float *Hs, float *Z, const int32_t *drop, int H, hipStream_t st);
 
 // ---- finalize: reduce partials, dynamic scale, coefficients ---------------------------------------
 struct FinalizeArgs {
@@ -48,6 +49,11 @@ struct FinalizeArgs {
     float *s_ws;         // [B]
     float *coef;         // [BH] lambda * a_h * s_b (may be null)
     int do_gate;         // 0: state part only
+    // branch dropping (Sec. 4.3): the gate part writes drop[b] = s_b < tau (and a zero coefficient), the
+    // state part skips samples with drop[b] != 0.  drop == nullptr: no dropping.
+    float tau;
+    int32_t *drop;       // [B] in the workspace
+    int32_t *dropped_out;// [B] caller's copy (may be null)
 };
 hipError_t launch_finalize(const FinalizeArgs &a, hipStream_t st);
 
@@ -72,6 +78,7 @@ struct AttnArgs {
     const uint32_t *tile_lists;     // [H * ntiles4][list_cap]
     const int32_t *tile_counts;     // [H * ntiles4]
     int list_cap;
+    const int32_t *drop;            // [B] or null: samples whose linear branch is pruned (out = O_s)
 };
 hipError_t launch_sparse_attn_bf16(const AttnArgs &a, hipStream_t st);
 // union lists of the CSR rows of every 4-query-block tile (input of the large-tile attention kernel)
@@ -88,6 +95,7 @@ struct ApplyArgs {
     int BH, N, D;
     const u16 *hfrag; const float *Z; const float *coef; float eps;
     float *o_linear_dbg;
+    const int32_t *drop; int H;     // [B] or null: pruned samples are left as they are (out = O_s)
 };
 hipError_t launch_linear_apply_bf16(const ApplyArgs &a, hipStream_t st);
 

@@ -252,7 +252,7 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_kernel(AttnArgs a, in
     const float inv_l = l_tot > 0.f ? 1.f / l_tot : 0.f;
     f32x16 num[NDT];
     float lin_scale = 0.f, inv_den = 0.f;
-    const bool lin = a.use_linear && !a.write_sparse_only;
+    const bool lin = a.use_linear && !a.write_sparse_only && !(a.drop && a.drop[bh / a.H]);   // pruned sample (Sec. 4.3): out = O_s
     if (lin) {
         // phi(Q) = relu(Q) on the fragments already in registers
         float dpart = 0.f;
@@ -391,7 +391,8 @@ __global__ __launch_bounds__(256) void sparse_attn_f32_kernel(AttnArgs a)
     const float inv_l = l > 0.f ? 1.f / l : 0.f;
     float os0 = o0 * inv_l, os1 = o1 * inv_l;
     float ol0 = 0.f, ol1 = 0.f, r0 = os0, r1 = os1;
-    if (a.use_linear) {
+    const bool lin = a.use_linear && !(a.drop && a.drop[bh / a.H]);   // pruned sample (Sec. 4.3): out = O_s
+    if (lin) {
         const float *Hh = a.Hs + (size_t)bh * D * D;
         const float *Zh = a.Z + (size_t)bh * D;
         const float f0 = fmaxf(q0, 0.f), f1 = fmaxf(q1, 0.f);
@@ -414,7 +415,7 @@ __global__ __launch_bounds__(256) void sparse_attn_f32_kernel(AttnArgs a)
     if (h0) out[ob + c0] = r0;
     if (h1) out[ob + c1] = r1;
     if (a.o_sparse_dbg) { if (h0) a.o_sparse_dbg[ob + c0] = os0; if (h1) a.o_sparse_dbg[ob + c1] = os1; }
-    if (a.o_linear_dbg && a.use_linear) { if (h0) a.o_linear_dbg[ob + c0] = ol0; if (h1) a.o_linear_dbg[ob + c1] = ol1; }
+    if (a.o_linear_dbg && lin) { if (h0) a.o_linear_dbg[ob + c0] = ol0; if (h1) a.o_linear_dbg[ob + c1] = ol1; }
 }
 
 hipError_t launch_sparse_attn_f32(const AttnArgs &a, hipStream_t st)

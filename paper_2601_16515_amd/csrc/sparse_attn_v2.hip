@@ -260,7 +260,7 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_v2_kernel(AttnArgs a, int 
     const float inv_l = l_tot > 0.f ? 1.f / l_tot : 0.f;
     f32x16 num[NDT];
     float lin_scale = 0.f, inv_den = 0.f;
-    const bool lin = a.use_linear && !a.write_sparse_only;
+    const bool lin = a.use_linear && !a.write_sparse_only && !(a.drop && a.drop[bh / a.H]);   // pruned sample (Sec. 4.3): out = O_s
     if (lin) {
         float dpart = 0.f;
         const float *Zh = a.Z + (size_t)bh * D;

@@ -425,7 +425,7 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
         l_run += psum;
     };
 
-    const bool lin = a.use_linear && !a.write_sparse_only;
+    const bool lin = a.use_linear && !a.write_sparse_only && !(a.drop && a.drop[bh / a.H]);   // pruned sample (Sec. 4.3): out = O_s
     const u16 *hf = a.hfrag + (size_t)bh * 2 * D * D;
     // 64 KB of linear-state fragments (hi, lo) for the epilogue, staged into the K ring once it is idle
     auto stage_state = [&]() INL {

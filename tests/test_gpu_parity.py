@@ -281,6 +281,57 @@ def test_run_to_run_bit_reproducible():
     assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
 
 
+@pytest.mark.parametrize("flags", [0, sb.SALAD_FLAG_UNFUSED_EPILOGUE], ids=["fused", "unfused"])
+def test_branch_dropping(oracle, flags):
+    """Sec. 4.3: with a threshold between the two samples' dynamic scales only the lower one loses its linear
+    branch; its output is then the sparse branch alone, bit for bit what lambda = 0 gives."""
+    w = SMALL[1]                                      # B = 2, 3 heads, 11 blocks
+    inp = wl.make_inputs(w)
+    wg = inp["w_gate"]
+    inp["x_t"] = inp["x_t"].copy()
+    inp["x_t"][1] = wl.round_to_bf16(inp["x_t"][1] + (2.0 * wg / float(np.dot(wg, wg))).astype(np.float32))   # pre-activations of sample 1 up by ~2
+    dev = upload(w, inp)
+    kinds = wl.head_kinds(w)
+    kept = [4] * w.H
+    base = _oracle_layer(oracle, w, inp, kept, kinds, lam=20.0)
+    s = base["s"]
+    assert s[1] - s[0] > 0.2
+    tau = float(0.5 * (s[0] + s[1]))
+    ref = _oracle_layer(oracle, w, inp, kept, kinds, lam=20.0, drop_threshold=tau)
+    assert ref["dropped"].tolist() == [1, 0]
+    res = run_layer(w, inp, dev, kept, kinds, lam=20.0, flags=flags, drop_threshold=tau)
+    assert res["dropped"].tolist() == [1, 0]
+    assert np.abs(res["s"] - s).max() < 2e-6          # the reported scale is the gate's, pruned or not
+    compare_layer(res, ref, check_linear=False, label="drop")
+    sparse_only = run_layer(w, inp, dev, kept, kinds, lam=0.0, flags=0)["out_t"]
+    assert torch.equal(res["out_t"][0], sparse_only[0])            # pruned sample: exactly the sparse branch
+    assert not torch.equal(res["out_t"][1], sparse_only[1])        # the other one kept its linear branch
+    # thresholds outside the range: nobody / everybody
+    none = run_layer(w, inp, dev, kept, kinds, lam=20.0, flags=flags, drop_threshold=1e-6)
+    full = run_layer(w, inp, dev, kept, kinds, lam=20.0, flags=flags)
+    assert none["dropped"].tolist() == [0, 0] and torch.equal(none["out_t"], full["out_t"])
+    assert full["dropped"].tolist() == [-1, -1]       # not written when dropping is off
+    every = run_layer(w, inp, dev, kept, kinds, lam=20.0, flags=flags, drop_threshold=2.0)
+    assert every["dropped"].tolist() == [1, 1] and torch.equal(every["out_t"], sparse_only)
+
+
+def test_branch_dropping_fp32(oracle):
+    w = wl.small("drop-f32", 2, 2, 64, 3, 6, 8, "f32", 0.5, seed=112)       # N = 144
+    inp = wl.make_inputs(w)
+    wg = inp["w_gate"]
+    inp["x_t"] = inp["x_t"].copy()
+    inp["x_t"][0] += (2.0 * wg / float(np.dot(wg, wg))).astype(np.float32)
+    dev = upload(w, inp)
+    kinds = wl.head_kinds(w)
+    kept = [2, 2]
+    base = _oracle_layer(oracle, w, inp, kept, kinds, lam=5.0)
+    tau = float(0.5 * (base["s"][0] + base["s"][1]))
+    ref = _oracle_layer(oracle, w, inp, kept, kinds, lam=5.0, drop_threshold=tau)
+    res = run_layer(w, inp, dev, kept, kinds, lam=5.0, drop_threshold=tau)
+    assert ref["dropped"].tolist() == [0, 1] and res["dropped"].tolist() == [0, 1]
+    compare_layer(res, ref, check_linear=False, tol_abs=1e-4, tol_rel=1e-5, label="drop-f32")
+
+
 def test_layer_call_under_graph_capture():
     """The layer call allocates nothing and never synchronises, so it can be captured into a HIP graph.
     Replays (with eager work and synchronisation in between) give the bits of the eager call."""
