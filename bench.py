@@ -75,6 +75,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense-control", action="store_true")
     ap.add_argument("--cpu-sample-every", type=int, default=1)
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the extra timings of the sweep points and of the tiny, mid and 720p configurations")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="also run three plain device copies of Q (a kernel of known size) so that a "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run of this command can be scaled")
@@ -173,6 +175,39 @@ def main():
     ms_dr, _ = timed(pdrop, max(5, args.steps // 5), 2)
     result["branch_dropped"] = {"ms_per_call": ms_dr, "saving_vs_full_layer": 1.0 - ms_dr / ms,
                                 "paper_context": "dropping ~50 % of the linear branches moves the paper's end-to-end speedup from 1.52x to 1.59x"}
+
+    # ms/call and effective TFLOP/s (kept blocks only) of the other benchmark configurations: the sparsity sweep
+    # at the 480p shape (same tensors, another mask), then tiny (fp32), mid and 720p with their own seeded inputs
+    if not args.no_other_configs and args.sparsity is None:
+        others = []
+
+        def time_config(wc, tensors):
+            qc, kc, vc, xc, wgc, hsc = tensors
+            keptc = [sb.salad_kept_from_sparsity(wc.nb, wc.sparsity)] * wc.H
+            gridc = (wc.T, wc.Hh, wc.W)
+            rp, ci = sb.salad_block_mask(*gridc, wc.block, keptc)
+            flc = kept_flops(rp.cpu().numpy(), ci.cpu().numpy(), wc.H, wc.N, wc.d, wc.block, wc.B)
+            code = sb.SALAD_BF16 if wc.dtype == "bf16" else sb.SALAD_F32
+            wsc = sb.Workspace(wc.B, wc.H, wc.N, wc.d, code, dev)
+            outc = torch.empty_like(qc)
+            pc, keepc = sb.make_fwd_params(qc, kc, vc, outc, gridc, rp, ci, wl.head_kinds(wc), lam=wc.lam, head_scale=hsc,
+                                           x_t=xc, w_gate=wgc, eps=wc.eps, workspace=wsc)
+            msc, _ = timed(pc, 5 if flc > 2e12 else 10, 2)
+            others.append({"workload": wc.name, "sparsity": wc.sparsity, "N": wc.N, "H": wc.H, "d": wc.d, "dtype": wc.dtype,
+                           "kept_blocks_per_query_block": keptc[0], "kept_gflop": flc * 1e-9, "ms_per_call": msc,
+                           "TFLOP/s": flc / (msc * 1e-3) * 1e-12})
+
+        for rho in (0.5, 0.75, 0.95):
+            time_config(wl.WAN13_480P.with_sparsity(rho), (q, k, v, x, wg, hs))
+        for wc in (wl.TINY, wl.MID, wl.WAN14_720P):
+            ic = wl.make_inputs(wc)
+            tdt = torch.bfloat16 if wc.dtype == "bf16" else torch.float32
+            tens = tuple(torch.from_numpy(ic[t]).to(dev).to(tdt) for t in ("q", "k", "v", "x_t")) + \
+                (torch.from_numpy(ic["w_gate"]).to(dev), torch.from_numpy(ic["head_scale"]).to(dev))
+            time_config(wc, tens)
+            del tens, ic
+            torch.cuda.empty_cache()
+        result["other_configs"] = others
 
     # the same call captured once into a HIP graph and replayed (the call allocates nothing and never
     # synchronises); reported next to the eager figure, which stays the headline value
