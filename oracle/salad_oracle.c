@@ -30,6 +30,9 @@
  *   - the static projection is the per-layer scalar lambda times a per-head scalar a_h;
  *   - the gate is Linear: D -> 1 without learned bias (a test-only scalar bias is accepted),
  *     sigmoid per token, then the mean over tokens;
+ *   - with a full static projection W_p [D x D] (D = H d; row = input channel h_in d + a, column = output
+ *     channel h_out d + c) the residual sum is O_s + lambda s_b (O_l W_p), O_l being the heads' linear
+ *     outputs concatenated per token; the per-head form is W_p = blockdiag(a_h I);
  *   - "below the threshold" is the strict inequality s_b < tau; a dropped branch contributes
  *     exactly nothing (out = O_s), and tau <= 0 never drops since s_b > 0.
  *
@@ -299,6 +302,44 @@ int salad_oracle_gate(const float *x, const float *w, double bias, int B, int64_
 }
 
 /* ---- residual integration, Alg. 1 last block; Eq. (lambda scale), Sec. 4.2 ------------ */
+
+/* Residual integration with the full Level-1 projection (Alg. 1 "Proj", Sec. 4.2 layer-wise static scaling):
+ *   out[b, h_out, r, c] = O_s[b, h_out, r, c]
+ *                       + lambda s[b] sum_{h_in, a} O_l[b, h_in, n, a] W_p[h_in d + a][h_out d + c],
+ * n = rows[b, h_out, r] being the stored row of compact row r (rows differ between heads, so the linear
+ * outputs of all heads at row n are evaluated here from Q, Hs, Z: Eq. (3) quotient).
+ * o_s, out: [B, H, nrows, d]; rows: [B, H, nrows] (< 0: skipped, out = O_s); W_p: [D, D] double. */
+int salad_oracle_combine_proj(const float *q, const double *Hs, const double *Z, int B, int H, int64_t N, int d,
+                              double eps, const double *o_s, const int64_t *rows, int64_t nrows,
+                              const double *Wp, double lambda, const double *s, double *out)
+{
+    const int64_t total = (int64_t)B * H * nrows;
+    const int64_t D = (int64_t)H * d;
+#pragma omp parallel for schedule(static)
+    for (int64_t idx = 0; idx < total; ++idx) {
+        const int64_t bh = idx / nrows;
+        const int b = (int)(bh / H), ho = (int)(bh % H);
+        const int64_t n = rows[idx];
+        double *o = out + idx * d;
+        for (int c = 0; c < d; ++c) o[c] = o_s[idx * d + c];
+        if (n < 0 || n >= N) continue;
+        for (int hi = 0; hi < H; ++hi) {
+            const int64_t bhi = (int64_t)b * H + hi;
+            const float *qi = q + (bhi * N + n) * d;
+            /* O_l of head hi at row n */
+            double den = eps;
+            for (int a = 0; a < d; ++a) den += relu((double)qi[a]) * Z[bhi * d + a];
+            for (int a2 = 0; a2 < d; ++a2) {
+                double num = 0.0;
+                for (int a = 0; a < d; ++a) num += relu((double)qi[a]) * Hs[(bhi * d + a) * d + a2];
+                const double ol = num / den;
+                const double *wrow = Wp + ((int64_t)hi * d + a2) * D + (int64_t)ho * d;
+                for (int c = 0; c < d; ++c) o[c] += lambda * s[b] * ol * wrow[c];
+            }
+        }
+    }
+    return SO_OK;
+}
 
 /* Post-tuning branch dropping, Sec. 4.3: dropped[b] = 1 when the sample's dynamic scale is below the
  * threshold.  The comparison is made on the float32 value of s, the precision the device holds it in. */

@@ -162,6 +162,26 @@ def combine(o_s, o_l, lam: float, head_scale, s) -> np.ndarray:
     return out
 
 
+def combine_proj(q, Hs, Z, eps: float, o_s, rows, w_proj, lam: float, s) -> np.ndarray:
+    """Alg. 1 residual integration with the full projection: O_s + lambda s_b (O_l W_p), W_p [D,D] over the
+    concatenated heads; evaluated on the compact rows of each (b, h) (`rows`: their stored row indices)."""
+    q = _f32(q)
+    B, H, N, d = q.shape
+    o_s = np.ascontiguousarray(o_s, dtype=np.float64)
+    rows = np.ascontiguousarray(rows, dtype=np.int64)
+    nrows = rows.shape[-1]
+    Hs = np.ascontiguousarray(Hs, dtype=np.float64)
+    Z = np.ascontiguousarray(Z, dtype=np.float64)
+    wp = np.ascontiguousarray(w_proj, dtype=np.float64)
+    assert wp.shape == (H * d, H * d)
+    s = np.ascontiguousarray(s, dtype=np.float64)
+    out = np.zeros_like(o_s)
+    _load().salad_oracle_combine_proj(_p(q), _p(Hs), _p(Z), C.c_int(B), C.c_int(H), C.c_int64(N), C.c_int(d),
+                                      C.c_double(eps), _p(o_s), _p(rows), C.c_int64(nrows), _p(wp),
+                                      C.c_double(lam), _p(s), _p(out))
+    return out
+
+
 def branch_drop(s, tau: float) -> np.ndarray:
     """Sec. 4.3: which samples' linear branches are pruned (dynamic scale below the threshold)."""
     s = np.ascontiguousarray(s, dtype=np.float64)
@@ -171,7 +191,8 @@ def branch_drop(s, tau: float) -> np.ndarray:
 
 
 def salad_forward(q, k, v, x_t, w_gate, head_scale, grid, block, head_kind, kept, lam=1.0, eps=1e-6,
-                  b_gate=0.0, scale=None, sel=None, s_override=None, drop_threshold=0.0) -> Dict[str, np.ndarray]:
+                  b_gate=0.0, scale=None, sel=None, s_override=None, drop_threshold=0.0,
+                  w_proj=None) -> Dict[str, np.ndarray]:
     """Whole layer (Alg. 1 from SparseAttn to the residual sum) on the selected query blocks.
 
     Returns compact row sets [B,H,nsel*block,d] for o_sparse, o_linear and out, the stored row
@@ -184,6 +205,10 @@ def salad_forward(q, k, v, x_t, w_gate, head_scale, grid, block, head_kind, kept
     s = gate(x_t, w_gate, b_gate) if s_override is None else np.asarray(s_override, dtype=np.float64)
     dropped = branch_drop(s, drop_threshold)
     # a pruned branch contributes exactly nothing: its samples are combined with a zero dynamic scale
-    out = combine(o_s, o_l, lam, head_scale, np.where(dropped != 0, 0.0, s))
+    s_eff = np.where(dropped != 0, 0.0, s)
+    if w_proj is not None:       # full Level-1 projection across heads instead of the per-head scalars
+        out = combine_proj(q, Hs, Z, eps, o_s, rows, w_proj, lam, s_eff)
+    else:
+        out = combine(o_s, o_l, lam, head_scale, s_eff)
     return {"o_sparse": o_s, "o_linear": o_l, "out": out, "rows": rows, "Hs": Hs, "Z": Z, "s": s,
             "row_ptr": row_ptr, "col_idx": col_idx, "dropped": dropped}

@@ -257,6 +257,55 @@ def test_combination_closed_forms(oracle):
     assert np.abs(r["s"] - oracle.gate(inp["x_t"], inp["w_gate"])).max() == 0.0
 
 
+# ---------------------------------------------------------------- full Level-1 projection, Alg. 1 "Proj"
+
+def test_full_projection(oracle):
+    w = wl.small("proj", 2, 3, 16, 2, 6, 7, "f32", 0.5, seed=44, block=16)     # D = 48
+    inp = wl.make_inputs(w)
+    D = w.H * w.d
+    kw = dict(grid=(w.T, w.Hh, w.W), block=w.block, head_kind=[0, 1, 0], kept=[3, 3, 2], eps=1e-6)
+    args = (inp["q"], inp["k"], inp["v"], inp["x_t"], inp["w_gate"])
+    a = inp["head_scale"].astype(np.float64)
+    per_head = oracle.salad_forward(*args, inp["head_scale"], lam=0.8, **kw)
+    ok = per_head["rows"] >= 0
+    # the per-head form is the block-diagonal special case
+    wp = np.kron(np.diag(a), np.eye(w.d))
+    full = oracle.salad_forward(*args, None, lam=0.8, w_proj=wp, **kw)
+    assert np.abs(full["out"] - per_head["out"])[ok].max() < 1e-12
+    # zero-initialised projection (Sec. 4.2): the layer is the sparse branch, bit for bit
+    z = oracle.salad_forward(*args, None, lam=0.8, w_proj=np.zeros((D, D)), **kw)
+    assert np.array_equal(z["out"], z["o_sparse"])
+    # linear in W_p
+    w1 = wl.normal(44, "w1", (D, D)).astype(np.float64) * 0.1
+    w2 = wl.normal(44, "w2", (D, D)).astype(np.float64) * 0.1
+    o1 = oracle.salad_forward(*args, None, lam=0.8, w_proj=w1, **kw)["out"]
+    o2 = oracle.salad_forward(*args, None, lam=0.8, w_proj=w2, **kw)["out"]
+    o12 = oracle.salad_forward(*args, None, lam=0.8, w_proj=w1 + 2.0 * w2, **kw)["out"]
+    os_ = per_head["o_sparse"]
+    assert np.abs((o12 - os_) - ((o1 - os_) + 2.0 * (o2 - os_)))[ok].max() < 1e-12
+    # one non-zero entry W_p[(h1, a), (h2, c)] moves exactly column c of head h2, by lambda s_b O_l[h1, n, a];
+    # for a spatial head h2 and a spatial head h1 the compact rows of both are the same stored rows
+    h1, aa, h2, cc = 2, 5, 0, 9
+    e = np.zeros((D, D)); e[h1 * w.d + aa, h2 * w.d + cc] = 1.0
+    oe = oracle.salad_forward(*args, None, lam=0.8, w_proj=e, **kw)
+    delta = oe["out"] - oe["o_sparse"]
+    assert np.array_equal(oe["rows"][:, h1], oe["rows"][:, h2])
+    expect = 0.8 * oe["s"][:, None] * oe["o_linear"][:, h1, :, aa]
+    assert np.abs(delta[:, h2, :, cc] - expect)[ok[:, h2]].max() < 1e-12
+    delta[:, h2, :, cc] = 0.0
+    assert np.abs(delta).max() == 0.0
+    # a transposed projection is a different layer (index convention: row = input channel)
+    ot = oracle.salad_forward(*args, None, lam=0.8, w_proj=w1.T, **kw)["out"]
+    assert np.abs(ot - o1)[ok].max() > 1e-3
+    # a temporal output head takes the other heads' linear outputs at its own stored rows
+    assert not np.array_equal(oe["rows"][:, 1], oe["rows"][:, 0])
+    et = np.zeros((D, D)); et[0 * w.d + 3, 1 * w.d + 4] = 1.0
+    ot = oracle.salad_forward(*args, None, lam=0.8, w_proj=et, **kw)
+    ol0_full = oracle.linear_apply(inp["q"], ot["Hs"], ot["Z"], 1e-6, ot["rows"][:, 1:2].repeat(w.H, axis=1))[:, 0]
+    d1 = (ot["out"] - ot["o_sparse"])[:, 1, :, 4]
+    assert np.abs(d1 - 0.8 * ot["s"][:, None] * ol0_full[:, :, 3])[ok[:, 1]].max() < 1e-12
+
+
 # ---------------------------------------------------------------- branch dropping, Sec. 4.3
 
 def test_branch_dropping(oracle):
