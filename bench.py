@@ -209,6 +209,25 @@ def main():
             torch.cuda.empty_cache()
         result["other_configs"] = others
 
+    # Alg. 1 "Proj" as the full D x D projection across heads (the per-head scalars are its block-diagonal case):
+    # sparse kernel, O_l written to the workspace, then one bf16 MFMA GEMM [N, D] x [D, D] fused with the sum
+    try:
+        Dm = w.H * w.d
+        wp = (torch.from_numpy(wl.normal(w.seed, "w_proj", (Dm, Dm))).to(dev) / Dm ** 0.5).to(torch.bfloat16)
+        ws_p = sb.Workspace(w.B, w.H, w.N, w.d, sb.SALAD_BF16, dev, full_proj=True)
+        pp, keep_p = sb.make_fwd_params(q, k, v, out, grid, row_ptr, col_idx, kinds, lam=w.lam, head_scale=None, x_t=x,
+                                        w_gate=wg, eps=w.eps, workspace=ws_p, w_proj=wp)
+        ms_p, kt_p = timed(pp, max(5, args.steps // 5), 2)
+        proj_ms = kt_p.proj_ms / max(kt_p.calls, 1)
+        proj_flops = 2.0 * w.B * w.N * Dm * Dm
+        result["full_projection"] = {"ms_per_call": ms_p, "proj_gemm_ms": proj_ms, "proj_gflop": proj_flops * 1e-9,
+                                     "proj_TFLOP/s": proj_flops / (proj_ms * 1e-3) * 1e-12,
+                                     "proj_frac_of_bf16_peak": proj_flops / (proj_ms * 1e-3) * 1e-12 / PEAK_BF16_TFLOPS,
+                                     "emit_linear_branch_ms": kt_p.epilogue_ms / max(kt_p.calls, 1)}
+        del ws_p, wp
+    except Exception as exc:
+        result["full_projection"] = {"error": repr(exc)[:200]}
+
     # the same call captured once into a HIP graph and replayed (the call allocates nothing and never
     # synchronises); reported next to the eager figure, which stays the headline value
     try:

@@ -105,6 +105,9 @@ typedef struct salad_fwd_params {
     float drop_threshold;     /* post-tuning branch dropping (Sec. 4.3): tau_t; <= 0 disables         */
     int32_t *dropped_out;     /* optional device int32 [B]: 1 where the linear branch was pruned, else 0;
                                  written only when dropping is active (lambda != 0, drop_threshold > 0)  */
+    const void *w_proj;       /* optional device bf16 [H*d, H*d], row-major, row = input channel h_in*d + a,
+                                 column = output channel h_out*d + c: the full Level-1 projection (Alg. 1
+                                 "Proj").  Needs dtype bf16, d = 128 and head_scale == NULL                */
 } salad_fwd_params;
 
 /* Run the linear apply and the scale-and-sum as a separate streaming kernel after the sparse
@@ -112,7 +115,8 @@ typedef struct salad_fwd_params {
 #define SALAD_FLAG_UNFUSED_EPILOGUE 1
 
 /* Device scratch the forward needs for these shapes (partial states, partial gate sums, the
- * reduced state, per-tile block lists).  Reads only B, H, N, d, dtype.  0 on invalid shapes. */
+ * reduced state, per-tile block lists; with w_proj also O_l and the rearranged W_p).  Reads only B, H, N, d,
+ * dtype and whether w_proj is NULL.  0 on invalid shapes. */
 size_t salad_fwd_workspace_bytes(const salad_fwd_params *p);
 
 /* Alg. 1 from SparseAttn to the residual sum:
@@ -121,6 +125,11 @@ size_t salad_fwd_workspace_bytes(const salad_fwd_params *p);
  *   s_b = mean_n sigmoid(x_t[b,n,:].w_gate + b_gate)                             (Level 2)
  *   out = O_s + lambda * a_h * s_b * O_l                (Level 1 in per-head form + residual)
  * With lambda == 0 the linear branch is skipped and out is the sparse branch alone.
+ * With w_proj the static scaling is the paper's full projection across heads instead of per-head scalars:
+ *   out[b,n,:] = O_s[b,n,:] + lambda * s_b * (O_l[b,n,:] W_p),  O_l[b,n,:] the heads' outputs concatenated
+ * (per-head form: W_p = blockdiag(a_h I)).  It runs as separate kernels after the sparse kernel: O_l is written
+ * to the workspace (bf16), W_p is rearranged into MFMA fragment order, and one bf16 MFMA GEMM adds lambda s_b O_l W_p
+ * to O_s (fp32 accumulation, one rounding of the sum).  o_linear_dbg is not written in this mode.
  * Post-tuning branch dropping (Sec. 4.3, App. A.3): with drop_threshold = tau > 0, a sample whose dynamic
  * scale s_b < tau (strict, compared in fp32) loses its linear branch: out[b] = O_s[b], exactly as with
  * lambda == 0.  The decision is taken on the device (no host synchronisation): the gate is reduced first,
@@ -147,6 +156,7 @@ salad_status salad_gate_fwd(const void *x_t, const float *w_gate, float b_gate, 
 typedef struct salad_kernel_times {
     float gate_ms, state_ms, finalize_ms, attn_ms, epilogue_ms; /* summed over calls            */
     int32_t calls;
+    float proj_ms;            /* full Level-1 projection: W_p rearrangement + GEMM (0 without w_proj)   */
 } salad_kernel_times;
 
 /* When enabled, the layer call brackets each of its kernels with HIP events on its stream. */

@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(_HERE, "libsalad.so")
 SOURCES = ["salad_api.hip", "mask_gate_finalize.hip", "linear_state.hip", "sparse_attn.hip",
-           "sparse_attn_v2.hip", "sparse_attn_v5.hip", "linear_apply.hip"]
+           "sparse_attn_v2.hip", "sparse_attn_v5.hip", "linear_apply.hip", "proj.hip"]
 
 SALAD_OK, SALAD_EINVAL, SALAD_ENOTSUP, SALAD_ENOSPC, SALAD_EHIP = range(5)
 SALAD_F32, SALAD_BF16 = 0, 1
@@ -61,12 +61,13 @@ class FwdParams(C.Structure):
         ("hip_stream", C.c_void_p),
         ("drop_threshold", C.c_float),
         ("dropped_out", C.c_void_p),
+        ("w_proj", C.c_void_p),
     ]
 
 
 class KernelTimes(C.Structure):
     _fields_ = [("gate_ms", C.c_float), ("state_ms", C.c_float), ("finalize_ms", C.c_float),
-                ("attn_ms", C.c_float), ("epilogue_ms", C.c_float), ("calls", C.c_int32)]
+                ("attn_ms", C.c_float), ("epilogue_ms", C.c_float), ("calls", C.c_int32), ("proj_ms", C.c_float)]
 
 
 def build_library(verbose: bool = False) -> str:
@@ -171,18 +172,19 @@ def salad_block_mask(T: int, Hh: int, W: int, block: int, kept: Sequence[int], d
     return row_ptr, col_idx[:nnz]
 
 
-def salad_fwd_workspace_bytes(B: int, H: int, N: int, d: int, dtype: int) -> int:
+def salad_fwd_workspace_bytes(B: int, H: int, N: int, d: int, dtype: int, full_proj: bool = False) -> int:
     p = FwdParams()
     p.B, p.H, p.N, p.d, p.dtype = B, H, N, d, dtype
+    p.w_proj = 1 if full_proj else None          # the query only looks at whether the pointer is NULL
     return int(lib().salad_fwd_workspace_bytes(C.byref(p)))
 
 
 class Workspace:
     """Caller-owned scratch for the layer call, sized by the library's query."""
 
-    def __init__(self, B: int, H: int, N: int, d: int, dtype: int, device="cuda"):
+    def __init__(self, B: int, H: int, N: int, d: int, dtype: int, device="cuda", full_proj: bool = False):
         import torch
-        self.bytes = salad_fwd_workspace_bytes(B, H, N, d, dtype)
+        self.bytes = salad_fwd_workspace_bytes(B, H, N, d, dtype, full_proj)
         self.buf = torch.empty(max(self.bytes, 256) + 256, dtype=torch.uint8, device=device)
         self.ptr = (self.buf.data_ptr() + 255) & ~255
 
@@ -191,7 +193,7 @@ def make_fwd_params(q, k, v, out, grid: Tuple[int, int, int], row_ptr, col_idx, 
                     lam: float = 1.0, head_scale=None, s=None, x_t=None, w_gate=None, b_gate: float = 0.0,
                     eps: float = 1e-6, softmax_scale: float = 0.0, s_out=None, o_sparse_dbg=None,
                     o_linear_dbg=None, workspace: Optional[Workspace] = None, flags: int = 0, block: int = 64,
-                    drop_threshold: float = 0.0, dropped_out=None):
+                    drop_threshold: float = 0.0, dropped_out=None, w_proj=None):
     """Fill a salad_fwd_params from torch tensors.  Returns (params, keepalive)."""
     B, H, N, d = q.shape
     p = FwdParams()
@@ -224,6 +226,7 @@ def make_fwd_params(q, k, v, out, grid: Tuple[int, int, int], row_ptr, col_idx, 
     p.hip_stream = _stream()
     p.drop_threshold = drop_threshold
     p.dropped_out = _ptr(dropped_out)
+    p.w_proj = _ptr(w_proj)
     return p, (hk, workspace)
 
 
@@ -237,7 +240,7 @@ def salad_sparse_linear_attn_fwd(q, k, v, grid, row_ptr, col_idx, head_kind=None
     if out is None:
         out = torch.empty_like(q)
     if kw.get("workspace") is None:
-        kw["workspace"] = Workspace(B, H, N, d, _dtype_code(q), q.device)
+        kw["workspace"] = Workspace(B, H, N, d, _dtype_code(q), q.device, full_proj=kw.get("w_proj") is not None)
     p, keep = make_fwd_params(q, k, v, out, grid, row_ptr, col_idx, head_kind, **kw)
     _check(lib().salad_sparse_linear_attn_fwd(C.byref(p)))
     return out

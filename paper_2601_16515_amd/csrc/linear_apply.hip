@@ -119,7 +119,9 @@ __global__ __launch_bounds__(256) void linear_apply_kernel(ApplyArgs a, int rows
 // d = 128.  Per wave and 32-row block: Q rows -> LDS -> B-operand fragments; relu, denominator; for each
 // half of the 128 output columns 32 MFMAs against the hi + lo state fragments, scaled results (fp32) -> LDS ->
 // row layout, added to O_s in fp32, one rounding to bf16, stored.
-template <bool DBG>
+// EMIT: instead of adding to O_s, write the unscaled O_l (bf16) to a.emit, same [B,H,N,d] layout (input of
+// the full Level-1 projection).
+template <bool DBG, bool EMIT>
 __global__ __launch_bounds__(512) void linear_apply128_kernel(ApplyArgs a, int rows_per_wg)
 {
     constexpr int D = 128, NS = 8;
@@ -143,7 +145,7 @@ __global__ __launch_bounds__(512) void linear_apply128_kernel(ApplyArgs a, int r
     __syncthreads();
     const int N = a.N;
     const u16 *qh = a.q + (size_t)bh * N * D;
-    u16 *oh = a.out + (size_t)bh * N * D;
+    u16 *oh = (EMIT ? a.emit : a.out) + (size_t)bh * N * D;
     const int r8 = lane >> 3, c8 = lane & 7;          // row layout of a half: 8 rows x 8 chunks of 16 bytes per instruction
     const int r4 = lane >> 4, c16 = lane & 15;        // row layout of full rows: 4 rows x 16 chunks
     const int row_end = min(N, (int)(blockIdx.x + 1) * rows_per_wg);
@@ -162,7 +164,7 @@ __global__ __launch_bounds__(512) void linear_apply128_kernel(ApplyArgs a, int r
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const int row = min(rb + 8 * k + r8, N - 1);
-                os[h][k] = *reinterpret_cast<const uint4 *>(oh + (size_t)row * D + h * 64 + c8 * 8);
+                os[h][k] = EMIT ? make_uint4(0, 0, 0, 0) : *reinterpret_cast<const uint4 *>(oh + (size_t)row * D + h * 64 + c8 * 8);
             }
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
@@ -190,7 +192,7 @@ __global__ __launch_bounds__(512) void linear_apply128_kernel(ApplyArgs a, int r
         }
         asm volatile("" ::: "memory");   // the wave's LDS operations execute in order; as above
         const float inv_den = 1.f / (dpart + __shfl_xor(dpart, 32) + a.eps);
-        const float sc = coef * inv_den;
+        const float sc = EMIT ? inv_den : coef * inv_den;
         const bool rvalid = rb + l32 < N;
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
@@ -262,12 +264,14 @@ hipError_t launch_linear_apply_bf16(const ApplyArgs &a, hipStream_t st)
         if (rows_per_wg < 256) rows_per_wg = 256;
         dim3 grid((a.N + rows_per_wg - 1) / rows_per_wg, a.BH), block(512);
         constexpr int lds = 2 * 128 * 128 * 2 + 1024 + 8 * 8192;
-        static bool done_plain[16] = {}, done_dbg[16] = {};
-        hipError_t e = a.o_linear_dbg ? dyn_lds_attr_once(reinterpret_cast<const void *>(linear_apply128_kernel<true>), lds, done_dbg)
-                                      : dyn_lds_attr_once(reinterpret_cast<const void *>(linear_apply128_kernel<false>), lds, done_plain);
+        static bool done_plain[16] = {}, done_dbg[16] = {}, done_emit[16] = {};
+        hipError_t e = a.emit ? dyn_lds_attr_once(reinterpret_cast<const void *>(linear_apply128_kernel<false, true>), lds, done_emit)
+                     : a.o_linear_dbg ? dyn_lds_attr_once(reinterpret_cast<const void *>(linear_apply128_kernel<true, false>), lds, done_dbg)
+                                      : dyn_lds_attr_once(reinterpret_cast<const void *>(linear_apply128_kernel<false, false>), lds, done_plain);
         if (e != hipSuccess) return e;
-        if (a.o_linear_dbg) hipLaunchKernelGGL(linear_apply128_kernel<true>, grid, block, lds, st, a, rows_per_wg);
-        else hipLaunchKernelGGL(linear_apply128_kernel<false>, grid, block, lds, st, a, rows_per_wg);
+        if (a.emit) hipLaunchKernelGGL((linear_apply128_kernel<false, true>), grid, block, lds, st, a, rows_per_wg);
+        else if (a.o_linear_dbg) hipLaunchKernelGGL((linear_apply128_kernel<true, false>), grid, block, lds, st, a, rows_per_wg);
+        else hipLaunchKernelGGL((linear_apply128_kernel<false, false>), grid, block, lds, st, a, rows_per_wg);
         return hipGetLastError();
     }
     // rows per workgroup (a multiple of 128): about two workgroups per CU, so that the 2*d*d*2 bytes of

@@ -36,11 +36,11 @@ salad_status hip_fail(hipError_t e, const char *what)
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct WsLayout {
-    size_t gate_partial, state_partial, Hs, Z, hfrag, s, coef, drop, tile_lists, tile_counts, total;
+    size_t gate_partial, state_partial, Hs, Z, hfrag, s, coef, drop, tile_lists, tile_counts, ol, wfrag, total;
     int nparts, P;
 };
 
-WsLayout ws_layout(int B, int H, int N, int d, int dtype)
+WsLayout ws_layout(int B, int H, int N, int d, int dtype, bool full_proj = false)
 {
     WsLayout w{};
     const size_t BH = (size_t)B * H;
@@ -61,6 +61,9 @@ WsLayout ws_layout(int B, int H, int N, int d, int dtype)
         w.tile_lists = off; off = align256(off + (need ? sizeof(uint32_t) * (size_t)H * ntiles * tile_list_cap(nb) : 0));
         w.tile_counts = off; off = align256(off + (need ? sizeof(int32_t) * (size_t)H * ntiles : 0));
     }
+    // full Level-1 projection: the unscaled linear branch (bf16, [B,H,N,d]) and W_p in fragment order
+    w.ol = off; off = align256(off + (full_proj ? sizeof(u16) * BH * (size_t)N * d : 0));
+    w.wfrag = off; off = align256(off + (full_proj ? sizeof(u16) * (size_t)H * d * H * d : 0));
     w.total = off;
     return w;
 }
@@ -77,7 +80,7 @@ bool shape_ok(int B, int H, int N, int d, int dtype)
 // ---- timing -----------------------------------------------------------------------------------
 std::mutex g_tmu;
 bool g_timing = false;
-struct CallEvents { hipEvent_t e[6]; bool has_epilogue, has_linear; };
+struct CallEvents { hipEvent_t e[7]; bool has_epilogue, has_linear; };
 std::vector<CallEvents> g_calls;
 std::vector<hipEvent_t> g_free_events;
 
@@ -154,7 +157,7 @@ salad_status salad_block_mask(int32_t T, int32_t Hh, int32_t W, int32_t block, i
 size_t salad_fwd_workspace_bytes(const salad_fwd_params *p)
 {
     if (!p || !shape_ok(p->B, p->H, p->N, p->d, p->dtype)) return 0;
-    return ws_layout(p->B, p->H, p->N, p->d, p->dtype).total;
+    return ws_layout(p->B, p->H, p->N, p->d, p->dtype, p->w_proj != nullptr).total;
 }
 
 salad_status salad_linear_state_fwd(const void *k, const void *v, int32_t B, int32_t H, int32_t N, int32_t d,
@@ -236,10 +239,16 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
         if (!p->x_t || !p->w_gate) return fail(SALAD_EINVAL, "fwd: lambda != 0 needs s_dev, or x_t and w_gate");
         if (Dm > 5120) return fail(SALAD_ENOTSUP, "fwd: gate over D=H*d=%d above 5120; pass s_dev", Dm);
     }
-    const bool unfused = (p->flags & SALAD_FLAG_UNFUSED_EPILOGUE) != 0;
+    // with the full projection the sparse kernel always stores O_s alone and the linear branch follows in its own kernels
+    const bool unfused = (p->flags & SALAD_FLAG_UNFUSED_EPILOGUE) != 0 || (p->w_proj != nullptr && p->lambda != 0.f);
     if (unfused && p->dtype != SALAD_BF16) return fail(SALAD_ENOTSUP, "fwd: unfused epilogue is bf16 only");
     if (p->flags & ~SALAD_FLAG_UNFUSED_EPILOGUE) return fail(SALAD_EINVAL, "fwd: unknown flags 0x%x", p->flags);
-    const WsLayout w = ws_layout(p->B, p->H, p->N, p->d, p->dtype);
+    const bool full_proj = p->w_proj != nullptr && p->lambda != 0.f;
+    if (p->w_proj) {
+        if (p->dtype != SALAD_BF16 || p->d != 128) return fail(SALAD_ENOTSUP, "fwd: w_proj needs dtype bf16 and d = 128");
+        if (p->head_scale) return fail(SALAD_EINVAL, "fwd: w_proj and head_scale exclude each other");
+    }
+    const WsLayout w = ws_layout(p->B, p->H, p->N, p->d, p->dtype, p->w_proj != nullptr);
     const bool need_lists = p->dtype == SALAD_BF16 && p->d == 128 && (size_t)tile_list_cap((p->N + 63) / 64) * 4 <= 24 * 1024;
     if (use_linear || need_lists) {
         if (!p->workspace || ((uintptr_t)p->workspace & 255)) return fail(SALAD_EINVAL, "fwd: workspace null or not 256-byte aligned");
@@ -346,12 +355,26 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
         ApplyArgs ap{};
         ap.q = (const u16 *)p->q; ap.out = (u16 *)p->out; ap.BH = BH; ap.N = p->N; ap.D = p->d;
         ap.hfrag = (const u16 *)(ws + w.hfrag); ap.Z = (const float *)(ws + w.Z); ap.coef = (const float *)(ws + w.coef);
-        ap.eps = p->eps; ap.o_linear_dbg = p->o_linear_dbg;
+        ap.eps = p->eps; ap.o_linear_dbg = full_proj ? nullptr : p->o_linear_dbg;
         ap.drop = drop; ap.H = p->H;
+        ap.emit = full_proj ? (u16 *)(ws + w.ol) : nullptr;
         e = launch_linear_apply_bf16(ap, st);
         if (e != hipSuccess) return hip_fail(e, "linear apply launch");
+        mark(5);
+        if (full_proj) {
+            // Alg. 1 "Proj" as one GEMM over the concatenated heads, fused with the residual sum
+            e = launch_proj_pack((const u16 *)p->w_proj, p->H, (u16 *)(ws + w.wfrag), st);
+            if (e != hipSuccess) return hip_fail(e, "projection pack launch");
+            ProjArgs pa{};
+            pa.ol = (const u16 *)(ws + w.ol); pa.out = (u16 *)p->out; pa.wfrag = (const u16 *)(ws + w.wfrag);
+            pa.coef = (const float *)(ws + w.coef); pa.drop = drop; pa.B = p->B; pa.H = p->H; pa.N = p->N;
+            e = launch_proj_apply(pa, st);
+            if (e != hipSuccess) return hip_fail(e, "projection launch");
+        }
+    } else {
+        mark(5);
     }
-    mark(5);
+    mark(6);
     if (timing) {
         std::lock_guard<std::mutex> lk(g_tmu);
         g_calls.push_back(ev);
@@ -372,10 +395,10 @@ salad_status salad_timing_read(salad_kernel_times *out, int32_t reset)
     std::lock_guard<std::mutex> lk(g_tmu);
     std::memset(out, 0, sizeof(*out));
     for (auto &c : g_calls) {
-        hipError_t e = hipEventSynchronize(c.e[5]);
+        hipError_t e = hipEventSynchronize(c.e[6]);
         if (e != hipSuccess) return hip_fail(e, "hipEventSynchronize");
-        float ms[5] = {0, 0, 0, 0, 0};
-        for (int i = 0; i < 5; ++i) {
+        float ms[6] = {0, 0, 0, 0, 0, 0};
+        for (int i = 0; i < 6; ++i) {
             e = hipEventElapsedTime(&ms[i], c.e[i], c.e[i + 1]);
             if (e != hipSuccess) return hip_fail(e, "hipEventElapsedTime");
         }
@@ -384,6 +407,7 @@ salad_status salad_timing_read(salad_kernel_times *out, int32_t reset)
         out->finalize_ms += ms[2];
         out->attn_ms += ms[3];
         out->epilogue_ms += ms[4];
+        out->proj_ms += ms[5];
         out->calls += 1;
     }
     if (reset) {

@@ -332,6 +332,35 @@ def test_branch_dropping_fp32(oracle):
     compare_layer(res, ref, check_linear=False, tol_abs=1e-4, tol_rel=1e-5, label="drop-f32")
 
 
+def test_full_projection(oracle):
+    """Alg. 1 "Proj" as a full D x D matrix across heads: O_s + lambda s_b (O_l W_p), against the oracle; the
+    block-diagonal W_p reproduces the per-head form; pruned samples stay the sparse branch."""
+    w = SMALL[1]                                      # B = 2, H = 3 (odd: one output-head pair is half empty), N = 693
+    inp = wl.make_inputs(w)
+    dev = upload(w, inp)
+    kinds = wl.head_kinds(w)
+    kept = [4] * w.H
+    D = w.H * w.d
+    wp = wl.round_to_bf16((wl.normal(113, "w_proj", (D, D)) / np.sqrt(D)).astype(np.float32))
+    wp_dev = torch.from_numpy(wp).cuda().to(torch.bfloat16)
+    ref = _oracle_layer(oracle, w, inp, kept, kinds, lam=25.0, w_proj=wp.astype(np.float64))
+    ref_ps = _oracle_layer(oracle, w, inp, kept, kinds, lam=25.0)
+    assert errors(ref["out"], ref_ps["out"])[1] > 0.05                 # the projection is not a small effect here
+    res = run_layer(w, inp, dev, kept, kinds, lam=25.0, head_scale=None, w_proj=wp_dev)
+    compare_layer(res, ref, check_linear=False, label="full-proj")
+    # block-diagonal projection = per-head scalars (a_h representable in bf16)
+    a = wl.round_to_bf16(inp["head_scale"])
+    wd = torch.from_numpy(np.kron(np.diag(a), np.eye(w.d, dtype=np.float32)).astype(np.float32)).cuda().to(torch.bfloat16)
+    res_d = run_layer(w, inp, dev, kept, kinds, lam=25.0, head_scale=None, w_proj=wd)
+    res_h = run_layer(w, inp, dev, kept, kinds, lam=25.0, head_scale=torch.from_numpy(a).cuda())
+    assert errors(res_d["out"], res_h["out"])[1] < 3e-3
+    # with branch dropping: the pruned sample is the sparse branch alone
+    tau = 2.0
+    res_dr = run_layer(w, inp, dev, kept, kinds, lam=25.0, head_scale=None, w_proj=wp_dev, drop_threshold=tau)
+    sparse_only = run_layer(w, inp, dev, kept, kinds, lam=0.0)["out_t"]
+    assert res_dr["dropped"].tolist() == [1, 1] and torch.equal(res_dr["out_t"], sparse_only)
+
+
 def test_layer_call_under_graph_capture():
     """The layer call allocates nothing and never synchronises, so it can be captured into a HIP graph.
     Replays (with eager work and synchronisation in between) give the bits of the eager call."""
