@@ -119,8 +119,11 @@ __global__ __launch_bounds__(256) void linear_apply_kernel(ApplyArgs a, int rows
 // d = 128.  Per wave and 32-row block: Q rows -> LDS -> B-operand fragments; relu, denominator; for each
 // half of the 128 output columns 32 MFMAs against the hi + lo state fragments, scaled results (fp32) -> LDS ->
 // row layout, added to O_s in fp32, one rounding to bf16, stored.
-// EMIT: instead of adding to O_s, write the unscaled O_l (bf16) to a.emit, same [B,H,N,d] layout (input of
-// the full Level-1 projection).
+// EMIT: instead of adding to O_s, write the unscaled O_l (bf16) to a.emit (input of the full Level-1
+// projection) in the order that kernel's MFMA B operand wants: [B][ceil(N/32)][H] blocks of 32 rows x 128
+// channels, 16-byte chunk c (channels 8c .. 8c+7) of block row r at ((c/2 * 64 + (c%2) * 32 + r) * 16 bytes, so
+// that one 16-byte load per lane fetches a whole 32 x 16 fragment from 1 KB of contiguous memory.  Rows past N
+// in the last block are written too (from the clamped Q row): finite values nobody uses.
 template <bool DBG, bool EMIT>
 __global__ __launch_bounds__(512) void linear_apply128_kernel(ApplyArgs a, int rows_per_wg)
 {
@@ -145,7 +148,7 @@ __global__ __launch_bounds__(512) void linear_apply128_kernel(ApplyArgs a, int r
     __syncthreads();
     const int N = a.N;
     const u16 *qh = a.q + (size_t)bh * N * D;
-    u16 *oh = (EMIT ? a.emit : a.out) + (size_t)bh * N * D;
+    u16 *oh = a.out + (size_t)bh * N * D;
     const int r8 = lane >> 3, c8 = lane & 7;          // row layout of a half: 8 rows x 8 chunks of 16 bytes per instruction
     const int r4 = lane >> 4, c16 = lane & 15;        // row layout of full rows: 4 rows x 16 chunks
     const int row_end = min(N, (int)(blockIdx.x + 1) * rows_per_wg);
@@ -247,7 +250,11 @@ __global__ __launch_bounds__(512) void linear_apply128_kernel(ApplyArgs a, int r
                     pk.w = __builtin_bit_cast(uint32_t, __builtin_convertvector(x3, bf16x2));
                 }
                 const int row = rb + lrow;
-                if (row < N) *reinterpret_cast<uint4 *>(oh + (size_t)row * D + h * 64 + c8 * 8) = pk;
+                if (EMIT) {
+                    const int c = h * 8 + c8;
+                    u16 *blk = a.emit + ((((size_t)(bh / a.H) * ((N + 31) >> 5) + (rb >> 5)) * a.H + bh % a.H) << 12);
+                    *reinterpret_cast<uint4 *>(blk + (((c >> 1) * 64 + (c & 1) * 32 + lrow) << 3)) = pk;
+                } else if (row < N) *reinterpret_cast<uint4 *>(oh + (size_t)row * D + h * 64 + c8 * 8) = pk;
             }
             asm volatile("" ::: "memory");
         }

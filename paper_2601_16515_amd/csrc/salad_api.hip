@@ -62,7 +62,7 @@ WsLayout ws_layout(int B, int H, int N, int d, int dtype, bool full_proj = false
         w.tile_counts = off; off = align256(off + (need ? sizeof(int32_t) * (size_t)H * ntiles : 0));
     }
     // full Level-1 projection: the unscaled linear branch (bf16, [B,H,N,d]) and W_p in fragment order
-    w.ol = off; off = align256(off + (full_proj ? sizeof(u16) * BH * (size_t)N * d : 0));
+    w.ol = off; off = align256(off + (full_proj ? sizeof(u16) * BH * (size_t)((N + 31) / 32 * 32) * d : 0));   // whole 32-row tiles
     w.wfrag = off; off = align256(off + (full_proj ? sizeof(u16) * (size_t)H * d * H * d : 0));
     w.total = off;
     return w;

@@ -96,13 +96,13 @@ struct ApplyArgs {
     const u16 *hfrag; const float *Z; const float *coef; float eps;
     float *o_linear_dbg;
     const int32_t *drop; int H;     // [B] or null: pruned samples are left as they are (out = O_s)
-    u16 *emit;                      // d = 128: non-null -> write the unscaled O_l (bf16, [B,H,N,d]) here, leave out alone
+    u16 *emit;                      // d = 128: non-null -> write the unscaled O_l (bf16, [B][ceil(N/32)][H] fragment blocks) here, leave out alone
 };
 hipError_t launch_linear_apply_bf16(const ApplyArgs &a, hipStream_t st);
 
 // ---- full Level-1 projection (Alg. 1 "Proj"): out = out + coef[b] * (O_l W_p), d = 128, bf16 ------------------
 struct ProjArgs {
-    const u16 *ol;                  // [B,H,N,128] unscaled linear branch (bf16)
+    const u16 *ol;                  // unscaled linear branch (bf16) as [B][ceil(N/32)][H] blocks of 32 rows in B-operand fragment order
     u16 *out;                       // [B,H,N,128], holds O_s on entry
     const u16 *wfrag;               // [H_in][H_out][128*128] W_p blocks in MFMA A-operand fragment order
     const float *coef;              // [B*H]; entry b*H is lambda * s_b (0 for a pruned sample)

@@ -428,6 +428,30 @@ def test_wan13_480p_90_sampled(oracle):
     assert np.array_equal(fast["out"], res["out"])
 
 
+def test_wan13_480p_full_projection_sampled(oracle):
+    """Alg. 1 "Proj" with the full D x D matrix at the headline size (H = 12, N = 32760: 128 row tiles of the
+    projection GEMM, the last one with 248 rows), in the launch configuration the benchmark times; the oracle
+    evaluates sampled query blocks of every head (first, last = tail, middle, seeded picks)."""
+    w = wl.WAN13_480P
+    say("480p-proj: generating inputs")
+    inp = wl.make_inputs(w)
+    dev = upload(w, inp)
+    kinds = wl.head_kinds(w)
+    kept = [sb.salad_kept_from_sparsity(w.nb, w.sparsity)] * w.H
+    D = w.H * w.d
+    wp = wl.round_to_bf16((wl.normal(w.seed, "w_proj", (D, D)) / np.sqrt(D)).astype(np.float32))
+    wp_dev = torch.from_numpy(wp).cuda().to(torch.bfloat16)
+    say("480p-proj: GPU call")
+    res = run_layer(w, inp, dev, kept, kinds, head_scale=None, w_proj=wp_dev, dbg=False)
+    sel = wl.sample_blocks(w.nb, 4, w.seed)
+    say(f"480p-proj: oracle on {len(sel)} query blocks per head")
+    ref = _oracle_layer(oracle, w, inp, kept, kinds, sel=sel, w_proj=wp.astype(np.float64))
+    ref_ps = _oracle_layer(oracle, w, inp, kept, kinds, sel=sel)
+    assert errors(ref["out"], ref_ps["out"])[1] > 1e-3                 # the projection changes the result
+    compare_layer(res, ref, check_linear=False, label="480p-proj")
+    assert np.isfinite(res["out"]).all()
+
+
 @pytest.mark.parametrize("rho", [0.0, 0.5, 0.75, 0.95])
 def test_wan13_480p_sweep_sampled(oracle, rho):
     """The other points of the sparsity sweep at the 480p shape (same seeded inputs)."""
