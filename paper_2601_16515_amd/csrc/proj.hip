@@ -45,21 +45,24 @@ constexpr int BLK = 128 * 128;   // elements of one (h_in, h_out) block
 // idx = ((c/32 * 8 + a/16) * 64 + ((a%16)/8) * 32 + c%32) * 8 + a%8   (A-operand fragments of the block's transpose)
 __global__ __launch_bounds__(256) void proj_pack_kernel(const u16 *__restrict__ w, int H, u16 *__restrict__ wfrag)
 {
-    // one (h_in, h_out) block per workgroup: rows read in full 256-byte segments into LDS, fragments written 16 bytes
-    // per lane in lane order
-    __shared__ uint32_t tile[128][65];                 // [a][c / 2], padded
-    const int hi = blockIdx.x, ho = blockIdx.y;
+    // a workgroup takes 32 input channels (two d-steps) of one (h_in, h_out) block: rows read in full 256-byte
+    // segments into LDS, the 8 fragments written 16 bytes per lane in lane order
+    __shared__ uint32_t tile[32][65];                  // [a - 32 j][c / 2], padded
+    const int hi = blockIdx.x, ho = blockIdx.y, j = blockIdx.z;
     const size_t D = (size_t)H * 128;
-    const u16 *src = w + (size_t)hi * 128 * D + (size_t)ho * 128;
-    for (int i = threadIdx.x; i < 128 * 64; i += 256) {
+    const u16 *src = w + ((size_t)hi * 128 + 32 * j) * D + (size_t)ho * 128;
+#pragma unroll
+    for (int i = threadIdx.x; i < 32 * 64; i += 256) {
         const int r = i >> 6, c2 = i & 63;
         tile[r][c2] = *reinterpret_cast<const uint32_t *>(src + (size_t)r * D + 2 * c2);
     }
     __syncthreads();
     u16 *dst = wfrag + ((size_t)hi * H + ho) * BLK;
-    for (int t = threadIdx.x; t < BLK / 8; t += 256) {
-        const int c32 = t & 31, h2 = (t >> 5) & 1, u = t >> 6, st = u & 7, ct = u >> 3;
-        const int a0 = st * 16 + h2 * 8, c = ct * 32 + c32;
+#pragma unroll
+    for (int q = threadIdx.x; q < 8 * 64; q += 256) {
+        const int c32 = q & 31, h2 = (q >> 5) & 1, s2 = (q >> 6) & 1, ct = q >> 7;
+        const int t = (ct * 8 + 2 * j + s2) * 64 + h2 * 32 + c32;   // 16-byte slot of the packed block
+        const int a0 = s2 * 16 + h2 * 8, c = ct * 32 + c32;
         uint32_t v[8];
 #pragma unroll
         for (int a8 = 0; a8 < 8; ++a8) v[a8] = (tile[a0 + a8][c >> 1] >> ((c & 1) * 16)) & 0xffffu;
@@ -70,7 +73,7 @@ __global__ __launch_bounds__(256) void proj_pack_kernel(const u16 *__restrict__ 
 
 hipError_t launch_proj_pack(const u16 *w_proj, int H, u16 *wfrag, hipStream_t st)
 {
-    hipLaunchKernelGGL(proj_pack_kernel, dim3(H, H), dim3(256), 0, st, w_proj, H, wfrag);
+    hipLaunchKernelGGL(proj_pack_kernel, dim3(H, H, 4), dim3(256), 0, st, w_proj, H, wfrag);
     return hipGetLastError();
 }
 
