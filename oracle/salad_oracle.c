@@ -21,6 +21,8 @@
  *   static and dynamic scale  Alg. 1 (Level 1 / Level 2 / residual integration), Sec. 4.2
  *   branch dropping           Sec. 4.3, App. A.3 (the linear branch of a sample is pruned when its
  *                             dynamic scale lies below the threshold)
+ *   Top-K block-sparse mask   Sec. 3 "Top-K attention", App. A.1.2 (block means of the keys, query-to-mean
+ *                             similarity, the k best blocks per query token, attention on their tokens)
  *
  * Readings where the paper is silent (all listed in the design notes of the repository):
  *   - the sliding window keeps a constant count of `kept` consecutive KV blocks per query
@@ -33,6 +35,9 @@
  *   - with a full static projection W_p [D x D] (D = H d; row = input channel h_in d + a, column = output
  *     channel h_out d + c) the residual sum is O_s + lambda s_b (O_l W_p), O_l being the heads' linear
  *     outputs concatenated per token; the per-head form is W_p = blockdiag(a_h I);
+ *   - Top-K: key blocks are runs of key_block consecutive tokens of the stored order, the similarity is the
+ *     plain dot product q.mean(K_block), every query token selects for itself, ties go to the lower block
+ *     index, no block is forced in; the selection is computed in float32 in a fixed order (see there);
  *   - "below the threshold" is the strict inequality s_b < tau; a dropped branch contributes
  *     exactly nothing (out = O_s), and tau <= 0 never drops since s_b > 0.
  *
@@ -195,6 +200,122 @@ int salad_oracle_sparse_attn(const float *q, const float *k, const float *v,
         free(krow);
     }
     return bad ? SO_EINVAL : SO_OK;
+}
+
+/* ---- Top-K block-sparse attention, Sec. 3 "Top-K attention", App. A.1.2 ---------------- */
+
+/* Steps 1 and 2 of App. A.1.2: the keys are cut into blocks of key_block consecutive tokens of the stored
+ * order, each block is reduced to the mean of its keys, and every query token keeps the topk blocks whose
+ * mean has the largest dot product with the query.  mask[(b*H + h)*N + n] has bit J set when query n keeps
+ * block J (nbk = ceil(N / key_block) <= 64 blocks; topk >= nbk keeps all of them).
+ *
+ * Here floating point decides an integer, so the decision is taken in the arithmetic the device uses for it,
+ * written out step by step: float32 throughout; a block's sum is accumulated token by token in ascending order
+ * and divided by the token count; a score is accumulated channel by channel in ascending order with a fused
+ * multiply-add; a block replaces a kept one only on a strictly larger score, so ties go to the lower index.
+ * (tests pin the outcome to the float64 definition wherever the float64 scores leave a clear margin). */
+int salad_oracle_topk_select(const float *q, const float *k, int B, int H, int64_t N, int d,
+                             int key_block, int topk, uint64_t *mask)
+{
+    if (key_block <= 0 || topk <= 0 || N <= 0 || d <= 0) return SO_EINVAL;
+    const int64_t nbk = (N + key_block - 1) / key_block;
+    if (nbk > 64) return SO_EINVAL;
+    const int kk = topk < nbk ? topk : (int)nbk;
+    const int64_t BH = (int64_t)B * H;
+    float *mean = (float *)malloc(sizeof(float) * (size_t)(BH * nbk * d));
+    if (!mean) return SO_EINVAL;
+#pragma omp parallel for schedule(static)
+    for (int64_t e = 0; e < BH * nbk; ++e) {
+        const int64_t bh = e / nbk, J = e % nbk;
+        const int64_t t0 = J * key_block, t1 = (t0 + key_block < N) ? t0 + key_block : N;
+        for (int c = 0; c < d; ++c) {
+            volatile float sum = 0.0f;           /* volatile: one rounding per addition, in this order */
+            for (int64_t t = t0; t < t1; ++t) sum = sum + k[(bh * N + t) * d + c];
+            mean[e * d + c] = sum / (float)(t1 - t0);
+        }
+    }
+#pragma omp parallel for schedule(static)
+    for (int64_t e = 0; e < BH * N; ++e) {
+        const int64_t bh = e / N;
+        const float *qi = q + e * d;
+        float best[64];
+        int bidx[64];
+        int cnt = 0;
+        for (int64_t J = 0; J < nbk; ++J) {
+            const float *mj = mean + (bh * nbk + J) * d;
+            float sc = 0.0f;
+            for (int c = 0; c < d; ++c) sc = fmaf(qi[c], mj[c], sc);
+            /* insert into the descending list of the best kk so far; equal scores stay behind earlier blocks */
+            int pos = cnt;
+            while (pos > 0 && sc > best[pos - 1]) --pos;
+            if (pos >= kk) continue;
+            const int last = cnt < kk ? cnt : kk - 1;
+            for (int i = last; i > pos; --i) { best[i] = best[i - 1]; bidx[i] = bidx[i - 1]; }
+            best[pos] = sc;
+            bidx[pos] = (int)J;
+            if (cnt < kk) ++cnt;
+        }
+        uint64_t m = 0;
+        for (int i = 0; i < cnt; ++i) m |= (uint64_t)1 << bidx[i];
+        mask[e] = m;
+    }
+    free(mean);
+    return SO_OK;
+}
+
+/* Step 3 of App. A.1.2: every query token attends to the tokens of the key blocks it kept, Eq. (2) with that
+ * token-level mask: two-pass softmax in double precision over exactly those keys, logits q.k*scale.
+ * rows [B, H, nrows]: stored rows to evaluate (< 0: skipped, output left zero); out [B, H, nrows, d]. */
+int salad_oracle_topk_attn(const float *q, const float *k, const float *v, int B, int H, int64_t N, int d,
+                           int key_block, const uint64_t *mask, double scale,
+                           const int64_t *rows, int64_t nrows, double *out)
+{
+    if (key_block <= 0 || N <= 0 || d <= 0) return SO_EINVAL;
+    const int64_t nbk = (N + key_block - 1) / key_block;
+    if (nbk > 64) return SO_EINVAL;
+    const int64_t total = (int64_t)B * H * nrows;
+#pragma omp parallel
+    {
+        double *logit = (double *)malloc(sizeof(double) * (size_t)N);
+        int64_t *krow = (int64_t *)malloc(sizeof(int64_t) * (size_t)N);
+#pragma omp for schedule(dynamic, 16)
+        for (int64_t idx = 0; idx < total; ++idx) {
+            const int64_t bh = idx / nrows;
+            const int64_t n = rows[idx];
+            double *o = out + idx * d;
+            for (int c = 0; c < d; ++c) o[c] = 0.0;
+            if (n < 0 || n >= N) continue;
+            const float *qi = q + (bh * N + n) * d;
+            const uint64_t m = mask[bh * N + n];
+            int64_t cnt = 0;
+            double mx = -INFINITY;
+            for (int64_t J = 0; J < nbk; ++J) {
+                if (!((m >> J) & 1)) continue;
+                const int64_t t1 = ((J + 1) * key_block < N) ? (J + 1) * key_block : N;
+                for (int64_t t = J * key_block; t < t1; ++t) {
+                    const float *kj = k + (bh * N + t) * d;
+                    double acc = 0.0;
+                    for (int x = 0; x < d; ++x) acc += (double)qi[x] * (double)kj[x];
+                    acc *= scale;
+                    logit[cnt] = acc;
+                    krow[cnt] = t;
+                    if (acc > mx) mx = acc;
+                    ++cnt;
+                }
+            }
+            if (cnt == 0) continue;
+            double denom = 0.0;
+            for (int64_t t = 0; t < cnt; ++t) { logit[t] = exp(logit[t] - mx); denom += logit[t]; }
+            for (int64_t t = 0; t < cnt; ++t) {
+                const float *vj = v + (bh * N + krow[t]) * d;
+                const double wgt = logit[t] / denom;
+                for (int c = 0; c < d; ++c) o[c] += wgt * (double)vj[c];
+            }
+        }
+        free(logit);
+        free(krow);
+    }
+    return SO_OK;
 }
 
 /* ---- ReLU linear attention, Eq. (3) ------------------------------------------------- */

@@ -182,6 +182,39 @@ def combine_proj(q, Hs, Z, eps: float, o_s, rows, w_proj, lam: float, s) -> np.n
     return out
 
 
+def topk_select(q, k, key_block: int, topk: int) -> np.ndarray:
+    """App. A.1.2 steps 1-2: per query token the `topk` key blocks (runs of `key_block` stored tokens) whose mean
+    key has the largest dot product with the query, as a uint64 bit mask [B,H,N] (bit J = block J kept)."""
+    q, k = _f32(q), _f32(k)
+    B, H, N, d = q.shape
+    mask = np.zeros((B, H, N), dtype=np.uint64)
+    rc = _load().salad_oracle_topk_select(_p(q), _p(k), C.c_int(B), C.c_int(H), C.c_int64(N), C.c_int(d),
+                                          C.c_int(key_block), C.c_int(topk), _p(mask))
+    if rc != 0:
+        raise ValueError("salad_oracle_topk_select: invalid arguments (more than 64 key blocks?)")
+    return mask
+
+
+def topk_attn(q, k, v, key_block: int, mask, scale: Optional[float] = None,
+              rows: Optional[np.ndarray] = None) -> np.ndarray:
+    """App. A.1.2 step 3: Eq. (2) with the token-level mask of `topk_select`, on stored rows `rows` [B,H,nrows]
+    (default: every row).  Returns [B,H,nrows,d] float64."""
+    q, k, v = _f32(q), _f32(k), _f32(v)
+    B, H, N, d = q.shape
+    if rows is None:
+        rows = np.broadcast_to(np.arange(N, dtype=np.int64), (B, H, N))
+    rows = np.ascontiguousarray(rows, dtype=np.int64)
+    mask = np.ascontiguousarray(mask, dtype=np.uint64)
+    out = np.zeros((B, H, rows.shape[-1], d), dtype=np.float64)
+    sc = (1.0 / np.sqrt(d)) if scale is None else float(scale)
+    rc = _load().salad_oracle_topk_attn(_p(q), _p(k), _p(v), C.c_int(B), C.c_int(H), C.c_int64(N), C.c_int(d),
+                                        C.c_int(key_block), _p(mask), C.c_double(sc), _p(rows),
+                                        C.c_int64(rows.shape[-1]), _p(out))
+    if rc != 0:
+        raise ValueError("salad_oracle_topk_attn: invalid arguments")
+    return out
+
+
 def branch_drop(s, tau: float) -> np.ndarray:
     """Sec. 4.3: which samples' linear branches are pruned (dynamic scale below the threshold)."""
     s = np.ascontiguousarray(s, dtype=np.float64)
@@ -192,14 +225,24 @@ def branch_drop(s, tau: float) -> np.ndarray:
 
 def salad_forward(q, k, v, x_t, w_gate, head_scale, grid, block, head_kind, kept, lam=1.0, eps=1e-6,
                   b_gate=0.0, scale=None, sel=None, s_override=None, drop_threshold=0.0,
-                  w_proj=None) -> Dict[str, np.ndarray]:
+                  w_proj=None, topk: int = 0, key_block: int = 0) -> Dict[str, np.ndarray]:
     """Whole layer (Alg. 1 from SparseAttn to the residual sum) on the selected query blocks.
 
     Returns compact row sets [B,H,nsel*block,d] for o_sparse, o_linear and out, the stored row
     index of each compact row (`rows`, -1 = beyond N), the full state (Hs, Z) and s [B]."""
     T, Hh, W = grid
     row_ptr, col_idx = block_mask(T, Hh, W, block, kept)
-    o_s, rows = sparse_attn(q, k, v, grid, block, head_kind, row_ptr, col_idx, scale, sel)
+    topk_mask = None
+    if topk > 0:   # Top-K dynamic mask (App. A.1.2) instead of the sliding window; stored token order only
+        N = q.shape[2]
+        nb = (N + block - 1) // block
+        sel_b = np.arange(nb) if sel is None else np.asarray(sel)
+        pos = (sel_b[:, None] * block + np.arange(block)[None, :]).reshape(-1)
+        rows = np.broadcast_to(np.where(pos < N, pos, -1).astype(np.int64), q.shape[:2] + (pos.size,)).copy()
+        topk_mask = topk_select(q, k, key_block, topk)
+        o_s = topk_attn(q, k, v, key_block, topk_mask, scale, rows)
+    else:
+        o_s, rows = sparse_attn(q, k, v, grid, block, head_kind, row_ptr, col_idx, scale, sel)
     Hs, Z = linear_state(k, v)
     o_l = linear_apply(q, Hs, Z, eps, rows)
     s = gate(x_t, w_gate, b_gate) if s_override is None else np.asarray(s_override, dtype=np.float64)
@@ -211,4 +254,4 @@ def salad_forward(q, k, v, x_t, w_gate, head_scale, grid, block, head_kind, kept
     else:
         out = combine(o_s, o_l, lam, head_scale, s_eff)
     return {"o_sparse": o_s, "o_linear": o_l, "out": out, "rows": rows, "Hs": Hs, "Z": Z, "s": s,
-            "row_ptr": row_ptr, "col_idx": col_idx, "dropped": dropped}
+            "row_ptr": row_ptr, "col_idx": col_idx, "dropped": dropped, "topk_mask": topk_mask}

@@ -357,3 +357,116 @@ def test_tiny_config_runs_in_seconds(oracle):
     assert 0.45 < r["s"][0] < 0.55          # w_gate ~ N(0, 0.02^2): pre-activations are small
     # the linear branch is smaller than the sparse one on N(0,1) inputs
     assert np.abs(r["o_linear"]).mean() < 0.5 * np.abs(r["o_sparse"]).mean()
+
+
+# ----------------------------------------------------------------------- Top-K block-sparse mask (App. A.1.2)
+
+def _bits(mask):
+    """uint64 [...] -> bool [..., 64]"""
+    return ((mask[..., None] >> np.arange(64, dtype=np.uint64)) & np.uint64(1)).astype(bool)
+
+
+def _scores64(q, k, key_block):
+    """The plain definition in float64: q . mean of each key block (numpy, not the oracle)."""
+    B, H, N, d = q.shape
+    nbk = -(-N // key_block)
+    means = np.stack([k[:, :, J * key_block:min(N, (J + 1) * key_block)].astype(np.float64).mean(axis=2)
+                      for J in range(nbk)], axis=2)                                  # [B,H,nbk,d]
+    return np.einsum("bhnd,bhjd->bhnj", q.astype(np.float64), means)
+
+
+@pytest.mark.parametrize("B,H,N,d,key_block,topk", [(1, 2, 300, 16, 64, 2), (2, 1, 517, 32, 128, 3),
+                                                    (1, 1, 1000, 128, 64, 4), (1, 2, 130, 8, 64, 1)])
+def test_topk_select_against_float64_definition(oracle, B, H, N, d, key_block, topk):
+    """The float32 fixed-order selection equals the top-k of the float64 scores wherever those leave a clear
+    margin between the k-th and the (k+1)-th block, always keeps exactly k blocks, and never keeps a block whose
+    float64 score is clearly below the k-th (ragged last block: its mean is over its own tokens)."""
+    q, k, _ = _qkv(31, B, H, N, d)
+    q, k = wl.round_to_bf16(q), wl.round_to_bf16(k)
+    sel = _bits(oracle.topk_select(q, k, key_block, topk))
+    sc = _scores64(q, k, key_block)
+    nbk = sc.shape[-1]
+    assert not sel[..., nbk:].any()
+    kk = min(topk, nbk)
+    assert (sel.sum(-1) == kk).all()
+    srt = np.sort(sc, axis=-1)[..., ::-1]
+    kth = srt[..., kk - 1]
+    tol = 1e-4 * np.abs(sc).max()
+    assert (np.where(sel[..., :nbk], sc, np.inf).min(-1) >= kth - tol).all()
+    if kk < nbk:
+        clear = (kth - srt[..., kk]) > tol
+        assert clear.mean() > 0.9                      # the pin bites on almost every query
+        want = sc >= kth[..., None]
+        assert (sel[..., :nbk] == want)[clear].all()
+
+
+def test_topk_select_exact_cases(oracle):
+    """Integer-valued data, where float32 is exact: block J's keys all equal (J+1) e_J, so the score of block J is
+    (J+1) q_J and the selection is the top-k of those integers; equal scores go to the lower block index."""
+    d, key_block, nbk = 8, 64, 6
+    N = key_block * nbk - 10                           # ragged last block (constant keys: the mean is unchanged)
+    k = np.zeros((1, 1, N, d), dtype=np.float32)
+    for J in range(nbk):
+        k[0, 0, J * key_block:(J + 1) * key_block, J] = J + 1
+    rng = np.random.default_rng(5)
+    q = rng.integers(-4, 5, size=(1, 1, N, d)).astype(np.float32)
+    sc = q[0, 0, :, :nbk] * np.arange(1, nbk + 1)
+    for topk in (1, 2, 4):
+        sel = _bits(oracle.topk_select(q, k, key_block, topk))[0, 0, :, :nbk]
+        order = np.argsort(-sc, axis=-1, kind="stable")[:, :topk]     # stable: ties keep the lower index first
+        want = np.zeros_like(sel)
+        np.put_along_axis(want, order, True, axis=-1)
+        assert (sel == want).all()
+    # all keys identical: every score ties, the first k blocks win
+    k1 = np.ones((1, 1, N, d), dtype=np.float32)
+    sel = _bits(oracle.topk_select(q, k1, key_block, 3))[0, 0]
+    assert sel[:, :3].all() and not sel[:, 3:].any()
+    # k >= number of blocks keeps everything
+    sel = _bits(oracle.topk_select(q, k, key_block, 99))[0, 0]
+    assert sel[:, :nbk].all() and not sel[:, nbk:].any()
+
+
+def test_topk_attention_against_masked_softmax(oracle):
+    """Step 3: attention over the tokens of the kept blocks = a library softmax over a token mask built here;
+    with every block kept it is dense attention."""
+    B, H, N, d, key_block = 1, 2, 333, 16, 64
+    q, k, v = _qkv(37, B, H, N, d)
+    rng = np.random.default_rng(11)
+    nbk = -(-N // key_block)
+    mask = np.zeros((B, H, N), dtype=np.uint64)
+    pick = rng.random((B, H, N, nbk)) < 0.4
+    pick[..., 0] |= ~pick.any(-1)                      # at least one block each
+    for J in range(nbk):
+        mask |= pick[..., J].astype(np.uint64) << np.uint64(J)
+    out = oracle.topk_attn(q, k, v, key_block, mask)
+    tok = np.repeat(pick, key_block, axis=-1)[..., :N]                        # [B,H,N(query),N(key)]
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(q).double(), torch.from_numpy(k).double(), torch.from_numpy(v).double(),
+        attn_mask=torch.from_numpy(tok)).numpy()
+    assert np.abs(out - ref).max() < 1e-12
+    full = np.full((B, H, N), (1 << nbk) - 1, dtype=np.uint64)
+    dense = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(q).double(), torch.from_numpy(k).double(), torch.from_numpy(v).double()).numpy()
+    assert np.abs(oracle.topk_attn(q, k, v, key_block, full) - dense).max() < 1e-12
+    # rows argument: a subset in another order, negative entries skipped
+    rows = np.broadcast_to(np.array([5, -1, 332, 64], dtype=np.int64), (B, H, 4)).copy()
+    sub = oracle.topk_attn(q, k, v, key_block, mask, rows=rows)
+    assert np.abs(sub[:, :, [0, 2, 3]] - ref[:, :, [5, 332, 64]]).max() < 1e-12 and (sub[:, :, 1] == 0).all()
+
+
+def test_topk_layer(oracle):
+    """The whole layer with the Top-K mask: the sparse branch is topk_attn on the selected mask, the rest of the
+    layer is unchanged; keeping every block reproduces the dense layer."""
+    w = wl.small("topk", 1, 2, 16, 3, 5, 9, "f32", 0.5, seed=41)              # N = 135
+    inp = wl.make_inputs(w)
+    kinds = np.zeros(w.H, dtype=np.uint8)
+    common = dict(grid=(w.T, w.Hh, w.W), block=w.block, head_kind=kinds, lam=1.5)
+    args = (inp["q"], inp["k"], inp["v"], inp["x_t"], inp["w_gate"], inp["head_scale"])
+    r = oracle.salad_forward(*args, kept=[1] * w.H, topk=2, key_block=64, **common)
+    m = oracle.topk_select(inp["q"], inp["k"], 64, 2)
+    assert np.array_equal(r["topk_mask"], m)
+    ok = r["rows"][0, 0] >= 0
+    assert np.abs(r["o_sparse"][:, :, ok] - oracle.topk_attn(inp["q"], inp["k"], inp["v"], 64, m)).max() < 1e-14
+    dense = oracle.salad_forward(*args, kept=[w.nb] * w.H, **common)
+    allk = oracle.salad_forward(*args, kept=[1] * w.H, topk=64, key_block=64, **common)
+    assert np.abs(dense["out"] - allk["out"]).max() < 1e-12
