@@ -108,6 +108,12 @@ typedef struct salad_fwd_params {
     const void *w_proj;       /* optional device bf16 [H*d, H*d], row-major, row = input channel h_in*d + a,
                                  column = output channel h_out*d + c: the full Level-1 projection (Alg. 1
                                  "Proj").  Needs dtype bf16, d = 128 and head_scale == NULL                */
+    int32_t topk;             /* > 0: Top-K dynamic block mask (Sec. 3 "Top-K attention", App. A.1.2) instead of the
+                                 CSR: every query token keeps the topk (<= 8) key blocks whose mean key has the
+                                 largest dot product with it; row_ptr / col_idx are ignored (may be NULL).  Needs
+                                 dtype bf16, d = 128, all heads SPATIAL (blocks are runs of the stored order)    */
+    int32_t topk_key_block;   /* tokens per key block: a multiple of 64 with ceil(N / topk_key_block) <= 64         */
+    uint64_t *topk_mask_out;  /* optional device uint64 [B,H,N]: bit J set = the query keeps key block J            */
 } salad_fwd_params;
 
 /* Run the linear apply and the scale-and-sum as a separate streaming kernel after the sparse
@@ -115,8 +121,9 @@ typedef struct salad_fwd_params {
 #define SALAD_FLAG_UNFUSED_EPILOGUE 1
 
 /* Device scratch the forward needs for these shapes (partial states, partial gate sums, the
- * reduced state, per-tile block lists; with w_proj also O_l and the rearranged W_p).  Reads only B, H, N, d,
- * dtype and whether w_proj is NULL.  0 on invalid shapes. */
+ * reduced state, per-tile block lists; with w_proj also O_l and the rearranged W_p; with topk the key-block means,
+ * the masks and per-sample lists).  Reads only B, H, N, d, dtype, whether w_proj is NULL and whether topk > 0.
+ * 0 on invalid shapes. */
 size_t salad_fwd_workspace_bytes(const salad_fwd_params *p);
 
 /* Alg. 1 from SparseAttn to the residual sum:
@@ -130,6 +137,11 @@ size_t salad_fwd_workspace_bytes(const salad_fwd_params *p);
  * (per-head form: W_p = blockdiag(a_h I)).  It runs as separate kernels after the sparse kernel: O_l is written
  * to the workspace (bf16), W_p is rearranged into MFMA fragment order, and one bf16 MFMA GEMM adds lambda s_b O_l W_p
  * to O_s (fp32 accumulation, one rounding of the sum).  o_linear_dbg is not written in this mode.
+ * With topk > 0 the sparse branch uses the Top-K block mask of App. A.1.2 in place of the CSR: the keys are cut into
+ * blocks of topk_key_block consecutive stored tokens, each block is reduced to its mean key, every query token
+ * keeps the topk blocks with the largest q.mean and attends to exactly their tokens.  The selection runs on the
+ * device in a fixed float32 order (block sums token by token, scores channel by channel with fused multiply-adds,
+ * ties to the lower block index), so that it can be reproduced bit for bit.
  * Post-tuning branch dropping (Sec. 4.3, App. A.3): with drop_threshold = tau > 0, a sample whose dynamic
  * scale s_b < tau (strict, compared in fp32) loses its linear branch: out[b] = O_s[b], exactly as with
  * lambda == 0.  The decision is taken on the device (no host synchronisation): the gate is reduced first,

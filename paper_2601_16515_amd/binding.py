@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(_HERE, "libsalad.so")
 SOURCES = ["salad_api.hip", "mask_gate_finalize.hip", "linear_state.hip", "sparse_attn.hip",
-           "sparse_attn_v2.hip", "sparse_attn_v5.hip", "linear_apply.hip", "proj.hip"]
+           "sparse_attn_v2.hip", "sparse_attn_v5.hip", "linear_apply.hip", "proj.hip", "topk.hip"]
 
 SALAD_OK, SALAD_EINVAL, SALAD_ENOTSUP, SALAD_ENOSPC, SALAD_EHIP = range(5)
 SALAD_F32, SALAD_BF16 = 0, 1
@@ -62,6 +62,9 @@ class FwdParams(C.Structure):
         ("drop_threshold", C.c_float),
         ("dropped_out", C.c_void_p),
         ("w_proj", C.c_void_p),
+        ("topk", C.c_int32),
+        ("topk_key_block", C.c_int32),
+        ("topk_mask_out", C.c_void_p),
     ]
 
 
@@ -172,19 +175,22 @@ def salad_block_mask(T: int, Hh: int, W: int, block: int, kept: Sequence[int], d
     return row_ptr, col_idx[:nnz]
 
 
-def salad_fwd_workspace_bytes(B: int, H: int, N: int, d: int, dtype: int, full_proj: bool = False) -> int:
+def salad_fwd_workspace_bytes(B: int, H: int, N: int, d: int, dtype: int, full_proj: bool = False,
+                              topk: bool = False) -> int:
     p = FwdParams()
     p.B, p.H, p.N, p.d, p.dtype = B, H, N, d, dtype
     p.w_proj = 1 if full_proj else None          # the query only looks at whether the pointer is NULL
+    p.topk = 1 if topk else 0                    # ... and at whether topk is positive
     return int(lib().salad_fwd_workspace_bytes(C.byref(p)))
 
 
 class Workspace:
     """Caller-owned scratch for the layer call, sized by the library's query."""
 
-    def __init__(self, B: int, H: int, N: int, d: int, dtype: int, device="cuda", full_proj: bool = False):
+    def __init__(self, B: int, H: int, N: int, d: int, dtype: int, device="cuda", full_proj: bool = False,
+                 topk: bool = False):
         import torch
-        self.bytes = salad_fwd_workspace_bytes(B, H, N, d, dtype, full_proj)
+        self.bytes = salad_fwd_workspace_bytes(B, H, N, d, dtype, full_proj, topk)
         self.buf = torch.empty(max(self.bytes, 256) + 256, dtype=torch.uint8, device=device)
         self.ptr = (self.buf.data_ptr() + 255) & ~255
 
@@ -193,7 +199,8 @@ def make_fwd_params(q, k, v, out, grid: Tuple[int, int, int], row_ptr, col_idx, 
                     lam: float = 1.0, head_scale=None, s=None, x_t=None, w_gate=None, b_gate: float = 0.0,
                     eps: float = 1e-6, softmax_scale: float = 0.0, s_out=None, o_sparse_dbg=None,
                     o_linear_dbg=None, workspace: Optional[Workspace] = None, flags: int = 0, block: int = 64,
-                    drop_threshold: float = 0.0, dropped_out=None, w_proj=None):
+                    drop_threshold: float = 0.0, dropped_out=None, w_proj=None, topk: int = 0,
+                    topk_key_block: int = 0, topk_mask_out=None):
     """Fill a salad_fwd_params from torch tensors.  Returns (params, keepalive)."""
     B, H, N, d = q.shape
     p = FwdParams()
@@ -202,7 +209,7 @@ def make_fwd_params(q, k, v, out, grid: Tuple[int, int, int], row_ptr, col_idx, 
     p.T, p.Hh, p.W = grid
     p.block = block
     p.q, p.k, p.v, p.out = q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr()
-    p.row_ptr, p.col_idx = row_ptr.data_ptr(), col_idx.data_ptr()
+    p.row_ptr, p.col_idx = _ptr(row_ptr), _ptr(col_idx)
     hk = None
     if head_kind is not None:
         hk = (C.c_uint8 * H)(*[int(x) for x in head_kind])
@@ -227,6 +234,7 @@ def make_fwd_params(q, k, v, out, grid: Tuple[int, int, int], row_ptr, col_idx, 
     p.drop_threshold = drop_threshold
     p.dropped_out = _ptr(dropped_out)
     p.w_proj = _ptr(w_proj)
+    p.topk, p.topk_key_block, p.topk_mask_out = int(topk), int(topk_key_block), _ptr(topk_mask_out)
     return p, (hk, workspace)
 
 
@@ -240,7 +248,8 @@ def salad_sparse_linear_attn_fwd(q, k, v, grid, row_ptr, col_idx, head_kind=None
     if out is None:
         out = torch.empty_like(q)
     if kw.get("workspace") is None:
-        kw["workspace"] = Workspace(B, H, N, d, _dtype_code(q), q.device, full_proj=kw.get("w_proj") is not None)
+        kw["workspace"] = Workspace(B, H, N, d, _dtype_code(q), q.device, full_proj=kw.get("w_proj") is not None,
+                                    topk=kw.get("topk", 0) > 0)
     p, keep = make_fwd_params(q, k, v, out, grid, row_ptr, col_idx, head_kind, **kw)
     _check(lib().salad_sparse_linear_attn_fwd(C.byref(p)))
     return out

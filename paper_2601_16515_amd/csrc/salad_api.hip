@@ -36,11 +36,11 @@ salad_status hip_fail(hipError_t e, const char *what)
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct WsLayout {
-    size_t gate_partial, state_partial, Hs, Z, hfrag, s, coef, drop, tile_lists, tile_counts, ol, wfrag, total;
+    size_t gate_partial, state_partial, Hs, Z, hfrag, s, coef, drop, tile_lists, tile_counts, ol, wfrag, kmeans, topk_mask, total;
     int nparts, P;
 };
 
-WsLayout ws_layout(int B, int H, int N, int d, int dtype, bool full_proj = false)
+WsLayout ws_layout(int B, int H, int N, int d, int dtype, bool full_proj = false, bool topk = false)
 {
     WsLayout w{};
     const size_t BH = (size_t)B * H;
@@ -58,12 +58,16 @@ WsLayout ws_layout(int B, int H, int N, int d, int dtype, bool full_proj = false
     {   // union lists per (head, 4-block tile) for the large-tile attention kernel
         const int nb = (N + 63) / 64, ntiles = (nb + 3) / 4;
         const bool need = dtype == SALAD_BF16 && d == 128 && (size_t)tile_list_cap(nb) * 4 <= 24 * 1024;
-        w.tile_lists = off; off = align256(off + (need ? sizeof(uint32_t) * (size_t)H * ntiles * tile_list_cap(nb) : 0));
-        w.tile_counts = off; off = align256(off + (need ? sizeof(int32_t) * (size_t)H * ntiles : 0));
+        const size_t nl = topk ? BH : (size_t)H;       // Top-K masks differ between samples
+        w.tile_lists = off; off = align256(off + (need ? sizeof(uint32_t) * nl * ntiles * tile_list_cap(nb) : 0));
+        w.tile_counts = off; off = align256(off + (need ? sizeof(int32_t) * nl * ntiles : 0));
     }
     // full Level-1 projection: the unscaled linear branch (bf16, [B,H,N,d]) and W_p in fragment order
     w.ol = off; off = align256(off + (full_proj ? sizeof(u16) * BH * (size_t)((N + 31) / 32 * 32) * d : 0));   // whole 32-row tiles
     w.wfrag = off; off = align256(off + (full_proj ? sizeof(u16) * (size_t)H * d * H * d : 0));
+    // Top-K mask: mean keys of up to 64 key blocks per head, and the per-query block masks
+    w.kmeans = off; off = align256(off + (topk ? sizeof(float) * BH * 64 * (size_t)d : 0));
+    w.topk_mask = off; off = align256(off + (topk ? sizeof(uint64_t) * BH * (size_t)N : 0));
     w.total = off;
     return w;
 }
@@ -157,7 +161,7 @@ salad_status salad_block_mask(int32_t T, int32_t Hh, int32_t W, int32_t block, i
 size_t salad_fwd_workspace_bytes(const salad_fwd_params *p)
 {
     if (!p || !shape_ok(p->B, p->H, p->N, p->d, p->dtype)) return 0;
-    return ws_layout(p->B, p->H, p->N, p->d, p->dtype, p->w_proj != nullptr).total;
+    return ws_layout(p->B, p->H, p->N, p->d, p->dtype, p->w_proj != nullptr, p->topk > 0).total;
 }
 
 salad_status salad_linear_state_fwd(const void *k, const void *v, int32_t B, int32_t H, int32_t N, int32_t d,
@@ -226,7 +230,22 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
     if (!shape_ok(p->B, p->H, p->N, p->d, p->dtype)) return fail(SALAD_EINVAL, "fwd: tensor too large");
     if (!p->q || !p->k || !p->v || !p->out) return fail(SALAD_EINVAL, "fwd: q, k, v, out must be non-null");
     if (p->out == p->q || p->out == p->k || p->out == p->v) return fail(SALAD_EINVAL, "fwd: out aliases an input");
-    if (!p->row_ptr || !p->col_idx) return fail(SALAD_EINVAL, "fwd: CSR pointers must be non-null");
+    const bool topk = p->topk > 0;
+    if (p->topk < 0) return fail(SALAD_EINVAL, "fwd: topk must be >= 0");
+    if (!topk && (!p->row_ptr || !p->col_idx)) return fail(SALAD_EINVAL, "fwd: CSR pointers must be non-null");
+    int nbk = 0;
+    if (topk) {
+        if (p->dtype != SALAD_BF16 || p->d != 128) return fail(SALAD_ENOTSUP, "fwd: topk needs dtype bf16 and d = 128");
+        if (p->topk > 8) return fail(SALAD_ENOTSUP, "fwd: topk = %d above 8", p->topk);
+        if (p->topk_key_block < 64 || p->topk_key_block % 64) return fail(SALAD_EINVAL, "fwd: topk_key_block = %d must be a positive multiple of 64", p->topk_key_block);
+        nbk = (p->N + p->topk_key_block - 1) / p->topk_key_block;
+        if (nbk > 64) return fail(SALAD_ENOTSUP, "fwd: %d key blocks above 64 (raise topk_key_block)", nbk);
+        if (p->head_kind_host)
+            for (int h = 0; h < p->H; ++h)
+                if (p->head_kind_host[h] != SALAD_HEAD_SPATIAL) return fail(SALAD_ENOTSUP, "fwd: topk works on the stored token order (head %d is not SPATIAL)", h);
+        if ((size_t)tile_list_cap((p->N + 63) / 64) * 4 > 24 * 1024 || (unsigned long long)p->N * 256ull >= (1ull << 32))
+            return fail(SALAD_ENOTSUP, "fwd: topk: N = %d too long for the large-tile kernel", p->N);
+    }
     if (p->phi != SALAD_PHI_RELU) return fail(SALAD_ENOTSUP, "fwd: feature map %d not supported (ReLU only)", p->phi);
     if (!(p->eps >= 0.f)) return fail(SALAD_EINVAL, "fwd: eps must be >= 0");
     if (!(p->softmax_scale >= 0.f) || !std::isfinite(p->softmax_scale)) return fail(SALAD_EINVAL, "fwd: softmax_scale must be finite and >= 0");
@@ -248,7 +267,7 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
         if (p->dtype != SALAD_BF16 || p->d != 128) return fail(SALAD_ENOTSUP, "fwd: w_proj needs dtype bf16 and d = 128");
         if (p->head_scale) return fail(SALAD_EINVAL, "fwd: w_proj and head_scale exclude each other");
     }
-    const WsLayout w = ws_layout(p->B, p->H, p->N, p->d, p->dtype, p->w_proj != nullptr);
+    const WsLayout w = ws_layout(p->B, p->H, p->N, p->d, p->dtype, p->w_proj != nullptr, topk);
     const bool need_lists = p->dtype == SALAD_BF16 && p->d == 128 && (size_t)tile_list_cap((p->N + 63) / 64) * 4 <= 24 * 1024;
     if (use_linear || need_lists) {
         if (!p->workspace || ((uintptr_t)p->workspace & 255)) return fail(SALAD_EINVAL, "fwd: workspace null or not 256-byte aligned");
@@ -340,7 +359,25 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
     a.o_sparse_dbg = p->o_sparse_dbg; a.o_linear_dbg = unfused ? nullptr : p->o_linear_dbg;
     a.write_sparse_only = unfused;
     a.drop = drop;
-    if (need_lists) {
+    if (topk) {
+        // App. A.1.2: key-block means -> per-query selection -> per-tile visit lists; the mask never leaves the device
+        float *means = (float *)(ws + w.kmeans);
+        unsigned long long *mask = (unsigned long long *)(ws + w.topk_mask);
+        e = launch_kblock_mean((const u16 *)p->k, BH, p->N, p->topk_key_block, nbk, means, st);
+        if (e != hipSuccess) return hip_fail(e, "key-block mean launch");
+        e = launch_topk_select((const u16 *)p->q, means, BH, p->N, nbk, p->topk, mask, st);
+        if (e != hipSuccess) return hip_fail(e, "top-k selection launch");
+        if (p->topk_mask_out) {
+            e = hipMemcpyAsync(p->topk_mask_out, mask, sizeof(uint64_t) * (size_t)BH * p->N, hipMemcpyDeviceToDevice, st);
+            if (e != hipSuccess) return hip_fail(e, "top-k mask copy");
+        }
+        a.tile_lists = (const uint32_t *)(ws + w.tile_lists);
+        a.tile_counts = (const int32_t *)(ws + w.tile_counts);
+        a.list_cap = tile_list_cap(a.nb);
+        a.topk_mask = mask;
+        e = launch_topk_tile_lists(mask, BH, p->N, a.nb, p->topk_key_block, nbk, (uint32_t *)(ws + w.tile_lists), (int32_t *)(ws + w.tile_counts), st);
+        if (e != hipSuccess) return hip_fail(e, "top-k tile list launch");
+    } else if (need_lists) {
         a.tile_lists = (const uint32_t *)(ws + w.tile_lists);
         a.tile_counts = (const int32_t *)(ws + w.tile_counts);
         a.list_cap = tile_list_cap(a.nb);

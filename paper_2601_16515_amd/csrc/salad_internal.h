@@ -79,6 +79,10 @@ struct AttnArgs {
     const int32_t *tile_counts;     // [H * ntiles4]
     int list_cap;
     const int32_t *drop;            // [B] or null: samples whose linear branch is pruned (out = O_s)
+    // Top-K token-level mask (App. A.1.2), large-tile kernel only: bit J of topk_mask[(b*H + h)*N + n] = query n
+    // keeps key block J; tile_lists / tile_counts are then per (b, h, tile) with entries
+    // block | J << 16 | wave mask << 24.  null: block rows (CSR) as above.
+    const unsigned long long *topk_mask;
 };
 hipError_t launch_sparse_attn_bf16(const AttnArgs &a, hipStream_t st);
 // union lists of the CSR rows of every 4-query-block tile (input of the large-tile attention kernel)
@@ -88,6 +92,17 @@ hipError_t launch_tile_lists(const int32_t *row_ptr, const int32_t *col_idx, int
 hipError_t launch_sparse_attn_f32(const AttnArgs &a, hipStream_t st);
 hipError_t launch_sparse_attn_v2(const AttnArgs &a, hipStream_t st);   // d = 128 only
 hipError_t launch_sparse_attn_v5(const AttnArgs &a, hipStream_t st);   // d = 128 only
+
+// ---- Top-K dynamic mask (App. A.1.2), d = 128 bf16 ---------------------------------------------------------
+// means [BH][nbk][128] fp32: mean key of each run of key_block stored tokens (sequential fp32 sum / count)
+hipError_t launch_kblock_mean(const u16 *k, int BH, int N, int key_block, int nbk, float *means, hipStream_t st);
+// mask [BH][N]: bit J set for the topk key blocks with the largest q.mean (fp32, channels in ascending order,
+// fused multiply-add; ties to the lower index)
+hipError_t launch_topk_select(const u16 *q, const float *means, int BH, int N, int nbk, int topk,
+                              unsigned long long *mask, hipStream_t st);
+// per (b, h, tile of 256 queries): the 64-token blocks of every key block some query of the tile keeps
+hipError_t launch_topk_tile_lists(const unsigned long long *mask, int BH, int N, int nb, int key_block, int nbk,
+                                  uint32_t *lists, int32_t *counts, hipStream_t st);
 
 // ---- unfused linear apply + scale + sum (bf16): out = out + coef * phi(Q) Hs / (phi(Q).Z + eps) ----
 struct ApplyArgs {

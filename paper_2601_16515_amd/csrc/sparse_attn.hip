@@ -322,6 +322,10 @@ hipError_t launch_sparse_attn_bf16(const AttnArgs &a, hipStream_t st)
     // d = 128: the large-tile ping-pong kernel unless its block list does not fit in LDS or a variant is
     // forced (attn_variant & 15: 0 = automatic, 1 = double-buffered 128-row kernel, 2 = first-generation kernel)
     const int variant = g_attn_variant & 15;
+    if (a.topk_mask) {   // token-level mask: the large-tile kernel only (the host checks that the shape fits it)
+        if (a.D != 128 || !a.tile_lists) return hipErrorInvalidValue;
+        return launch_sparse_attn_v5(a, st);
+    }
     if (a.D == 128 && variant != 2) {
         // the large-tile kernel addresses rows with 32-bit byte offsets and divides by T with a
         // multiply (t_magic); a T = 1 grid makes the temporal order the identity

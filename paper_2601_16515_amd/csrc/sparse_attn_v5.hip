@@ -189,7 +189,10 @@ hipError_t launch_tile_lists(const int32_t *row_ptr, const int32_t *col_idx, int
 // priority of the vector phase, 7 of the matrix phase, 8 recomputes the row maximum for every block, 9 drops
 // the per-block barrier (timing only: results are wrong), 10 always fetches block 0, 11 keeps the prefetch's
 // address arithmetic but not its loads.
-template <int PD, bool DBG, int SKIP>
+// TOPK: token-level Top-K mask (App. A.1.2) instead of block rows.  The tile lists are per (sample, head, tile);
+// an entry is block | key-block index << 16 | wave mask << 24 (bit 24 + w: some query of wave w keeps the block);
+// each lane tests its own query's bit of a.topk_mask and contributes nothing for a block it did not select.
+template <int PD, bool DBG, int SKIP, bool TOPK = false>
 __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int ntiles, int total, int per_xcd, int list_cap, long long *trace, int trace_block)
 {
     constexpr int skip = SKIP;
@@ -208,8 +211,9 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
     const int bh = L / ntiles, tile = L - bh * ntiles;
     const int h = bh % a.H;
     const int N = a.N, T = a.T, HW = a.HW, nb = a.nb;
-    const int kind = T > 1 ? (int)((a.kind_mask >> h) & 1ull) : 0;
+    const int kind = (T > 1 && !TOPK) ? (int)((a.kind_mask >> h) & 1ull) : 0;
     const unsigned magic = a.t_magic;
+    constexpr uint32_t BLKMASK = TOPK ? 0xffffu : 0xffffffu;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hh = lane >> 5;
@@ -227,7 +231,7 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
 
     const int qsub = wave >> 1;
     const int qblk = tile * 4 + qsub;
-    const unsigned mybit = qblk < nb ? (1u << (24 + qsub)) : 0u;
+    const unsigned mybit = qblk < nb ? (1u << (24 + (TOPK ? (wave & 7) : qsub))) : 0u;
     const int qpos = qblk * 64 + (wave & 1) * 32 + l32;
     const bool qvalid = (qblk < nb) && (qpos < N);
     const int qrow = row_of_position5(kind, qvalid ? qpos : N - 1, T, HW, magic);
@@ -239,9 +243,15 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
 
     // ---- this tile's union list (built by the pre-pass): the whole row of list_cap slots is copied, so
     // the copy does not wait for the count (slots past the count hold stale words that are never used)
-    const int n = a.tile_counts[h * ntiles + tile];
+    const int n = a.tile_counts[(TOPK ? bh : h) * ntiles + tile];
+    uint32_t qm_lo = 0u, qm_hi = 0u;     // TOPK: this lane's query's key-block bits
+    if (TOPK && qvalid) {
+        const unsigned long long m = a.topk_mask[(size_t)bh * N + qrow];
+        qm_lo = (uint32_t)m;
+        qm_hi = (uint32_t)(m >> 32);
+    }
     {
-        const uint32_t *src = a.tile_lists + ((size_t)h * ntiles + tile) * list_cap;
+        const uint32_t *src = a.tile_lists + ((size_t)(TOPK ? bh : h) * ntiles + tile) * list_cap;
         for (int i = tid; i < list_cap; i += 512) blist[i] = src[i];
     }
     __syncthreads();
@@ -250,6 +260,7 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
 #pragma unroll
     for (int s = 0; s < NS; ++s)
         asm volatile("" : "+v"(qf[s].w[0]), "+v"(qf[s].w[1]), "+v"(qf[s].w[2]), "+v"(qf[s].w[3]));
+    asm volatile("" : "+v"(qm_lo), "+v"(qm_hi));
 
     const float c2 = a.scale * 1.44269504088896340736f;   // logits are handled in the log2 domain
 
@@ -302,7 +313,7 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[i][r] = 0.f;
     float m_run = 0.f, l_run = 0.f;
-    bool have_ref = false;                 // wave-uniform: m_run has been set from a block's true maximum
+    bool have_ref = false;                 // m_run has been set from a block's true maximum (wave-uniform unless TOPK)
     f32x16 s[2];
     Frag5 pf[4];
 
@@ -360,7 +371,17 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
         for (int i = 0; i < RING; ++i) read_frag(16 + i, nullptr, Kt, ring[(16 + i) % RING]);
         run_steps(nullptr, Kt, 16, 32);
     };
-    auto stage_softmax = [&](int blk) INL {
+    auto stage_softmax = [&](uint32_t e) INL {
+        const int blk = (int)(e & BLKMASK);
+        // TOPK: a lane whose query did not select this key block gets P = 0 (scale 0, reference +inf) and takes
+        // no part in the reference updates
+        bool sel = true;
+        if (TOPK) {
+            const int J = (int)((e >> 16) & 63u);
+            sel = (((J & 32) ? qm_hi : qm_lo) >> (J & 31)) & 1u;
+        }
+        const float cs = (TOPK && !sel) ? 0.f : c2;
+        const float ms = (TOPK && !sel) ? INFINITY : m_run;
         if (skip & 1) {   // development: keep S alive and P defined without doing the work
 #pragma unroll
             for (int i = 0; i < 4; ++i)
@@ -374,7 +395,7 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
             for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
-                    if (kbase + kt * 32 + 16 * (r >> 3) + (r & 7) >= N) s[kt][r] = -INFINITY;
+                    if (kbase + kt * 32 + 16 * (r >> 3) + (r & 7) >= N) s[kt][r] = TOPK ? -1e30f : -INFINITY;   // TOPK: stays finite times a zero scale
         }
         // P = 2^(S c2 - m) rounded to bf16; returns the lane's sum of the rounded values (what the PV product sees)
         auto exp_pack = [&]() INL -> float {
@@ -383,8 +404,9 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
             for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
                 for (int r = 0; r < 16; r += 2) {
-                    const uint32_t w = pack2e(__builtin_amdgcn_exp2f(fmaf(s[kt][r], c2, -m_run)),
-                                              __builtin_amdgcn_exp2f(fmaf(s[kt][r + 1], c2, -m_run)));
+                    const float mref = TOPK ? (sel ? m_run : ms) : m_run;
+                    const uint32_t w = pack2e(__builtin_amdgcn_exp2f(fmaf(s[kt][r], cs, -mref)),
+                                              __builtin_amdgcn_exp2f(fmaf(s[kt][r + 1], cs, -mref)));
                     pf[kt * 2 + (r >> 3)].w[(r & 7) >> 1] = w;
                     if (r & 2) ps1 = add_bf16_pair(ps1, w); else ps0 = add_bf16_pair(ps0, w);
                 }
@@ -397,10 +419,10 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
         // sums say that some logit rose more than 13 binades above the reference (or no reference exists
         // yet): then the reference moves to the true maximum and the block is redone.
         float psum = 0.f;
-        bool redo = !have_ref || (skip & 256);
-        if (have_ref && !(skip & 256)) {
+        bool redo = (sel && !have_ref) || (skip & 256);
+        if (!redo) {
             psum = exp_pack();
-            redo = __any(!(psum <= 8192.f));
+            redo = __any(!(psum <= 8192.f)) && sel;
         }
         if (redo) {
             float mx = s[0][0];
@@ -441,7 +463,7 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
     if (n > 0) {
 #pragma unroll
         for (int b = 0; b < PD; ++b)
-            if (b < n && !(skip & 8)) fetch((int)(entry(b) & 0xffffffu), b, b);
+            if (b < n && !(skip & 8)) fetch((int)(entry(b) & BLKMASK), b, b);
         uint32_t e_prev = 0u;
         uint32_t eq[PD];                          // eq[i] = entry j + i
 #pragma unroll
@@ -488,16 +510,16 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
                 TSTAMP(2);
                 if (skip & 64) __builtin_amdgcn_s_setprio(3);
                 if (dS) preload_V(Vc);                  // for PV(j) in the next iteration; lands under the softmax
-                if (dM0) stage_softmax((int)(e_cur & 0xffffffu));
+                if (dM0) stage_softmax(e_cur);
                 TSTAMP(3);
-                if (do_fetch) fetch((int)(e_f & 0xffffffu), kslot_f, vslot_f);
+                if (do_fetch) fetch((int)(e_f & BLKMASK), kslot_f, vslot_f);
                 if (skip & 64) __builtin_amdgcn_s_setprio(0);
             } else {
                 if (skip & 64) __builtin_amdgcn_s_setprio(3);
                 if (dP) preload_V(Vt);                  // for PV(j-1) right after the barrier; lands under the softmax
-                if (dM1) stage_softmax((int)(e_prev & 0xffffffu));
+                if (dM1) stage_softmax(e_prev);
                 TSTAMP(1);
-                if (do_fetch) fetch((int)(e_f & 0xffffffu), kslot_f, vslot_f);
+                if (do_fetch) fetch((int)(e_f & BLKMASK), kslot_f, vslot_f);
                 if (skip & 64) __builtin_amdgcn_s_setprio(0);
                 if (skip & 16) __builtin_amdgcn_s_barrier();
                 asm volatile("" ::: "memory");
@@ -525,7 +547,7 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
             int vslot_prev = vslot - 1; if (vslot_prev < 0) vslot_prev += NV;
             const u16 *Vt = Vb + vslot_prev * TILE;
             const bool kP = (e_prev & mybit) != 0;
-            if (group == 1 && kP) { preload_V(Vt); stage_softmax((int)(e_prev & 0xffffffu)); }
+            if (group == 1 && kP) { preload_V(Vt); stage_softmax(e_prev); }
             if (kP && !(skip & 4)) stage_PV(Vt);
         }
     }
@@ -612,7 +634,7 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
 #undef TSTAMP
 }
 
-template <int PD, bool DBG, int SKIP>
+template <int PD, bool DBG, int SKIP, bool TOPK = false>
 static hipError_t launch_v5(const AttnArgs &a, hipStream_t st)
 {
     const int ntiles = (a.nb + 3) / 4;
@@ -623,7 +645,7 @@ static hipError_t launch_v5(const AttnArgs &a, hipStream_t st)
     static_assert(PD + 1 >= 4, "the epilogue stages 64 KB of state fragments in the K ring");
     constexpr int kMaxDyn = 160 * 1024 - 2048;   // the static part is rounded up to its 1 KB alignment
     if (lds > (size_t)kMaxDyn) return hipErrorInvalidValue;
-    auto kern = sparse_attn_v5_kernel<PD, DBG, SKIP>;
+    auto kern = sparse_attn_v5_kernel<PD, DBG, SKIP, TOPK>;
     static bool attr_done[16] = {};
     if (hipError_t e = dyn_lds_attr_once(reinterpret_cast<const void *>(kern), kMaxDyn, attr_done); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(512), lds, st, a, ntiles, total, per_xcd, list_cap, g_trace_ptr, g_trace_block);
@@ -633,6 +655,7 @@ static hipError_t launch_v5(const AttnArgs &a, hipStream_t st)
 hipError_t launch_sparse_attn_v5(const AttnArgs &a, hipStream_t st)
 {
     const bool dbg = a.o_sparse_dbg || a.o_linear_dbg;
+    if (a.topk_mask) return dbg ? launch_v5<3, true, 0, true>(a, st) : launch_v5<3, false, 0, true>(a, st);
 #ifdef SALAD_DIAG
     switch (g_attn_variant >> 4) {
     case 0: break;

@@ -49,7 +49,8 @@ def gather_rows(full, rows):
 
 
 def run_layer(w, inp, dev, kept, kinds, *, lam=None, dbg=True, flags=0, s=None, head_scale="default",
-              b_gate=0.0, csr=None, softmax_scale=0.0, eps=None, drop_threshold=0.0, w_proj=None):
+              b_gate=0.0, csr=None, softmax_scale=0.0, eps=None, drop_threshold=0.0, w_proj=None,
+              topk=0, topk_key_block=0):
     """One layer call; returns dict of numpy float64 arrays (out, o_sparse, o_linear, s)."""
     grid = (w.T, w.Hh, w.W)
     if csr is None:
@@ -61,17 +62,21 @@ def run_layer(w, inp, dev, kept, kinds, *, lam=None, dbg=True, flags=0, s=None, 
     o_l = torch.full(q.shape, float("nan"), dtype=torch.float32, device="cuda") if dbg else None
     s_out = torch.zeros(w.B, dtype=torch.float32, device="cuda")
     dropped = torch.full((w.B,), -1, dtype=torch.int32, device="cuda")
+    tmask = torch.zeros((w.B, w.H, w.N), dtype=torch.int64, device="cuda") if topk > 0 else None
     hs = dev["head_scale"] if isinstance(head_scale, str) else head_scale
     out = sb.salad_sparse_linear_attn_fwd(
         q, dev["k"], dev["v"], grid, row_ptr, col_idx, kinds,
         lam=w.lam if lam is None else lam, head_scale=hs, s=s,
         x_t=None if s is not None else dev.get("x_t"), w_gate=None if s is not None else dev["w_gate"],
         b_gate=b_gate, eps=w.eps if eps is None else eps, softmax_scale=softmax_scale, s_out=s_out,
-        o_sparse_dbg=o_s, o_linear_dbg=o_l, flags=flags, drop_threshold=drop_threshold, dropped_out=dropped, w_proj=w_proj)
+        o_sparse_dbg=o_s, o_linear_dbg=o_l, flags=flags, drop_threshold=drop_threshold, dropped_out=dropped, w_proj=w_proj,
+        topk=topk, topk_key_block=topk_key_block, topk_mask_out=tmask)
     torch.cuda.synchronize()
     res = {"out": out.float().cpu().numpy().astype(np.float64), "s": s_out.cpu().numpy().astype(np.float64),
            "row_ptr": row_ptr.cpu().numpy(), "col_idx": col_idx.cpu().numpy(), "out_t": out,
            "dropped": dropped.cpu().numpy()}
+    if tmask is not None:
+        res["topk_mask"] = tmask.cpu().numpy().view(np.uint64)
     if dbg:
         res["o_sparse"] = o_s.cpu().numpy().astype(np.float64)
         res["o_linear"] = o_l.cpu().numpy().astype(np.float64)

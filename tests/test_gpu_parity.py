@@ -361,6 +361,28 @@ def test_full_projection(oracle):
     assert res_dr["dropped"].tolist() == [1, 1] and torch.equal(res_dr["out_t"], sparse_only)
 
 
+@pytest.mark.parametrize("wi,key_block,topk", [(1, 64, 4), (7, 128, 2), (0, 64, 8), (6, 64, 1), (4, 64, 3)],
+                         ids=["N693-B2-kb64-k4", "N1170-kb128-k2", "N270-all-blocks", "single-token", "N512-k3"])
+def test_topk_mask_layer(oracle, wi, key_block, topk):
+    """Top-K dynamic mask (App. A.1.2): the per-query block selection matches the oracle bit for bit (both sides
+    take the decision in the same fixed float32 order), and the layer output on that mask meets the bf16 bar."""
+    w = SMALL[wi]
+    inp = wl.make_inputs(w)
+    dev = upload(w, inp)
+    kinds = np.zeros(w.H, dtype=np.uint8)               # Top-K works on the stored order
+    kept = [1] * w.H                                    # unused by the Top-K path
+    ref = _oracle_layer(oracle, w, inp, kept, kinds, topk=topk, key_block=key_block)
+    res = run_layer(w, inp, dev, kept, kinds, topk=topk, topk_key_block=key_block)
+    assert np.array_equal(res["topk_mask"], ref["topk_mask"])
+    nbk = -(-w.N // key_block)
+    pop = np.array([bin(int(x)).count("1") for x in res["topk_mask"].reshape(-1)])
+    assert (pop == min(topk, nbk)).all()
+    compare_layer(res, ref, label=f"topk-{w.name}")
+    if topk >= nbk:                                      # every block kept: the dense layer
+        dense = run_layer(w, inp, dev, [w.nb] * w.H, kinds)
+        assert errors(res["out"], dense["out"])[1] < 3e-3
+
+
 def test_layer_call_under_graph_capture():
     """The layer call allocates nothing and never synchronises, so it can be captured into a HIP graph.
     Replays (with eager work and synchronisation in between) give the bits of the eager call."""
@@ -449,6 +471,26 @@ def test_wan13_480p_full_projection_sampled(oracle):
     ref_ps = _oracle_layer(oracle, w, inp, kept, kinds, sel=sel)
     assert errors(ref["out"], ref_ps["out"])[1] > 1e-3                 # the projection changes the result
     compare_layer(res, ref, check_linear=False, label="480p-proj")
+    assert np.isfinite(res["out"]).all()
+
+
+def test_wan13_480p_topk_sampled(oracle):
+    """Top-K mask at the headline size and sparsity: 40 key blocks of 832 tokens (13 blocks of 64; the last one
+    312 tokens), 4 kept per query token = 90 % sparsity.  The full mask is compared bit for bit, the output on
+    sampled query blocks."""
+    w = wl.WAN13_480P
+    say("480p-topk: generating inputs")
+    inp = wl.make_inputs(w)
+    dev = upload(w, inp)
+    kinds = np.zeros(w.H, dtype=np.uint8)
+    kept = [1] * w.H
+    say("480p-topk: GPU call")
+    res = run_layer(w, inp, dev, kept, kinds, topk=4, topk_key_block=832, dbg=False)
+    sel = wl.sample_blocks(w.nb, 4, w.seed)
+    say(f"480p-topk: oracle selection for every query, attention on {len(sel)} query blocks per head")
+    ref = _oracle_layer(oracle, w, inp, kept, kinds, sel=sel, topk=4, key_block=832)
+    assert np.array_equal(res["topk_mask"], ref["topk_mask"])
+    compare_layer(res, ref, check_linear=False, label="480p-topk")
     assert np.isfinite(res["out"]).all()
 
 
