@@ -228,6 +228,50 @@ def main():
     except Exception as exc:
         result["full_projection"] = {"error": repr(exc)[:200]}
 
+    # Top-K dynamic block mask (App. A.1.2) at the same shape and sparsity: 40 key blocks of 832 tokens, 4 kept per
+    # query token; key-block means + selection + visit lists, then the attention kernel in its token-mask mode
+    try:
+        kb_tok, topk = 832, 4
+        ws_t = sb.Workspace(w.B, w.H, w.N, w.d, sb.SALAD_BF16, dev, topk=topk)
+        mask_t = torch.zeros((w.B, w.H, w.N), dtype=torch.int64, device=dev)
+        spatial = np.zeros(w.H, dtype=np.uint8)
+        pt, keep_t = sb.make_fwd_params(q, k, v, out, grid, None, None, spatial, lam=w.lam, head_scale=hs, x_t=x, w_gate=wg,
+                                        eps=w.eps, workspace=ws_t, topk=topk, topk_key_block=kb_tok, topk_mask_out=mask_t)
+        nbk = -(-w.N // kb_tok)
+
+        def topk_stats(ms_t, kt_t):
+            sizes = torch.tensor([min(w.N, (j + 1) * kb_tok) - j * kb_tok for j in range(nbk)], dtype=torch.float64, device=dev)
+            bits = ((mask_t.unsqueeze(-1) >> torch.arange(nbk, device=dev)) & 1)                       # [B,H,N,nbk]
+            fl_tok = float((bits.double() * sizes).sum()) * 4.0 * w.d                                   # token level
+            pad = (-w.N) % 32                                                                           # a wave = 32 queries
+            bw = torch.nn.functional.pad(bits, (0, 0, 0, pad)).reshape(w.B, w.H, -1, 32, nbk).amax(3)   # per wave
+            fl_wave = float((bw.double() * sizes).sum()) * 32 * 4.0 * w.d
+            attn_t = kt_t.attn_ms / max(kt_t.calls, 1)
+            return {"ms_per_call": ms_t, "mask_steps_ms": kt_t.topk_ms / max(kt_t.calls, 1), "attention_ms": attn_t,
+                    "kept_gflop_token_level": fl_tok * 1e-9, "computed_gflop_wave_level": fl_wave * 1e-9,
+                    "attention_TFLOP/s_on_kept": fl_tok / (attn_t * 1e-3) * 1e-12,
+                    "attention_TFLOP/s_on_computed": fl_wave / (attn_t * 1e-3) * 1e-12}
+
+        ms_t, kt_t = timed(pt, max(5, args.steps // 5), 2)
+        entry = {"key_block": kb_tok, "topk": topk, "key_blocks": nbk}
+        entry.update(topk_stats(ms_t, kt_t))
+        # The benchmark's Q, K are independent per token, so 32 neighbouring queries pick unrelated blocks and a wave
+        # has to visit nearly all of them.  Video latents vary slowly along the token axis: the same measurement with
+        # Q and K low-pass filtered along N (moving average over 257 tokens, rescaled to unit variance).
+        def smooth(t):
+            y = torch.nn.functional.avg_pool1d(t.float().reshape(-1, w.N, w.d).transpose(1, 2), 257, 1, 128, count_include_pad=False)
+            y = y.transpose(1, 2).reshape(t.shape)
+            return (y / y.std()).to(t.dtype).contiguous()
+        q_s, k_s = smooth(q), smooth(k)
+        ps, keep_s = sb.make_fwd_params(q_s, k_s, v, out, grid, None, None, spatial, lam=w.lam, head_scale=hs, x_t=x, w_gate=wg,
+                                        eps=w.eps, workspace=ws_t, topk=topk, topk_key_block=kb_tok, topk_mask_out=mask_t)
+        ms_s, kt_s = timed(ps, max(5, args.steps // 5), 2)
+        entry["smooth_inputs"] = topk_stats(ms_s, kt_s)
+        result["topk_mask"] = entry
+        del ws_t, mask_t, q_s, k_s
+    except Exception as exc:
+        result["topk_mask"] = {"error": repr(exc)[:200]}
+
     # the same call captured once into a HIP graph and replayed (the call allocates nothing and never
     # synchronises); reported next to the eager figure, which stays the headline value
     try:

@@ -122,7 +122,7 @@ typedef struct salad_fwd_params {
 
 /* Device scratch the forward needs for these shapes (partial states, partial gate sums, the
  * reduced state, per-tile block lists; with w_proj also O_l and the rearranged W_p; with topk the key-block means,
- * the masks and per-sample lists).  Reads only B, H, N, d, dtype, whether w_proj is NULL and whether topk > 0.
+ * the masks and per-sample lists).  Reads only B, H, N, d, dtype, whether w_proj is NULL and topk.
  * 0 on invalid shapes. */
 size_t salad_fwd_workspace_bytes(const salad_fwd_params *p);
 
@@ -169,6 +169,8 @@ typedef struct salad_kernel_times {
     float gate_ms, state_ms, finalize_ms, attn_ms, epilogue_ms; /* summed over calls            */
     int32_t calls;
     float proj_ms;            /* full Level-1 projection: W_p rearrangement + GEMM (0 without w_proj)   */
+    float topk_ms;            /* Top-K mask: key-block means, selection, visit lists (0 without topk);
+                                 attn_ms is then the attention kernel alone                             */
 } salad_kernel_times;
 
 /* When enabled, the layer call brackets each of its kernels with HIP events on its stream. */
@@ -181,7 +183,9 @@ salad_status salad_timing_read(salad_kernel_times *out, int32_t reset);
 
 /* Launch-shape knobs for experiments; results do not depend on them beyond rounding order.
  *   "state_wgs"  target workgroup count of the linear-state kernel (changes the workspace size:
- *                query salad_fwd_workspace_bytes again after setting it). */
+ *                query salad_fwd_workspace_bytes again after setting it).
+ *   "topk_variant"  0 (default): Top-K attention regrouped by key block (queries that keep a block are gathered,
+ *                partial results merged); 1: token mask applied on ordinary query tiles. */
 salad_status salad_tune(const char *key, int32_t value);
 
 #ifdef __cplusplus

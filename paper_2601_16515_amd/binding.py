@@ -70,7 +70,7 @@ class FwdParams(C.Structure):
 
 class KernelTimes(C.Structure):
     _fields_ = [("gate_ms", C.c_float), ("state_ms", C.c_float), ("finalize_ms", C.c_float),
-                ("attn_ms", C.c_float), ("epilogue_ms", C.c_float), ("calls", C.c_int32), ("proj_ms", C.c_float)]
+                ("attn_ms", C.c_float), ("epilogue_ms", C.c_float), ("calls", C.c_int32), ("proj_ms", C.c_float), ("topk_ms", C.c_float)]
 
 
 def build_library(verbose: bool = False) -> str:
@@ -176,11 +176,11 @@ def salad_block_mask(T: int, Hh: int, W: int, block: int, kept: Sequence[int], d
 
 
 def salad_fwd_workspace_bytes(B: int, H: int, N: int, d: int, dtype: int, full_proj: bool = False,
-                              topk: bool = False) -> int:
+                              topk: int = 0) -> int:
     p = FwdParams()
     p.B, p.H, p.N, p.d, p.dtype = B, H, N, d, dtype
     p.w_proj = 1 if full_proj else None          # the query only looks at whether the pointer is NULL
-    p.topk = 1 if topk else 0                    # ... and at whether topk is positive
+    p.topk = int(topk)                           # ... and at topk (slots per query of the regrouped Top-K path)
     return int(lib().salad_fwd_workspace_bytes(C.byref(p)))
 
 
@@ -188,7 +188,7 @@ class Workspace:
     """Caller-owned scratch for the layer call, sized by the library's query."""
 
     def __init__(self, B: int, H: int, N: int, d: int, dtype: int, device="cuda", full_proj: bool = False,
-                 topk: bool = False):
+                 topk: int = 0):
         import torch
         self.bytes = salad_fwd_workspace_bytes(B, H, N, d, dtype, full_proj, topk)
         self.buf = torch.empty(max(self.bytes, 256) + 256, dtype=torch.uint8, device=device)
@@ -249,7 +249,7 @@ def salad_sparse_linear_attn_fwd(q, k, v, grid, row_ptr, col_idx, head_kind=None
         out = torch.empty_like(q)
     if kw.get("workspace") is None:
         kw["workspace"] = Workspace(B, H, N, d, _dtype_code(q), q.device, full_proj=kw.get("w_proj") is not None,
-                                    topk=kw.get("topk", 0) > 0)
+                                    topk=kw.get("topk", 0))
     p, keep = make_fwd_params(q, k, v, out, grid, row_ptr, col_idx, head_kind, **kw)
     _check(lib().salad_sparse_linear_attn_fwd(C.byref(p)))
     return out

@@ -36,11 +36,11 @@ salad_status hip_fail(hipError_t e, const char *what)
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct WsLayout {
-    size_t gate_partial, state_partial, Hs, Z, hfrag, s, coef, drop, tile_lists, tile_counts, ol, wfrag, kmeans, topk_mask, total;
+    size_t gate_partial, state_partial, Hs, Z, hfrag, s, coef, drop, tile_lists, tile_counts, ol, wfrag, kmeans, topk_mask, g_counts, g_seg, g_total, g_desc, g_idx, g_slot, g_lse, g_po, total;
     int nparts, P;
 };
 
-WsLayout ws_layout(int B, int H, int N, int d, int dtype, bool full_proj = false, bool topk = false)
+WsLayout ws_layout(int B, int H, int N, int d, int dtype, bool full_proj = false, int topk = 0)
 {
     WsLayout w{};
     const size_t BH = (size_t)B * H;
@@ -68,6 +68,18 @@ WsLayout ws_layout(int B, int H, int N, int d, int dtype, bool full_proj = false
     // Top-K mask: mean keys of up to 64 key blocks per head, and the per-query block masks
     w.kmeans = off; off = align256(off + (topk ? sizeof(float) * BH * 64 * (size_t)d : 0));
     w.topk_mask = off; off = align256(off + (topk ? sizeof(uint64_t) * BH * (size_t)N : 0));
+    {   // regrouping by key block: one slot per kept (query, key block) pair
+        const int kk = topk > 8 ? 8 : topk;
+        const size_t pairs = BH * (size_t)N * kk;
+        w.g_counts = off; off = align256(off + (topk ? sizeof(int32_t) * BH * 64 : 0));
+        w.g_seg = off; off = align256(off + (topk ? sizeof(int32_t) * BH * 64 : 0));
+        w.g_total = off; off = align256(off + (topk ? 256 : 0));
+        w.g_desc = off; off = align256(off + (topk ? sizeof(uint4) * (size_t)topk_max_tiles((int)BH, N, kk, 64) : 0));
+        w.g_idx = off; off = align256(off + (topk ? sizeof(int32_t) * pairs : 0));
+        w.g_slot = off; off = align256(off + (topk ? sizeof(int32_t) * pairs : 0));
+        w.g_lse = off; off = align256(off + (topk ? sizeof(float) * pairs : 0));
+        w.g_po = off; off = align256(off + (topk ? sizeof(float) * pairs * d : 0));
+    }
     w.total = off;
     return w;
 }
@@ -83,8 +95,9 @@ bool shape_ok(int B, int H, int N, int d, int dtype)
 
 // ---- timing -----------------------------------------------------------------------------------
 std::mutex g_tmu;
+int g_topk_variant = 0;
 bool g_timing = false;
-struct CallEvents { hipEvent_t e[7]; bool has_epilogue, has_linear; };
+struct CallEvents { hipEvent_t e[8]; bool has_epilogue, has_linear; };   // e[7]: end of the Top-K mask steps
 std::vector<CallEvents> g_calls;
 std::vector<hipEvent_t> g_free_events;
 
@@ -161,7 +174,7 @@ salad_status salad_block_mask(int32_t T, int32_t Hh, int32_t W, int32_t block, i
 size_t salad_fwd_workspace_bytes(const salad_fwd_params *p)
 {
     if (!p || !shape_ok(p->B, p->H, p->N, p->d, p->dtype)) return 0;
-    return ws_layout(p->B, p->H, p->N, p->d, p->dtype, p->w_proj != nullptr, p->topk > 0).total;
+    return ws_layout(p->B, p->H, p->N, p->d, p->dtype, p->w_proj != nullptr, p->topk > 0 ? p->topk : 0).total;
 }
 
 salad_status salad_linear_state_fwd(const void *k, const void *v, int32_t B, int32_t H, int32_t N, int32_t d,
@@ -259,7 +272,11 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
         if (Dm > 5120) return fail(SALAD_ENOTSUP, "fwd: gate over D=H*d=%d above 5120; pass s_dev", Dm);
     }
     // with the full projection the sparse kernel always stores O_s alone and the linear branch follows in its own kernels
-    const bool unfused = (p->flags & SALAD_FLAG_UNFUSED_EPILOGUE) != 0 || (p->w_proj != nullptr && p->lambda != 0.f);
+    // Top-K regrouped by key block (the default Top-K path): the sparse branch is assembled by a merge kernel, so the
+    // linear branch follows in its own kernel as well
+    const bool topk_regroup = p->topk > 0 && g_topk_variant == 0;
+    const bool unfused = (p->flags & SALAD_FLAG_UNFUSED_EPILOGUE) != 0 || (p->w_proj != nullptr && p->lambda != 0.f) ||
+                         (topk_regroup && p->lambda != 0.f);
     if (unfused && p->dtype != SALAD_BF16) return fail(SALAD_ENOTSUP, "fwd: unfused epilogue is bf16 only");
     if (p->flags & ~SALAD_FLAG_UNFUSED_EPILOGUE) return fail(SALAD_EINVAL, "fwd: unknown flags 0x%x", p->flags);
     const bool full_proj = p->w_proj != nullptr && p->lambda != 0.f;
@@ -267,7 +284,7 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
         if (p->dtype != SALAD_BF16 || p->d != 128) return fail(SALAD_ENOTSUP, "fwd: w_proj needs dtype bf16 and d = 128");
         if (p->head_scale) return fail(SALAD_EINVAL, "fwd: w_proj and head_scale exclude each other");
     }
-    const WsLayout w = ws_layout(p->B, p->H, p->N, p->d, p->dtype, p->w_proj != nullptr, topk);
+    const WsLayout w = ws_layout(p->B, p->H, p->N, p->d, p->dtype, p->w_proj != nullptr, topk ? p->topk : 0);
     const bool need_lists = p->dtype == SALAD_BF16 && p->d == 128 && (size_t)tile_list_cap((p->N + 63) / 64) * 4 <= 24 * 1024;
     if (use_linear || need_lists) {
         if (!p->workspace || ((uintptr_t)p->workspace & 255)) return fail(SALAD_EINVAL, "fwd: workspace null or not 256-byte aligned");
@@ -375,18 +392,37 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
         a.tile_counts = (const int32_t *)(ws + w.tile_counts);
         a.list_cap = tile_list_cap(a.nb);
         a.topk_mask = mask;
-        e = launch_topk_tile_lists(mask, BH, p->N, a.nb, p->topk_key_block, nbk, (uint32_t *)(ws + w.tile_lists), (int32_t *)(ws + w.tile_counts), st);
-        if (e != hipSuccess) return hip_fail(e, "top-k tile list launch");
+        if (topk_regroup) {
+            const int kk = p->topk < nbk ? p->topk : nbk;
+            e = launch_topk_group(mask, BH, p->N, nbk, kk, (int32_t *)(ws + w.g_counts), (int32_t *)(ws + w.g_seg),
+                                  (uint4 *)(ws + w.g_desc), (int32_t *)(ws + w.g_total), (int32_t *)(ws + w.g_idx),
+                                  (int32_t *)(ws + w.g_slot), st);
+            if (e != hipSuccess) return hip_fail(e, "top-k regrouping launch");
+            a.g_desc = (const uint4 *)(ws + w.g_desc); a.g_total = (const int32_t *)(ws + w.g_total);
+            a.g_idx = (const int32_t *)(ws + w.g_idx); a.g_po = (float *)(ws + w.g_po); a.g_lse = (float *)(ws + w.g_lse);
+            a.g_kk = kk; a.g_bpb = p->topk_key_block / 64; a.g_max_tiles = topk_max_tiles(BH, p->N, kk, nbk);
+        } else {
+            e = launch_topk_tile_lists(mask, BH, p->N, a.nb, p->topk_key_block, nbk, (uint32_t *)(ws + w.tile_lists), (int32_t *)(ws + w.tile_counts), st);
+            if (e != hipSuccess) return hip_fail(e, "top-k tile list launch");
+        }
+        mark(7);
     } else if (need_lists) {
+        mark(7);
         a.tile_lists = (const uint32_t *)(ws + w.tile_lists);
         a.tile_counts = (const int32_t *)(ws + w.tile_counts);
         a.list_cap = tile_list_cap(a.nb);
         e = launch_tile_lists(p->row_ptr, p->col_idx, p->H, a.nb, (uint32_t *)(ws + w.tile_lists), (int32_t *)(ws + w.tile_counts), st);
         if (e != hipSuccess) return hip_fail(e, "tile list launch");
     }
+    if (!topk && !need_lists) mark(7);
     a.t_magic = ((uint64_t)p->N * (uint64_t)p->T < (1ull << 32) && p->T > 1) ? (unsigned)((1ull << 32) / (uint64_t)p->T + 1) : 0u;
     e = bf16 ? launch_sparse_attn_bf16(a, st) : launch_sparse_attn_f32(a, st);
     if (e != hipSuccess) return hip_fail(e, "sparse attention launch");
+    if (a.g_desc) {
+        e = launch_topk_merge(a.g_po, a.g_lse, (const int32_t *)(ws + w.g_slot), a.topk_mask, BH, p->N, a.g_kk,
+                              (u16 *)p->out, p->o_sparse_dbg, st);
+        if (e != hipSuccess) return hip_fail(e, "top-k merge launch");
+    }
     mark(4);
     if (unfused && use_linear) {
         ApplyArgs ap{};
@@ -439,6 +475,11 @@ salad_status salad_timing_read(salad_kernel_times *out, int32_t reset)
             e = hipEventElapsedTime(&ms[i], c.e[i], c.e[i + 1]);
             if (e != hipSuccess) return hip_fail(e, "hipEventElapsedTime");
         }
+        float topk_ms = 0.f;
+        e = hipEventElapsedTime(&topk_ms, c.e[3], c.e[7]);
+        if (e != hipSuccess) return hip_fail(e, "hipEventElapsedTime");
+        ms[3] -= topk_ms;
+        out->topk_ms += topk_ms;
         out->gate_ms += ms[0];
         out->state_ms += ms[1];
         out->finalize_ms += ms[2];
@@ -478,6 +519,11 @@ salad_status salad_tune(const char *key, int32_t value)
     if (!std::strcmp(key, "gate_tok")) { g_gate_tok = value; return SALAD_OK; }
     if (!std::strcmp(key, "attn_variant")) {
         g_attn_variant = value;
+        return SALAD_OK;
+    }
+    if (!std::strcmp(key, "topk_variant")) {   // 0: regrouped by key block (default), 1: token mask on query tiles
+        if (value < 0 || value > 1) return fail(SALAD_EINVAL, "salad_tune: topk_variant out of range");
+        g_topk_variant = value;
         return SALAD_OK;
     }
     return fail(SALAD_EINVAL, "salad_tune: unknown key %s", key);

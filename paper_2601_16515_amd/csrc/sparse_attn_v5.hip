@@ -189,10 +189,14 @@ hipError_t launch_tile_lists(const int32_t *row_ptr, const int32_t *col_idx, int
 // priority of the vector phase, 7 of the matrix phase, 8 recomputes the row maximum for every block, 9 drops
 // the per-block barrier (timing only: results are wrong), 10 always fetches block 0, 11 keeps the prefetch's
 // address arithmetic but not its loads.
-// TOPK: token-level Top-K mask (App. A.1.2) instead of block rows.  The tile lists are per (sample, head, tile);
-// an entry is block | key-block index << 16 | wave mask << 24 (bit 24 + w: some query of wave w keeps the block);
-// each lane tests its own query's bit of a.topk_mask and contributes nothing for a block it did not select.
-template <int PD, bool DBG, int SKIP, bool TOPK = false>
+// MODE 0: block rows (CSR) through the per-tile union lists.
+// MODE 1: token-level Top-K mask (App. A.1.2).  The tile lists are per (sample, head, tile); an entry is
+//   block | key-block index << 16 | wave mask << 24 (bit 24 + w: some query of wave w keeps the block); each lane
+//   tests its own query's bit of a.topk_mask and contributes nothing for a block it did not select.
+// MODE 2: Top-K regrouped by key block.  A query tile is a run of up to 256 gathered queries that all keep the same
+//   key block; the list is that key block's 64-token blocks; the normalised partial result and its log-sum-exp go
+//   to a.g_po / a.g_lse (one slot per kept (query, key block) pair) for the merge kernel.
+template <int PD, bool DBG, int SKIP, int MODE = 0>
 __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int ntiles, int total, int per_xcd, int list_cap, long long *trace, int trace_block)
 {
     constexpr int skip = SKIP;
@@ -205,10 +209,18 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
     u16 *Vb = Kb + NK * TILE;                                       // NV tiles
     uint32_t *blist = reinterpret_cast<uint32_t *>(Vb + NV * TILE);      // [list_cap] union list: blk | mask << 24
 
+    constexpr bool TOPK = MODE == 1, GATHER = MODE == 2;
     const int g = blockIdx.x;
     const int L = (g & 7) * per_xcd + (g >> 3);
     if (L >= total) return;
-    const int bh = L / ntiles, tile = L - bh * ntiles;
+    int bh = L / ntiles, tile = L - bh * ntiles;
+    int g_J = 0, g_slot0 = 0, g_cnt = 0;
+    if (GATHER) {
+        if (L >= *a.g_total) return;
+        const uint4 dsc = a.g_desc[L];
+        bh = (int)dsc.x; g_J = (int)dsc.y; g_slot0 = (int)dsc.z; g_cnt = (int)dsc.w;
+        tile = 0;
+    }
     const int h = bh % a.H;
     const int N = a.N, T = a.T, HW = a.HW, nb = a.nb;
     const int kind = (T > 1 && !TOPK) ? (int)((a.kind_mask >> h) & 1ull) : 0;
@@ -231,10 +243,21 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
 
     const int qsub = wave >> 1;
     const int qblk = tile * 4 + qsub;
-    const unsigned mybit = qblk < nb ? (1u << (24 + (TOPK ? (wave & 7) : qsub))) : 0u;
+    unsigned mybit = qblk < nb ? (1u << (24 + (TOPK ? (wave & 7) : qsub))) : 0u;
     const int qpos = qblk * 64 + (wave & 1) * 32 + l32;
-    const bool qvalid = (qblk < nb) && (qpos < N);
-    const int qrow = row_of_position5(kind, qvalid ? qpos : N - 1, T, HW, magic);
+    bool qvalid = (qblk < nb) && (qpos < N);
+    int qrow;
+    size_t g_slot = 0;                    // GATHER: this lane's (query, key block) pair
+    if (GATHER) {
+        const int qi = wave * 32 + l32;   // position in the run of gathered queries
+        qvalid = qi < g_cnt;
+        mybit = wave * 32 < g_cnt ? (1u << (24 + (wave & 7))) : 0u;
+        g_slot = (size_t)bh * N * a.g_kk + g_slot0 + (qvalid ? qi : 0);
+        qrow = a.g_idx[g_slot];
+        qrow = min(max(qrow, 0), N - 1);
+    } else {
+        qrow = row_of_position5(kind, qvalid ? qpos : N - 1, T, HW, magic);
+    }
 
     Frag5 qf[NS];
 #pragma unroll
@@ -243,14 +266,17 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
 
     // ---- this tile's union list (built by the pre-pass): the whole row of list_cap slots is copied, so
     // the copy does not wait for the count (slots past the count hold stale words that are never used)
-    const int n = a.tile_counts[(TOPK ? bh : h) * ntiles + tile];
+    const int g_blk0 = g_J * a.g_bpb;
+    const int n = GATHER ? min(min(nb, g_blk0 + a.g_bpb) - g_blk0, list_cap) : a.tile_counts[(TOPK ? bh : h) * ntiles + tile];
     uint32_t qm_lo = 0u, qm_hi = 0u;     // TOPK: this lane's query's key-block bits
     if (TOPK && qvalid) {
         const unsigned long long m = a.topk_mask[(size_t)bh * N + qrow];
         qm_lo = (uint32_t)m;
         qm_hi = (uint32_t)(m >> 32);
     }
-    {
+    if (GATHER) {
+        for (int i = tid; i < list_cap; i += 512) blist[i] = (uint32_t)min(g_blk0 + i, nb - 1) | 0xff000000u;
+    } else {
         const uint32_t *src = a.tile_lists + ((size_t)(TOPK ? bh : h) * ntiles + tile) * list_cap;
         for (int i = tid; i < list_cap; i += 512) blist[i] = src[i];
     }
@@ -447,7 +473,7 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
         l_run += psum;
     };
 
-    const bool lin = a.use_linear && !a.write_sparse_only && !(a.drop && a.drop[bh / a.H]);   // pruned sample (Sec. 4.3): out = O_s
+    const bool lin = !GATHER && a.use_linear && !a.write_sparse_only && !(a.drop && a.drop[bh / a.H]);   // pruned sample (Sec. 4.3): out = O_s
     const u16 *hf = a.hfrag + (size_t)bh * 2 * D * D;
     // 64 KB of linear-state fragments (hi, lo) for the epilogue, staged into the K ring once it is idle
     auto stage_state = [&]() INL {
@@ -592,6 +618,18 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
         }
     }
     if (!qvalid) return;
+    if (GATHER) {
+        // normalised partial result of this (query, key block) pair and its log-sum-exp (log2 domain)
+        float *po = a.g_po + g_slot * D;
+#pragma unroll
+        for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4)
+                *reinterpret_cast<float4 *>(po + dt * 32 + 8 * g4 + 4 * hh) =
+                    make_float4(o[dt][g4 * 4 + 0] * inv_l, o[dt][g4 * 4 + 1] * inv_l, o[dt][g4 * 4 + 2] * inv_l, o[dt][g4 * 4 + 3] * inv_l);
+        if (hh == 0) a.g_lse[g_slot] = l_tot > 0.f ? m_run + log2f(l_tot) : -INFINITY;
+        return;
+    }
     const size_t obase = ((size_t)bh * N + qrow) * D;
     u16 *outp = reinterpret_cast<u16 *>(a.out) + obase;
 #pragma unroll
@@ -634,18 +672,18 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
 #undef TSTAMP
 }
 
-template <int PD, bool DBG, int SKIP, bool TOPK = false>
+template <int PD, bool DBG, int SKIP, int MODE = 0>
 static hipError_t launch_v5(const AttnArgs &a, hipStream_t st)
 {
     const int ntiles = (a.nb + 3) / 4;
-    const int total = a.B * a.H * ntiles;
+    const int total = MODE == 2 ? a.g_max_tiles : a.B * a.H * ntiles;
     const int per_xcd = (total + 7) / 8;
     const int list_cap = (a.nb + 63) & ~63;
     const size_t lds = (size_t)(2 * PD + 3) * 64 * 128 * 2 + (size_t)list_cap * 4;
     static_assert(PD + 1 >= 4, "the epilogue stages 64 KB of state fragments in the K ring");
     constexpr int kMaxDyn = 160 * 1024 - 2048;   // the static part is rounded up to its 1 KB alignment
     if (lds > (size_t)kMaxDyn) return hipErrorInvalidValue;
-    auto kern = sparse_attn_v5_kernel<PD, DBG, SKIP, TOPK>;
+    auto kern = sparse_attn_v5_kernel<PD, DBG, SKIP, MODE>;
     static bool attr_done[16] = {};
     if (hipError_t e = dyn_lds_attr_once(reinterpret_cast<const void *>(kern), kMaxDyn, attr_done); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(512), lds, st, a, ntiles, total, per_xcd, list_cap, g_trace_ptr, g_trace_block);
@@ -655,7 +693,8 @@ static hipError_t launch_v5(const AttnArgs &a, hipStream_t st)
 hipError_t launch_sparse_attn_v5(const AttnArgs &a, hipStream_t st)
 {
     const bool dbg = a.o_sparse_dbg || a.o_linear_dbg;
-    if (a.topk_mask) return dbg ? launch_v5<3, true, 0, true>(a, st) : launch_v5<3, false, 0, true>(a, st);
+    if (a.g_desc) return launch_v5<3, false, 0, 2>(a, st);
+    if (a.topk_mask) return dbg ? launch_v5<3, true, 0, 1>(a, st) : launch_v5<3, false, 0, 1>(a, st);
 #ifdef SALAD_DIAG
     switch (g_attn_variant >> 4) {
     case 0: break;

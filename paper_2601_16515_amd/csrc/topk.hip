@@ -169,4 +169,164 @@ hipError_t launch_topk_tile_lists(const unsigned long long *mask, int BH, int N,
     return hipGetLastError();
 }
 
+// ---- regrouping by key block -----------------------------------------------------------------------------------
+// The queries that keep key block J are gathered into runs of 256 ("query tiles" of the attention kernel), so that
+// the work is the kept (query, key block) pairs whatever the selection looks like; every pair gets a slot in
+// [0, N * kk) of its (sample, head), key blocks ascending, queries ascending inside a key block.
+
+// grid (nbk, BH), 256 threads: counts[bh * nbk + J] = number of queries keeping block J
+__global__ __launch_bounds__(256) void topk_count_kernel(const unsigned long long *__restrict__ mask, int N, int nbk,
+                                                         int32_t *__restrict__ counts)
+{
+    __shared__ int part[4];
+    const int J = blockIdx.x, bh = blockIdx.y, t = threadIdx.x;
+    int c = 0;
+    for (int n = t; n < N; n += 256) c += (int)((mask[(size_t)bh * N + n] >> J) & 1ull);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o);
+    if ((t & 63) == 0) part[t >> 6] = c;
+    __syncthreads();
+    if (t == 0) counts[bh * nbk + J] = part[0] + part[1] + part[2] + part[3];
+}
+
+// one workgroup of 256 threads: seg_start[e] = first slot of pair group e = (bh, J) within its (sample, head);
+// tile descriptors (bh, J, first slot, queries) for every run of up to 256 queries, groups in order; *total = tiles.
+__global__ __launch_bounds__(256) void topk_plan_kernel(const int32_t *__restrict__ counts, int BH, int nbk,
+                                                        int32_t *__restrict__ seg_start, uint4 *__restrict__ desc,
+                                                        int max_tiles, int32_t *__restrict__ total)
+{
+    __shared__ int tsum[256];
+    const int t = threadIdx.x;
+    const int E = BH * nbk, per = (E + 255) / 256;
+    const int e0 = min(E, t * per), e1 = min(E, e0 + per);
+    int tiles = 0;
+    for (int e = e0; e < e1; ++e) tiles += (counts[e] + 255) >> 8;
+    tsum[t] = tiles;
+    __syncthreads();
+    if (t == 0) {
+        int run = 0;
+        for (int i = 0; i < 256; ++i) { const int x = tsum[i]; tsum[i] = run; run += x; }
+        *total = min(run, max_tiles);
+    }
+    __syncthreads();
+    int tile = tsum[t];
+    for (int e = e0; e < e1; ++e) {
+        const int bh = e / nbk, J = e - bh * nbk;
+        // slots of this (sample, head) before key block J
+        int s0 = 0;
+        for (int j = 0; j < J; ++j) s0 += counts[bh * nbk + j];
+        seg_start[e] = s0;
+        const int c = counts[e];
+        for (int i = 0; i < c; i += 256) {
+            if (tile < max_tiles) desc[tile] = make_uint4((uint32_t)bh, (uint32_t)J, (uint32_t)(s0 + i), (uint32_t)min(256, c - i));
+            ++tile;
+        }
+    }
+}
+
+// grid (nbk, BH), 256 threads: gidx[bh * slots + seg_start + pos] = n for the pos-th query (ascending) keeping block J,
+// slot_of[(bh * N + n) * kk + r] = that slot, r = rank of J among the query's kept blocks.
+__global__ __launch_bounds__(256) void topk_group_kernel(const unsigned long long *__restrict__ mask, int N, int nbk, int kk,
+                                                         const int32_t *__restrict__ seg_start,
+                                                         int32_t *__restrict__ gidx, int32_t *__restrict__ slot_of)
+{
+    __shared__ int wcnt[4];
+    const int J = blockIdx.x, bh = blockIdx.y, t = threadIdx.x, lane = t & 63, wv = t >> 6;
+    const size_t slots = (size_t)N * kk;
+    int base = seg_start[bh * nbk + J];
+    for (int n0 = 0; n0 < N; n0 += 256) {
+        const int n = n0 + t;
+        const unsigned long long m = n < N ? mask[(size_t)bh * N + n] : 0ull;
+        const bool keep = (m >> J) & 1ull;
+        const unsigned long long bal = __ballot(keep);
+        if (lane == 0) wcnt[wv] = __popcll(bal);
+        __syncthreads();
+        int before = 0;
+        for (int w = 0; w < wv; ++w) before += wcnt[w];
+        const int all = wcnt[0] + wcnt[1] + wcnt[2] + wcnt[3];
+        if (keep) {
+            const int slot = base + before + __popcll(bal & ((1ull << lane) - 1ull));
+            const int r = __popcll(m & ((1ull << J) - 1ull));
+            if (slot < (int)slots && r < kk) {
+                gidx[(size_t)bh * slots + slot] = n;
+                slot_of[((size_t)bh * N + n) * kk + r] = slot;
+            }
+        }
+        base += all;
+        __syncthreads();
+    }
+}
+
+// out[bh, n, :] = sum_r w_r O_r / sum_r w_r over the query's kk partial results (normalised per key block, with
+// log2-domain log-sum-exp lse_r), w_r = 2^(lse_r - max lse): Eq. (2) over the union of the kept blocks.
+// 32 lanes per query (4 channels each); grid ceil(BH * N / 8), 256 threads.
+__global__ __launch_bounds__(256) void topk_merge_kernel(const float *__restrict__ po, const float *__restrict__ lse,
+                                                         const int32_t *__restrict__ slot_of,
+                                                         const unsigned long long *__restrict__ mask, int BH, int N, int kk,
+                                                         u16 *__restrict__ out, float *__restrict__ o_dbg)
+{
+    const size_t qi = (size_t)blockIdx.x * 8 + (threadIdx.x >> 5);
+    if (qi >= (size_t)BH * N) return;
+    const int c4 = (threadIdx.x & 31) * 4;
+    const size_t bh = qi / N;
+    const size_t slots = (size_t)N * kk;
+    float l[8];
+    int sl[8];
+    float mx = -INFINITY;
+    kk = min(kk, (int)__popcll(mask[qi]));          // only the ranks the regrouping pass filled in
+    const int kk_stride = (int)(slots / N);
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        sl[r] = 0;
+        l[r] = -INFINITY;
+        if (r < kk) {
+            sl[r] = slot_of[qi * kk_stride + r];
+            l[r] = lse[bh * slots + sl[r]];
+            mx = fmaxf(mx, l[r]);
+        }
+    }
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    float den = 0.f;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        if (r < kk) {
+            const float wgt = __builtin_amdgcn_exp2f(l[r] - mx);
+            const float4 x = *reinterpret_cast<const float4 *>(po + (bh * slots + sl[r]) * D + c4);
+            acc.x = fmaf(wgt, x.x, acc.x); acc.y = fmaf(wgt, x.y, acc.y);
+            acc.z = fmaf(wgt, x.z, acc.z); acc.w = fmaf(wgt, x.w, acc.w);
+            den += wgt;
+        }
+    }
+    const float inv = den > 0.f ? 1.f / den : 0.f;
+    acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    uint2 pk;
+    pk.x = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2_t){acc.x, acc.y}, bf16x2_t));
+    pk.y = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2_t){acc.z, acc.w}, bf16x2_t));
+    *reinterpret_cast<uint2 *>(out + qi * D + c4) = pk;
+    if (o_dbg) *reinterpret_cast<float4 *>(o_dbg + qi * D + c4) = acc;
+}
+
+int topk_max_tiles(int BH, int N, int kk, int nbk) { return BH * ((int)(((long long)N * kk + 255) / 256) + nbk); }
+
+hipError_t launch_topk_group(const unsigned long long *mask, int BH, int N, int nbk, int kk, int32_t *counts,
+                             int32_t *seg_start, uint4 *desc, int32_t *total, int32_t *gidx, int32_t *slot_of,
+                             hipStream_t st)
+{
+    hipLaunchKernelGGL(topk_count_kernel, dim3(nbk, BH), dim3(256), 0, st, mask, N, nbk, counts);
+    hipLaunchKernelGGL(topk_plan_kernel, dim3(1), dim3(256), 0, st, counts, BH, nbk, seg_start, desc,
+                       topk_max_tiles(BH, N, kk, nbk), total);
+    hipLaunchKernelGGL(topk_group_kernel, dim3(nbk, BH), dim3(256), 0, st, mask, N, nbk, kk, seg_start, gidx, slot_of);
+    return hipGetLastError();
+}
+
+hipError_t launch_topk_merge(const float *po, const float *lse, const int32_t *slot_of, const unsigned long long *mask,
+                             int BH, int N, int kk, u16 *out, float *o_dbg, hipStream_t st)
+{
+    const size_t nq = (size_t)BH * N;
+    hipLaunchKernelGGL(topk_merge_kernel, dim3((unsigned)((nq + 7) / 8)), dim3(256), 0, st, po, lse, slot_of, mask, BH, N, kk, out, o_dbg);
+    return hipGetLastError();
+}
+
 }  // namespace salad

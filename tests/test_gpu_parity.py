@@ -361,11 +361,14 @@ def test_full_projection(oracle):
     assert res_dr["dropped"].tolist() == [1, 1] and torch.equal(res_dr["out_t"], sparse_only)
 
 
+@pytest.mark.parametrize("variant", [0, 1], ids=["regrouped", "token-mask"])
 @pytest.mark.parametrize("wi,key_block,topk", [(1, 64, 4), (7, 128, 2), (0, 64, 8), (6, 64, 1), (4, 64, 3)],
                          ids=["N693-B2-kb64-k4", "N1170-kb128-k2", "N270-all-blocks", "single-token", "N512-k3"])
-def test_topk_mask_layer(oracle, wi, key_block, topk):
+def test_topk_mask_layer(oracle, topk_variant, wi, key_block, topk, variant):
     """Top-K dynamic mask (App. A.1.2): the per-query block selection matches the oracle bit for bit (both sides
-    take the decision in the same fixed float32 order), and the layer output on that mask meets the bf16 bar."""
+    take the decision in the same fixed float32 order), and the layer output on that mask meets the bf16 bar, for
+    both attention paths (queries regrouped by key block and merged; token mask on ordinary query tiles)."""
+    topk_variant(variant)
     w = SMALL[wi]
     inp = wl.make_inputs(w)
     dev = upload(w, inp)
@@ -380,7 +383,13 @@ def test_topk_mask_layer(oracle, wi, key_block, topk):
     compare_layer(res, ref, label=f"topk-{w.name}")
     if topk >= nbk:                                      # every block kept: the dense layer
         dense = run_layer(w, inp, dev, [w.nb] * w.H, kinds)
-        assert errors(res["out"], dense["out"])[1] < 3e-3
+        assert errors(res["out"], dense["out"])[1] < 5e-3   # two independently rounded bf16 results
+
+
+@pytest.fixture
+def topk_variant():
+    yield lambda v: sb.salad_tune("topk_variant", v)
+    sb.salad_tune("topk_variant", 0)
 
 
 def test_layer_call_under_graph_capture():
