@@ -36,7 +36,7 @@ salad_status hip_fail(hipError_t e, const char *what)
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct WsLayout {
-    size_t gate_partial, state_partial, Hs, Z, hfrag, s, coef, drop, tile_lists, tile_counts, ol, wfrag, kmeans, topk_mask, g_counts, g_seg, g_total, g_desc, g_idx, g_slot, g_lse, g_po, total;
+    size_t gate_partial, state_partial, Hs, Z, hfrag, s, coef, drop, tile_lists, tile_counts, ol, wfrag, kmeans, topk_mask, g_counts, g_ccnt, g_seg, g_total, g_desc, g_idx, g_slot, g_lse, g_po, total;
     int nparts, P;
 };
 
@@ -71,14 +71,16 @@ WsLayout ws_layout(int B, int H, int N, int d, int dtype, bool full_proj = false
     {   // regrouping by key block: one slot per kept (query, key block) pair
         const int kk = topk > 8 ? 8 : topk;
         const size_t pairs = BH * (size_t)N * kk;
+        const size_t nch = ((size_t)N + 1023) / 1024;
         w.g_counts = off; off = align256(off + (topk ? sizeof(int32_t) * BH * 64 : 0));
-        w.g_seg = off; off = align256(off + (topk ? sizeof(int32_t) * BH * 64 : 0));
+        w.g_ccnt = off; off = align256(off + (topk ? sizeof(int32_t) * BH * nch * 64 : 0));
+        w.g_seg = off; off = align256(off + (topk ? sizeof(int32_t) * BH * nch * 64 : 0));
         w.g_total = off; off = align256(off + (topk ? 256 : 0));
         w.g_desc = off; off = align256(off + (topk ? sizeof(uint4) * (size_t)topk_max_tiles((int)BH, N, kk, 64) : 0));
         w.g_idx = off; off = align256(off + (topk ? sizeof(int32_t) * pairs : 0));
         w.g_slot = off; off = align256(off + (topk ? sizeof(int32_t) * pairs : 0));
         w.g_lse = off; off = align256(off + (topk ? sizeof(float) * pairs : 0));
-        w.g_po = off; off = align256(off + (topk ? sizeof(float) * pairs * d : 0));
+        w.g_po = off; off = align256(off + (topk ? sizeof(u16) * pairs * d : 0));
     }
     w.total = off;
     return w;
@@ -394,12 +396,12 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
         a.topk_mask = mask;
         if (topk_regroup) {
             const int kk = p->topk < nbk ? p->topk : nbk;
-            e = launch_topk_group(mask, BH, p->N, nbk, kk, (int32_t *)(ws + w.g_counts), (int32_t *)(ws + w.g_seg),
-                                  (uint4 *)(ws + w.g_desc), (int32_t *)(ws + w.g_total), (int32_t *)(ws + w.g_idx),
+            e = launch_topk_group(mask, BH, p->N, nbk, kk, (int32_t *)(ws + w.g_ccnt), (int32_t *)(ws + w.g_seg),
+                                  (int32_t *)(ws + w.g_counts), (uint4 *)(ws + w.g_desc), (int32_t *)(ws + w.g_total), (int32_t *)(ws + w.g_idx),
                                   (int32_t *)(ws + w.g_slot), st);
             if (e != hipSuccess) return hip_fail(e, "top-k regrouping launch");
             a.g_desc = (const uint4 *)(ws + w.g_desc); a.g_total = (const int32_t *)(ws + w.g_total);
-            a.g_idx = (const int32_t *)(ws + w.g_idx); a.g_po = (float *)(ws + w.g_po); a.g_lse = (float *)(ws + w.g_lse);
+            a.g_idx = (const int32_t *)(ws + w.g_idx); a.g_po = (u16 *)(ws + w.g_po); a.g_lse = (float *)(ws + w.g_lse);
             a.g_kk = kk; a.g_bpb = p->topk_key_block / 64; a.g_max_tiles = topk_max_tiles(BH, p->N, kk, nbk);
         } else {
             e = launch_topk_tile_lists(mask, BH, p->N, a.nb, p->topk_key_block, nbk, (uint32_t *)(ws + w.tile_lists), (int32_t *)(ws + w.tile_counts), st);

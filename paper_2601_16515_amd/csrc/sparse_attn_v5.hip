@@ -620,13 +620,16 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
     if (!qvalid) return;
     if (GATHER) {
         // normalised partial result of this (query, key block) pair and its log-sum-exp (log2 domain)
-        float *po = a.g_po + g_slot * D;
+        u16 *po = a.g_po + g_slot * D;
 #pragma unroll
         for (int dt = 0; dt < NDT; ++dt)
 #pragma unroll
-            for (int g4 = 0; g4 < 4; ++g4)
-                *reinterpret_cast<float4 *>(po + dt * 32 + 8 * g4 + 4 * hh) =
-                    make_float4(o[dt][g4 * 4 + 0] * inv_l, o[dt][g4 * 4 + 1] * inv_l, o[dt][g4 * 4 + 2] * inv_l, o[dt][g4 * 4 + 3] * inv_l);
+            for (int g4 = 0; g4 < 4; ++g4) {
+                uint2 pk;
+                pk.x = pack2e(o[dt][g4 * 4 + 0] * inv_l, o[dt][g4 * 4 + 1] * inv_l);
+                pk.y = pack2e(o[dt][g4 * 4 + 2] * inv_l, o[dt][g4 * 4 + 3] * inv_l);
+                *reinterpret_cast<uint2 *>(po + dt * 32 + 8 * g4 + 4 * hh) = pk;
+            }
         if (hh == 0) a.g_lse[g_slot] = l_tot > 0.f ? m_run + log2f(l_tot) : -INFINITY;
         return;
     }

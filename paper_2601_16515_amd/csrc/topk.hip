@@ -46,54 +46,71 @@ hipError_t launch_kblock_mean(const u16 *k, int BH, int N, int key_block, int nb
     return hipGetLastError();
 }
 
-// grid (ceil(N / 256), BH), 256 threads: a thread owns one query; the block means are the same for every lane
-// (scalar loads).  The best 8 scores are kept in descending order; the first topk of them are the selection.
+// grid (ceil(N / 256), BH), 256 threads: a thread owns one query and keeps one score accumulator per key block
+// (NBK of them, the smallest instantiation >= nbk: the chains are independent, each runs over the channels in
+// ascending order).  The head's block means sit in LDS; every lane reads the same word (broadcast).  The best 8
+// scores are then collected in descending order, blocks in ascending order; the first topk of them are the selection.
+template <int NBK>
 __global__ __launch_bounds__(256) void topk_select_kernel(const u16 *__restrict__ q, const float *__restrict__ means,
                                                           int N, int nbk, int topk,
                                                           unsigned long long *__restrict__ mask)
 {
+    __shared__ float sm[NBK * D];
     const int bh = blockIdx.y;
     const int n = blockIdx.x * 256 + threadIdx.x;
     const int nr = n < N ? n : N - 1;
-    float qv[D];
-    {
-        const uint4 *src = reinterpret_cast<const uint4 *>(q + ((size_t)bh * N + nr) * D);
+    for (int i = threadIdx.x; i < NBK * D; i += 256) sm[i] = i < nbk * D ? means[(size_t)bh * nbk * D + i] : 0.f;
+    __syncthreads();
+    float sc[NBK];
 #pragma unroll
-        for (int i = 0; i < D / 8; ++i) {
-            const uint4 u = src[i];
-            const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+    for (int J = 0; J < NBK; ++J) sc[J] = 0.f;
+    const uint4 *src = reinterpret_cast<const uint4 *>(q + ((size_t)bh * N + nr) * D);
+#pragma unroll 1
+    for (int c8 = 0; c8 < D / 8; ++c8) {               // 8 channels of the query at a time
+        const uint4 u = src[c8];
+        const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+        float qv[8];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                qv[i * 8 + 2 * j] = __uint_as_float(w[j] << 16);
-                qv[i * 8 + 2 * j + 1] = __uint_as_float(w[j] & 0xffff0000u);
-            }
+        for (int j = 0; j < 4; ++j) {
+            qv[2 * j] = __uint_as_float(w[j] << 16);
+            qv[2 * j + 1] = __uint_as_float(w[j] & 0xffff0000u);
+        }
+        const float *mc = sm + c8 * 8;
+#pragma unroll
+        for (int J = 0; J < NBK; ++J) {
+            const float4 m0 = *reinterpret_cast<const float4 *>(mc + J * D);
+            const float4 m1 = *reinterpret_cast<const float4 *>(mc + J * D + 4);
+            float x = sc[J];
+            x = __fmaf_rn(qv[0], m0.x, x); x = __fmaf_rn(qv[1], m0.y, x);
+            x = __fmaf_rn(qv[2], m0.z, x); x = __fmaf_rn(qv[3], m0.w, x);
+            x = __fmaf_rn(qv[4], m1.x, x); x = __fmaf_rn(qv[5], m1.y, x);
+            x = __fmaf_rn(qv[6], m1.z, x); x = __fmaf_rn(qv[7], m1.w, x);
+            sc[J] = x;
         }
     }
     float best[8];
     int bidx[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) { best[i] = -INFINITY; bidx[i] = -1; }
-    const float *mrow = means + (size_t)bh * nbk * D;
-    for (int J = 0; J < nbk; ++J) {
-        float sc = 0.f;
 #pragma unroll
-        for (int c = 0; c < D; ++c) sc = __fmaf_rn(qv[c], mrow[c], sc);
-        mrow += D;
-        // bubble the new pair down the descending list; a strict comparison keeps earlier blocks ahead on ties.
-        // An empty slot (index -1) always gives way, whatever the score (-inf scores included).
-        float v = sc;
-        int id = J;
-        bool carry = false;                    // once placed, the displaced pairs all move down one slot
+    for (int J = 0; J < NBK; ++J) {
+        if (J < nbk) {
+            // bubble the pair down the descending list; a strict comparison keeps earlier blocks ahead on ties; an
+            // empty slot (index -1) always gives way; once placed, the displaced pairs all move down one slot
+            float v = sc[J];
+            int id = J;
+            bool carry = false;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const bool take = (id >= 0) && (carry || bidx[i] < 0 || v > best[i]);
-            carry = carry || take;
-            const float tv = best[i];
-            const int ti = bidx[i];
-            best[i] = take ? v : tv;
-            bidx[i] = take ? id : ti;
-            v = take ? tv : v;
-            id = take ? ti : id;
+            for (int i = 0; i < 8; ++i) {
+                const bool take = (id >= 0) && (carry || bidx[i] < 0 || v > best[i]);
+                carry = carry || take;
+                const float tv = best[i];
+                const int ti = bidx[i];
+                best[i] = take ? v : tv;
+                bidx[i] = take ? id : ti;
+                v = take ? tv : v;
+                id = take ? ti : id;
+            }
         }
     }
     unsigned long long m = 0ull;
@@ -106,7 +123,11 @@ __global__ __launch_bounds__(256) void topk_select_kernel(const u16 *__restrict_
 hipError_t launch_topk_select(const u16 *q, const float *means, int BH, int N, int nbk, int topk,
                               unsigned long long *mask, hipStream_t st)
 {
-    hipLaunchKernelGGL(topk_select_kernel, dim3((N + 255) / 256, BH), dim3(256), 0, st, q, means, N, nbk, topk, mask);
+    const dim3 grid((N + 255) / 256, BH), block(256);
+    if (nbk <= 16) hipLaunchKernelGGL(topk_select_kernel<16>, grid, block, 0, st, q, means, N, nbk, topk, mask);
+    else if (nbk <= 32) hipLaunchKernelGGL(topk_select_kernel<32>, grid, block, 0, st, q, means, N, nbk, topk, mask);
+    else if (nbk <= 48) hipLaunchKernelGGL(topk_select_kernel<48>, grid, block, 0, st, q, means, N, nbk, topk, mask);
+    else hipLaunchKernelGGL(topk_select_kernel<64>, grid, block, 0, st, q, means, N, nbk, topk, mask);
     return hipGetLastError();
 }
 
@@ -174,49 +195,74 @@ hipError_t launch_topk_tile_lists(const unsigned long long *mask, int BH, int N,
 // the work is the kept (query, key block) pairs whatever the selection looks like; every pair gets a slot in
 // [0, N * kk) of its (sample, head), key blocks ascending, queries ascending inside a key block.
 
-// grid (nbk, BH), 256 threads: counts[bh * nbk + J] = number of queries keeping block J
-__global__ __launch_bounds__(256) void topk_count_kernel(const unsigned long long *__restrict__ mask, int N, int nbk,
-                                                         int32_t *__restrict__ counts)
+// Chunks of 1024 queries.  Wave w of a chunk publishes, for every key block J, the ballot of its 64 queries' bit J.
+__device__ inline void chunk_ballots(unsigned long long m, int nbk, unsigned long long (*wb)[64], int wv, int lane)
 {
-    __shared__ int part[4];
-    const int J = blockIdx.x, bh = blockIdx.y, t = threadIdx.x;
-    int c = 0;
-    for (int n = t; n < N; n += 256) c += (int)((mask[(size_t)bh * N + n] >> J) & 1ull);
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o);
-    if ((t & 63) == 0) part[t >> 6] = c;
-    __syncthreads();
-    if (t == 0) counts[bh * nbk + J] = part[0] + part[1] + part[2] + part[3];
+    for (int J = 0; J < nbk; ++J) {
+        const unsigned long long bal = __ballot((m >> J) & 1ull);
+        if (lane == 0) wb[wv][J] = bal;
+    }
 }
 
-// one workgroup of 256 threads: seg_start[e] = first slot of pair group e = (bh, J) within its (sample, head);
-// tile descriptors (bh, J, first slot, queries) for every run of up to 256 queries, groups in order; *total = tiles.
-__global__ __launch_bounds__(256) void topk_plan_kernel(const int32_t *__restrict__ counts, int BH, int nbk,
-                                                        int32_t *__restrict__ seg_start, uint4 *__restrict__ desc,
-                                                        int max_tiles, int32_t *__restrict__ total)
+// grid (nch, BH), 1024 threads: ccnt[(bh * nch + chunk) * 64 + J] = queries of the chunk keeping block J
+__global__ __launch_bounds__(1024) void topk_count_kernel(const unsigned long long *__restrict__ mask, int N, int nbk,
+                                                          int nch, int32_t *__restrict__ ccnt)
 {
-    __shared__ int tsum[256];
+    __shared__ unsigned long long wb[16][64];
+    const int chunk = blockIdx.x, bh = blockIdx.y, t = threadIdx.x, lane = t & 63, wv = t >> 6;
+    const int n = chunk * 1024 + t;
+    const unsigned long long m = n < N ? mask[(size_t)bh * N + n] : 0ull;
+    chunk_ballots(m, nbk, wb, wv, lane);
+    __syncthreads();
+    if (t < 64) {
+        int c = 0;
+        if (t < nbk)
+#pragma unroll
+            for (int w = 0; w < 16; ++w) c += __popcll(wb[w][t]);
+        ccnt[((size_t)bh * nch + chunk) * 64 + t] = c;
+    }
+}
+
+// one workgroup of 1024 threads.  Pair group e = (bh, J): cbase[(bh * nch + chunk) * 64 + J] = first slot (within the
+// sample-head) of the chunk's queries keeping J = slots of key blocks < J + those of earlier chunks; tile descriptors
+// (bh, J, first slot, queries) for every run of up to 256 queries, groups in order; *total = tiles.
+__global__ __launch_bounds__(1024) void topk_plan_kernel(const int32_t *__restrict__ ccnt, int BH, int nbk, int nch,
+                                                         int32_t *__restrict__ counts, int32_t *__restrict__ cbase,
+                                                         uint4 *__restrict__ desc, int max_tiles, int32_t *__restrict__ total)
+{
+    __shared__ int tsum[1024];
     const int t = threadIdx.x;
-    const int E = BH * nbk, per = (E + 255) / 256;
+    const int E = BH * nbk, per = (E + 1023) / 1024;
     const int e0 = min(E, t * per), e1 = min(E, e0 + per);
     int tiles = 0;
-    for (int e = e0; e < e1; ++e) tiles += (counts[e] + 255) >> 8;
+    for (int e = e0; e < e1; ++e) {
+        const int bh = e / nbk, J = e - bh * nbk;
+        int c = 0;
+        for (int ch = 0; ch < nch; ++ch) c += ccnt[((size_t)bh * nch + ch) * 64 + J];
+        counts[e] = c;
+        tiles += (c + 255) >> 8;
+    }
     tsum[t] = tiles;
+    __threadfence_block();
     __syncthreads();
     if (t == 0) {
         int run = 0;
-        for (int i = 0; i < 256; ++i) { const int x = tsum[i]; tsum[i] = run; run += x; }
+        for (int i = 0; i < 1024; ++i) { const int x = tsum[i]; tsum[i] = run; run += x; }
         *total = min(run, max_tiles);
     }
     __syncthreads();
     int tile = tsum[t];
     for (int e = e0; e < e1; ++e) {
         const int bh = e / nbk, J = e - bh * nbk;
-        // slots of this (sample, head) before key block J
-        int s0 = 0;
+        int s0 = 0;                                     // slots of this (sample, head) before key block J
         for (int j = 0; j < J; ++j) s0 += counts[bh * nbk + j];
-        seg_start[e] = s0;
-        const int c = counts[e];
+        int run = s0;
+        for (int ch = 0; ch < nch; ++ch) {
+            const size_t i = ((size_t)bh * nch + ch) * 64 + J;
+            cbase[i] = run;
+            run += ccnt[i];
+        }
+        const int c = run - s0;
         for (int i = 0; i < c; i += 256) {
             if (tile < max_tiles) desc[tile] = make_uint4((uint32_t)bh, (uint32_t)J, (uint32_t)(s0 + i), (uint32_t)min(256, c - i));
             ++tile;
@@ -224,43 +270,48 @@ __global__ __launch_bounds__(256) void topk_plan_kernel(const int32_t *__restric
     }
 }
 
-// grid (nbk, BH), 256 threads: gidx[bh * slots + seg_start + pos] = n for the pos-th query (ascending) keeping block J,
-// slot_of[(bh * N + n) * kk + r] = that slot, r = rank of J among the query's kept blocks.
-__global__ __launch_bounds__(256) void topk_group_kernel(const unsigned long long *__restrict__ mask, int N, int nbk, int kk,
-                                                         const int32_t *__restrict__ seg_start,
-                                                         int32_t *__restrict__ gidx, int32_t *__restrict__ slot_of)
+// grid (nch, BH), 1024 threads: gidx[bh * slots + slot] = n and slot_of[(bh * N + n) * kk + r] = slot for every kept
+// pair of the chunk; inside a key block the queries stay in ascending order (slot = chunk base + queries of lower
+// waves + lower lanes keeping the block), r = rank of the block among the query's kept blocks.
+__global__ __launch_bounds__(1024) void topk_group_kernel(const unsigned long long *__restrict__ mask, int N, int nbk, int kk,
+                                                          int nch, const int32_t *__restrict__ cbase,
+                                                          int32_t *__restrict__ gidx, int32_t *__restrict__ slot_of)
 {
-    __shared__ int wcnt[4];
-    const int J = blockIdx.x, bh = blockIdx.y, t = threadIdx.x, lane = t & 63, wv = t >> 6;
+    __shared__ unsigned long long wb[16][64];
+    __shared__ int wpre[16][64];
+    const int chunk = blockIdx.x, bh = blockIdx.y, t = threadIdx.x, lane = t & 63, wv = t >> 6;
+    const int n = chunk * 1024 + t;
     const size_t slots = (size_t)N * kk;
-    int base = seg_start[bh * nbk + J];
-    for (int n0 = 0; n0 < N; n0 += 256) {
-        const int n = n0 + t;
-        const unsigned long long m = n < N ? mask[(size_t)bh * N + n] : 0ull;
-        const bool keep = (m >> J) & 1ull;
-        const unsigned long long bal = __ballot(keep);
-        if (lane == 0) wcnt[wv] = __popcll(bal);
-        __syncthreads();
-        int before = 0;
-        for (int w = 0; w < wv; ++w) before += wcnt[w];
-        const int all = wcnt[0] + wcnt[1] + wcnt[2] + wcnt[3];
-        if (keep) {
-            const int slot = base + before + __popcll(bal & ((1ull << lane) - 1ull));
-            const int r = __popcll(m & ((1ull << J) - 1ull));
-            if (slot < (int)slots && r < kk) {
+    unsigned long long m = n < N ? mask[(size_t)bh * N + n] : 0ull;
+    chunk_ballots(m, nbk, wb, wv, lane);
+    __syncthreads();
+    {
+        const int J = lane;                             // thread (wv, J): queries of lower waves keeping J
+        int c = 0;
+        if (J < nbk)
+            for (int w = 0; w < wv; ++w) c += __popcll(wb[w][J]);
+        wpre[wv][J] = c + (J < nbk ? cbase[((size_t)bh * nch + chunk) * 64 + J] : 0);
+    }
+    __syncthreads();
+    int r = 0;
+    while (m != 0ull && r < kk) {
+        const int J = __ffsll((long long)m) - 1;
+        m &= m - 1ull;
+        if (J < nbk) {
+            const int slot = wpre[wv][J] + __popcll(wb[wv][J] & ((1ull << lane) - 1ull));
+            if (slot >= 0 && (size_t)slot < slots) {
                 gidx[(size_t)bh * slots + slot] = n;
                 slot_of[((size_t)bh * N + n) * kk + r] = slot;
             }
         }
-        base += all;
-        __syncthreads();
+        ++r;
     }
 }
 
-// out[bh, n, :] = sum_r w_r O_r / sum_r w_r over the query's kk partial results (normalised per key block, with
+// out[bh, n, :] = sum_r w_r O_r / sum_r w_r over the query's kk partial results (normalised per key block, bf16, with
 // log2-domain log-sum-exp lse_r), w_r = 2^(lse_r - max lse): Eq. (2) over the union of the kept blocks.
 // 32 lanes per query (4 channels each); grid ceil(BH * N / 8), 256 threads.
-__global__ __launch_bounds__(256) void topk_merge_kernel(const float *__restrict__ po, const float *__restrict__ lse,
+__global__ __launch_bounds__(256) void topk_merge_kernel(const u16 *__restrict__ po, const float *__restrict__ lse,
                                                          const int32_t *__restrict__ slot_of,
                                                          const unsigned long long *__restrict__ mask, int BH, int N, int kk,
                                                          u16 *__restrict__ out, float *__restrict__ o_dbg)
@@ -291,9 +342,9 @@ __global__ __launch_bounds__(256) void topk_merge_kernel(const float *__restrict
     for (int r = 0; r < 8; ++r) {
         if (r < kk) {
             const float wgt = __builtin_amdgcn_exp2f(l[r] - mx);
-            const float4 x = *reinterpret_cast<const float4 *>(po + (bh * slots + sl[r]) * D + c4);
-            acc.x = fmaf(wgt, x.x, acc.x); acc.y = fmaf(wgt, x.y, acc.y);
-            acc.z = fmaf(wgt, x.z, acc.z); acc.w = fmaf(wgt, x.w, acc.w);
+            const uint2 x = *reinterpret_cast<const uint2 *>(po + (bh * slots + sl[r]) * D + c4);
+            acc.x = fmaf(wgt, __uint_as_float(x.x << 16), acc.x); acc.y = fmaf(wgt, __uint_as_float(x.x & 0xffff0000u), acc.y);
+            acc.z = fmaf(wgt, __uint_as_float(x.y << 16), acc.z); acc.w = fmaf(wgt, __uint_as_float(x.y & 0xffff0000u), acc.w);
             den += wgt;
         }
     }
@@ -310,18 +361,19 @@ __global__ __launch_bounds__(256) void topk_merge_kernel(const float *__restrict
 
 int topk_max_tiles(int BH, int N, int kk, int nbk) { return BH * ((int)(((long long)N * kk + 255) / 256) + nbk); }
 
-hipError_t launch_topk_group(const unsigned long long *mask, int BH, int N, int nbk, int kk, int32_t *counts,
-                             int32_t *seg_start, uint4 *desc, int32_t *total, int32_t *gidx, int32_t *slot_of,
-                             hipStream_t st)
+hipError_t launch_topk_group(const unsigned long long *mask, int BH, int N, int nbk, int kk, int32_t *ccnt,
+                             int32_t *cbase, int32_t *counts, uint4 *desc, int32_t *total, int32_t *gidx,
+                             int32_t *slot_of, hipStream_t st)
 {
-    hipLaunchKernelGGL(topk_count_kernel, dim3(nbk, BH), dim3(256), 0, st, mask, N, nbk, counts);
-    hipLaunchKernelGGL(topk_plan_kernel, dim3(1), dim3(256), 0, st, counts, BH, nbk, seg_start, desc,
+    const int nch = (N + 1023) / 1024;
+    hipLaunchKernelGGL(topk_count_kernel, dim3(nch, BH), dim3(1024), 0, st, mask, N, nbk, nch, ccnt);
+    hipLaunchKernelGGL(topk_plan_kernel, dim3(1), dim3(1024), 0, st, ccnt, BH, nbk, nch, counts, cbase, desc,
                        topk_max_tiles(BH, N, kk, nbk), total);
-    hipLaunchKernelGGL(topk_group_kernel, dim3(nbk, BH), dim3(256), 0, st, mask, N, nbk, kk, seg_start, gidx, slot_of);
+    hipLaunchKernelGGL(topk_group_kernel, dim3(nch, BH), dim3(1024), 0, st, mask, N, nbk, kk, nch, cbase, gidx, slot_of);
     return hipGetLastError();
 }
 
-hipError_t launch_topk_merge(const float *po, const float *lse, const int32_t *slot_of, const unsigned long long *mask,
+hipError_t launch_topk_merge(const u16 *po, const float *lse, const int32_t *slot_of, const unsigned long long *mask,
                              int BH, int N, int kk, u16 *out, float *o_dbg, hipStream_t st)
 {
     const size_t nq = (size_t)BH * N;
