@@ -101,6 +101,16 @@ def _params(**over):
     (dict(flags=8), sb.SALAD_EINVAL, "flags"),
     (dict(flags=1, dtype=sb.SALAD_F32), sb.SALAD_ENOTSUP, "bf16"),
     (dict(lam=float("nan")), sb.SALAD_EINVAL, "lambda"),
+    (dict(drop_threshold=float("nan")), sb.SALAD_EINVAL, "drop_threshold"),
+    (dict(w_proj=0x8000), sb.SALAD_ENOTSUP, "w_proj"),                                   # d = 64
+    (dict(w_proj=0x8000, d=128, head_scale=0x9000), sb.SALAD_EINVAL, "exclude"),
+    (dict(topk=-1), sb.SALAD_EINVAL, "topk"),
+    (dict(topk=4, topk_key_block=128), sb.SALAD_ENOTSUP, "d = 128"),                     # d = 64
+    (dict(topk=9, topk_key_block=128, d=128), sb.SALAD_ENOTSUP, "above 8"),
+    (dict(topk=4, topk_key_block=100, d=128), sb.SALAD_EINVAL, "multiple of 64"),
+    (dict(topk=4, topk_key_block=0, d=128), sb.SALAD_EINVAL, "multiple of 64"),
+    (dict(topk=4, topk_key_block=64, d=128, N=8192, T=32), sb.SALAD_ENOTSUP, "key blocks"),   # 128 key blocks
+    (dict(topk=4, topk_key_block=128, d=128, workspace_bytes=1 << 16), sb.SALAD_ENOSPC, "workspace"),
 ])
 def test_fwd_argument_errors(lib, over, status, needle):
     p = _params(**over)
@@ -116,7 +126,20 @@ def test_fwd_null_params_and_head_kind(lib):
     assert "head_kind" in _err(lib)
 
 
+def test_topk_rejects_temporal_heads_and_ignores_csr(lib):
+    hk = (C.c_uint8 * 2)(0, 1)
+    p = _params(topk=2, topk_key_block=128, d=128, head_kind_host=C.cast(hk, C.c_void_p))
+    assert lib.salad_sparse_linear_attn_fwd(C.byref(p)) == sb.SALAD_ENOTSUP
+    assert "stored token order" in _err(lib)
+    # the CSR pointers may be null with topk: the next check that fails is a different one (workspace size)
+    p = _params(topk=2, topk_key_block=128, d=128, row_ptr=None, col_idx=None, workspace_bytes=256)
+    assert lib.salad_sparse_linear_attn_fwd(C.byref(p)) == sb.SALAD_ENOSPC
+
+
 def test_workspace_query(lib):
+    base = sb.salad_fwd_workspace_bytes(1, 12, 32760, 128, sb.SALAD_BF16)
+    assert sb.salad_fwd_workspace_bytes(1, 12, 32760, 128, sb.SALAD_BF16, full_proj=True) > base + 2 * 12 * 32760 * 128
+    assert sb.salad_fwd_workspace_bytes(1, 12, 32760, 128, sb.SALAD_BF16, topk=4) > base + 2 * 4 * 12 * 32760 * 128
     assert sb.salad_fwd_workspace_bytes(1, 12, 32760, 128, sb.SALAD_BF16) > 12 * (128 * 128 + 128) * 4
     assert sb.salad_fwd_workspace_bytes(1, 2, 1024, 64, sb.SALAD_F32) > 0
     assert sb.salad_fwd_workspace_bytes(1, 2, 1024, 96, sb.SALAD_BF16) == 0
