@@ -38,6 +38,8 @@
  *   - Top-K: key blocks are runs of key_block consecutive tokens of the stored order, the similarity is the
  *     plain dot product q.mean(K_block), every query token selects for itself, ties go to the lower block
  *     index, no block is forced in; the selection is computed in float32 in a fixed order (see there);
+ *   - RoPE in the linear branch: rotation of phi(Q), phi(K) in the numerator only, angles supplied as tables,
+ *     channel pairs (2p, 2p+1) (see salad_oracle_linear_state_rope);
  *   - "below the threshold" is the strict inequality s_b < tau; a dropped branch contributes
  *     exactly nothing (out = O_s), and tau <= 0 never drops since s_b > 0.
  *
@@ -371,6 +373,78 @@ int salad_oracle_linear_apply(const float *q, const double *Hs, const double *Z,
         }
         den += eps;
         for (int c = 0; c < d; ++c) o[c] /= den;
+    }
+    return SO_OK;
+}
+
+/* ---- rotary position embedding inside the linear branch (Sec. 4.1: the linear branch incorporates 3D RoPE) ----
+ *
+ * The paper gives no formula; the reading taken here: the feature-mapped queries and keys are rotated in the
+ * numerator only, the normaliser keeps the unrotated (non-negative) features:
+ *   O_l[i] = sum_j (R_i phi(Q_i)) . (R_j phi(K_j)) V_j / (phi(Q_i) . sum_j phi(K_j) + eps),
+ * R_n rotating channel pair (2p, 2p+1) of token n by the angle whose cosine and sine are cs[n][p], sn[n][p]
+ * (float32 tables [N, d/2] from the caller, who owns the split of the pairs over the t, y, x axes and the
+ * frequencies).  Reassociated like Eq. (3): Hr = sum_j (R_j phi(K_j))^T V_j, numerator = (R_i phi(Q_i)) Hr. */
+static inline void rope_rotate(const float *x, const float *cs, const float *sn, int d, double *out)
+{
+    for (int p = 0; p < d / 2; ++p) {
+        const double a = relu((double)x[2 * p]), b = relu((double)x[2 * p + 1]);
+        out[2 * p] = a * (double)cs[p] - b * (double)sn[p];
+        out[2 * p + 1] = a * (double)sn[p] + b * (double)cs[p];
+    }
+}
+
+/* Hr [B,H,d,d] = sum_j (R_j relu(K_j))^T V_j. */
+int salad_oracle_linear_state_rope(const float *k, const float *v, const float *cs, const float *sn,
+                                   int B, int H, int64_t N, int d, double *Hr)
+{
+    if (d % 2) return SO_EINVAL;
+    const int64_t BH = (int64_t)B * H;
+#pragma omp parallel for schedule(static)
+    for (int64_t bh = 0; bh < BH; ++bh) {
+        double *kr = (double *)malloc(sizeof(double) * (size_t)d);
+        double *h = Hr + bh * d * d;
+        for (int64_t e = 0; e < (int64_t)d * d; ++e) h[e] = 0.0;
+        for (int64_t j = 0; j < N; ++j) {
+            rope_rotate(k + (bh * N + j) * d, cs + j * (d / 2), sn + j * (d / 2), d, kr);
+            const float *vj = v + (bh * N + j) * d;
+            for (int a = 0; a < d; ++a)
+                for (int c = 0; c < d; ++c) h[a * d + c] += kr[a] * (double)vj[c];
+        }
+        free(kr);
+    }
+    return SO_OK;
+}
+
+/* O_l for the listed stored rows: (R_n relu(Q_n)) Hr / (relu(Q_n).Z + eps); same argument shapes as
+ * salad_oracle_linear_apply. */
+int salad_oracle_linear_apply_rope(const float *q, const double *Hr, const double *Z, const float *cs, const float *sn,
+                                   int B, int H, int64_t N, int d, double eps,
+                                   const int64_t *rows, int64_t nrows, double *out)
+{
+    if (d % 2) return SO_EINVAL;
+    const int64_t total = (int64_t)B * H * nrows;
+#pragma omp parallel
+    {
+        double *qr = (double *)malloc(sizeof(double) * (size_t)d);
+#pragma omp for schedule(static)
+        for (int64_t idx = 0; idx < total; ++idx) {
+            const int64_t bh = idx / nrows;
+            const int64_t n = rows[idx];
+            double *o = out + idx * d;
+            for (int c = 0; c < d; ++c) o[c] = 0.0;
+            if (n < 0 || n >= N) continue;
+            const float *qi = q + (bh * N + n) * d;
+            rope_rotate(qi, cs + n * (d / 2), sn + n * (d / 2), d, qr);
+            double den = eps;
+            for (int a = 0; a < d; ++a) {
+                den += relu((double)qi[a]) * Z[bh * d + a];
+                const double *hrow = Hr + (bh * d + a) * d;
+                for (int c = 0; c < d; ++c) o[c] += qr[a] * hrow[c];
+            }
+            for (int c = 0; c < d; ++c) o[c] /= den;
+        }
+        free(qr);
     }
     return SO_OK;
 }

@@ -127,6 +127,40 @@ def linear_apply(q, Hs, Z, eps: float, rows: Optional[np.ndarray] = None) -> np.
     return out
 
 
+def linear_state_rope(k, v, cos, sin) -> np.ndarray:
+    """Rotated linear state Hr [B,H,d,d] = sum_j (R_j relu(K_j))^T V_j; cos, sin: float32 [N, d/2] (pair (2p, 2p+1))."""
+    k, v = _f32(k), _f32(v)
+    cos, sin = _f32(cos), _f32(sin)
+    B, H, N, d = k.shape
+    assert cos.shape == (N, d // 2) and sin.shape == (N, d // 2)
+    Hr = np.zeros((B, H, d, d), dtype=np.float64)
+    rc = _load().salad_oracle_linear_state_rope(_p(k), _p(v), _p(cos), _p(sin), C.c_int(B), C.c_int(H), C.c_int64(N),
+                                                C.c_int(d), _p(Hr))
+    if rc != 0:
+        raise ValueError("salad_oracle_linear_state_rope: invalid arguments")
+    return Hr
+
+
+def linear_apply_rope(q, Hr, Z, eps: float, cos, sin, rows: Optional[np.ndarray] = None) -> np.ndarray:
+    """(R_n relu(Q_n)) Hr / (relu(Q_n).Z + eps) for stored rows `rows` [B,H,nrows] (default: every row)."""
+    q = _f32(q)
+    cos, sin = _f32(cos), _f32(sin)
+    B, H, N, d = q.shape
+    if rows is None:
+        rows = np.broadcast_to(np.arange(N, dtype=np.int64), (B, H, N))
+    rows = np.ascontiguousarray(rows, dtype=np.int64)
+    nrows = rows.shape[-1]
+    Hr = np.ascontiguousarray(Hr, dtype=np.float64)
+    Z = np.ascontiguousarray(Z, dtype=np.float64)
+    out = np.zeros((B, H, nrows, d), dtype=np.float64)
+    rc = _load().salad_oracle_linear_apply_rope(_p(q), _p(Hr), _p(Z), _p(cos), _p(sin), C.c_int(B), C.c_int(H),
+                                                C.c_int64(N), C.c_int(d), C.c_double(eps), _p(rows),
+                                                C.c_int64(nrows), _p(out))
+    if rc != 0:
+        raise ValueError("salad_oracle_linear_apply_rope: invalid arguments")
+    return out
+
+
 def linear_attn_quadratic(q, k, v, eps: float) -> np.ndarray:
     """Un-reassociated linear attention of one head, [N,d] inputs; O(N^2 d)."""
     q, k, v = _f32(q), _f32(k), _f32(v)
@@ -225,7 +259,7 @@ def branch_drop(s, tau: float) -> np.ndarray:
 
 def salad_forward(q, k, v, x_t, w_gate, head_scale, grid, block, head_kind, kept, lam=1.0, eps=1e-6,
                   b_gate=0.0, scale=None, sel=None, s_override=None, drop_threshold=0.0,
-                  w_proj=None, topk: int = 0, key_block: int = 0) -> Dict[str, np.ndarray]:
+                  w_proj=None, topk: int = 0, key_block: int = 0, rope=None) -> Dict[str, np.ndarray]:
     """Whole layer (Alg. 1 from SparseAttn to the residual sum) on the selected query blocks.
 
     Returns compact row sets [B,H,nsel*block,d] for o_sparse, o_linear and out, the stored row
@@ -244,11 +278,17 @@ def salad_forward(q, k, v, x_t, w_gate, head_scale, grid, block, head_kind, kept
     else:
         o_s, rows = sparse_attn(q, k, v, grid, block, head_kind, row_ptr, col_idx, scale, sel)
     Hs, Z = linear_state(k, v)
-    o_l = linear_apply(q, Hs, Z, eps, rows)
+    if rope is not None:         # (cos, sin) tables [N, d/2]: rotary embedding inside the linear branch
+        Hs = linear_state_rope(k, v, rope[0], rope[1])
+        o_l = linear_apply_rope(q, Hs, Z, eps, rope[0], rope[1], rows)
+    else:
+        o_l = linear_apply(q, Hs, Z, eps, rows)
     s = gate(x_t, w_gate, b_gate) if s_override is None else np.asarray(s_override, dtype=np.float64)
     dropped = branch_drop(s, drop_threshold)
     # a pruned branch contributes exactly nothing: its samples are combined with a zero dynamic scale
     s_eff = np.where(dropped != 0, 0.0, s)
+    if w_proj is not None and rope is not None:
+        raise ValueError("the full projection and the rotary linear branch are not combined here")
     if w_proj is not None:       # full Level-1 projection across heads instead of the per-head scalars
         out = combine_proj(q, Hs, Z, eps, o_s, rows, w_proj, lam, s_eff)
     else:

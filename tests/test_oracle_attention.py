@@ -470,3 +470,81 @@ def test_topk_layer(oracle):
     dense = oracle.salad_forward(*args, kept=[w.nb] * w.H, **common)
     allk = oracle.salad_forward(*args, kept=[1] * w.H, topk=64, key_block=64, **common)
     assert np.abs(dense["out"] - allk["out"]).max() < 1e-12
+
+
+# ------------------------------------------------------------- rotary embedding inside the linear branch (Sec. 4.1)
+
+def _rope_tables(N, d, seed=3, scale=1.0):
+    """Angles theta[n, p] = position-like ramp times per-pair frequencies (any table serves the definition)."""
+    rng = np.random.default_rng(seed)
+    freq = 10000.0 ** (-np.arange(d // 2) / (d // 2)) * scale
+    pos = np.arange(N, dtype=np.float64)[:, None] + rng.integers(0, 3, size=(N, 1))
+    th = pos * freq[None, :]
+    return np.cos(th).astype(np.float32), np.sin(th).astype(np.float32), th
+
+
+def test_rope_linear_branch_against_complex_quadratic_form(oracle):
+    """Channel pairs as complex numbers: (R_i phi q_i) . (R_j phi k_j) = Re(sum_p conj(a_ip) b_jp) with
+    a = phi(q) e^{i theta}.  The reassociated oracle must equal that quadratic form (written here with numpy),
+    numerator rotated, normaliser not."""
+    B, H, N, d, eps = 1, 2, 70, 8, 1e-3
+    q, k, v = _qkv(51, B, H, N, d)
+    cs, sn, _ = _rope_tables(N, d)
+    rot = cs.astype(np.float64) + 1j * sn.astype(np.float64)                        # [N, d/2] as stored (float32 values)
+    fq, fk = np.maximum(q, 0).astype(np.float64), np.maximum(k, 0).astype(np.float64)
+    a = (fq[..., 0::2] + 1j * fq[..., 1::2]) * rot
+    b = (fk[..., 0::2] + 1j * fk[..., 1::2]) * rot
+    A = np.real(np.einsum("bhip,bhjp->bhij", a, np.conj(b)))                        # rotated similarities
+    num = np.einsum("bhij,bhjd->bhid", A, v.astype(np.float64))
+    den = np.einsum("bhid,bhd->bhi", fq, fk.sum(axis=2)) + eps
+    ref = num / den[..., None]
+    Hr = oracle.linear_state_rope(k, v, cs, sn)
+    _, Z = oracle.linear_state(k, v)
+    got = oracle.linear_apply_rope(q, Hr, Z, eps, cs, sn)
+    assert np.abs(got - ref).max() < 1e-12 * max(1.0, np.abs(ref).max())
+    assert np.abs(A - np.einsum("bhid,bhjd->bhij", fq, fk)).max() > 0.1             # the rotation matters here
+
+
+def test_rope_special_cases(oracle):
+    """Zero angles give the plain linear branch; a common shift of all angles cancels (only differences of
+    angles enter the numerator); a quarter turn of one pair is the closed form (a, b) -> (-b, a)."""
+    B, H, N, d, eps = 1, 1, 40, 4, 1e-2
+    q, k, v = _qkv(53, B, H, N, d)
+    Hs, Z = oracle.linear_state(k, v)
+    plain = oracle.linear_apply(q, Hs, Z, eps)
+    one, zero = np.ones((N, d // 2), np.float32), np.zeros((N, d // 2), np.float32)
+    assert np.abs(oracle.linear_apply_rope(q, oracle.linear_state_rope(k, v, one, zero), Z, eps, one, zero) - plain).max() < 1e-13
+    assert np.abs(oracle.linear_state_rope(k, v, one, zero) - Hs).max() < 1e-13
+    _, _, th = _rope_tables(N, d, scale=30.0)
+    outs = []
+    for shift in (0.0, 0.7):
+        cs, sn = np.cos(th + shift), np.sin(th + shift)                             # float64 tables rounded alike
+        cs, sn = cs.astype(np.float32), sn.astype(np.float32)
+        outs.append(oracle.linear_apply_rope(q, oracle.linear_state_rope(k, v, cs, sn), Z, eps, cs, sn))
+    assert np.abs(outs[0] - outs[1]).max() < 1e-5 * np.abs(outs[0]).max()           # float32 tables: ~1e-7 each
+    assert np.abs(outs[0] - plain).max() > 1e-2
+    # quarter turn on pair 0 of the keys only (queries unrotated): Hr rows 0, 1 = (-b, a) combinations
+    k1 = np.abs(k)
+    csq = np.ones((N, 2), np.float32); snq = np.zeros((N, 2), np.float32)
+    csq[:, 0], snq[:, 0] = 0.0, 1.0
+    Hr = oracle.linear_state_rope(k1, v, csq, snq)
+    H0, _ = oracle.linear_state(k1, v)
+    assert np.abs(Hr[0, 0, 0] + H0[0, 0, 1]).max() < 1e-12 and np.abs(Hr[0, 0, 1] - H0[0, 0, 0]).max() < 1e-12
+    assert np.abs(Hr[0, 0, 2:] - H0[0, 0, 2:]).max() < 1e-12
+
+
+def test_rope_layer(oracle):
+    """The layer with the rotary linear branch: sparse branch, gate and normaliser unchanged, O_l the rotated form."""
+    w = wl.small("rope", 1, 2, 16, 3, 5, 9, "f32", 0.5, seed=43)
+    inp = wl.make_inputs(w)
+    kinds = wl.head_kinds(w)
+    cs, sn, _ = _rope_tables(w.N, w.d)
+    common = dict(grid=(w.T, w.Hh, w.W), block=w.block, head_kind=kinds, kept=[2] * w.H, lam=1.5)
+    args = (inp["q"], inp["k"], inp["v"], inp["x_t"], inp["w_gate"], inp["head_scale"])
+    plain = oracle.salad_forward(*args, **common)
+    r = oracle.salad_forward(*args, rope=(cs, sn), **common)
+    assert np.array_equal(r["o_sparse"], plain["o_sparse"]) and np.array_equal(r["Z"], plain["Z"])
+    want = oracle.linear_apply_rope(inp["q"], oracle.linear_state_rope(inp["k"], inp["v"], cs, sn), r["Z"], w.eps, cs, sn, r["rows"])
+    assert np.array_equal(r["o_linear"], want)
+    coef = 1.5 * inp["head_scale"].astype(np.float64)[None, :, None, None] * r["s"][:, None, None, None]
+    assert np.abs(r["out"] - (r["o_sparse"] + coef * r["o_linear"])).max() < 1e-12
