@@ -114,6 +114,10 @@ typedef struct salad_fwd_params {
                                  dtype bf16, d = 128, all heads SPATIAL (blocks are runs of the stored order)    */
     int32_t topk_key_block;   /* tokens per key block: a multiple of 64 with ceil(N / topk_key_block) <= 64         */
     uint64_t *topk_mask_out;  /* optional device uint64 [B,H,N]: bit J set = the query keeps key block J            */
+    const float *rope_cos;    /* optional device fp32 [N, d/2] (shared by all samples and heads), with rope_sin: rotary  */
+    const float *rope_sin;    /*   position embedding inside the linear branch (Sec. 4.1): cosine and sine of the angle
+                                   of channel pair (2p, 2p+1) of token n at [n*d/2 + p].  Needs dtype bf16, d = 128,
+                                   w_proj == NULL                                                                    */
 } salad_fwd_params;
 
 /* Run the linear apply and the scale-and-sum as a separate streaming kernel after the sparse
@@ -142,6 +146,12 @@ size_t salad_fwd_workspace_bytes(const salad_fwd_params *p);
  * keeps the topk blocks with the largest q.mean and attends to exactly their tokens.  The selection runs on the
  * device in a fixed float32 order (block sums token by token, scores channel by channel with fused multiply-adds,
  * ties to the lower block index), so that it can be reproduced bit for bit.
+ * With rope_cos / rope_sin the linear branch carries a rotary position embedding (the paper states that it does and
+ * gives no formula; the reading implemented): phi(Q), phi(K) are rotated pairwise by the given angles in the numerator,
+ * the normaliser keeps the unrotated features:
+ *   O_l[i] = sum_j (R_i phi(Q_i)).(R_j phi(K_j)) V_j / (phi(Q_i).Z + eps) = (R_i phi(Q_i)) Hr / (phi(Q_i).Z + eps),
+ *   Hr = sum_j (R_j phi(K_j))^T V_j.  The caller owns the split of the pairs over the t, y, x axes and the frequencies
+ * (they are in the tables).  Runs with the separate linear-apply kernel.
  * Post-tuning branch dropping (Sec. 4.3, App. A.3): with drop_threshold = tau > 0, a sample whose dynamic
  * scale s_b < tau (strict, compared in fp32) loses its linear branch: out[b] = O_s[b], exactly as with
  * lambda == 0.  The decision is taken on the device (no host synchronisation): the gate is reduced first,

@@ -65,6 +65,8 @@ class FwdParams(C.Structure):
         ("topk", C.c_int32),
         ("topk_key_block", C.c_int32),
         ("topk_mask_out", C.c_void_p),
+        ("rope_cos", C.c_void_p),
+        ("rope_sin", C.c_void_p),
     ]
 
 
@@ -200,7 +202,7 @@ def make_fwd_params(q, k, v, out, grid: Tuple[int, int, int], row_ptr, col_idx, 
                     eps: float = 1e-6, softmax_scale: float = 0.0, s_out=None, o_sparse_dbg=None,
                     o_linear_dbg=None, workspace: Optional[Workspace] = None, flags: int = 0, block: int = 64,
                     drop_threshold: float = 0.0, dropped_out=None, w_proj=None, topk: int = 0,
-                    topk_key_block: int = 0, topk_mask_out=None):
+                    topk_key_block: int = 0, topk_mask_out=None, rope_cos=None, rope_sin=None):
     """Fill a salad_fwd_params from torch tensors.  Returns (params, keepalive)."""
     B, H, N, d = q.shape
     p = FwdParams()
@@ -235,6 +237,7 @@ def make_fwd_params(q, k, v, out, grid: Tuple[int, int, int], row_ptr, col_idx, 
     p.dropped_out = _ptr(dropped_out)
     p.w_proj = _ptr(w_proj)
     p.topk, p.topk_key_block, p.topk_mask_out = int(topk), int(topk_key_block), _ptr(topk_mask_out)
+    p.rope_cos, p.rope_sin = _ptr(rope_cos), _ptr(rope_sin)
     return p, (hk, workspace)
 
 

@@ -124,7 +124,11 @@ __global__ __launch_bounds__(256) void linear_apply_kernel(ApplyArgs a, int rows
 // channels, 16-byte chunk c (channels 8c .. 8c+7) of block row r at ((c/2 * 64 + (c%2) * 32 + r) * 16 bytes, so
 // that one 16-byte load per lane fetches a whole 32 x 16 fragment from 1 KB of contiguous memory.  Rows past N
 // in the last block are written too (from the clamped Q row): finite values nobody uses.
-template <bool DBG, bool EMIT>
+// ROPE: the rotary linear branch (Sec. 4.1).  The denominator is taken from the unrotated relu(Q); then the rows'
+// cosine and sine tables (fp32 [N, 64]: 256 bytes per row, the same geometry as a bf16 Q row) go through the same
+// LDS staging as Q, and channel pair (2p, 2p+1) of relu(Q) is rotated before it becomes the numerator's MFMA operand
+// (the state fragments then hold the rotated state).
+template <bool DBG, bool EMIT, bool ROPE = false>
 __global__ __launch_bounds__(512) void linear_apply128_kernel(ApplyArgs a, int rows_per_wg)
 {
     constexpr int D = 128, NS = 8;
@@ -194,6 +198,42 @@ __global__ __launch_bounds__(512) void linear_apply128_kernel(ApplyArgs a, int r
             }
         }
         asm volatile("" ::: "memory");   // the wave's LDS operations execute in order; as above
+        if (ROPE) {
+            uint4 cf[NS];                 // 4 cosines of the lane's 4 channel pairs per d-step, then the sines
+#pragma unroll
+            for (int pass = 0; pass < 2; ++pass) {
+                const float *tab = pass ? a.rope_sin : a.rope_cos;
+                uint4 tc[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int row = min(rb + 4 * i + r4, N - 1);
+                    tc[i] = *reinterpret_cast<const uint4 *>(tab + (size_t)row * (D / 2) + c16 * 4);
+                }
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int lrow = 4 * i + r4;
+                    *reinterpret_cast<uint4 *>(stage + lrow * 256 + ((c16 ^ (lrow & 15)) << 4)) = tc[i];
+                }
+                asm volatile("" ::: "memory");
+#pragma unroll
+                for (int st = 0; st < NS; ++st) {
+                    const uint4 t = *reinterpret_cast<const uint4 *>(stage + l32 * 256 + (((2 * st + hh) ^ (l32 & 15)) << 4));
+                    if (pass == 0) cf[st] = t;
+                    else {
+                        const float cc[4] = {__uint_as_float(cf[st].x), __uint_as_float(cf[st].y), __uint_as_float(cf[st].z), __uint_as_float(cf[st].w)};
+                        const float ss[4] = {__uint_as_float(t.x), __uint_as_float(t.y), __uint_as_float(t.z), __uint_as_float(t.w)};
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const uint32_t w = qf[st].w[j];
+                            const float x = __uint_as_float(w << 16), y = __uint_as_float(w & 0xffff0000u);
+                            f32x2 r = {x * cc[j] - y * ss[j], x * ss[j] + y * cc[j]};
+                            qf[st].w[j] = __builtin_bit_cast(uint32_t, __builtin_convertvector(r, bf16x2));
+                        }
+                    }
+                }
+                asm volatile("" ::: "memory");
+            }
+        }
         const float inv_den = 1.f / (dpart + __shfl_xor(dpart, 32) + a.eps);
         const float sc = EMIT ? inv_den : coef * inv_den;
         const bool rvalid = rb + l32 < N;
@@ -271,14 +311,24 @@ hipError_t launch_linear_apply_bf16(const ApplyArgs &a, hipStream_t st)
         if (rows_per_wg < 256) rows_per_wg = 256;
         dim3 grid((a.N + rows_per_wg - 1) / rows_per_wg, a.BH), block(512);
         constexpr int lds = 2 * 128 * 128 * 2 + 1024 + 8 * 8192;
-        static bool done_plain[16] = {}, done_dbg[16] = {}, done_emit[16] = {};
-        hipError_t e = a.emit ? dyn_lds_attr_once(reinterpret_cast<const void *>(linear_apply128_kernel<false, true>), lds, done_emit)
-                     : a.o_linear_dbg ? dyn_lds_attr_once(reinterpret_cast<const void *>(linear_apply128_kernel<true, false>), lds, done_dbg)
-                                      : dyn_lds_attr_once(reinterpret_cast<const void *>(linear_apply128_kernel<false, false>), lds, done_plain);
-        if (e != hipSuccess) return e;
-        if (a.emit) hipLaunchKernelGGL((linear_apply128_kernel<false, true>), grid, block, lds, st, a, rows_per_wg);
-        else if (a.o_linear_dbg) hipLaunchKernelGGL((linear_apply128_kernel<true, false>), grid, block, lds, st, a, rows_per_wg);
-        else hipLaunchKernelGGL((linear_apply128_kernel<false, false>), grid, block, lds, st, a, rows_per_wg);
+        static bool done[6][16] = {};
+        // variant: 0 plain, 1 debug output, 2 emit; + 3 with the rotary tables
+        const int var = (a.emit ? 2 : a.o_linear_dbg ? 1 : 0) + (a.rope_cos ? 3 : 0);
+        const void *kerns[6] = {reinterpret_cast<const void *>(linear_apply128_kernel<false, false, false>),
+                                reinterpret_cast<const void *>(linear_apply128_kernel<true, false, false>),
+                                reinterpret_cast<const void *>(linear_apply128_kernel<false, true, false>),
+                                reinterpret_cast<const void *>(linear_apply128_kernel<false, false, true>),
+                                reinterpret_cast<const void *>(linear_apply128_kernel<true, false, true>),
+                                reinterpret_cast<const void *>(linear_apply128_kernel<false, true, true>)};
+        if (hipError_t e = dyn_lds_attr_once(kerns[var], lds, done[var]); e != hipSuccess) return e;
+        switch (var) {
+        case 0: hipLaunchKernelGGL((linear_apply128_kernel<false, false, false>), grid, block, lds, st, a, rows_per_wg); break;
+        case 1: hipLaunchKernelGGL((linear_apply128_kernel<true, false, false>), grid, block, lds, st, a, rows_per_wg); break;
+        case 2: hipLaunchKernelGGL((linear_apply128_kernel<false, true, false>), grid, block, lds, st, a, rows_per_wg); break;
+        case 3: hipLaunchKernelGGL((linear_apply128_kernel<false, false, true>), grid, block, lds, st, a, rows_per_wg); break;
+        case 4: hipLaunchKernelGGL((linear_apply128_kernel<true, false, true>), grid, block, lds, st, a, rows_per_wg); break;
+        default: hipLaunchKernelGGL((linear_apply128_kernel<false, true, true>), grid, block, lds, st, a, rows_per_wg); break;
+        }
         return hipGetLastError();
     }
     // rows per workgroup (a multiple of 128): about two workgroups per CU, so that the 2*d*d*2 bytes of

@@ -21,6 +21,8 @@ namespace salad {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef short s16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 int g_state_target_wgs = 512;
 
@@ -56,12 +58,17 @@ __device__ inline uint32_t relu_bf16x2(uint32_t x)
     return __builtin_bit_cast(uint32_t, v);
 }
 
-template <int D>
+// ROPE: the rotary linear branch (Sec. 4.1): after the ReLU and the Z sums (which stay unrotated), channel pair
+// (2p, 2p+1) of token n is rotated by the angle with cosine rope_cos[n * D/2 + p] and sine rope_sin[...] before it
+// enters the outer products, so the state is sum_j (R_j relu(K_j))^T V_j.
+template <int D, bool ROPE = false>
 __global__ __launch_bounds__(256, 2) void state_partial_kernel(const u16 *__restrict__ k,
                                                                const u16 *__restrict__ v, int N,
                                                                int tiles_per_chunk, int P,
                                                                float *__restrict__ partial,
-                                                               const int32_t *__restrict__ drop, int H)
+                                                               const int32_t *__restrict__ drop, int H,
+                                                               const float *__restrict__ rope_cos = nullptr,
+                                                               const float *__restrict__ rope_sin = nullptr)
 {
     if (drop && drop[blockIdx.y / H]) return;          // pruned sample (Sec. 4.3): K, V are not read
     constexpr int CH = D / 8;          // 16-byte chunks per row
@@ -95,16 +102,22 @@ __global__ __launch_bounds__(256, 2) void state_partial_kernel(const u16 *__rest
 
     // two tiles of global loads are kept in flight per thread (register buffers 0 and 1)
     uint4 kreg[2][TPT], vreg[2][TPT];
-    auto gload = [&](uint4 (&kr)[TPT], uint4 (&vr)[TPT], int tile) __attribute__((always_inline)) {
+    float4 creg[2][ROPE ? TPT : 1], sreg[2][ROPE ? TPT : 1];   // cosines, sines of the patch's 4 channel pairs
+    auto gload = [&](uint4 (&kr)[TPT], uint4 (&vr)[TPT], float4 *cr, float4 *sr, int tile) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < TPT; ++i) {
             int n = tile * 64 + tq * TPT + i;
             if (n < N) {
                 kr[i] = *reinterpret_cast<const uint4 *>(kb + (size_t)n * D + fg * 8);
                 vr[i] = *reinterpret_cast<const uint4 *>(vb + (size_t)n * D + fg * 8);
+                if (ROPE) {
+                    cr[i] = *reinterpret_cast<const float4 *>(rope_cos + (size_t)n * (D / 2) + fg * 4);
+                    sr[i] = *reinterpret_cast<const float4 *>(rope_sin + (size_t)n * (D / 2) + fg * 4);
+                }
             } else {
                 kr[i] = make_uint4(0, 0, 0, 0);
                 vr[i] = make_uint4(0, 0, 0, 0);
+                if (ROPE) { cr[i] = make_float4(1.f, 1.f, 1.f, 1.f); sr[i] = make_float4(0.f, 0.f, 0.f, 0.f); }
             }
         }
     };
@@ -130,7 +143,7 @@ __global__ __launch_bounds__(256, 2) void state_partial_kernel(const u16 *__rest
     };
 
     const int wa = wave >> 1, wc = wave & 1;
-    auto step = [&](uint4 (&kr)[TPT], uint4 (&vr)[TPT], int tile) __attribute__((always_inline)) {
+    auto step = [&](uint4 (&kr)[TPT], uint4 (&vr)[TPT], float4 *cr, float4 *sr, int tile) __attribute__((always_inline)) {
         // ReLU on K, running sums for Z
 #pragma unroll
         for (int i = 0; i < TPT; ++i) {
@@ -142,11 +155,21 @@ __global__ __launch_bounds__(256, 2) void state_partial_kernel(const u16 *__rest
                 zacc[2 * j] += __uint_as_float(w4[j] << 16);
                 zacc[2 * j + 1] += __uint_as_float(w4[j] & 0xffff0000u);
             }
+            if (ROPE) {
+                const float cc[4] = {cr[i].x, cr[i].y, cr[i].z, cr[i].w}, ss[4] = {sr[i].x, sr[i].y, sr[i].z, sr[i].w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float x = __uint_as_float(w4[j] << 16), y = __uint_as_float(w4[j] & 0xffff0000u);
+                    f32x2 r = {x * cc[j] - y * ss[j], x * ss[j] + y * cc[j]};
+                    w4[j] = __builtin_bit_cast(uint32_t, __builtin_convertvector(r, bf16x2));
+                }
+                kr[i] = make_uint4(w4[0], w4[1], w4[2], w4[3]);
+            }
         }
         tstore(KT, kr);
         tstore(VT, vr);
         __syncthreads();
-        if (tile + 2 < tile1) gload(kr, vr, tile + 2);
+        if (tile + 2 < tile1) gload(kr, vr, cr, sr, tile + 2);
 #pragma unroll
         for (int s = 0; s < 4; ++s) {   // 16 tokens per MFMA
             bf16x8 af[QT], bfr[QT];
@@ -165,11 +188,11 @@ __global__ __launch_bounds__(256, 2) void state_partial_kernel(const u16 *__rest
         }
         __syncthreads();
     };
-    if (tile0 < tile1) gload(kreg[0], vreg[0], tile0);
-    if (tile0 + 1 < tile1) gload(kreg[1], vreg[1], tile0 + 1);
+    if (tile0 < tile1) gload(kreg[0], vreg[0], creg[0], sreg[0], tile0);
+    if (tile0 + 1 < tile1) gload(kreg[1], vreg[1], creg[1], sreg[1], tile0 + 1);
     for (int tile = tile0; tile < tile1; tile += 2) {
-        step(kreg[0], vreg[0], tile);
-        if (tile + 1 < tile1) step(kreg[1], vreg[1], tile + 1);
+        step(kreg[0], vreg[0], creg[0], sreg[0], tile);
+        if (tile + 1 < tile1) step(kreg[1], vreg[1], creg[1], sreg[1], tile + 1);
     }
 
     // partial Hs: accumulator register r of lane (l32, hh) is row a = 8*(r/4) + 4*hh + r%4, col c = l32
@@ -202,15 +225,21 @@ __global__ __launch_bounds__(256, 2) void state_partial_kernel(const u16 *__rest
 }
 
 hipError_t launch_state_partial_bf16(const u16 *k, const u16 *v, int BH, int N, int D,
-                                     float *partial, const int32_t *drop, int H, hipStream_t st)
+                                     float *partial, const int32_t *drop, int H, hipStream_t st,
+                                     const float *rope_cos, const float *rope_sin)
 {
     int tpc = state_tiles_per_chunk(BH, N);
     int P = state_num_chunks(BH, N);
     dim3 grid(P, BH), block(256);
+    if (rope_cos) {
+        if (D != 128) return hipErrorInvalidValue;
+        hipLaunchKernelGGL((state_partial_kernel<128, true>), grid, block, 0, st, k, v, N, tpc, P, partial, drop, H, rope_cos, rope_sin);
+        return hipGetLastError();
+    }
     if (D == 128)
-        hipLaunchKernelGGL(state_partial_kernel<128>, grid, block, 0, st, k, v, N, tpc, P, partial, drop, H);
+        hipLaunchKernelGGL((state_partial_kernel<128, false>), grid, block, 0, st, k, v, N, tpc, P, partial, drop, H, nullptr, nullptr);
     else
-        hipLaunchKernelGGL(state_partial_kernel<64>, grid, block, 0, st, k, v, N, tpc, P, partial, drop, H);
+        hipLaunchKernelGGL((state_partial_kernel<64, false>), grid, block, 0, st, k, v, N, tpc, P, partial, drop, H, nullptr, nullptr);
     return hipGetLastError();
 }
 

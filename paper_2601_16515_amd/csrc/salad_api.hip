@@ -277,8 +277,15 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
     // Top-K regrouped by key block (the default Top-K path): the sparse branch is assembled by a merge kernel, so the
     // linear branch follows in its own kernel as well
     const bool topk_regroup = p->topk > 0 && g_topk_variant == 0;
+    // rotary linear branch (Sec. 4.1): the rotation lives in the state kernel and the separate apply kernel
+    const bool rope = p->rope_cos != nullptr || p->rope_sin != nullptr;
+    if (rope) {
+        if (!p->rope_cos || !p->rope_sin) return fail(SALAD_EINVAL, "fwd: rope_cos and rope_sin must be given together");
+        if (p->dtype != SALAD_BF16 || p->d != 128) return fail(SALAD_ENOTSUP, "fwd: the rotary linear branch needs dtype bf16 and d = 128");
+        if (p->w_proj) return fail(SALAD_ENOTSUP, "fwd: the rotary linear branch and w_proj are not combined");
+    }
     const bool unfused = (p->flags & SALAD_FLAG_UNFUSED_EPILOGUE) != 0 || (p->w_proj != nullptr && p->lambda != 0.f) ||
-                         (topk_regroup && p->lambda != 0.f);
+                         (topk_regroup && p->lambda != 0.f) || (rope && p->lambda != 0.f);
     if (unfused && p->dtype != SALAD_BF16) return fail(SALAD_ENOTSUP, "fwd: unfused epilogue is bf16 only");
     if (p->flags & ~SALAD_FLAG_UNFUSED_EPILOGUE) return fail(SALAD_EINVAL, "fwd: unknown flags 0x%x", p->flags);
     const bool full_proj = p->w_proj != nullptr && p->lambda != 0.f;
@@ -348,7 +355,8 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
         }
         mark(1);
         if (bf16)
-            e = launch_state_partial_bf16((const u16 *)p->k, (const u16 *)p->v, BH, p->N, p->d, (float *)(ws + w.state_partial), drop, p->H, st);
+            e = launch_state_partial_bf16((const u16 *)p->k, (const u16 *)p->v, BH, p->N, p->d, (float *)(ws + w.state_partial), drop, p->H, st,
+                                          p->rope_cos, p->rope_sin);
         else
             e = launch_state_f32((const float *)p->k, (const float *)p->v, BH, p->N, p->d, (float *)(ws + w.Hs), (float *)(ws + w.Z), drop, p->H, st);
         if (e != hipSuccess) return hip_fail(e, "state launch");
@@ -433,6 +441,7 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
         ap.eps = p->eps; ap.o_linear_dbg = full_proj ? nullptr : p->o_linear_dbg;
         ap.drop = drop; ap.H = p->H;
         ap.emit = full_proj ? (u16 *)(ws + w.ol) : nullptr;
+        ap.rope_cos = p->rope_cos; ap.rope_sin = p->rope_sin;
         e = launch_linear_apply_bf16(ap, st);
         if (e != hipSuccess) return hip_fail(e, "linear apply launch");
         mark(5);

@@ -183,3 +183,21 @@ def sample_blocks(nb: int, count: int, seed: int) -> np.ndarray:
             break
         fixed.add(int(x * nb) % nb)
     return np.array(sorted(fixed), dtype=np.int32)
+
+
+def rope_tables(T: int, Hh: int, W: int, d: int, base: float = 10000.0):
+    """Cosine and sine tables [N, d/2] (float32) of a 3D rotary embedding for the token grid, token n = (t, y, x) in
+    stored order: the d/2 channel pairs are split over the t, y, x axes (the remainder goes to t) and pair i of an
+    axis with m pairs turns by position * base^(-i/m).  An input generator like the others: the layer only ever
+    sees the two tables."""
+    half = d // 2
+    my = mx = half // 3
+    mt = half - my - mx
+    n = np.arange(T * Hh * W)
+    pos = {"t": n // (Hh * W), "y": (n // W) % Hh, "x": n % W}
+    cols = []
+    for axis, m in (("t", mt), ("y", my), ("x", mx)):
+        freq = base ** (-np.arange(m, dtype=np.float64) / max(m, 1))
+        cols.append(pos[axis][:, None].astype(np.float64) * freq[None, :])
+    theta = np.concatenate(cols, axis=1)
+    return np.cos(theta).astype(np.float32), np.sin(theta).astype(np.float32)

@@ -386,6 +386,48 @@ def test_topk_mask_layer(oracle, topk_variant, wi, key_block, topk, variant):
         assert errors(res["out"], dense["out"])[1] < 5e-3   # two independently rounded bf16 results
 
 
+@pytest.mark.parametrize("wi", [1, 7, 0, 4], ids=["N693-B2", "N1170", "N270-tail14", "N512"])
+def test_rotary_linear_branch(oracle, wi):
+    """RoPE inside the linear branch (Sec. 4.1; numerator rotated, normaliser not): the layer against the oracle,
+    with a static scale large enough that the linear branch carries weight; zero angles reproduce the plain layer."""
+    w = SMALL[wi]
+    inp = wl.make_inputs(w)
+    dev = upload(w, inp)
+    kinds = wl.head_kinds(w)
+    kept = [3] * w.H if w.nb >= 3 else [1] * w.H
+    cs, sn = wl.rope_tables(w.T, w.Hh, w.W, w.d)
+    rope_dev = (torch.from_numpy(cs).cuda(), torch.from_numpy(sn).cuda())
+    ref = _oracle_layer(oracle, w, inp, kept, kinds, lam=20.0, rope=(cs, sn))
+    ref_plain = _oracle_layer(oracle, w, inp, kept, kinds, lam=20.0)
+    res = run_layer(w, inp, dev, kept, kinds, lam=20.0, rope=rope_dev)
+    compare_layer(res, ref, label=f"rope-{w.name}")
+    if w.N > 1:
+        assert errors(ref["o_linear"], ref_plain["o_linear"])[1] > 0.05          # the rotation is not a small effect
+    one = torch.ones_like(rope_dev[0]); zero = torch.zeros_like(rope_dev[0])
+    res0 = run_layer(w, inp, dev, kept, kinds, lam=20.0, rope=(one, zero))
+    plain = run_layer(w, inp, dev, kept, kinds, lam=20.0, flags=sb.SALAD_FLAG_UNFUSED_EPILOGUE)
+    assert torch.equal(res0["out_t"], plain["out_t"])                            # identity rotation: the same bits
+
+
+def test_wan13_480p_rotary_sampled(oracle):
+    """The rotary linear branch at the headline size: full rotated state and sampled rows against the oracle."""
+    w = wl.WAN13_480P
+    say("480p-rope: generating inputs")
+    inp = wl.make_inputs(w)
+    dev = upload(w, inp)
+    kinds = wl.head_kinds(w)
+    kept = [sb.salad_kept_from_sparsity(w.nb, w.sparsity)] * w.H
+    cs, sn = wl.rope_tables(w.T, w.Hh, w.W, w.d)
+    rope_dev = (torch.from_numpy(cs).cuda(), torch.from_numpy(sn).cuda())
+    say("480p-rope: GPU call")
+    res = run_layer(w, inp, dev, kept, kinds, rope=rope_dev)
+    sel = wl.sample_blocks(w.nb, 4, w.seed)
+    say(f"480p-rope: oracle on {len(sel)} query blocks per head")
+    ref = _oracle_layer(oracle, w, inp, kept, kinds, sel=sel, rope=(cs, sn))
+    compare_layer(res, ref, label="480p-rope")
+    assert np.isfinite(res["out"]).all()
+
+
 @pytest.fixture
 def topk_variant():
     yield lambda v: sb.salad_tune("topk_variant", v)
