@@ -272,6 +272,22 @@ def main():
     except Exception as exc:
         result["topk_mask"] = {"error": repr(exc)[:200]}
 
+    # rotary position embedding inside the linear branch (Sec. 4.1): rotation in the state kernel and in the
+    # separate linear-apply kernel, compared with the same unfused call without it
+    try:
+        cs_np, sn_np = wl.rope_tables(w.T, w.Hh, w.W, w.d)
+        cs_t, sn_t = torch.from_numpy(cs_np).to(dev), torch.from_numpy(sn_np).to(dev)
+        ws_r = sb.Workspace(w.B, w.H, w.N, w.d, sb.SALAD_BF16, dev, rope=True)
+        pr, keep_r = sb.make_fwd_params(q, k, v, out, grid, row_ptr, col_idx, kinds, lam=w.lam, head_scale=hs, x_t=x,
+                                        w_gate=wg, eps=w.eps, workspace=ws_r, rope_cos=cs_t, rope_sin=sn_t)
+        ms_r, kt_r = timed(pr, max(5, args.steps // 5), 2)
+        nc = max(kt_r.calls, 1)
+        result["rotary_linear_branch"] = {"ms_per_call": ms_r, "linear_state_ms": kt_r.state_ms / nc,
+                                          "linear_apply_ms": kt_r.epilogue_ms / nc,
+                                          "table_bytes": int(cs_np.nbytes + sn_np.nbytes)}
+    except Exception as exc:
+        result["rotary_linear_branch"] = {"error": repr(exc)[:200]}
+
     # the same call captured once into a HIP graph and replayed (the call allocates nothing and never
     # synchronises); reported next to the eager figure, which stays the headline value
     try:

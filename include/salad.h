@@ -126,7 +126,7 @@ typedef struct salad_fwd_params {
 
 /* Device scratch the forward needs for these shapes (partial states, partial gate sums, the
  * reduced state, per-tile block lists; with w_proj also O_l and the rearranged W_p; with topk the key-block means,
- * the masks and per-sample lists).  Reads only B, H, N, d, dtype, whether w_proj is NULL and topk.
+ * the masks and per-sample lists).  Reads only B, H, N, d, dtype, topk and whether w_proj and rope_cos are NULL.
  * 0 on invalid shapes. */
 size_t salad_fwd_workspace_bytes(const salad_fwd_params *p);
 
@@ -151,7 +151,8 @@ size_t salad_fwd_workspace_bytes(const salad_fwd_params *p);
  * the normaliser keeps the unrotated features:
  *   O_l[i] = sum_j (R_i phi(Q_i)).(R_j phi(K_j)) V_j / (phi(Q_i).Z + eps) = (R_i phi(Q_i)) Hr / (phi(Q_i).Z + eps),
  *   Hr = sum_j (R_j phi(K_j))^T V_j.  The caller owns the split of the pairs over the t, y, x axes and the frequencies
- * (they are in the tables).  Runs with the separate linear-apply kernel.
+ * (they are in the tables; the kernels read them as fp16 pairs packed once per call).  Runs with the separate
+ * linear-apply kernel.
  * Post-tuning branch dropping (Sec. 4.3, App. A.3): with drop_threshold = tau > 0, a sample whose dynamic
  * scale s_b < tau (strict, compared in fp32) loses its linear branch: out[b] = O_s[b], exactly as with
  * lambda == 0.  The decision is taken on the device (no host synchronisation): the gate is reduced first,

@@ -178,11 +178,12 @@ def salad_block_mask(T: int, Hh: int, W: int, block: int, kept: Sequence[int], d
 
 
 def salad_fwd_workspace_bytes(B: int, H: int, N: int, d: int, dtype: int, full_proj: bool = False,
-                              topk: int = 0) -> int:
+                              topk: int = 0, rope: bool = False) -> int:
     p = FwdParams()
     p.B, p.H, p.N, p.d, p.dtype = B, H, N, d, dtype
     p.w_proj = 1 if full_proj else None          # the query only looks at whether the pointer is NULL
     p.topk = int(topk)                           # ... and at topk (slots per query of the regrouped Top-K path)
+    p.rope_cos = 1 if rope else None             # ... and at whether the rotary tables are given
     return int(lib().salad_fwd_workspace_bytes(C.byref(p)))
 
 
@@ -190,9 +191,9 @@ class Workspace:
     """Caller-owned scratch for the layer call, sized by the library's query."""
 
     def __init__(self, B: int, H: int, N: int, d: int, dtype: int, device="cuda", full_proj: bool = False,
-                 topk: int = 0):
+                 topk: int = 0, rope: bool = False):
         import torch
-        self.bytes = salad_fwd_workspace_bytes(B, H, N, d, dtype, full_proj, topk)
+        self.bytes = salad_fwd_workspace_bytes(B, H, N, d, dtype, full_proj, topk, rope)
         self.buf = torch.empty(max(self.bytes, 256) + 256, dtype=torch.uint8, device=device)
         self.ptr = (self.buf.data_ptr() + 255) & ~255
 
@@ -252,7 +253,7 @@ def salad_sparse_linear_attn_fwd(q, k, v, grid, row_ptr, col_idx, head_kind=None
         out = torch.empty_like(q)
     if kw.get("workspace") is None:
         kw["workspace"] = Workspace(B, H, N, d, _dtype_code(q), q.device, full_proj=kw.get("w_proj") is not None,
-                                    topk=kw.get("topk", 0))
+                                    topk=kw.get("topk", 0), rope=kw.get("rope_cos") is not None)
     p, keep = make_fwd_params(q, k, v, out, grid, row_ptr, col_idx, head_kind, **kw)
     _check(lib().salad_sparse_linear_attn_fwd(C.byref(p)))
     return out

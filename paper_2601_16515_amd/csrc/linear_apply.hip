@@ -14,6 +14,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef short s16x2 __attribute__((ext_vector_type(2)));
 
 union Frag8a {
@@ -125,9 +126,9 @@ __global__ __launch_bounds__(256) void linear_apply_kernel(ApplyArgs a, int rows
 // that one 16-byte load per lane fetches a whole 32 x 16 fragment from 1 KB of contiguous memory.  Rows past N
 // in the last block are written too (from the clamped Q row): finite values nobody uses.
 // ROPE: the rotary linear branch (Sec. 4.1).  The denominator is taken from the unrotated relu(Q); then the rows'
-// cosine and sine tables (fp32 [N, 64]: 256 bytes per row, the same geometry as a bf16 Q row) go through the same
-// LDS staging as Q, and channel pair (2p, 2p+1) of relu(Q) is rotated before it becomes the numerator's MFMA operand
-// (the state fragments then hold the rotated state).
+// (cos, sin) words (two fp16 values per channel pair, [N, 64] words: 256 bytes per row, the same geometry as a bf16
+// Q row) go through the same LDS staging as Q, and channel pair (2p, 2p+1) of relu(Q) is rotated before it becomes
+// the numerator's MFMA operand (the state fragments then hold the rotated state).
 template <bool DBG, bool EMIT, bool ROPE = false>
 __global__ __launch_bounds__(512) void linear_apply128_kernel(ApplyArgs a, int rows_per_wg)
 {
@@ -138,7 +139,8 @@ __global__ __launch_bounds__(512) void linear_apply128_kernel(ApplyArgs a, int r
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     unsigned char *stage = smem + 2 * D * D * 2 + 1024 + wave * 8192;             // wave-private, 8 KB
     const int l32 = lane & 31, hh = lane >> 5;
-    const int bh = blockIdx.y;
+    // ROPE: sample-head index fastest (neighbours in the grid share the angle-table rows)
+    const int bh = ROPE ? blockIdx.x : blockIdx.y, rblk = ROPE ? blockIdx.y : blockIdx.x;
     if (a.drop && a.drop[bh / a.H]) return;            // pruned sample (Sec. 4.3): out already holds O_s
     {   // fragments are lane-linear in memory: copy as is (16 bytes per lane per load)
         const u16 *hf = a.hfrag + (size_t)bh * 2 * D * D;
@@ -155,8 +157,8 @@ __global__ __launch_bounds__(512) void linear_apply128_kernel(ApplyArgs a, int r
     u16 *oh = a.out + (size_t)bh * N * D;
     const int r8 = lane >> 3, c8 = lane & 7;          // row layout of a half: 8 rows x 8 chunks of 16 bytes per instruction
     const int r4 = lane >> 4, c16 = lane & 15;        // row layout of full rows: 4 rows x 16 chunks
-    const int row_end = min(N, (int)(blockIdx.x + 1) * rows_per_wg);
-    for (int rb = blockIdx.x * rows_per_wg + wave * 32; rb < row_end; rb += 256) {
+    const int row_end = min(N, (rblk + 1) * rows_per_wg);
+    for (int rb = rblk * rows_per_wg + wave * 32; rb < row_end; rb += 256) {
         // ---- Q: 8 coalesced loads, swizzled into LDS (chunk ^ (row & 15)), read back as B-operand fragments
         uint4 qc[8];
 #pragma unroll
@@ -199,40 +201,34 @@ __global__ __launch_bounds__(512) void linear_apply128_kernel(ApplyArgs a, int r
         }
         asm volatile("" ::: "memory");   // the wave's LDS operations execute in order; as above
         if (ROPE) {
-            uint4 cf[NS];                 // 4 cosines of the lane's 4 channel pairs per d-step, then the sines
+            // (cos, sin) words of the rows, 256 bytes per row: staged like the Q rows, then 4 words per d-step per lane
+            uint4 tc[8];
 #pragma unroll
-            for (int pass = 0; pass < 2; ++pass) {
-                const float *tab = pass ? a.rope_sin : a.rope_cos;
-                uint4 tc[8];
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const int row = min(rb + 4 * i + r4, N - 1);
-                    tc[i] = *reinterpret_cast<const uint4 *>(tab + (size_t)row * (D / 2) + c16 * 4);
-                }
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const int lrow = 4 * i + r4;
-                    *reinterpret_cast<uint4 *>(stage + lrow * 256 + ((c16 ^ (lrow & 15)) << 4)) = tc[i];
-                }
-                asm volatile("" ::: "memory");
-#pragma unroll
-                for (int st = 0; st < NS; ++st) {
-                    const uint4 t = *reinterpret_cast<const uint4 *>(stage + l32 * 256 + (((2 * st + hh) ^ (l32 & 15)) << 4));
-                    if (pass == 0) cf[st] = t;
-                    else {
-                        const float cc[4] = {__uint_as_float(cf[st].x), __uint_as_float(cf[st].y), __uint_as_float(cf[st].z), __uint_as_float(cf[st].w)};
-                        const float ss[4] = {__uint_as_float(t.x), __uint_as_float(t.y), __uint_as_float(t.z), __uint_as_float(t.w)};
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const uint32_t w = qf[st].w[j];
-                            const float x = __uint_as_float(w << 16), y = __uint_as_float(w & 0xffff0000u);
-                            f32x2 r = {x * cc[j] - y * ss[j], x * ss[j] + y * cc[j]};
-                            qf[st].w[j] = __builtin_bit_cast(uint32_t, __builtin_convertvector(r, bf16x2));
-                        }
-                    }
-                }
-                asm volatile("" ::: "memory");
+            for (int i = 0; i < 8; ++i) {
+                const int row = min(rb + 4 * i + r4, N - 1);
+                tc[i] = *reinterpret_cast<const uint4 *>(a.rope_tab + (size_t)row * (D / 2) + c16 * 4);
             }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int lrow = 4 * i + r4;
+                *reinterpret_cast<uint4 *>(stage + lrow * 256 + ((c16 ^ (lrow & 15)) << 4)) = tc[i];
+            }
+            asm volatile("" ::: "memory");
+#pragma unroll
+            for (int st = 0; st < NS; ++st) {
+                const uint4 t = *reinterpret_cast<const uint4 *>(stage + l32 * 256 + (((2 * st + hh) ^ (l32 & 15)) << 4));
+                const uint32_t cw[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t w = qf[st].w[j];
+                    const float x = __uint_as_float(w << 16), y = __uint_as_float(w & 0xffff0000u);
+                    const f16x2 hcs = __builtin_bit_cast(f16x2, cw[j]);
+                    const float cc = (float)hcs[0], ss = (float)hcs[1];
+                    f32x2 r = {x * cc - y * ss, x * ss + y * cc};
+                    qf[st].w[j] = __builtin_bit_cast(uint32_t, __builtin_convertvector(r, bf16x2));
+                }
+            }
+            asm volatile("" ::: "memory");
         }
         const float inv_den = 1.f / (dpart + __shfl_xor(dpart, 32) + a.eps);
         const float sc = EMIT ? inv_den : coef * inv_den;
@@ -313,7 +309,7 @@ hipError_t launch_linear_apply_bf16(const ApplyArgs &a, hipStream_t st)
         constexpr int lds = 2 * 128 * 128 * 2 + 1024 + 8 * 8192;
         static bool done[6][16] = {};
         // variant: 0 plain, 1 debug output, 2 emit; + 3 with the rotary tables
-        const int var = (a.emit ? 2 : a.o_linear_dbg ? 1 : 0) + (a.rope_cos ? 3 : 0);
+        const int var = (a.emit ? 2 : a.o_linear_dbg ? 1 : 0) + (a.rope_tab ? 3 : 0);
         const void *kerns[6] = {reinterpret_cast<const void *>(linear_apply128_kernel<false, false, false>),
                                 reinterpret_cast<const void *>(linear_apply128_kernel<true, false, false>),
                                 reinterpret_cast<const void *>(linear_apply128_kernel<false, true, false>),
@@ -321,13 +317,14 @@ hipError_t launch_linear_apply_bf16(const ApplyArgs &a, hipStream_t st)
                                 reinterpret_cast<const void *>(linear_apply128_kernel<true, false, true>),
                                 reinterpret_cast<const void *>(linear_apply128_kernel<false, true, true>)};
         if (hipError_t e = dyn_lds_attr_once(kerns[var], lds, done[var]); e != hipSuccess) return e;
+        const dim3 grid_r(grid.y, grid.x);     // rotary variants: sample-head index fastest
         switch (var) {
         case 0: hipLaunchKernelGGL((linear_apply128_kernel<false, false, false>), grid, block, lds, st, a, rows_per_wg); break;
         case 1: hipLaunchKernelGGL((linear_apply128_kernel<true, false, false>), grid, block, lds, st, a, rows_per_wg); break;
         case 2: hipLaunchKernelGGL((linear_apply128_kernel<false, true, false>), grid, block, lds, st, a, rows_per_wg); break;
-        case 3: hipLaunchKernelGGL((linear_apply128_kernel<false, false, true>), grid, block, lds, st, a, rows_per_wg); break;
-        case 4: hipLaunchKernelGGL((linear_apply128_kernel<true, false, true>), grid, block, lds, st, a, rows_per_wg); break;
-        default: hipLaunchKernelGGL((linear_apply128_kernel<false, true, true>), grid, block, lds, st, a, rows_per_wg); break;
+        case 3: hipLaunchKernelGGL((linear_apply128_kernel<false, false, true>), grid_r, block, lds, st, a, rows_per_wg); break;
+        case 4: hipLaunchKernelGGL((linear_apply128_kernel<true, false, true>), grid_r, block, lds, st, a, rows_per_wg); break;
+        default: hipLaunchKernelGGL((linear_apply128_kernel<false, true, true>), grid_r, block, lds, st, a, rows_per_wg); break;
         }
         return hipGetLastError();
     }

@@ -23,6 +23,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef short s16x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 
 int g_state_target_wgs = 512;
 
@@ -59,18 +60,20 @@ __device__ inline uint32_t relu_bf16x2(uint32_t x)
 }
 
 // ROPE: the rotary linear branch (Sec. 4.1): after the ReLU and the Z sums (which stay unrotated), channel pair
-// (2p, 2p+1) of token n is rotated by the angle with cosine rope_cos[n * D/2 + p] and sine rope_sin[...] before it
-// enters the outer products, so the state is sum_j (R_j relu(K_j))^T V_j.
+// (2p, 2p+1) of token n is rotated by the angle whose cosine and sine sit, as two fp16 values in one word, at
+// rope_tab[n * D/2 + p], before it enters the outer products, so the state is sum_j (R_j relu(K_j))^T V_j.
 template <int D, bool ROPE = false>
 __global__ __launch_bounds__(256, 2) void state_partial_kernel(const u16 *__restrict__ k,
                                                                const u16 *__restrict__ v, int N,
                                                                int tiles_per_chunk, int P,
                                                                float *__restrict__ partial,
                                                                const int32_t *__restrict__ drop, int H,
-                                                               const float *__restrict__ rope_cos = nullptr,
-                                                               const float *__restrict__ rope_sin = nullptr)
+                                                               const uint32_t *__restrict__ rope_tab = nullptr)
 {
-    if (drop && drop[blockIdx.y / H]) return;          // pruned sample (Sec. 4.3): K, V are not read
+    // ROPE: the sample-head index runs fastest over the grid, so that the workgroups that read the same rows of the
+    // angle tables (same token chunk, different heads) run at the same time and the tables come from HBM once
+    const int bh = ROPE ? blockIdx.x : blockIdx.y, chunk = ROPE ? blockIdx.y : blockIdx.x;
+    if (drop && drop[bh / H]) return;                  // pruned sample (Sec. 4.3): K, V are not read
     constexpr int CH = D / 8;          // 16-byte chunks per row
     constexpr int TPT = D / 32;        // tokens per thread per tile (4 for d=128, 2 for d=64)
     constexpr int QT = D / 64;         // 32x32 tiles per side of a wave's quadrant
@@ -80,7 +83,6 @@ __global__ __launch_bounds__(256, 2) void state_partial_kernel(const u16 *__rest
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hh = lane >> 5;
-    const int bh = blockIdx.y, chunk = blockIdx.x;
     const int fg = tid % CH, tq = tid / CH;   // feature group (8 features), token group (TPT tokens)
     const u16 *kb = k + (size_t)bh * N * D;
     const u16 *vb = v + (size_t)bh * N * D;
@@ -102,22 +104,19 @@ __global__ __launch_bounds__(256, 2) void state_partial_kernel(const u16 *__rest
 
     // two tiles of global loads are kept in flight per thread (register buffers 0 and 1)
     uint4 kreg[2][TPT], vreg[2][TPT];
-    float4 creg[2][ROPE ? TPT : 1], sreg[2][ROPE ? TPT : 1];   // cosines, sines of the patch's 4 channel pairs
-    auto gload = [&](uint4 (&kr)[TPT], uint4 (&vr)[TPT], float4 *cr, float4 *sr, int tile) __attribute__((always_inline)) {
+    uint4 creg[2][ROPE ? TPT : 1];     // (cos, sin) of the patch's 4 channel pairs
+    auto gload = [&](uint4 (&kr)[TPT], uint4 (&vr)[TPT], uint4 *cr, int tile) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < TPT; ++i) {
             int n = tile * 64 + tq * TPT + i;
             if (n < N) {
                 kr[i] = *reinterpret_cast<const uint4 *>(kb + (size_t)n * D + fg * 8);
                 vr[i] = *reinterpret_cast<const uint4 *>(vb + (size_t)n * D + fg * 8);
-                if (ROPE) {
-                    cr[i] = *reinterpret_cast<const float4 *>(rope_cos + (size_t)n * (D / 2) + fg * 4);
-                    sr[i] = *reinterpret_cast<const float4 *>(rope_sin + (size_t)n * (D / 2) + fg * 4);
-                }
+                if (ROPE) cr[i] = *reinterpret_cast<const uint4 *>(rope_tab + (size_t)n * (D / 2) + fg * 4);
             } else {
                 kr[i] = make_uint4(0, 0, 0, 0);
                 vr[i] = make_uint4(0, 0, 0, 0);
-                if (ROPE) { cr[i] = make_float4(1.f, 1.f, 1.f, 1.f); sr[i] = make_float4(0.f, 0.f, 0.f, 0.f); }
+                if (ROPE) cr[i] = make_uint4(0x3c00u, 0x3c00u, 0x3c00u, 0x3c00u);   // cos = 1, sin = 0
             }
         }
     };
@@ -143,7 +142,7 @@ __global__ __launch_bounds__(256, 2) void state_partial_kernel(const u16 *__rest
     };
 
     const int wa = wave >> 1, wc = wave & 1;
-    auto step = [&](uint4 (&kr)[TPT], uint4 (&vr)[TPT], float4 *cr, float4 *sr, int tile) __attribute__((always_inline)) {
+    auto step = [&](uint4 (&kr)[TPT], uint4 (&vr)[TPT], uint4 *cr, int tile) __attribute__((always_inline)) {
         // ReLU on K, running sums for Z
 #pragma unroll
         for (int i = 0; i < TPT; ++i) {
@@ -156,11 +155,13 @@ __global__ __launch_bounds__(256, 2) void state_partial_kernel(const u16 *__rest
                 zacc[2 * j + 1] += __uint_as_float(w4[j] & 0xffff0000u);
             }
             if (ROPE) {
-                const float cc[4] = {cr[i].x, cr[i].y, cr[i].z, cr[i].w}, ss[4] = {sr[i].x, sr[i].y, sr[i].z, sr[i].w};
+                const uint32_t cw[4] = {cr[i].x, cr[i].y, cr[i].z, cr[i].w};
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const float x = __uint_as_float(w4[j] << 16), y = __uint_as_float(w4[j] & 0xffff0000u);
-                    f32x2 r = {x * cc[j] - y * ss[j], x * ss[j] + y * cc[j]};
+                    const f16x2 hcs = __builtin_bit_cast(f16x2, cw[j]);
+                    const float cc = (float)hcs[0], ss = (float)hcs[1];
+                    f32x2 r = {x * cc - y * ss, x * ss + y * cc};
                     w4[j] = __builtin_bit_cast(uint32_t, __builtin_convertvector(r, bf16x2));
                 }
                 kr[i] = make_uint4(w4[0], w4[1], w4[2], w4[3]);
@@ -169,7 +170,7 @@ __global__ __launch_bounds__(256, 2) void state_partial_kernel(const u16 *__rest
         tstore(KT, kr);
         tstore(VT, vr);
         __syncthreads();
-        if (tile + 2 < tile1) gload(kr, vr, cr, sr, tile + 2);
+        if (tile + 2 < tile1) gload(kr, vr, cr, tile + 2);
 #pragma unroll
         for (int s = 0; s < 4; ++s) {   // 16 tokens per MFMA
             bf16x8 af[QT], bfr[QT];
@@ -188,11 +189,11 @@ __global__ __launch_bounds__(256, 2) void state_partial_kernel(const u16 *__rest
         }
         __syncthreads();
     };
-    if (tile0 < tile1) gload(kreg[0], vreg[0], creg[0], sreg[0], tile0);
-    if (tile0 + 1 < tile1) gload(kreg[1], vreg[1], creg[1], sreg[1], tile0 + 1);
+    if (tile0 < tile1) gload(kreg[0], vreg[0], creg[0], tile0);
+    if (tile0 + 1 < tile1) gload(kreg[1], vreg[1], creg[1], tile0 + 1);
     for (int tile = tile0; tile < tile1; tile += 2) {
-        step(kreg[0], vreg[0], creg[0], sreg[0], tile);
-        if (tile + 1 < tile1) step(kreg[1], vreg[1], creg[1], sreg[1], tile + 1);
+        step(kreg[0], vreg[0], creg[0], tile);
+        if (tile + 1 < tile1) step(kreg[1], vreg[1], creg[1], tile + 1);
     }
 
     // partial Hs: accumulator register r of lane (l32, hh) is row a = 8*(r/4) + 4*hh + r%4, col c = l32
@@ -226,20 +227,36 @@ __global__ __launch_bounds__(256, 2) void state_partial_kernel(const u16 *__rest
 
 hipError_t launch_state_partial_bf16(const u16 *k, const u16 *v, int BH, int N, int D,
                                      float *partial, const int32_t *drop, int H, hipStream_t st,
-                                     const float *rope_cos, const float *rope_sin)
+                                     const uint32_t *rope_tab)
 {
     int tpc = state_tiles_per_chunk(BH, N);
     int P = state_num_chunks(BH, N);
     dim3 grid(P, BH), block(256);
-    if (rope_cos) {
+    if (rope_tab) {
         if (D != 128) return hipErrorInvalidValue;
-        hipLaunchKernelGGL((state_partial_kernel<128, true>), grid, block, 0, st, k, v, N, tpc, P, partial, drop, H, rope_cos, rope_sin);
+        hipLaunchKernelGGL((state_partial_kernel<128, true>), dim3(BH, P), block, 0, st, k, v, N, tpc, P, partial, drop, H, rope_tab);
         return hipGetLastError();
     }
     if (D == 128)
-        hipLaunchKernelGGL((state_partial_kernel<128, false>), grid, block, 0, st, k, v, N, tpc, P, partial, drop, H, nullptr, nullptr);
+        hipLaunchKernelGGL((state_partial_kernel<128, false>), grid, block, 0, st, k, v, N, tpc, P, partial, drop, H, nullptr);
     else
-        hipLaunchKernelGGL((state_partial_kernel<64, false>), grid, block, 0, st, k, v, N, tpc, P, partial, drop, H, nullptr, nullptr);
+        hipLaunchKernelGGL((state_partial_kernel<64, false>), grid, block, 0, st, k, v, N, tpc, P, partial, drop, H, nullptr);
+    return hipGetLastError();
+}
+
+// (cos, sin) tables of the rotary linear branch, fp32 [n] each -> one word per angle: fp16 cos | fp16 sin << 16
+__global__ __launch_bounds__(256) void rope_pack_kernel(const float *__restrict__ c, const float *__restrict__ s_, size_t n,
+                                                        uint32_t *__restrict__ out)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    f16x2 h = {(_Float16)c[i], (_Float16)s_[i]};
+    out[i] = __builtin_bit_cast(uint32_t, h);
+}
+
+hipError_t launch_rope_pack(const float *rope_cos, const float *rope_sin, size_t n, uint32_t *tab, hipStream_t st)
+{
+    hipLaunchKernelGGL(rope_pack_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, rope_cos, rope_sin, n, tab);
     return hipGetLastError();
 }
 

@@ -36,11 +36,11 @@ salad_status hip_fail(hipError_t e, const char *what)
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct WsLayout {
-    size_t gate_partial, state_partial, Hs, Z, hfrag, s, coef, drop, tile_lists, tile_counts, ol, wfrag, kmeans, topk_mask, g_counts, g_ccnt, g_seg, g_total, g_desc, g_idx, g_slot, g_lse, g_po, total;
+    size_t gate_partial, state_partial, Hs, Z, hfrag, s, coef, drop, tile_lists, tile_counts, ol, wfrag, kmeans, topk_mask, g_counts, g_ccnt, g_seg, g_total, g_desc, g_idx, g_slot, g_lse, g_po, rope_tab, total;
     int nparts, P;
 };
 
-WsLayout ws_layout(int B, int H, int N, int d, int dtype, bool full_proj = false, int topk = 0)
+WsLayout ws_layout(int B, int H, int N, int d, int dtype, bool full_proj = false, int topk = 0, bool rope = false)
 {
     WsLayout w{};
     const size_t BH = (size_t)B * H;
@@ -82,6 +82,7 @@ WsLayout ws_layout(int B, int H, int N, int d, int dtype, bool full_proj = false
         w.g_lse = off; off = align256(off + (topk ? sizeof(float) * pairs : 0));
         w.g_po = off; off = align256(off + (topk ? sizeof(u16) * pairs * d : 0));
     }
+    w.rope_tab = off; off = align256(off + (rope ? sizeof(uint32_t) * (size_t)N * (d / 2) : 0));
     w.total = off;
     return w;
 }
@@ -176,7 +177,7 @@ salad_status salad_block_mask(int32_t T, int32_t Hh, int32_t W, int32_t block, i
 size_t salad_fwd_workspace_bytes(const salad_fwd_params *p)
 {
     if (!p || !shape_ok(p->B, p->H, p->N, p->d, p->dtype)) return 0;
-    return ws_layout(p->B, p->H, p->N, p->d, p->dtype, p->w_proj != nullptr, p->topk > 0 ? p->topk : 0).total;
+    return ws_layout(p->B, p->H, p->N, p->d, p->dtype, p->w_proj != nullptr, p->topk > 0 ? p->topk : 0, p->rope_cos != nullptr).total;
 }
 
 salad_status salad_linear_state_fwd(const void *k, const void *v, int32_t B, int32_t H, int32_t N, int32_t d,
@@ -293,7 +294,7 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
         if (p->dtype != SALAD_BF16 || p->d != 128) return fail(SALAD_ENOTSUP, "fwd: w_proj needs dtype bf16 and d = 128");
         if (p->head_scale) return fail(SALAD_EINVAL, "fwd: w_proj and head_scale exclude each other");
     }
-    const WsLayout w = ws_layout(p->B, p->H, p->N, p->d, p->dtype, p->w_proj != nullptr, topk ? p->topk : 0);
+    const WsLayout w = ws_layout(p->B, p->H, p->N, p->d, p->dtype, p->w_proj != nullptr, topk ? p->topk : 0, p->rope_cos != nullptr);
     const bool need_lists = p->dtype == SALAD_BF16 && p->d == 128 && (size_t)tile_list_cap((p->N + 63) / 64) * 4 <= 24 * 1024;
     if (use_linear || need_lists) {
         if (!p->workspace || ((uintptr_t)p->workspace & 255)) return fail(SALAD_EINVAL, "fwd: workspace null or not 256-byte aligned");
@@ -355,8 +356,14 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
         }
         mark(1);
         if (bf16)
+        {
+            if (rope) {     // the two fp32 tables -> one word per angle, read by the state and the apply kernels
+                e = launch_rope_pack(p->rope_cos, p->rope_sin, (size_t)p->N * (p->d / 2), (uint32_t *)(ws + w.rope_tab), st);
+                if (e != hipSuccess) return hip_fail(e, "rotary table launch");
+            }
             e = launch_state_partial_bf16((const u16 *)p->k, (const u16 *)p->v, BH, p->N, p->d, (float *)(ws + w.state_partial), drop, p->H, st,
-                                          p->rope_cos, p->rope_sin);
+                                          rope ? (const uint32_t *)(ws + w.rope_tab) : nullptr);
+        }
         else
             e = launch_state_f32((const float *)p->k, (const float *)p->v, BH, p->N, p->d, (float *)(ws + w.Hs), (float *)(ws + w.Z), drop, p->H, st);
         if (e != hipSuccess) return hip_fail(e, "state launch");
@@ -441,7 +448,7 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
         ap.eps = p->eps; ap.o_linear_dbg = full_proj ? nullptr : p->o_linear_dbg;
         ap.drop = drop; ap.H = p->H;
         ap.emit = full_proj ? (u16 *)(ws + w.ol) : nullptr;
-        ap.rope_cos = p->rope_cos; ap.rope_sin = p->rope_sin;
+        ap.rope_tab = rope ? (const uint32_t *)(ws + w.rope_tab) : nullptr;
         e = launch_linear_apply_bf16(ap, st);
         if (e != hipSuccess) return hip_fail(e, "linear apply launch");
         mark(5);

@@ -28,10 +28,11 @@ int gate_num_parts(int N);
 int state_tiles_per_chunk(int BH, int N);
 int state_num_chunks(int BH, int N);
 // drop (may be null): int32 [B], workgroups of a sample with drop[b] != 0 return at once (H heads per sample)
-// rope_cos / rope_sin (both or neither; d = 128 only): fp32 [N, d/2] tables of the rotary linear branch
+// rope_tab (d = 128 only): [N, d/2] words (fp16 cos | fp16 sin << 16) of the rotary linear branch, or null
 hipError_t launch_state_partial_bf16(const u16 *k, const u16 *v, int BH, int N, int D,
                                      float *partial, const int32_t *drop, int H, hipStream_t st,
-                                     const float *rope_cos = nullptr, const float *rope_sin = nullptr);
+                                     const uint32_t *rope_tab = nullptr);
+hipError_t launch_rope_pack(const float *rope_cos, const float *rope_sin, size_t n, uint32_t *tab, hipStream_t st);
 // fp32: direct evaluation, one thread per state element (small shapes).
 hipError_t launch_state_f32(const float *k, const float *v, int BH, int N, int D,
                             float *Hs, float *Z, const int32_t *drop, int H, hipStream_t st);
@@ -131,7 +132,7 @@ struct ApplyArgs {
     const u16 *hfrag; const float *Z; const float *coef; float eps;
     float *o_linear_dbg;
     const int32_t *drop; int H;     // [B] or null: pruned samples are left as they are (out = O_s)
-    const float *rope_cos, *rope_sin;   // d = 128: fp32 [N, 64] tables of the rotary linear branch, or null
+    const uint32_t *rope_tab;       // d = 128: [N, 64] words (fp16 cos | fp16 sin << 16) of the rotary linear branch, or null
     u16 *emit;                      // d = 128: non-null -> write the unscaled O_l (bf16, [B][ceil(N/32)][H] fragment blocks) here, leave out alone
 };
 hipError_t launch_linear_apply_bf16(const ApplyArgs &a, hipStream_t st);
