@@ -387,6 +387,8 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
         for (int i = first; i < last; ++i) {
             mfma_step(i, ring[i % RING]);
             if (i + RING < last) read_frag(i + RING, Vt, Kt, ring[i % RING]);
+            if (skip & 4096) asm volatile("s_nop 7\n\ts_nop 7");
+            if (skip & 8192) asm volatile("s_nop 7");
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -703,7 +705,7 @@ hipError_t launch_sparse_attn_v5(const AttnArgs &a, hipStream_t st)
     case 0: break;
 #define SALAD_DIAG_CASE(k) case k: return launch_v5<3, false, k>(a, st);
     SALAD_DIAG_CASE(1) SALAD_DIAG_CASE(6) SALAD_DIAG_CASE(7) SALAD_DIAG_CASE(8) SALAD_DIAG_CASE(9) SALAD_DIAG_CASE(14)
-    SALAD_DIAG_CASE(15) SALAD_DIAG_CASE(16) SALAD_DIAG_CASE(32) SALAD_DIAG_CASE(33) SALAD_DIAG_CASE(47) SALAD_DIAG_CASE(64) SALAD_DIAG_CASE(96) SALAD_DIAG_CASE(192) SALAD_DIAG_CASE(224) SALAD_DIAG_CASE(256) SALAD_DIAG_CASE(80) SALAD_DIAG_CASE(512) SALAD_DIAG_CASE(520) SALAD_DIAG_CASE(513) SALAD_DIAG_CASE(1024) SALAD_DIAG_CASE(2048)
+    SALAD_DIAG_CASE(15) SALAD_DIAG_CASE(16) SALAD_DIAG_CASE(32) SALAD_DIAG_CASE(33) SALAD_DIAG_CASE(47) SALAD_DIAG_CASE(64) SALAD_DIAG_CASE(96) SALAD_DIAG_CASE(192) SALAD_DIAG_CASE(224) SALAD_DIAG_CASE(256) SALAD_DIAG_CASE(80) SALAD_DIAG_CASE(512) SALAD_DIAG_CASE(520) SALAD_DIAG_CASE(513) SALAD_DIAG_CASE(1024) SALAD_DIAG_CASE(2048) SALAD_DIAG_CASE(4096) SALAD_DIAG_CASE(8192) SALAD_DIAG_CASE(12288) SALAD_DIAG_CASE(4160) SALAD_DIAG_CASE(12352)
 #undef SALAD_DIAG_CASE
     default: return hipErrorInvalidValue;
     }

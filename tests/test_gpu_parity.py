@@ -428,6 +428,29 @@ def test_wan13_480p_rotary_sampled(oracle):
     assert np.isfinite(res["out"]).all()
 
 
+def test_topk_rotary_dropping_together(oracle):
+    """The widened pieces in one call: Top-K mask for the sparse branch, rotary linear branch, and branch dropping
+    with a threshold between the two samples' dynamic scales (sample 0 keeps its branch, sample 1 loses it)."""
+    w = SMALL[1]                                        # B = 2, H = 3, N = 693
+    inp = wl.make_inputs(w)
+    dev = upload(w, inp)
+    kinds = np.zeros(w.H, dtype=np.uint8)
+    kept = [1] * w.H
+    cs, sn = wl.rope_tables(w.T, w.Hh, w.W, w.d)
+    rope_dev = (torch.from_numpy(cs).cuda(), torch.from_numpy(sn).cuda())
+    s = oracle.gate(inp["x_t"], inp["w_gate"], 0.0)
+    tau = float(0.5 * (s.min() + s.max()))
+    assert s.min() < tau < s.max()
+    ref = _oracle_layer(oracle, w, inp, kept, kinds, lam=10.0, topk=3, key_block=128, rope=(cs, sn), drop_threshold=tau)
+    res = run_layer(w, inp, dev, kept, kinds, lam=10.0, topk=3, topk_key_block=128, rope=rope_dev, drop_threshold=tau)
+    assert res["dropped"].tolist() == ref["dropped"].tolist() and sorted(res["dropped"].tolist()) == [0, 1]
+    assert np.array_equal(res["topk_mask"], ref["topk_mask"])
+    compare_layer(res, ref, check_linear=False, label="topk+rope+drop")
+    b_drop = int(np.argmax(ref["dropped"]))
+    sparse_only = run_layer(w, inp, dev, kept, kinds, lam=0.0, topk=3, topk_key_block=128)["out_t"]
+    assert torch.equal(res["out_t"][b_drop], sparse_only[b_drop])
+
+
 @pytest.fixture
 def topk_variant():
     yield lambda v: sb.salad_tune("topk_variant", v)
