@@ -48,9 +48,10 @@ hipError_t launch_kblock_mean(const u16 *k, int BH, int N, int key_block, int nb
 
 // grid (ceil(N / 256), BH), 256 threads: a thread owns one query and keeps one score accumulator per key block
 // (NBK of them, the smallest instantiation >= nbk: the chains are independent, each runs over the channels in
-// ascending order).  The head's block means sit in LDS; every lane reads the same word (broadcast).  The best 8
-// scores are then collected in descending order, blocks in ascending order; the first topk of them are the selection.
-template <int NBK>
+// ascending order).  The head's block means sit in LDS; every lane reads the same word (broadcast).  The best SLOTS
+// (4 or 8, >= topk) scores are then collected in descending order, blocks in ascending order; the first topk of them
+// are the selection.
+template <int NBK, int SLOTS>
 __global__ __launch_bounds__(256) void topk_select_kernel(const u16 *__restrict__ q, const float *__restrict__ means,
                                                           int N, int nbk, int topk,
                                                           unsigned long long *__restrict__ mask)
@@ -66,32 +67,37 @@ __global__ __launch_bounds__(256) void topk_select_kernel(const u16 *__restrict_
     for (int J = 0; J < NBK; ++J) sc[J] = 0.f;
     const uint4 *src = reinterpret_cast<const uint4 *>(q + ((size_t)bh * N + nr) * D);
 #pragma unroll 1
-    for (int c8 = 0; c8 < D / 8; ++c8) {               // 8 channels of the query at a time
-        const uint4 u = src[c8];
-        const uint32_t w[4] = {u.x, u.y, u.z, u.w};
-        float qv[8];
+    for (int c64 = 0; c64 < D / 64; ++c64) {           // 64 channels = one 128-byte line of the query row at a time:
+        uint4 u[8];                                    // its 8 loads go out together, so the line is fetched once
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            qv[2 * j] = __uint_as_float(w[j] << 16);
-            qv[2 * j + 1] = __uint_as_float(w[j] & 0xffff0000u);
-        }
-        const float *mc = sm + c8 * 8;
+        for (int i = 0; i < 8; ++i) u[i] = src[c64 * 8 + i];
 #pragma unroll
-        for (int J = 0; J < NBK; ++J) {
-            const float4 m0 = *reinterpret_cast<const float4 *>(mc + J * D);
-            const float4 m1 = *reinterpret_cast<const float4 *>(mc + J * D + 4);
-            float x = sc[J];
-            x = __fmaf_rn(qv[0], m0.x, x); x = __fmaf_rn(qv[1], m0.y, x);
-            x = __fmaf_rn(qv[2], m0.z, x); x = __fmaf_rn(qv[3], m0.w, x);
-            x = __fmaf_rn(qv[4], m1.x, x); x = __fmaf_rn(qv[5], m1.y, x);
-            x = __fmaf_rn(qv[6], m1.z, x); x = __fmaf_rn(qv[7], m1.w, x);
-            sc[J] = x;
+        for (int i = 0; i < 8; ++i) {
+            const uint32_t w[4] = {u[i].x, u[i].y, u[i].z, u[i].w};
+            float qv[8];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                qv[2 * j] = __uint_as_float(w[j] << 16);
+                qv[2 * j + 1] = __uint_as_float(w[j] & 0xffff0000u);
+            }
+            const float *mc = sm + c64 * 64 + i * 8;
+#pragma unroll
+            for (int J = 0; J < NBK; ++J) {
+                const float4 m0 = *reinterpret_cast<const float4 *>(mc + J * D);
+                const float4 m1 = *reinterpret_cast<const float4 *>(mc + J * D + 4);
+                float x = sc[J];
+                x = __fmaf_rn(qv[0], m0.x, x); x = __fmaf_rn(qv[1], m0.y, x);
+                x = __fmaf_rn(qv[2], m0.z, x); x = __fmaf_rn(qv[3], m0.w, x);
+                x = __fmaf_rn(qv[4], m1.x, x); x = __fmaf_rn(qv[5], m1.y, x);
+                x = __fmaf_rn(qv[6], m1.z, x); x = __fmaf_rn(qv[7], m1.w, x);
+                sc[J] = x;
+            }
         }
     }
-    float best[8];
-    int bidx[8];
+    float best[SLOTS];                                 // SLOTS >= topk: 4 or 8
+    int bidx[SLOTS];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) { best[i] = -INFINITY; bidx[i] = -1; }
+    for (int i = 0; i < SLOTS; ++i) { best[i] = -INFINITY; bidx[i] = -1; }
 #pragma unroll
     for (int J = 0; J < NBK; ++J) {
         if (J < nbk) {
@@ -101,7 +107,7 @@ __global__ __launch_bounds__(256) void topk_select_kernel(const u16 *__restrict_
             int id = J;
             bool carry = false;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
+            for (int i = 0; i < SLOTS; ++i) {
                 const bool take = (id >= 0) && (carry || bidx[i] < 0 || v > best[i]);
                 carry = carry || take;
                 const float tv = best[i];
@@ -115,7 +121,7 @@ __global__ __launch_bounds__(256) void topk_select_kernel(const u16 *__restrict_
     }
     unsigned long long m = 0ull;
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < SLOTS; ++i)
         if (i < topk && bidx[i] >= 0) m |= 1ull << bidx[i];
     if (n < N) mask[(size_t)bh * N + n] = m;
 }
@@ -124,10 +130,16 @@ hipError_t launch_topk_select(const u16 *q, const float *means, int BH, int N, i
                               unsigned long long *mask, hipStream_t st)
 {
     const dim3 grid((N + 255) / 256, BH), block(256);
-    if (nbk <= 16) hipLaunchKernelGGL(topk_select_kernel<16>, grid, block, 0, st, q, means, N, nbk, topk, mask);
-    else if (nbk <= 32) hipLaunchKernelGGL(topk_select_kernel<32>, grid, block, 0, st, q, means, N, nbk, topk, mask);
-    else if (nbk <= 48) hipLaunchKernelGGL(topk_select_kernel<48>, grid, block, 0, st, q, means, N, nbk, topk, mask);
-    else hipLaunchKernelGGL(topk_select_kernel<64>, grid, block, 0, st, q, means, N, nbk, topk, mask);
+#define SALAD_TOPK_SELECT(NBK_)                                                                                              \
+    do {                                                                                                                     \
+        if (topk <= 4) hipLaunchKernelGGL((topk_select_kernel<NBK_, 4>), grid, block, 0, st, q, means, N, nbk, topk, mask);  \
+        else hipLaunchKernelGGL((topk_select_kernel<NBK_, 8>), grid, block, 0, st, q, means, N, nbk, topk, mask);            \
+    } while (0)
+    if (nbk <= 16) SALAD_TOPK_SELECT(16);
+    else if (nbk <= 32) SALAD_TOPK_SELECT(32);
+    else if (nbk <= 48) SALAD_TOPK_SELECT(48);
+    else SALAD_TOPK_SELECT(64);
+#undef SALAD_TOPK_SELECT
     return hipGetLastError();
 }
 
