@@ -488,6 +488,7 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
     // The fetch of block j+PD is issued from each group's vector phase, where its address arithmetic
     // runs under the other group's MFMAs; the slots it goes to were last read in iteration j-1.
     STAMP(1);
+    int v_last = 0;                         // V-ring slot of the last block: the only tile still read after the loop
     if (n > 0) {
 #pragma unroll
         for (int b = 0; b < PD; ++b)
@@ -573,6 +574,7 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
         if (lin) stage_state();
         {
             int vslot_prev = vslot - 1; if (vslot_prev < 0) vslot_prev += NV;
+            v_last = vslot_prev;
             const u16 *Vt = Vb + vslot_prev * TILE;
             const bool kP = (e_prev & mybit) != 0;
             if (group == 1 && kP) { preload_V(Vt); stage_softmax(e_prev); }
@@ -619,22 +621,44 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
             }
         }
     }
-    if (!qvalid) return;
-    if (GATHER) {
-        // normalised partial result of this (query, key block) pair and its log-sum-exp (log2 domain)
-        u16 *po = a.g_po + g_slot * D;
+    if (!DBG && !(skip & 16384)) {
+        // bf16 results leave through LDS so that every global store is a run of full 256-byte rows: accumulator
+        // layout (lane = query l32; 4 consecutive columns per (dt, g4, hh)) -> a wave-private 8 KB of the V ring
+        // (the four slots that do not hold the last block: nobody reads them any more), 16-byte chunk c of row r at
+        // r * 256 + ((c ^ (r & 15)) << 4) -> row layout (4 rows x 16 chunks per instruction).
+        int vs = v_last + 1 + (wave >> 1);
+        if (vs >= NV) vs -= NV;
+        unsigned char *stg = reinterpret_cast<unsigned char *>(Vb + vs * TILE) + (wave & 1) * 8192;
 #pragma unroll
         for (int dt = 0; dt < NDT; ++dt)
 #pragma unroll
             for (int g4 = 0; g4 < 4; ++g4) {
+                float ov[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const float os = o[dt][g4 * 4 + t] * inv_l;
+                    ov[t] = lin ? fmaf(num[dt][g4 * 4 + t], lin_scale, os) : os;
+                }
                 uint2 pk;
-                pk.x = pack2e(o[dt][g4 * 4 + 0] * inv_l, o[dt][g4 * 4 + 1] * inv_l);
-                pk.y = pack2e(o[dt][g4 * 4 + 2] * inv_l, o[dt][g4 * 4 + 3] * inv_l);
-                *reinterpret_cast<uint2 *>(po + dt * 32 + 8 * g4 + 4 * hh) = pk;
+                pk.x = pack2e(ov[0], ov[1]);
+                pk.y = pack2e(ov[2], ov[3]);
+                *reinterpret_cast<uint2 *>(stg + l32 * 256 + (((dt * 4 + g4) ^ (l32 & 15)) << 4) + hh * 8) = pk;
             }
-        if (hh == 0) a.g_lse[g_slot] = l_tot > 0.f ? m_run + log2f(l_tot) : -INFINITY;
-        return;
-    }
+        asm volatile("" ::: "memory");       // the wave's LDS operations execute in order
+        // destination of row r: the stored row (or the pair slot) of the lane that owns query r
+        const int dest_mine = !qvalid ? -1 : GATHER ? g_slot0 + wave * 32 + l32 : qrow;
+        const int r4 = lane >> 4, c16 = lane & 15;
+        u16 *dbase = GATHER ? a.g_po + (size_t)bh * N * a.g_kk * D : reinterpret_cast<u16 *>(a.out) + (size_t)bh * N * D;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int r = 4 * i + r4;
+            const uint4 v = *reinterpret_cast<const uint4 *>(stg + r * 256 + ((c16 ^ (r & 15)) << 4));
+            const int dest = __shfl(dest_mine, r);
+            if (dest >= 0) *reinterpret_cast<uint4 *>(dbase + (size_t)dest * D + c16 * 8) = v;
+        }
+        if (GATHER && qvalid && hh == 0) a.g_lse[g_slot] = l_tot > 0.f ? m_run + log2f(l_tot) : -INFINITY;
+    } else {
+    if (!qvalid) return;
     const size_t obase = ((size_t)bh * N + qrow) * D;
     u16 *outp = reinterpret_cast<u16 *>(a.out) + obase;
 #pragma unroll
@@ -653,14 +677,13 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
             pk.x = pack2e(ov[0], ov[1]);
             pk.y = pack2e(ov[2], ov[3]);
             *reinterpret_cast<uint2 *>(outp + col) = pk;
-            if (DBG) {
-                if (a.o_sparse_dbg)
-                    *reinterpret_cast<float4 *>(a.o_sparse_dbg + obase + col) = make_float4(os[0], os[1], os[2], os[3]);
-                if (a.o_linear_dbg && lin)
-                    *reinterpret_cast<float4 *>(a.o_linear_dbg + obase + col) =
-                        make_float4(ol[0] * inv_den, ol[1] * inv_den, ol[2] * inv_den, ol[3] * inv_den);
-            }
+            if (DBG && a.o_sparse_dbg)
+                *reinterpret_cast<float4 *>(a.o_sparse_dbg + obase + col) = make_float4(os[0], os[1], os[2], os[3]);
+            if (DBG && a.o_linear_dbg && lin)
+                *reinterpret_cast<float4 *>(a.o_linear_dbg + obase + col) =
+                    make_float4(ol[0] * inv_den, ol[1] * inv_den, ol[2] * inv_den, ol[3] * inv_den);
         }
+    }
     }
     if (DIAG && trace != nullptr && (int)blockIdx.x == trace_block) {
 #pragma unroll
@@ -705,7 +728,7 @@ hipError_t launch_sparse_attn_v5(const AttnArgs &a, hipStream_t st)
     case 0: break;
 #define SALAD_DIAG_CASE(k) case k: return launch_v5<3, false, k>(a, st);
     SALAD_DIAG_CASE(1) SALAD_DIAG_CASE(6) SALAD_DIAG_CASE(7) SALAD_DIAG_CASE(8) SALAD_DIAG_CASE(9) SALAD_DIAG_CASE(14)
-    SALAD_DIAG_CASE(15) SALAD_DIAG_CASE(16) SALAD_DIAG_CASE(32) SALAD_DIAG_CASE(33) SALAD_DIAG_CASE(47) SALAD_DIAG_CASE(64) SALAD_DIAG_CASE(96) SALAD_DIAG_CASE(192) SALAD_DIAG_CASE(224) SALAD_DIAG_CASE(256) SALAD_DIAG_CASE(80) SALAD_DIAG_CASE(512) SALAD_DIAG_CASE(520) SALAD_DIAG_CASE(513) SALAD_DIAG_CASE(1024) SALAD_DIAG_CASE(2048) SALAD_DIAG_CASE(4096) SALAD_DIAG_CASE(8192) SALAD_DIAG_CASE(12288) SALAD_DIAG_CASE(4160) SALAD_DIAG_CASE(12352)
+    SALAD_DIAG_CASE(15) SALAD_DIAG_CASE(16) SALAD_DIAG_CASE(32) SALAD_DIAG_CASE(33) SALAD_DIAG_CASE(47) SALAD_DIAG_CASE(64) SALAD_DIAG_CASE(96) SALAD_DIAG_CASE(192) SALAD_DIAG_CASE(224) SALAD_DIAG_CASE(256) SALAD_DIAG_CASE(80) SALAD_DIAG_CASE(512) SALAD_DIAG_CASE(520) SALAD_DIAG_CASE(513) SALAD_DIAG_CASE(1024) SALAD_DIAG_CASE(2048) SALAD_DIAG_CASE(16384) SALAD_DIAG_CASE(4096) SALAD_DIAG_CASE(8192) SALAD_DIAG_CASE(12288) SALAD_DIAG_CASE(4160) SALAD_DIAG_CASE(12352)
 #undef SALAD_DIAG_CASE
     default: return hipErrorInvalidValue;
     }
