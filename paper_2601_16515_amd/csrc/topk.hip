@@ -322,53 +322,83 @@ __global__ __launch_bounds__(1024) void topk_group_kernel(const unsigned long lo
 
 // out[bh, n, :] = sum_r w_r O_r / sum_r w_r over the query's kk partial results (normalised per key block, bf16, with
 // log2-domain log-sum-exp lse_r), w_r = 2^(lse_r - max lse): Eq. (2) over the union of the kept blocks.
-// 32 lanes per query (4 channels each); grid ceil(BH * N / 8), 256 threads.
+// 16 lanes per query (8 channels each) and two queries per thread, so that enough independent gathers are in flight
+// (the chain mask -> slot -> partial row is three dependent loads); grid ceil(BH * N / 32), 256 threads.
 __global__ __launch_bounds__(256) void topk_merge_kernel(const u16 *__restrict__ po, const float *__restrict__ lse,
                                                          const int32_t *__restrict__ slot_of,
                                                          const unsigned long long *__restrict__ mask, int BH, int N, int kk,
                                                          u16 *__restrict__ out, float *__restrict__ o_dbg)
 {
-    const size_t qi = (size_t)blockIdx.x * 8 + (threadIdx.x >> 5);
-    if (qi >= (size_t)BH * N) return;
-    const int c4 = (threadIdx.x & 31) * 4;
-    const size_t bh = qi / N;
+    const size_t nq = (size_t)BH * N;
+    const size_t q0 = (size_t)blockIdx.x * 32 + (threadIdx.x >> 4);
+    const int c8 = (threadIdx.x & 15) * 8;
     const size_t slots = (size_t)N * kk;
-    float l[8];
-    int sl[8];
-    float mx = -INFINITY;
-    kk = min(kk, (int)__popcll(mask[qi]));          // only the ranks the regrouping pass filled in
-    const int kk_stride = (int)(slots / N);
+    size_t qi[2];
+    int cnt[2], sl[2][8];
+    float l[2][8], mx[2];
 #pragma unroll
-    for (int r = 0; r < 8; ++r) {
-        sl[r] = 0;
-        l[r] = -INFINITY;
-        if (r < kk) {
-            sl[r] = slot_of[qi * kk_stride + r];
-            l[r] = lse[bh * slots + sl[r]];
-            mx = fmaxf(mx, l[r]);
+    for (int u = 0; u < 2; ++u) {
+        qi[u] = q0 + 16 * u;
+        cnt[u] = qi[u] < nq ? min(kk, (int)__popcll(mask[qi[u]])) : 0;     // only the ranks the regrouping pass filled in
+    }
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int r = 0; r < 8; ++r) sl[u][r] = r < cnt[u] ? slot_of[qi[u] * kk + r] : 0;
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const size_t bh = qi[u] < nq ? qi[u] / N : 0;
+        mx[u] = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            l[u][r] = r < cnt[u] ? lse[bh * slots + sl[u][r]] : -INFINITY;
+            mx[u] = fmaxf(mx[u], l[u][r]);
         }
     }
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    float den = 0.f;
+    uint4 x[2][8];
 #pragma unroll
-    for (int r = 0; r < 8; ++r) {
-        if (r < kk) {
-            const float wgt = __builtin_amdgcn_exp2f(l[r] - mx);
-            const uint2 x = *reinterpret_cast<const uint2 *>(po + (bh * slots + sl[r]) * D + c4);
-            acc.x = fmaf(wgt, __uint_as_float(x.x << 16), acc.x); acc.y = fmaf(wgt, __uint_as_float(x.x & 0xffff0000u), acc.y);
-            acc.z = fmaf(wgt, __uint_as_float(x.y << 16), acc.z); acc.w = fmaf(wgt, __uint_as_float(x.y & 0xffff0000u), acc.w);
-            den += wgt;
+    for (int u = 0; u < 2; ++u) {
+        const size_t bh = qi[u] < nq ? qi[u] / N : 0;
+#pragma unroll
+        for (int r = 0; r < 8; ++r)
+            if (r < cnt[u]) x[u][r] = *reinterpret_cast<const uint4 *>(po + (bh * slots + sl[u][r]) * D + c8);
+    }
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        if (qi[u] >= nq) continue;
+        float acc[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+        float den = 0.f;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            if (r < cnt[u]) {
+                const float wgt = __builtin_amdgcn_exp2f(l[u][r] - mx[u]);
+                const uint32_t w4[4] = {x[u][r].x, x[u][r].y, x[u][r].z, x[u][r].w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    acc[2 * j] = fmaf(wgt, __uint_as_float(w4[j] << 16), acc[2 * j]);
+                    acc[2 * j + 1] = fmaf(wgt, __uint_as_float(w4[j] & 0xffff0000u), acc[2 * j + 1]);
+                }
+                den += wgt;
+            }
+        }
+        const float inv = den > 0.f ? 1.f / den : 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] *= inv;
+        typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+        typedef float f32x2_t __attribute__((ext_vector_type(2)));
+        uint4 pk;
+        pk.x = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2_t){acc[0], acc[1]}, bf16x2_t));
+        pk.y = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2_t){acc[2], acc[3]}, bf16x2_t));
+        pk.z = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2_t){acc[4], acc[5]}, bf16x2_t));
+        pk.w = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2_t){acc[6], acc[7]}, bf16x2_t));
+        *reinterpret_cast<uint4 *>(out + qi[u] * D + c8) = pk;
+        if (o_dbg) {
+            *reinterpret_cast<float4 *>(o_dbg + qi[u] * D + c8) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+            *reinterpret_cast<float4 *>(o_dbg + qi[u] * D + c8 + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
         }
     }
-    const float inv = den > 0.f ? 1.f / den : 0.f;
-    acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
-    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-    typedef float f32x2_t __attribute__((ext_vector_type(2)));
-    uint2 pk;
-    pk.x = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2_t){acc.x, acc.y}, bf16x2_t));
-    pk.y = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2_t){acc.z, acc.w}, bf16x2_t));
-    *reinterpret_cast<uint2 *>(out + qi * D + c4) = pk;
-    if (o_dbg) *reinterpret_cast<float4 *>(o_dbg + qi * D + c4) = acc;
 }
 
 int topk_max_tiles(int BH, int N, int kk, int nbk) { return BH * ((int)(((long long)N * kk + 255) / 256) + nbk); }
@@ -389,7 +419,7 @@ hipError_t launch_topk_merge(const u16 *po, const float *lse, const int32_t *slo
                              int BH, int N, int kk, u16 *out, float *o_dbg, hipStream_t st)
 {
     const size_t nq = (size_t)BH * N;
-    hipLaunchKernelGGL(topk_merge_kernel, dim3((unsigned)((nq + 7) / 8)), dim3(256), 0, st, po, lse, slot_of, mask, BH, N, kk, out, o_dbg);
+    hipLaunchKernelGGL(topk_merge_kernel, dim3((unsigned)((nq + 31) / 32)), dim3(256), 0, st, po, lse, slot_of, mask, BH, N, kk, out, o_dbg);
     return hipGetLastError();
 }
 
