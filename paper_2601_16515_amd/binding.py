@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(_HERE, "libsalad.so")
 SOURCES = ["salad_api.hip", "mask_gate_finalize.hip", "linear_state.hip", "sparse_attn.hip",
-           "sparse_attn_v2.hip", "sparse_attn_v5.hip", "linear_apply.hip", "proj.hip", "topk.hip"]
+           "sparse_attn_v2.hip", "sparse_attn_v5.hip", "linear_apply.hip", "proj.hip", "topk.hip", "sparse_attn_v7.hip"]
 
 SALAD_OK, SALAD_EINVAL, SALAD_ENOTSUP, SALAD_ENOSPC, SALAD_EHIP = range(5)
 SALAD_F32, SALAD_BF16 = 0, 1

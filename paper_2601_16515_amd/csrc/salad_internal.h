@@ -104,6 +104,7 @@ hipError_t launch_tile_lists(const int32_t *row_ptr, const int32_t *col_idx, int
 hipError_t launch_sparse_attn_f32(const AttnArgs &a, hipStream_t st);
 hipError_t launch_sparse_attn_v2(const AttnArgs &a, hipStream_t st);   // d = 128 only
 hipError_t launch_sparse_attn_v5(const AttnArgs &a, hipStream_t st);   // d = 128 only
+hipError_t launch_sparse_attn_v7(const AttnArgs &a, hipStream_t st);   // d = 128 only, 64 queries per wave
 
 // ---- Top-K dynamic mask (App. A.1.2), d = 128 bf16 ---------------------------------------------------------
 // means [BH][nbk][128] fp32: mean key of each run of key_block stored tokens (sequential fp32 sum / count)

@@ -332,6 +332,7 @@ hipError_t launch_sparse_attn_bf16(const AttnArgs &a, hipStream_t st)
         const bool temporal = a.kind_mask != 0 && a.T > 1;
         const bool fits = (size_t)tile_list_cap(a.nb) * 4 <= 24 * 1024 && (unsigned long long)a.N * 256ull < (1ull << 32) &&
                           (!temporal || a.t_magic != 0);
+        if (variant == 7 && fits && a.tile_lists) return launch_sparse_attn_v7(a, st);
         if ((variant == 0 || variant == 5) && fits && a.tile_lists) return launch_sparse_attn_v5(a, st);
         return launch_sparse_attn_v2(a, st);
     }
