@@ -428,6 +428,22 @@ def test_wan13_480p_rotary_sampled(oracle):
     assert np.isfinite(res["out"]).all()
 
 
+@pytest.mark.parametrize("grid,key_block,topk", [((10, 10, 20), 64, 5), ((10, 20, 20), 64, 4), ((7, 11, 13), 192, 6)],
+                         ids=["32-key-blocks-k5", "63-key-blocks-k4", "6-key-blocks-k6-all"])
+def test_topk_selection_kernel_instantiations(oracle, grid, key_block, topk):
+    """Shapes that reach the other instantiations of the selection kernel (up to 32 and up to 64 key blocks, four
+    and eight kept slots) and a ragged everything: N = 2000, 4000, 1001; both attention paths share the mask."""
+    w = wl.small("topk-shapes", 1, 2, 128, *grid, "bf16", 0.5, seed=211 + topk)
+    inp = wl.make_inputs(w)
+    dev = upload(w, inp)
+    kinds = np.zeros(w.H, dtype=np.uint8)
+    kept = [1] * w.H
+    ref = _oracle_layer(oracle, w, inp, kept, kinds, topk=topk, key_block=key_block)
+    res = run_layer(w, inp, dev, kept, kinds, topk=topk, topk_key_block=key_block)
+    assert np.array_equal(res["topk_mask"], ref["topk_mask"])
+    compare_layer(res, ref, label=f"topk-N{w.N}-kb{key_block}-k{topk}")
+
+
 def test_topk_rotary_dropping_together(oracle):
     """The widened pieces in one call: Top-K mask for the sparse branch, rotary linear branch, and branch dropping
     with a threshold between the two samples' dynamic scales (sample 0 keeps its branch, sample 1 loses it)."""
