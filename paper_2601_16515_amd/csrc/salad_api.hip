@@ -412,10 +412,9 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
         if (topk_regroup) {
             const int kk = p->topk < nbk ? p->topk : nbk;
             e = launch_topk_group(mask, BH, p->N, nbk, kk, (int32_t *)(ws + w.g_ccnt), (int32_t *)(ws + w.g_seg),
-                                  (int32_t *)(ws + w.g_counts), (uint4 *)(ws + w.g_desc), (int32_t *)(ws + w.g_total), (int32_t *)(ws + w.g_idx),
-                                  (int32_t *)(ws + w.g_slot), st);
+                                  (uint4 *)(ws + w.g_desc), (int32_t *)(ws + w.g_idx), (int32_t *)(ws + w.g_slot), st);
             if (e != hipSuccess) return hip_fail(e, "top-k regrouping launch");
-            a.g_desc = (const uint4 *)(ws + w.g_desc); a.g_total = (const int32_t *)(ws + w.g_total);
+            a.g_desc = (const uint4 *)(ws + w.g_desc);
             a.g_idx = (const int32_t *)(ws + w.g_idx); a.g_po = (u16 *)(ws + w.g_po); a.g_lse = (float *)(ws + w.g_lse);
             a.g_kk = kk; a.g_bpb = p->topk_key_block / 64; a.g_max_tiles = topk_max_tiles(BH, p->N, kk, nbk);
         } else {

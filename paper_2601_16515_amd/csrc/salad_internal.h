@@ -86,12 +86,11 @@ struct AttnArgs {
     // keeps key block J; tile_lists / tile_counts are then per (b, h, tile) with entries
     // block | J << 16 | wave mask << 24.  null: block rows (CSR) as above.
     const unsigned long long *topk_mask;
-    // Top-K regrouped by key block, large-tile kernel only (g_desc != null): query tile L < *g_total is the run of
-    // g_desc[L].w queries (g_desc[L] = sample-head, key block, first slot, queries) whose stored rows are
+    // Top-K regrouped by key block, large-tile kernel only (g_desc != null): query tile L < g_max_tiles is the run of
+    // g_desc[L].w queries (none: the workgroup returns; g_desc[L] = sample-head, key block, first slot, queries) whose stored rows are
     // g_idx[bh * N * g_kk + slot], attending to the 64-token blocks of that one key block (g_bpb per key block);
     // results go to g_po [slot][128] (normalised, bf16) and g_lse [slot] (fp32, log2 domain), not to out.
     const uint4 *g_desc;
-    const int32_t *g_total;
     const int32_t *g_idx;
     u16 *g_po; float *g_lse;
     int g_kk, g_bpb, g_max_tiles;
@@ -116,10 +115,9 @@ hipError_t launch_topk_select(const u16 *q, const float *means, int BH, int N, i
 // per (b, h, tile of 256 queries): the 64-token blocks of every key block some query of the tile keeps
 // regrouping by key block: counts, slot plan and query-tile descriptors, gathered query rows, slot of every pair
 int topk_max_tiles(int BH, int N, int kk, int nbk);
-// (ccnt, cbase: [BH][ceil(N/1024)][64] per-chunk counts and first slots; counts: [BH * nbk])
+// (ccnt, cbase: [BH][ceil(N/1024)][64] per-chunk counts and first slots; desc: [topk_max_tiles])
 hipError_t launch_topk_group(const unsigned long long *mask, int BH, int N, int nbk, int kk, int32_t *ccnt,
-                             int32_t *cbase, int32_t *counts, uint4 *desc, int32_t *total, int32_t *gidx,
-                             int32_t *slot_of, hipStream_t st);
+                             int32_t *cbase, uint4 *desc, int32_t *gidx, int32_t *slot_of, hipStream_t st);
 // out = the kk partial results of every query combined by their log-sum-exp weights (bf16; o_dbg fp32 optional)
 hipError_t launch_topk_merge(const u16 *po, const float *lse, const int32_t *slot_of, const unsigned long long *mask,
                              int BH, int N, int kk, u16 *out, float *o_dbg, hipStream_t st);

@@ -216,9 +216,9 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
     int bh = L / ntiles, tile = L - bh * ntiles;
     int g_J = 0, g_slot0 = 0, g_cnt = 0;
     if (GATHER) {
-        if (L >= *a.g_total) return;
         const uint4 dsc = a.g_desc[L];
         bh = (int)dsc.x; g_J = (int)dsc.y; g_slot0 = (int)dsc.z; g_cnt = (int)dsc.w;
+        if (g_cnt == 0) return;            // unused descriptor
         tile = 0;
     }
     const int h = bh % a.H;

@@ -235,51 +235,39 @@ __global__ __launch_bounds__(1024) void topk_count_kernel(const unsigned long lo
     }
 }
 
-// one workgroup of 1024 threads.  Pair group e = (bh, J): cbase[(bh * nch + chunk) * 64 + J] = first slot (within the
-// sample-head) of the chunk's queries keeping J = slots of key blocks < J + those of earlier chunks; tile descriptors
-// (bh, J, first slot, queries) for every run of up to 256 queries, groups in order; *total = tiles.
-__global__ __launch_bounds__(1024) void topk_plan_kernel(const int32_t *__restrict__ ccnt, int BH, int nbk, int nch,
-                                                         int32_t *__restrict__ counts, int32_t *__restrict__ cbase,
-                                                         uint4 *__restrict__ desc, int max_tiles, int32_t *__restrict__ total)
+// grid (BH), 64 threads (lane J = key block J).  cbase[(bh * nch + chunk) * 64 + J] = first slot (within the
+// sample-head) of the chunk's queries keeping J = slots of key blocks < J + those of earlier chunks.  Tile descriptors
+// (bh, J, first slot, queries) for every run of up to 256 queries, key blocks in order, at desc[bh * mt ...]; the
+// unused descriptors of the sample-head's mt are written with zero queries (their workgroups return at once).
+__global__ __launch_bounds__(64) void topk_plan_kernel(const int32_t *__restrict__ ccnt, int nbk, int nch,
+                                                       int32_t *__restrict__ cbase, uint4 *__restrict__ desc, int mt)
 {
-    __shared__ int tsum[1024];
-    const int t = threadIdx.x;
-    const int E = BH * nbk, per = (E + 1023) / 1024;
-    const int e0 = min(E, t * per), e1 = min(E, e0 + per);
-    int tiles = 0;
-    for (int e = e0; e < e1; ++e) {
-        const int bh = e / nbk, J = e - bh * nbk;
-        int c = 0;
+    const int bh = blockIdx.x, J = threadIdx.x;
+    int c = 0;
+    if (J < nbk)
         for (int ch = 0; ch < nch; ++ch) c += ccnt[((size_t)bh * nch + ch) * 64 + J];
-        counts[e] = c;
-        tiles += (c + 255) >> 8;
+    // exclusive prefix sums over the key blocks: slots and tiles
+    const int tl = (c + 255) >> 8;
+    int s_incl = c, t_incl = tl;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int xs = __shfl_up(s_incl, o), xt = __shfl_up(t_incl, o);
+        if (J >= o) { s_incl += xs; t_incl += xt; }
     }
-    tsum[t] = tiles;
-    __threadfence_block();
-    __syncthreads();
-    if (t == 0) {
-        int run = 0;
-        for (int i = 0; i < 1024; ++i) { const int x = tsum[i]; tsum[i] = run; run += x; }
-        *total = min(run, max_tiles);
-    }
-    __syncthreads();
-    int tile = tsum[t];
-    for (int e = e0; e < e1; ++e) {
-        const int bh = e / nbk, J = e - bh * nbk;
-        int s0 = 0;                                     // slots of this (sample, head) before key block J
-        for (int j = 0; j < J; ++j) s0 += counts[bh * nbk + j];
+    const int s0 = s_incl - c, t0 = t_incl - tl;
+    const int used = __shfl(t_incl, 63);
+    if (J < nbk) {
         int run = s0;
         for (int ch = 0; ch < nch; ++ch) {
             const size_t i = ((size_t)bh * nch + ch) * 64 + J;
             cbase[i] = run;
             run += ccnt[i];
         }
-        const int c = run - s0;
-        for (int i = 0; i < c; i += 256) {
-            if (tile < max_tiles) desc[tile] = make_uint4((uint32_t)bh, (uint32_t)J, (uint32_t)(s0 + i), (uint32_t)min(256, c - i));
-            ++tile;
-        }
+        for (int i = 0; i < tl; ++i)
+            if (t0 + i < mt)
+                desc[(size_t)bh * mt + t0 + i] = make_uint4((uint32_t)bh, (uint32_t)J, (uint32_t)(s0 + i * 256), (uint32_t)min(256, c - i * 256));
     }
+    for (int i = used + J; i < mt; i += 64) desc[(size_t)bh * mt + i] = make_uint4((uint32_t)bh, 0u, 0u, 0u);
 }
 
 // grid (nch, BH), 1024 threads: gidx[bh * slots + slot] = n and slot_of[(bh * N + n) * kk + r] = slot for every kept
@@ -401,16 +389,16 @@ __global__ __launch_bounds__(256) void topk_merge_kernel(const u16 *__restrict__
     }
 }
 
-int topk_max_tiles(int BH, int N, int kk, int nbk) { return BH * ((int)(((long long)N * kk + 255) / 256) + nbk); }
+// query tiles per sample-head: every key block can leave one partly filled tile
+int topk_tiles_per_head(int N, int kk, int nbk) { return (int)(((long long)N * kk + 255) / 256) + nbk; }
+int topk_max_tiles(int BH, int N, int kk, int nbk) { return BH * topk_tiles_per_head(N, kk, nbk); }
 
 hipError_t launch_topk_group(const unsigned long long *mask, int BH, int N, int nbk, int kk, int32_t *ccnt,
-                             int32_t *cbase, int32_t *counts, uint4 *desc, int32_t *total, int32_t *gidx,
-                             int32_t *slot_of, hipStream_t st)
+                             int32_t *cbase, uint4 *desc, int32_t *gidx, int32_t *slot_of, hipStream_t st)
 {
     const int nch = (N + 1023) / 1024;
     hipLaunchKernelGGL(topk_count_kernel, dim3(nch, BH), dim3(1024), 0, st, mask, N, nbk, nch, ccnt);
-    hipLaunchKernelGGL(topk_plan_kernel, dim3(1), dim3(1024), 0, st, ccnt, BH, nbk, nch, counts, cbase, desc,
-                       topk_max_tiles(BH, N, kk, nbk), total);
+    hipLaunchKernelGGL(topk_plan_kernel, dim3(BH), dim3(64), 0, st, ccnt, nbk, nch, cbase, desc, topk_tiles_per_head(N, kk, nbk));
     hipLaunchKernelGGL(topk_group_kernel, dim3(nch, BH), dim3(1024), 0, st, mask, N, nbk, kk, nch, cbase, gidx, slot_of);
     return hipGetLastError();
 }
