@@ -381,6 +381,10 @@ def test_topk_mask_layer(oracle, topk_variant, wi, key_block, topk, variant):
     pop = np.array([bin(int(x)).count("1") for x in res["topk_mask"].reshape(-1)])
     assert (pop == min(topk, nbk)).all()
     compare_layer(res, ref, label=f"topk-{w.name}")
+    # the same call without the debug outputs
+    fast = run_layer(w, inp, dev, kept, kinds, topk=topk, topk_key_block=key_block, dbg=False)
+    compare_layer(fast, ref, label=f"topk-{w.name}-fast")
+    assert np.array_equal(fast["topk_mask"], ref["topk_mask"])
     if topk >= nbk:                                      # every block kept: the dense layer
         dense = run_layer(w, inp, dev, [w.nb] * w.H, kinds)
         assert errors(res["out"], dense["out"])[1] < 5e-3   # two independently rounded bf16 results
@@ -465,6 +469,10 @@ def test_topk_rotary_dropping_together(oracle):
     b_drop = int(np.argmax(ref["dropped"]))
     sparse_only = run_layer(w, inp, dev, kept, kinds, lam=0.0, topk=3, topk_key_block=128)["out_t"]
     assert torch.equal(res["out_t"][b_drop], sparse_only[b_drop])
+    # the same call without the debug outputs
+    fast = run_layer(w, inp, dev, kept, kinds, lam=10.0, topk=3, topk_key_block=128, rope=rope_dev, drop_threshold=tau, dbg=False)
+    compare_layer(fast, ref, check_linear=False, label="topk+rope+drop-fast")
+    assert torch.equal(fast["out_t"][b_drop], sparse_only[b_drop])
 
 
 @pytest.fixture
