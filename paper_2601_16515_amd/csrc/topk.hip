@@ -135,9 +135,13 @@ hipError_t launch_topk_select(const u16 *q, const float *means, int BH, int N, i
         if (topk <= 4) hipLaunchKernelGGL((topk_select_kernel<NBK_, 4>), grid, block, 0, st, q, means, N, nbk, topk, mask);  \
         else hipLaunchKernelGGL((topk_select_kernel<NBK_, 8>), grid, block, 0, st, q, means, N, nbk, topk, mask);            \
     } while (0)
-    if (nbk <= 16) SALAD_TOPK_SELECT(16);
+    if (nbk <= 8) SALAD_TOPK_SELECT(8);
+    else if (nbk <= 16) SALAD_TOPK_SELECT(16);
+    else if (nbk <= 24) SALAD_TOPK_SELECT(24);
     else if (nbk <= 32) SALAD_TOPK_SELECT(32);
+    else if (nbk <= 40) SALAD_TOPK_SELECT(40);
     else if (nbk <= 48) SALAD_TOPK_SELECT(48);
+    else if (nbk <= 56) SALAD_TOPK_SELECT(56);
     else SALAD_TOPK_SELECT(64);
 #undef SALAD_TOPK_SELECT
     return hipGetLastError();
