@@ -184,7 +184,11 @@ typedef struct salad_kernel_times {
                                  attn_ms is then the attention kernel alone                             */
 } salad_kernel_times;
 
-/* When enabled, the layer call brackets each of its kernels with HIP events on its stream. */
+/* on = 1: the layer call brackets each of its stages with HIP events on its stream (eight records per call; every
+ * record is a dependency between two kernels that would otherwise start back to back, so the call itself gets some
+ * 5 % slower).  on = 2: only the attention stage (pre-pass + attention kernel, Top-K: + merge) is bracketed, two
+ * records per call; salad_timing_read then fills attn_ms and calls only.  on = 0: no events.  Other values:
+ * SALAD_EINVAL. */
 salad_status salad_timing_enable(int32_t on);
 /* Waits for the recorded events, adds up the elapsed times since the last reset into *out and
  * (if reset != 0) clears the record.  This one call does synchronise with the host. */

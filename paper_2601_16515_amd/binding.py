@@ -289,8 +289,9 @@ def salad_gate_fwd(x_t, w_gate, b_gate: float = 0.0):
     return s
 
 
-def salad_timing_enable(on: bool) -> None:
-    _check(lib().salad_timing_enable(1 if on else 0))
+def salad_timing_enable(on) -> None:
+    """False/0 off, True/1 events around every stage, 2 around the attention stage only."""
+    _check(lib().salad_timing_enable(int(on)))
 
 
 def salad_timing_read(reset: bool = True) -> KernelTimes:

@@ -99,8 +99,8 @@ bool shape_ok(int B, int H, int N, int d, int dtype)
 // ---- timing -----------------------------------------------------------------------------------
 std::mutex g_tmu;
 int g_topk_variant = 0;
-bool g_timing = false;
-struct CallEvents { hipEvent_t e[8]; bool has_epilogue, has_linear; };   // e[7]: end of the Top-K mask steps
+int g_timing = 0;   // 0 off, 1 every stage, 2 the attention stage only
+struct CallEvents { hipEvent_t e[8]; bool has_epilogue, has_linear, attn_only; };   // e[7]: end of the Top-K mask steps
 std::vector<CallEvents> g_calls;
 std::vector<hipEvent_t> g_free_events;
 
@@ -314,19 +314,21 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
     hipError_t e;
 
     CallEvents ev{};
-    bool timing;
+    int timing;
     {
         std::lock_guard<std::mutex> lk(g_tmu);
         timing = g_timing;
         if (timing)
-            for (auto &x : ev.e) {
-                x = get_event();
-                if (!x) return fail(SALAD_EHIP, "fwd: hipEventCreate failed");
+            for (int i = 0; i < 8; ++i) {
+                if (timing == 2 && i != 7 && i != 4) continue;
+                ev.e[i] = get_event();
+                if (!ev.e[i]) return fail(SALAD_EHIP, "fwd: hipEventCreate failed");
             }
     }
     ev.has_linear = use_linear;
     ev.has_epilogue = unfused && use_linear;
-    auto mark = [&](int i) { if (timing) (void)hipEventRecord(ev.e[i], st); };
+    ev.attn_only = timing == 2;
+    auto mark = [&](int i) { if (timing == 1 || (timing == 2 && (i == 7 || i == 4))) (void)hipEventRecord(ev.e[i], st); };
 
     // Post-tuning branch dropping (Sec. 4.3): the dynamic scale has to be known before the state kernel, so the
     // gate is reduced first (finalize in gate-only form) and the later kernels skip the pruned samples.
@@ -475,7 +477,8 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
 salad_status salad_timing_enable(int32_t on)
 {
     std::lock_guard<std::mutex> lk(g_tmu);
-    g_timing = on != 0;
+    if (on < 0 || on > 2) return fail(SALAD_EINVAL, "salad_timing_enable: mode %d", (int)on);
+    g_timing = on;
     return SALAD_OK;
 }
 
@@ -485,6 +488,16 @@ salad_status salad_timing_read(salad_kernel_times *out, int32_t reset)
     std::lock_guard<std::mutex> lk(g_tmu);
     std::memset(out, 0, sizeof(*out));
     for (auto &c : g_calls) {
+        if (c.attn_only) {
+            hipError_t e = hipEventSynchronize(c.e[4]);
+            if (e != hipSuccess) return hip_fail(e, "hipEventSynchronize");
+            float ms_a = 0.f;
+            e = hipEventElapsedTime(&ms_a, c.e[7], c.e[4]);
+            if (e != hipSuccess) return hip_fail(e, "hipEventElapsedTime");
+            out->attn_ms += ms_a;
+            out->calls += 1;
+            continue;
+        }
         hipError_t e = hipEventSynchronize(c.e[6]);
         if (e != hipSuccess) return hip_fail(e, "hipEventSynchronize");
         float ms[6] = {0, 0, 0, 0, 0, 0};
@@ -507,7 +520,8 @@ salad_status salad_timing_read(salad_kernel_times *out, int32_t reset)
     }
     if (reset) {
         for (auto &c : g_calls)
-            for (auto &x : c.e) g_free_events.push_back(x);
+            for (auto &x : c.e)
+                if (x) g_free_events.push_back(x);
         g_calls.clear();
     }
     return SALAD_OK;

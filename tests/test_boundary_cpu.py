@@ -155,6 +155,8 @@ def test_step_entry_points_reject_bad_arguments(lib):
     assert lib.salad_gate_fwd(fake, fake, 0.0, 1, 64, 8192, sb.SALAD_BF16, fake, 0x4000, 1 << 20, None) == sb.SALAD_ENOTSUP
     assert lib.salad_gate_fwd(fake, None, 0.0, 1, 64, 128, sb.SALAD_BF16, fake, 0x4000, 1 << 20, None) == sb.SALAD_EINVAL
     assert lib.salad_timing_read(None, 0) == sb.SALAD_EINVAL
+    assert lib.salad_timing_enable(3) == sb.SALAD_EINVAL and lib.salad_timing_enable(-1) == sb.SALAD_EINVAL
+    assert lib.salad_timing_enable(0) == sb.SALAD_OK
     assert lib.salad_tune(b"no_such_knob", 1) == sb.SALAD_EINVAL
 
 

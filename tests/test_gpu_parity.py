@@ -509,6 +509,33 @@ def test_layer_call_under_graph_capture():
         assert torch.equal(out, eager), f"replay {rep} differs from the eager call"
 
 
+def test_timing_modes_leave_results_alone():
+    """Per-stage timing (mode 1), attention-only timing (mode 2) and no timing give the same bits; mode 2 reports
+    the attention stage alone."""
+    w = SMALL[7]
+    inp = wl.make_inputs(w)
+    dev = upload(w, inp)
+    kinds = wl.head_kinds(w)
+    kept = [4, 5, 4]
+    ref = run_layer(w, inp, dev, kept, kinds, dbg=False)["out_t"].clone()
+    try:
+        for mode in (1, 2):
+            sb.salad_timing_read(reset=True)
+            sb.salad_timing_enable(mode)
+            outs = [run_layer(w, inp, dev, kept, kinds, dbg=False)["out_t"].clone() for _ in range(3)]
+            sb.salad_timing_enable(0)
+            kt = sb.salad_timing_read(reset=True)
+            assert all(torch.equal(o, ref) for o in outs)
+            assert kt.calls == 3 and kt.attn_ms > 0
+            if mode == 1:
+                assert kt.gate_ms > 0 and kt.state_ms > 0 and kt.finalize_ms > 0
+            else:
+                assert kt.gate_ms == 0 and kt.state_ms == 0 and kt.finalize_ms == 0 and kt.epilogue_ms == 0
+    finally:
+        sb.salad_timing_enable(0)
+        sb.salad_timing_read(reset=True)
+
+
 # ------------------------------------------------------------------- benchmark configurations
 
 def _sampled_parity(oracle, w, nsel, label):
