@@ -178,3 +178,13 @@ def test_product_does_not_import_the_oracle():
         if f.endswith((".py", ".c")):
             text = open(os.path.join(ROOT, "oracle", f)).read()
             assert "paper_2601_16515_amd" not in text and "libsalad.so" not in text, f
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py is a one-GPU program: any other --gpus value ends with a message before anything touches a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=60)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
