@@ -181,6 +181,55 @@ def test_linear_dominant_case(oracle):
     assert r <= REL_L2
 
 
+@pytest.mark.parametrize("kept_n", [19, 6], ids=["all-blocks", "window-6"])
+@pytest.mark.parametrize("profile", ["rising", "falling", "mixed"])
+def test_softmax_reference_moves_across_blocks(oracle, profile, kept_n):
+    """Key magnitudes that change by large factors from one 64-token block to the next, so that the largest
+    logit a query has seen so far jumps by tens of binades between blocks (rising), never again reaches the
+    first block's (falling), or both (mixed): the running reference of the online softmax has to move, and
+    what was accumulated before has to be rescaled, many times per row."""
+    w = SMALL[7]                                   # N = 1170: 19 blocks, 3 heads (one temporal)
+    inp = wl.make_inputs(w)
+    blk = np.arange(w.N) // 64
+    if profile == "rising":
+        g = 1.0 + 3.0 * blk
+    elif profile == "falling":
+        g = 1.0 + 3.0 * (blk.max() - blk)
+    else:
+        g = np.array([1.0, 30.0, 2.0, 55.0, 8.0])[(blk * 7 + 3) % 5]
+    inp["k"] = wl.round_to_bf16(inp["k"] * g[None, None, :, None].astype(np.float32))
+    # With such keys the softmax is close to one-hot and the output is a single V row: values up to 4.5, where one
+    # bf16 rounding alone is 1.6e-2 and the two roundings of the regrouped Top-K path (partial results are stored in
+    # bf16) 3.1e-2.  A quarter of the magnitude keeps the absolute bar meaningful for every path; exact in bf16.
+    inp["v"] = inp["v"] * np.float32(0.25)
+    dev = upload(w, inp)
+    kinds = wl.head_kinds(w)
+    kept = [kept_n] * w.H
+    res = run_layer(w, inp, dev, kept, kinds)
+    ref = _oracle_layer(oracle, w, inp, kept, kinds)
+    compare_layer(res, ref, label=f"{profile}/{kept_n}: ")
+    if profile == "mixed":
+        # the other attention kernels keep their own running maximum
+        for variant in (1, 2, 7):
+            sb.salad_tune("attn_variant", variant)
+            try:
+                res = run_layer(w, inp, dev, kept, kinds)
+            finally:
+                sb.salad_tune("attn_variant", 0)
+            compare_layer(res, ref, label=f"{profile}/{kept_n}/variant{variant}: ")
+        # Top-K modes (stored order, all heads spatial): gathered queries and token mask
+        kinds0 = np.zeros(w.H, dtype=np.uint8)
+        ref_t = _oracle_layer(oracle, w, inp, [1] * w.H, kinds0, topk=3, key_block=128)
+        for tv in (0, 1):
+            sb.salad_tune("topk_variant", tv)
+            try:
+                res_t = run_layer(w, inp, dev, [1] * w.H, kinds0, topk=3, topk_key_block=128)
+            finally:
+                sb.salad_tune("topk_variant", 0)
+            assert np.array_equal(res_t["topk_mask"], ref_t["topk_mask"])
+            compare_layer(res_t, ref_t, label=f"{profile}/topk-variant{tv}: ")
+
+
 def test_precomputed_s_and_bias_and_scale_arguments(oracle):
     w = SMALL[2]
     inp = wl.make_inputs(w)
