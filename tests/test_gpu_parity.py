@@ -668,6 +668,24 @@ def test_wan13_480p_topk_sampled(oracle):
     assert np.isfinite(res["out"]).all()
 
 
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("case", ["list-too-long", "inexact-division"])
+def test_long_sequence_takes_the_fallback_by_itself(oracle, case):
+    """Shapes the large-tile kernel does not take, so that the dispatcher has to pick the 128-row kernel without being
+    told (the tuning knob stays at automatic).  list-too-long: 6152 key blocks per head, more than the per-tile block
+    list may hold in LDS.  inexact-division: N T >= 2^32, where the temporal order's multiply-high division by T is no
+    longer exact (the list would fit).  One spatial and one temporal head, 5 kept blocks per row, ragged last block."""
+    if case == "list-too-long":
+        w = wl.small("long-seq", 1, 2, 128, 31, 100, 127, "bf16", 1.0 - 5.0 / 6152.0, seed=131)
+        assert w.N == 393700 and w.nb == 6152 and w.N % 64 == 36
+    else:
+        w = wl.small("long-T", 1, 2, 128, 11078, 5, 7, "bf16", 1.0 - 5.0 / 6059.0, seed=132)
+        assert w.N == 387730 and w.nb == 6059 and w.N % 64 == 18 and w.N * w.T >= 1 << 32
+        assert ((w.nb + 63) & ~63) * 4 <= 24 * 1024
+    assert sb.salad_kept_from_sparsity(w.nb, w.sparsity) == 5
+    _sampled_parity(oracle, w, 8, w.name)
+
+
 @pytest.mark.parametrize("rho", [0.0, 0.5, 0.75, 0.95])
 def test_wan13_480p_sweep_sampled(oracle, rho):
     """The other points of the sparsity sweep at the 480p shape (same seeded inputs)."""
