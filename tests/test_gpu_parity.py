@@ -146,6 +146,28 @@ def test_fp32_path_ragged_d128(oracle):
     compare_layer(res, _oracle_layer(oracle, w, inp, kept, kinds), tol_abs=1e-4, tol_rel=1e-5, label="f32-d128")
 
 
+@pytest.mark.parametrize("d", [64, 128])
+def test_sixty_four_heads(oracle, d):
+    """The largest head count the boundary takes (64: the head-order mask is a 64-bit word, the last head temporal),
+    every head with its own window size.  d = 64: D = 4096 goes through the gate; d = 128: D = 8192 is beyond the gate
+    kernel, so the dynamic scale is passed in."""
+    w = wl.small(f"heads64-d{d}", 1, 64, d, 3, 5, 21, "bf16", 0.5, seed=140 + d)      # N = 315: 5 blocks, tail 59
+    inp = wl.make_inputs(w)
+    dev = upload(w, inp)
+    kinds = wl.head_kinds(w)
+    assert kinds[63] == 1
+    kept = [1 + (h * 7) % 5 for h in range(w.H)]
+    if d == 64:
+        res = run_layer(w, inp, dev, kept, kinds)
+        ref = _oracle_layer(oracle, w, inp, kept, kinds)
+        assert np.abs(res["s"] - ref["s"]).max() < 2e-6
+    else:
+        res = run_layer(w, inp, dev, kept, kinds, s=torch.tensor([0.4], device="cuda"))
+        ref = _oracle_layer(oracle, w, inp, kept, kinds, s_override=[0.4])
+    assert np.array_equal(res["row_ptr"], ref["row_ptr"]) and np.array_equal(res["col_idx"], ref["col_idx"])
+    compare_layer(res, ref, label=w.name)
+
+
 def test_zero_static_scale_gives_sparse_branch_exactly(oracle):
     """Zero-initialised static scale (Sec. 4.2): the layer output is the sparse branch alone; the
     three ways of switching the linear branch off agree bit for bit."""
