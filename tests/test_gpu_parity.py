@@ -503,11 +503,14 @@ def test_wan13_480p_rotary_sampled(oracle):
     assert np.isfinite(res["out"]).all()
 
 
-@pytest.mark.parametrize("grid,key_block,topk", [((10, 10, 20), 64, 5), ((10, 20, 20), 64, 4), ((7, 11, 13), 192, 6)],
-                         ids=["32-key-blocks-k5", "63-key-blocks-k4", "6-key-blocks-k6-all"])
+@pytest.mark.parametrize("grid,key_block,topk", [((10, 10, 20), 64, 5), ((10, 20, 20), 64, 4), ((7, 11, 13), 192, 6),
+                                                 ((16, 16, 16), 64, 8), ((4, 33, 31), 64, 8)],
+                         ids=["32-key-blocks-k5", "63-key-blocks-k4", "6-key-blocks-k6-all", "64-key-blocks-k8",
+                              "64-key-blocks-ragged-k8"])
 def test_topk_selection_kernel_instantiations(oracle, grid, key_block, topk):
     """Shapes that reach the other instantiations of the selection kernel (up to 32 and up to 64 key blocks, four
-    and eight kept slots) and a ragged everything: N = 2000, 4000, 1001; both attention paths share the mask."""
+    and eight kept slots), a ragged everything (N = 2000, 4000, 1001) and the limits: 64 key blocks (bit 63 of the
+    mask word) with 8 kept, N = 4096 and N = 4092 (last key block of 60 tokens)."""
     w = wl.small("topk-shapes", 1, 2, 128, *grid, "bf16", 0.5, seed=211 + topk)
     inp = wl.make_inputs(w)
     dev = upload(w, inp)
