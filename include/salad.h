@@ -174,6 +174,16 @@ salad_status salad_gate_fwd(const void *x_t, const float *w_gate, float b_gate, 
                             int32_t D, int32_t dtype, float *s_out,
                             void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* salad_gate_fwd for callers that cannot allocate or bring a workspace (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): same kernels and same result, with the partial sums in a static device
+ * buffer of SALAD_STATIC_SCRATCH_BYTES that is part of the library (one copy per GPU, held until the process ends).
+ * Calls no hipMalloc / hipFree or any allocating routine.  SALAD_ENOSPC when B is too large for the buffer
+ * (B * min(ceil(N/16), 512) partial sums + B results, each group rounded up to 256 bytes).  All calls on one GPU share
+ * the buffer: calls that may overlap on one GPU (different streams or threads) race; calls on one stream do not. */
+#define SALAD_STATIC_SCRATCH_BYTES 65536
+salad_status salad_gate_fwd_static(const void *x_t, const float *w_gate, float b_gate, int32_t B, int32_t N,
+                                   int32_t D, int32_t dtype, float *s_out, void *hip_stream);
+
 /* ---- per-kernel timing ----------------------------------------------------------------------- */
 
 typedef struct salad_kernel_times {

@@ -25,7 +25,7 @@ SALAD_FLAG_UNFUSED_EPILOGUE = 1
 
 EXPORTS = ["salad_last_error", "salad_kept_from_sparsity", "salad_block_mask_nnz", "salad_block_mask",
            "salad_fwd_workspace_bytes", "salad_sparse_linear_attn_fwd", "salad_linear_state_fwd",
-           "salad_gate_fwd", "salad_timing_enable", "salad_timing_read", "salad_tune"]
+           "salad_gate_fwd", "salad_gate_fwd_static", "salad_timing_enable", "salad_timing_read", "salad_tune"]
 
 
 class SaladError(RuntimeError):
@@ -116,6 +116,9 @@ def lib() -> C.CDLL:
         L.salad_gate_fwd.restype = C.c_int
         L.salad_gate_fwd.argtypes = [C.c_void_p, C.c_void_p, C.c_float, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                      C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.salad_gate_fwd_static.restype = C.c_int
+        L.salad_gate_fwd_static.argtypes = [C.c_void_p, C.c_void_p, C.c_float, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                            C.c_void_p, C.c_void_p]
         L.salad_timing_enable.restype = C.c_int
         L.salad_timing_enable.argtypes = [C.c_int32]
         L.salad_timing_read.restype = C.c_int
@@ -287,6 +290,16 @@ def salad_gate_fwd(x_t, w_gate, b_gate: float = 0.0):
     _check(lib().salad_gate_fwd(x_t.data_ptr(), w_gate.data_ptr(), b_gate, B, N, D, _dtype_code(x_t), s.data_ptr(),
                                 ptr, ws.numel() - 256, _stream()))
     return s
+
+
+def salad_gate_fwd_static(x_t, w_gate, s_out, b_gate: float = 0.0) -> None:
+    """The gate through the library's static scratch buffer: the caller passes the output, nothing is allocated."""
+    import torch
+    B, N, D = x_t.shape
+    assert x_t.is_cuda and x_t.is_contiguous() and w_gate.dtype == torch.float32 and w_gate.numel() == D
+    assert s_out.is_cuda and s_out.dtype == torch.float32 and s_out.numel() == B and s_out.is_contiguous()
+    _check(lib().salad_gate_fwd_static(x_t.data_ptr(), w_gate.data_ptr(), b_gate, B, N, D, _dtype_code(x_t),
+                                       s_out.data_ptr(), _stream()))
 
 
 def salad_timing_enable(on) -> None:

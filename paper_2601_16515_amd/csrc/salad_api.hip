@@ -116,6 +116,37 @@ hipEvent_t get_event()
     return e;
 }
 
+// ---- static scratch for the entry point that takes no workspace ----------------------------------
+// Device memory that lives in the code object: one copy per GPU the library is loaded on, held until the
+// process ends.  The array's name is only a host-side handle; the device address is asked for once per
+// device and that pointer is what kernels and copies get.
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[SALAD_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+std::mutex g_smu;
+void *g_scratch_ptr[64] = {};
+
+salad_status static_scratch_ptr(void **out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= 64) return fail(SALAD_ENOTSUP, "static scratch: device ordinal %d outside 0..63", dev);
+    std::lock_guard<std::mutex> lk(g_smu);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));     // the current device's copy of the array
+        if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+        if (!ptr || ((uintptr_t)ptr & 255)) return fail(SALAD_EHIP, "static scratch: bad device address %p", ptr);
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return SALAD_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -208,29 +239,61 @@ salad_status salad_linear_state_fwd(const void *k, const void *v, int32_t B, int
     return SALAD_OK;
 }
 
-salad_status salad_gate_fwd(const void *x_t, const float *w_gate, float b_gate, int32_t B, int32_t N, int32_t D,
-                            int32_t dtype, float *s_out, void *workspace, size_t workspace_bytes, void *hip_stream)
+// Shared by salad_gate_fwd and salad_gate_fwd_static: host checks, then gate pass 1 and the fixed-order reduce.
+// `scratch` holds the per-workgroup partial sums and, 256-byte aligned behind them, the reduced s.
+static size_t gate_scratch_bytes(int B, int N)
 {
-    if (!x_t || !w_gate || !s_out) return fail(SALAD_EINVAL, "salad_gate_fwd: null pointer");
-    if (B < 1 || N < 1 || D < 8 || (D & 7)) return fail(SALAD_EINVAL, "salad_gate_fwd: need B,N >= 1 and D a positive multiple of 8 (got %d,%d,%d)", B, N, D);
-    if (D > 5120) return fail(SALAD_ENOTSUP, "salad_gate_fwd: D=%d above 5120", D);
-    if (dtype != SALAD_BF16 && dtype != SALAD_F32) return fail(SALAD_EINVAL, "salad_gate_fwd: dtype %d", dtype);
+    return align256(sizeof(float) * (size_t)B * gate_num_parts(N)) + align256(sizeof(float) * (size_t)B);
+}
+
+static salad_status gate_check(const char *who, const void *x_t, const float *w_gate, int32_t B, int32_t N, int32_t D,
+                               int32_t dtype, const float *s_out)
+{
+    if (!x_t || !w_gate || !s_out) return fail(SALAD_EINVAL, "%s: null pointer", who);
+    if (B < 1 || N < 1 || D < 8 || (D & 7)) return fail(SALAD_EINVAL, "%s: need B,N >= 1 and D a positive multiple of 8 (got %d,%d,%d)", who, B, N, D);
+    if (D > 5120) return fail(SALAD_ENOTSUP, "%s: D=%d above 5120", who, D);
+    if (dtype != SALAD_BF16 && dtype != SALAD_F32) return fail(SALAD_EINVAL, "%s: dtype %d", who, dtype);
+    return SALAD_OK;
+}
+
+static salad_status gate_run(const void *x_t, const float *w_gate, float b_gate, int B, int N, int D, int dtype,
+                             float *s_out, void *scratch, hipStream_t st)
+{
     const int nparts = gate_num_parts(N);
-    const size_t need = align256(sizeof(float) * (size_t)B * nparts) + align256(sizeof(float) * B);
-    if (!workspace || ((uintptr_t)workspace & 255)) return fail(SALAD_EINVAL, "salad_gate_fwd: workspace null or not 256-byte aligned");
-    if (workspace_bytes < need) return fail(SALAD_ENOSPC, "salad_gate_fwd: workspace %zu < %zu bytes", workspace_bytes, need);
-    hipStream_t st = (hipStream_t)hip_stream;
-    float *partial = (float *)workspace;
+    float *partial = (float *)scratch;
     hipError_t e = launch_gate_partial(x_t, w_gate, b_gate, B, N, D, dtype == SALAD_BF16, partial, nparts, st);
     if (e != hipSuccess) return hip_fail(e, "gate launch");
     FinalizeArgs f{};
     f.B = B; f.H = 1; f.D = 64; f.P = 0;
     f.gate_partial = partial; f.nparts = nparts; f.N = N;
-    f.s_out = s_out; f.s_ws = (float *)((char *)workspace + align256(sizeof(float) * (size_t)B * nparts));
+    f.s_out = s_out; f.s_ws = (float *)((char *)scratch + align256(sizeof(float) * (size_t)B * nparts));
     f.coef = nullptr; f.do_gate = 1;
     e = launch_finalize(f, st);
     if (e != hipSuccess) return hip_fail(e, "finalize launch");
     return SALAD_OK;
+}
+
+salad_status salad_gate_fwd(const void *x_t, const float *w_gate, float b_gate, int32_t B, int32_t N, int32_t D,
+                            int32_t dtype, float *s_out, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (salad_status c = gate_check("salad_gate_fwd", x_t, w_gate, B, N, D, dtype, s_out); c != SALAD_OK) return c;
+    const size_t need = gate_scratch_bytes(B, N);
+    if (!workspace || ((uintptr_t)workspace & 255)) return fail(SALAD_EINVAL, "salad_gate_fwd: workspace null or not 256-byte aligned");
+    if (workspace_bytes < need) return fail(SALAD_ENOSPC, "salad_gate_fwd: workspace %zu < %zu bytes", workspace_bytes, need);
+    return gate_run(x_t, w_gate, b_gate, B, N, D, dtype, s_out, workspace, (hipStream_t)hip_stream);
+}
+
+salad_status salad_gate_fwd_static(const void *x_t, const float *w_gate, float b_gate, int32_t B, int32_t N, int32_t D,
+                                   int32_t dtype, float *s_out, void *hip_stream)
+{
+    if (salad_status c = gate_check("salad_gate_fwd_static", x_t, w_gate, B, N, D, dtype, s_out); c != SALAD_OK) return c;
+    const size_t need = gate_scratch_bytes(B, N);
+    if (need > SALAD_STATIC_SCRATCH_BYTES)
+        return fail(SALAD_ENOSPC, "salad_gate_fwd_static: B=%d needs %zu bytes of scratch, the static buffer holds %d", B, need, (int)SALAD_STATIC_SCRATCH_BYTES);
+    void *ptr = nullptr;
+    if (salad_status c = static_scratch_ptr(&ptr); c != SALAD_OK) return c;
+    // every partial sum and s[b] the reduce reads is written by this call's own pass 1: nothing has to start at zero
+    return gate_run(x_t, w_gate, b_gate, B, N, D, dtype, s_out, ptr, (hipStream_t)hip_stream);
 }
 
 salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
