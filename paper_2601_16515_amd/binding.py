@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(_HERE, "libsalad.so")
 SOURCES = ["salad_api.hip", "mask_gate_finalize.hip", "linear_state.hip", "sparse_attn.hip",
-           "sparse_attn_v2.hip", "sparse_attn_v5.hip", "linear_apply.hip", "proj.hip", "topk.hip", "sparse_attn_v7.hip"]
+           "sparse_attn_v2.hip", "sparse_attn_v5.hip", "linear_apply.hip", "proj.hip", "topk.hip"]
 
 SALAD_OK, SALAD_EINVAL, SALAD_ENOTSUP, SALAD_ENOSPC, SALAD_EHIP = range(5)
 SALAD_F32, SALAD_BF16 = 0, 1
@@ -77,15 +77,34 @@ class KernelTimes(C.Structure):
 
 def build_library(verbose: bool = False) -> str:
     """Compile csrc/*.hip for gfx950 into libsalad.so next to this file (hipcc cross-compiles
-    without a GPU)."""
-    cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-o", LIB_PATH] + [os.path.join(_CSRC, s) for s in SOURCES]
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if verbose or r.returncode != 0:
-        print(r.stdout, r.stderr)
-    if r.returncode != 0:
-        raise RuntimeError("hipcc failed building libsalad.so")
+    without a GPU).  One hipcc process per source file, side by side, then one link."""
+    import shutil
+    import tempfile
+    from concurrent.futures import ThreadPoolExecutor
+    flags = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
+             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+    tmp = tempfile.mkdtemp(prefix="salad_build_")
+    try:
+        def compile_one(src):
+            obj = os.path.join(tmp, src.replace(".hip", ".o"))
+            r = subprocess.run(["hipcc", "-c"] + flags + ["-o", obj, os.path.join(_CSRC, src)],
+                               capture_output=True, text=True)
+            return src, obj, r
+        with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
+            results = list(ex.map(compile_one, SOURCES))
+        for src, _, r in results:
+            if verbose or r.returncode != 0:
+                print(src, r.stdout, r.stderr)
+            if r.returncode != 0:
+                raise RuntimeError(f"hipcc failed compiling {src}")
+        r = subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH] + [o for _, o, _ in results],
+                           capture_output=True, text=True)
+        if verbose or r.returncode != 0:
+            print(r.stdout, r.stderr)
+        if r.returncode != 0:
+            raise RuntimeError("hipcc failed linking libsalad.so")
+    finally:
+        shutil.rmtree(tmp, ignore_errors=True)
     return LIB_PATH
 
 

@@ -25,21 +25,19 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 
-int g_state_target_wgs = 512;
-
-int state_tiles_per_chunk(int BH, int N)
+int state_tiles_per_chunk(int BH, int N, int target_wgs)
 {
     int tiles = (N + 63) / 64;
-    int want = g_state_target_wgs / (BH > 0 ? BH : 1);
+    int want = target_wgs / (BH > 0 ? BH : 1);
     if (want < 1) want = 1;
     if (want > tiles) want = tiles;
     return (tiles + want - 1) / want;
 }
 
-int state_num_chunks(int BH, int N)
+int state_num_chunks(int BH, int N, int target_wgs)
 {
     int tiles = (N + 63) / 64;
-    int tpc = state_tiles_per_chunk(BH, N);
+    int tpc = state_tiles_per_chunk(BH, N, target_wgs);
     return (tiles + tpc - 1) / tpc;
 }
 
@@ -226,11 +224,11 @@ __global__ __launch_bounds__(256, 2) void state_partial_kernel(const u16 *__rest
 }
 
 hipError_t launch_state_partial_bf16(const u16 *k, const u16 *v, int BH, int N, int D,
-                                     float *partial, const int32_t *drop, int H, hipStream_t st,
+                                     float *partial, const int32_t *drop, int H, int target_wgs, hipStream_t st,
                                      const uint32_t *rope_tab)
 {
-    int tpc = state_tiles_per_chunk(BH, N);
-    int P = state_num_chunks(BH, N);
+    int tpc = state_tiles_per_chunk(BH, N, target_wgs);
+    int P = state_num_chunks(BH, N, target_wgs);
     dim3 grid(P, BH), block(256);
     if (rope_tab) {
         if (D != 128) return hipErrorInvalidValue;

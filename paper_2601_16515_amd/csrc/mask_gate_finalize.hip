@@ -155,12 +155,12 @@ __global__ __launch_bounds__(256) void gate_partial_kernel(const void *x_t, cons
         partial[(size_t)b * nparts + blockIdx.x] = (wave_sum[0] + wave_sum[1]) + (wave_sum[2] + wave_sum[3]);
 }
 
-int g_gate_parts = 512, g_gate_tok = 2;
+constexpr int GATE_MAX_PARTS = 512;
 
 int gate_num_parts(int N)
 {
     int parts = (N + 15) / 16;          // a workgroup step covers 16 tokens (4 waves x up to 4 tokens)
-    return parts < g_gate_parts ? (parts < 1 ? 1 : parts) : g_gate_parts;
+    return parts < GATE_MAX_PARTS ? (parts < 1 ? 1 : parts) : GATE_MAX_PARTS;
 }
 
 static void gate_dispatch_bf16(dim3 grid, dim3 block, hipStream_t st, const void *x_t, const float *w, float bias, int N, int D,
@@ -169,8 +169,6 @@ static void gate_dispatch_bf16(dim3 grid, dim3 block, hipStream_t st, const void
     const int nch = (D / 8 + 63) / 64;
     if (nch <= 1) hipLaunchKernelGGL((gate_partial_kernel<true, 1, 4>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
     else if (nch <= 2) hipLaunchKernelGGL((gate_partial_kernel<true, 2, 4>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
-    else if (nch <= 3 && g_gate_tok == 1) hipLaunchKernelGGL((gate_partial_kernel<true, 3, 1>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
-    else if (nch <= 3 && g_gate_tok == 4) hipLaunchKernelGGL((gate_partial_kernel<true, 3, 4>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
     else if (nch <= 3) hipLaunchKernelGGL((gate_partial_kernel<true, 3, 2>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
     else if (nch <= 5) hipLaunchKernelGGL((gate_partial_kernel<true, 5, 2>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
     else hipLaunchKernelGGL((gate_partial_kernel<true, GATE_MAX_CHUNKS, 1>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <array>
+#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -40,12 +41,18 @@ struct WsLayout {
     int nparts, P;
 };
 
-WsLayout ws_layout(int B, int H, int N, int d, int dtype, bool full_proj = false, int topk = 0, bool rope = false)
+// tuning knobs (salad_tune): atomics, read once at the top of an entry point and passed down by value, so that a
+// concurrent salad_tune on another thread cannot change a call half way through
+std::atomic<int> g_state_target_wgs{512};
+std::atomic<int> g_topk_variant{0};
+std::atomic<int> g_attn_variant{0};
+
+WsLayout ws_layout(int B, int H, int N, int d, int dtype, int state_wgs, bool full_proj = false, int topk = 0, bool rope = false)
 {
     WsLayout w{};
     const size_t BH = (size_t)B * H;
     w.nparts = gate_num_parts(N);
-    w.P = dtype == SALAD_BF16 ? state_num_chunks((int)BH, N) : 0;
+    w.P = dtype == SALAD_BF16 ? state_num_chunks((int)BH, N, state_wgs) : 0;
     size_t off = 0;
     w.gate_partial = off; off = align256(off + sizeof(float) * (size_t)B * w.nparts);
     w.state_partial = off; off = align256(off + sizeof(float) * BH * (size_t)w.P * ((size_t)d * d + d));
@@ -98,7 +105,6 @@ bool shape_ok(int B, int H, int N, int d, int dtype)
 
 // ---- timing -----------------------------------------------------------------------------------
 std::mutex g_tmu;
-int g_topk_variant = 0;
 int g_timing = 0;   // 0 off, 1 every stage, 2 the attention stage only
 struct CallEvents { hipEvent_t e[8]; bool has_epilogue, has_linear, attn_only; };   // e[7]: end of the Top-K mask steps
 std::vector<CallEvents> g_calls;
@@ -208,7 +214,7 @@ salad_status salad_block_mask(int32_t T, int32_t Hh, int32_t W, int32_t block, i
 size_t salad_fwd_workspace_bytes(const salad_fwd_params *p)
 {
     if (!p || !shape_ok(p->B, p->H, p->N, p->d, p->dtype)) return 0;
-    return ws_layout(p->B, p->H, p->N, p->d, p->dtype, p->w_proj != nullptr, p->topk > 0 ? p->topk : 0, p->rope_cos != nullptr).total;
+    return ws_layout(p->B, p->H, p->N, p->d, p->dtype, g_state_target_wgs.load(), p->w_proj != nullptr, p->topk > 0 ? p->topk : 0, p->rope_cos != nullptr).total;
 }
 
 salad_status salad_linear_state_fwd(const void *k, const void *v, int32_t B, int32_t H, int32_t N, int32_t d,
@@ -223,11 +229,12 @@ salad_status salad_linear_state_fwd(const void *k, const void *v, int32_t B, int
         if (e != hipSuccess) return hip_fail(e, "state_f32 launch");
         return SALAD_OK;
     }
-    WsLayout w = ws_layout(B, H, N, d, dtype);
+    const int state_wgs = g_state_target_wgs.load();
+    WsLayout w = ws_layout(B, H, N, d, dtype, state_wgs);
     if (!workspace || ((uintptr_t)workspace & 255)) return fail(SALAD_EINVAL, "salad_linear_state_fwd: workspace null or not 256-byte aligned");
     if (workspace_bytes < w.total) return fail(SALAD_ENOSPC, "salad_linear_state_fwd: workspace %zu < %zu bytes", workspace_bytes, w.total);
     char *ws = (char *)workspace;
-    hipError_t e = launch_state_partial_bf16((const u16 *)k, (const u16 *)v, B * H, N, d, (float *)(ws + w.state_partial), nullptr, H, st);
+    hipError_t e = launch_state_partial_bf16((const u16 *)k, (const u16 *)v, B * H, N, d, (float *)(ws + w.state_partial), nullptr, H, state_wgs, st);
     if (e != hipSuccess) return hip_fail(e, "state_partial launch");
     FinalizeArgs f{};
     f.B = B; f.H = H; f.D = d;
@@ -340,7 +347,8 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
     // with the full projection the sparse kernel always stores O_s alone and the linear branch follows in its own kernels
     // Top-K regrouped by key block (the default Top-K path): the sparse branch is assembled by a merge kernel, so the
     // linear branch follows in its own kernel as well
-    const bool topk_regroup = p->topk > 0 && g_topk_variant == 0;
+    const int state_wgs = g_state_target_wgs.load(), attn_variant = g_attn_variant.load();
+    const bool topk_regroup = p->topk > 0 && g_topk_variant.load() == 0;
     // rotary linear branch (Sec. 4.1): the rotation lives in the state kernel and the separate apply kernel
     const bool rope = p->rope_cos != nullptr || p->rope_sin != nullptr;
     if (rope) {
@@ -357,7 +365,7 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
         if (p->dtype != SALAD_BF16 || p->d != 128) return fail(SALAD_ENOTSUP, "fwd: w_proj needs dtype bf16 and d = 128");
         if (p->head_scale) return fail(SALAD_EINVAL, "fwd: w_proj and head_scale exclude each other");
     }
-    const WsLayout w = ws_layout(p->B, p->H, p->N, p->d, p->dtype, p->w_proj != nullptr, topk ? p->topk : 0, p->rope_cos != nullptr);
+    const WsLayout w = ws_layout(p->B, p->H, p->N, p->d, p->dtype, state_wgs, p->w_proj != nullptr, topk ? p->topk : 0, p->rope_cos != nullptr);
     const bool need_lists = p->dtype == SALAD_BF16 && p->d == 128 && (size_t)tile_list_cap((p->N + 63) / 64) * 4 <= 24 * 1024;
     if (use_linear || need_lists) {
         if (!p->workspace || ((uintptr_t)p->workspace & 255)) return fail(SALAD_EINVAL, "fwd: workspace null or not 256-byte aligned");
@@ -378,6 +386,11 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
 
     CallEvents ev{};
     int timing;
+    auto give_back = [&]() {                       // an error path returns the events it took to the pool
+        std::lock_guard<std::mutex> lk(g_tmu);
+        for (auto &x : ev.e)
+            if (x) { g_free_events.push_back(x); x = nullptr; }
+    };
     {
         std::lock_guard<std::mutex> lk(g_tmu);
         timing = g_timing;
@@ -385,7 +398,11 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
             for (int i = 0; i < 8; ++i) {
                 if (timing == 2 && i != 7 && i != 4) continue;
                 ev.e[i] = get_event();
-                if (!ev.e[i]) return fail(SALAD_EHIP, "fwd: hipEventCreate failed");
+                if (!ev.e[i]) {
+                    for (auto &x : ev.e)
+                        if (x) { g_free_events.push_back(x); x = nullptr; }
+                    return fail(SALAD_EHIP, "fwd: hipEventCreate failed");
+                }
             }
     }
     ev.has_linear = use_linear;
@@ -401,7 +418,7 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
     if (use_linear) {
         if (need_gate) {
             e = launch_gate_partial(p->x_t, p->w_gate, p->b_gate, p->B, p->N, Dm, bf16, (float *)(ws + w.gate_partial), w.nparts, st);
-            if (e != hipSuccess) return hip_fail(e, "gate launch");
+            if (e != hipSuccess) return give_back(), hip_fail(e, "gate launch");
         }
         FinalizeArgs f{};
         f.B = p->B; f.H = p->H; f.D = p->d;
@@ -416,7 +433,7 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
             FinalizeArgs g = f;
             g.P = 0;                                   // gate part only: s, coefficients, drop flags
             e = launch_finalize(g, st);
-            if (e != hipSuccess) return hip_fail(e, "gate reduce launch");
+            if (e != hipSuccess) return give_back(), hip_fail(e, "gate reduce launch");
             f.do_gate = 0;
         }
         mark(1);
@@ -424,18 +441,18 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
         {
             if (rope) {     // the two fp32 tables -> one word per angle, read by the state and the apply kernels
                 e = launch_rope_pack(p->rope_cos, p->rope_sin, (size_t)p->N * (p->d / 2), (uint32_t *)(ws + w.rope_tab), st);
-                if (e != hipSuccess) return hip_fail(e, "rotary table launch");
+                if (e != hipSuccess) return give_back(), hip_fail(e, "rotary table launch");
             }
-            e = launch_state_partial_bf16((const u16 *)p->k, (const u16 *)p->v, BH, p->N, p->d, (float *)(ws + w.state_partial), drop, p->H, st,
+            e = launch_state_partial_bf16((const u16 *)p->k, (const u16 *)p->v, BH, p->N, p->d, (float *)(ws + w.state_partial), drop, p->H, state_wgs, st,
                                           rope ? (const uint32_t *)(ws + w.rope_tab) : nullptr);
         }
         else
             e = launch_state_f32((const float *)p->k, (const float *)p->v, BH, p->N, p->d, (float *)(ws + w.Hs), (float *)(ws + w.Z), drop, p->H, st);
-        if (e != hipSuccess) return hip_fail(e, "state launch");
+        if (e != hipSuccess) return give_back(), hip_fail(e, "state launch");
         mark(2);
         if (bf16 || f.do_gate) {                       // fp32: the state kernel wrote Hs, Z directly
             e = launch_finalize(f, st);
-            if (e != hipSuccess) return hip_fail(e, "finalize launch");
+            if (e != hipSuccess) return give_back(), hip_fail(e, "finalize launch");
         }
     } else {
         mark(1);
@@ -458,17 +475,18 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
     a.o_sparse_dbg = p->o_sparse_dbg; a.o_linear_dbg = unfused ? nullptr : p->o_linear_dbg;
     a.write_sparse_only = unfused;
     a.drop = drop;
+    a.variant = attn_variant;
     if (topk) {
         // App. A.1.2: key-block means -> per-query selection -> per-tile visit lists; the mask never leaves the device
         float *means = (float *)(ws + w.kmeans);
         unsigned long long *mask = (unsigned long long *)(ws + w.topk_mask);
         e = launch_kblock_mean((const u16 *)p->k, BH, p->N, p->topk_key_block, nbk, means, st);
-        if (e != hipSuccess) return hip_fail(e, "key-block mean launch");
+        if (e != hipSuccess) return give_back(), hip_fail(e, "key-block mean launch");
         e = launch_topk_select((const u16 *)p->q, means, BH, p->N, nbk, p->topk, mask, st);
-        if (e != hipSuccess) return hip_fail(e, "top-k selection launch");
+        if (e != hipSuccess) return give_back(), hip_fail(e, "top-k selection launch");
         if (p->topk_mask_out) {
             e = hipMemcpyAsync(p->topk_mask_out, mask, sizeof(uint64_t) * (size_t)BH * p->N, hipMemcpyDeviceToDevice, st);
-            if (e != hipSuccess) return hip_fail(e, "top-k mask copy");
+            if (e != hipSuccess) return give_back(), hip_fail(e, "top-k mask copy");
         }
         a.tile_lists = (const uint32_t *)(ws + w.tile_lists);
         a.tile_counts = (const int32_t *)(ws + w.tile_counts);
@@ -478,13 +496,13 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
             const int kk = p->topk < nbk ? p->topk : nbk;
             e = launch_topk_group(mask, BH, p->N, nbk, kk, (int32_t *)(ws + w.g_ccnt), (int32_t *)(ws + w.g_seg),
                                   (uint4 *)(ws + w.g_desc), (int32_t *)(ws + w.g_idx), (int32_t *)(ws + w.g_slot), st);
-            if (e != hipSuccess) return hip_fail(e, "top-k regrouping launch");
+            if (e != hipSuccess) return give_back(), hip_fail(e, "top-k regrouping launch");
             a.g_desc = (const uint4 *)(ws + w.g_desc);
             a.g_idx = (const int32_t *)(ws + w.g_idx); a.g_po = (u16 *)(ws + w.g_po); a.g_lse = (float *)(ws + w.g_lse);
             a.g_kk = kk; a.g_bpb = p->topk_key_block / 64; a.g_max_tiles = topk_max_tiles(BH, p->N, kk, nbk);
         } else {
             e = launch_topk_tile_lists(mask, BH, p->N, a.nb, p->topk_key_block, nbk, (uint32_t *)(ws + w.tile_lists), (int32_t *)(ws + w.tile_counts), st);
-            if (e != hipSuccess) return hip_fail(e, "top-k tile list launch");
+            if (e != hipSuccess) return give_back(), hip_fail(e, "top-k tile list launch");
         }
         mark(7);
     } else if (need_lists) {
@@ -493,16 +511,16 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
         a.tile_counts = (const int32_t *)(ws + w.tile_counts);
         a.list_cap = tile_list_cap(a.nb);
         e = launch_tile_lists(p->row_ptr, p->col_idx, p->H, a.nb, (uint32_t *)(ws + w.tile_lists), (int32_t *)(ws + w.tile_counts), st);
-        if (e != hipSuccess) return hip_fail(e, "tile list launch");
+        if (e != hipSuccess) return give_back(), hip_fail(e, "tile list launch");
     }
     if (!topk && !need_lists) mark(7);
     a.t_magic = ((uint64_t)p->N * (uint64_t)p->T < (1ull << 32) && p->T > 1) ? (unsigned)((1ull << 32) / (uint64_t)p->T + 1) : 0u;
     e = bf16 ? launch_sparse_attn_bf16(a, st) : launch_sparse_attn_f32(a, st);
-    if (e != hipSuccess) return hip_fail(e, "sparse attention launch");
+    if (e != hipSuccess) return give_back(), hip_fail(e, "sparse attention launch");
     if (a.g_desc) {
         e = launch_topk_merge(a.g_po, a.g_lse, (const int32_t *)(ws + w.g_slot), a.topk_mask, BH, p->N, a.g_kk,
                               (u16 *)p->out, p->o_sparse_dbg, st);
-        if (e != hipSuccess) return hip_fail(e, "top-k merge launch");
+        if (e != hipSuccess) return give_back(), hip_fail(e, "top-k merge launch");
     }
     mark(4);
     if (unfused && use_linear) {
@@ -514,17 +532,17 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
         ap.emit = full_proj ? (u16 *)(ws + w.ol) : nullptr;
         ap.rope_tab = rope ? (const uint32_t *)(ws + w.rope_tab) : nullptr;
         e = launch_linear_apply_bf16(ap, st);
-        if (e != hipSuccess) return hip_fail(e, "linear apply launch");
+        if (e != hipSuccess) return give_back(), hip_fail(e, "linear apply launch");
         mark(5);
         if (full_proj) {
             // Alg. 1 "Proj" as one GEMM over the concatenated heads, fused with the residual sum
             e = launch_proj_pack((const u16 *)p->w_proj, p->H, (u16 *)(ws + w.wfrag), st);
-            if (e != hipSuccess) return hip_fail(e, "projection pack launch");
+            if (e != hipSuccess) return give_back(), hip_fail(e, "projection pack launch");
             ProjArgs pa{};
             pa.ol = (const u16 *)(ws + w.ol); pa.out = (u16 *)p->out; pa.wfrag = (const u16 *)(ws + w.wfrag);
             pa.coef = (const float *)(ws + w.coef); pa.drop = drop; pa.B = p->B; pa.H = p->H; pa.N = p->N;
             e = launch_proj_apply(pa, st);
-            if (e != hipSuccess) return hip_fail(e, "projection launch");
+            if (e != hipSuccess) return give_back(), hip_fail(e, "projection launch");
         }
     } else {
         mark(5);
@@ -590,34 +608,24 @@ salad_status salad_timing_read(salad_kernel_times *out, int32_t reset)
     return SALAD_OK;
 }
 
-#ifdef SALAD_DIAG
-/* Development builds only, not declared in the public header: timestamps of one workgroup's phases. */
-void salad_debug_set_trace(void *ptr, int block)
-{
-    g_trace_ptr = (long long *)ptr;
-    g_trace_block = block;
-}
-#endif
-
-/* Tuning knobs for experiments; not part of the documented layer semantics.
- * "state_wgs": target number of workgroups of the linear-state kernel (changes the workspace size). */
+/* Launch-shape knobs for experiments.  Every accepted key is declared in include/salad.h and range-checked here; the
+ * values are atomics that an entry point reads once per call. */
 salad_status salad_tune(const char *key, int32_t value)
 {
     if (!key) return fail(SALAD_EINVAL, "salad_tune: null key");
     if (!std::strcmp(key, "state_wgs")) {
-        if (value < 1 || value > 65536) return fail(SALAD_EINVAL, "salad_tune: state_wgs out of range");
-        g_state_target_wgs = value;
+        if (value < 1 || value > 65536) return fail(SALAD_EINVAL, "salad_tune: state_wgs %d outside 1..65536", (int)value);
+        g_state_target_wgs.store(value);
         return SALAD_OK;
     }
-    if (!std::strcmp(key, "gate_parts")) { if (value < 1 || value > 2048) return fail(SALAD_EINVAL, "salad_tune: gate_parts out of range"); g_gate_parts = value; return SALAD_OK; }
-    if (!std::strcmp(key, "gate_tok")) { g_gate_tok = value; return SALAD_OK; }
-    if (!std::strcmp(key, "attn_variant")) {
-        g_attn_variant = value;
+    if (!std::strcmp(key, "attn_variant")) {   // 0: automatic, 1: 128-query tiles, 2: first-generation kernel
+        if (value < 0 || value > 2) return fail(SALAD_EINVAL, "salad_tune: attn_variant %d outside 0..2", (int)value);
+        g_attn_variant.store(value);
         return SALAD_OK;
     }
     if (!std::strcmp(key, "topk_variant")) {   // 0: regrouped by key block (default), 1: token mask on query tiles
-        if (value < 0 || value > 1) return fail(SALAD_EINVAL, "salad_tune: topk_variant out of range");
-        g_topk_variant = value;
+        if (value < 0 || value > 1) return fail(SALAD_EINVAL, "salad_tune: topk_variant %d outside 0..1", (int)value);
+        g_topk_variant.store(value);
         return SALAD_OK;
     }
     return fail(SALAD_EINVAL, "salad_tune: unknown key %s", key);

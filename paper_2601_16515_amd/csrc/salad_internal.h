@@ -25,12 +25,13 @@ int gate_num_parts(int N);
 
 // ---- linear state (Eq. (3) sums) ----------------------------------------------------------------
 // bf16: partial states over token chunks, MFMA.  partial[(bh*P + c)][D*D + D] fp32.
-int state_tiles_per_chunk(int BH, int N);
-int state_num_chunks(int BH, int N);
+// target_wgs: workgroups the launch aims for (the caller reads the tuning knob once per call)
+int state_tiles_per_chunk(int BH, int N, int target_wgs);
+int state_num_chunks(int BH, int N, int target_wgs);
 // drop (may be null): int32 [B], workgroups of a sample with drop[b] != 0 return at once (H heads per sample)
 // rope_tab (d = 128 only): [N, d/2] words (fp16 cos | fp16 sin << 16) of the rotary linear branch, or null
 hipError_t launch_state_partial_bf16(const u16 *k, const u16 *v, int BH, int N, int D,
-                                     float *partial, const int32_t *drop, int H, hipStream_t st,
+                                     float *partial, const int32_t *drop, int H, int target_wgs, hipStream_t st,
                                      const uint32_t *rope_tab = nullptr);
 hipError_t launch_rope_pack(const float *rope_cos, const float *rope_sin, size_t n, uint32_t *tab, hipStream_t st);
 // fp32: direct evaluation, one thread per state element (small shapes).
@@ -94,6 +95,7 @@ struct AttnArgs {
     const int32_t *g_idx;
     u16 *g_po; float *g_lse;
     int g_kk, g_bpb, g_max_tiles;
+    int variant;                    // 0: automatic choice of the d = 128 kernel; 1: 128-query tiles; 2: first-generation kernel
 };
 hipError_t launch_sparse_attn_bf16(const AttnArgs &a, hipStream_t st);
 // union lists of the CSR rows of every 4-query-block tile (input of the large-tile attention kernel)
@@ -103,7 +105,6 @@ hipError_t launch_tile_lists(const int32_t *row_ptr, const int32_t *col_idx, int
 hipError_t launch_sparse_attn_f32(const AttnArgs &a, hipStream_t st);
 hipError_t launch_sparse_attn_v2(const AttnArgs &a, hipStream_t st);   // d = 128 only
 hipError_t launch_sparse_attn_v5(const AttnArgs &a, hipStream_t st);   // d = 128 only
-hipError_t launch_sparse_attn_v7(const AttnArgs &a, hipStream_t st);   // d = 128 only, 64 queries per wave
 
 // ---- Top-K dynamic mask (App. A.1.2), d = 128 bf16 ---------------------------------------------------------
 // means [BH][nbk][128] fp32: mean key of each run of key_block stored tokens (sequential fp32 sum / count)
@@ -161,11 +162,5 @@ inline hipError_t dyn_lds_attr_once(const void *kernel, int bytes, bool (&done)[
     return e;
 }
 
-// tuning knobs (salad_tune)
-extern int g_state_target_wgs;
-extern int g_gate_parts, g_gate_tok;
-extern int g_attn_variant;
-extern long long *g_trace_ptr;   // development: per-phase timestamps of one workgroup
-extern int g_trace_block;
 
 }  // namespace salad

@@ -32,10 +32,6 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef short s16x2 __attribute__((ext_vector_type(2)));
 
-int g_attn_variant = 0;
-long long *g_trace_ptr = nullptr;
-int g_trace_block = 0;
-
 constexpr int XT_PITCH = 72;
 __device__ inline int vt_off(int row, int tok)
 {
@@ -320,8 +316,8 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_kernel(AttnArgs a, in
 hipError_t launch_sparse_attn_bf16(const AttnArgs &a, hipStream_t st)
 {
     // d = 128: the large-tile ping-pong kernel unless its block list does not fit in LDS or a variant is
-    // forced (attn_variant & 15: 0 = automatic, 1 = double-buffered 128-row kernel, 2 = first-generation kernel)
-    const int variant = g_attn_variant & 15;
+    // forced (a.variant: 0 = automatic, 1 = double-buffered 128-row kernel, 2 = first-generation kernel)
+    const int variant = a.variant;
     if (a.topk_mask) {   // token-level mask: the large-tile kernel only (the host checks that the shape fits it)
         if (a.D != 128 || !a.tile_lists) return hipErrorInvalidValue;
         return launch_sparse_attn_v5(a, st);
@@ -332,8 +328,7 @@ hipError_t launch_sparse_attn_bf16(const AttnArgs &a, hipStream_t st)
         const bool temporal = a.kind_mask != 0 && a.T > 1;
         const bool fits = (size_t)tile_list_cap(a.nb) * 4 <= 24 * 1024 && (unsigned long long)a.N * 256ull < (1ull << 32) &&
                           (!temporal || a.t_magic != 0);
-        if (variant == 7 && fits && a.tile_lists) return launch_sparse_attn_v7(a, st);
-        if ((variant == 0 || variant == 5) && fits && a.tile_lists) return launch_sparse_attn_v5(a, st);
+        if (variant == 0 && fits && a.tile_lists) return launch_sparse_attn_v5(a, st);
         return launch_sparse_attn_v2(a, st);
     }
     const int ntiles = (a.nb + 1) / 2;

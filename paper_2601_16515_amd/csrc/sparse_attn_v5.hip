@@ -184,11 +184,6 @@ hipError_t launch_tile_lists(const int32_t *row_ptr, const int32_t *col_idx, int
 
 // PD: prefetch distance in KV blocks.  K(b) is read in iteration b only, V(b) also in iteration b+1: the K ring
 // has PD + 1 slots, the V ring PD + 2.
-// SKIP (development builds only, -DSALAD_DIAG): bit 0 drops the softmax stage, 1 the S product, 2 the PV
-// product, 3 the K/V loads; 4 adds a barrier between the two phases of an iteration, 5 records timestamps, 6 raises the
-// priority of the vector phase, 7 of the matrix phase, 8 recomputes the row maximum for every block, 9 drops
-// the per-block barrier (timing only: results are wrong), 10 always fetches block 0, 11 keeps the prefetch's
-// address arithmetic but not its loads.
 // MODE 0: block rows (CSR) through the per-tile union lists.
 // MODE 1: token-level Top-K mask (App. A.1.2).  The tile lists are per (sample, head, tile); an entry is
 //   block | key-block index << 16 | wave mask << 24 (bit 24 + w: some query of wave w keeps the block); each lane
@@ -196,11 +191,9 @@ hipError_t launch_tile_lists(const int32_t *row_ptr, const int32_t *col_idx, int
 // MODE 2: Top-K regrouped by key block.  A query tile is a run of up to 256 gathered queries that all keep the same
 //   key block; the list is that key block's 64-token blocks; the normalised partial result and its log-sum-exp go
 //   to a.g_po / a.g_lse (one slot per kept (query, key block) pair) for the merge kernel.
-template <int PD, bool DBG, int SKIP, int MODE = 0>
-__global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int ntiles, int total, int per_xcd, int list_cap, long long *trace, int trace_block)
+template <int PD, bool DBG, int MODE = 0>
+__global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int ntiles, int total, int per_xcd, int list_cap)
 {
-    constexpr int skip = SKIP;
-    constexpr bool DIAG = (SKIP & 32) != 0;
     constexpr int D = 128, NS = 8, NDT = 4;
     constexpr int TILE = 64 * D;                 // elements
     constexpr int NK = PD + 1, NV = PD + 2;
@@ -230,13 +223,6 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hh = lane >> 5;
     const int group = wave >> 2;
-    long long stamp[4] = {0, 0, 0, 0};
-    const long long real0 = DIAG ? (long long)__builtin_amdgcn_s_memrealtime() : 0;   // 100 MHz
-#define STAMP(i) do { if (DIAG) stamp[i] = clock64(); } while (0)
-    uint32_t tv[4] = {0u, 0u, 0u, 0u};   // per-iteration timestamps, one lane per iteration (development builds)
-#define TSTAMP(k) do { if (DIAG) { const uint32_t t_ = (uint32_t)__builtin_amdgcn_s_memtime(); \
-        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tv_writelane_b32 %0, %1, m0" : "+v"(tv[k]) : "s"(t_), "s"(j & 63) : "m0"); } } while (0)
-    STAMP(0);
     const u16 *qb = reinterpret_cast<const u16 *>(a.q) + (size_t)bh * N * D;
     const u16 *kb = reinterpret_cast<const u16 *>(a.k) + (size_t)bh * N * D;
     const u16 *vb = reinterpret_cast<const u16 *>(a.v) + (size_t)bh * N * D;
@@ -299,7 +285,6 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
     const unsigned k_lds0 = lds_addr_of(Kb) + wave_u * 1024u;
     const unsigned v_lds0 = lds_addr_of(Vb) + wave_u * 1024u;
     auto fetch = [&](int blk, int kslot, int vslot) INL {
-        if (skip & 1024) blk = 0;      // development: always the same (cached) block
         const unsigned kl = k_lds0 + (unsigned)kslot * (unsigned)(TILE * 2);
         const unsigned vl = v_lds0 + (unsigned)vslot * (unsigned)(TILE * 2);
 #pragma unroll
@@ -307,12 +292,8 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
             int p = blk * 64 + i * 32 + lr;
             p = p < N ? p : N - 1;
             const unsigned row_b = (unsigned)row_of_position5(kind, p, T, HW, magic) * (unsigned)(D * 2);
-            if (skip & 2048) {       // development: the address arithmetic without the loads
-                asm volatile("" : : "v"(row_b + kchunk_b), "s"(kl + i * 8192u), "v"(row_b + vchunk_b), "s"(vl + i * 8192u));
-            } else {
-                lds_dma16_base(kb, row_b + kchunk_b, kl + i * 8192u);
-                lds_dma16_base(vb, row_b + vchunk_b, vl + i * 8192u);
-            }
+            lds_dma16_base(kb, row_b + kchunk_b, kl + i * 8192u);
+            lds_dma16_base(vb, row_b + vchunk_b, vl + i * 8192u);
         }
     };
     // list entries travel in a vector register (lane l holds entry 64 c + l of the current 64-entry
@@ -387,8 +368,6 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
         for (int i = first; i < last; ++i) {
             mfma_step(i, ring[i % RING]);
             if (i + RING < last) read_frag(i + RING, Vt, Kt, ring[i % RING]);
-            if (skip & 4096) asm volatile("s_nop 7\n\ts_nop 7");
-            if (skip & 8192) asm volatile("s_nop 7");
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -410,13 +389,6 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
         }
         const float cs = (TOPK && !sel) ? 0.f : c2;
         const float ms = (TOPK && !sel) ? INFINITY : m_run;
-        if (skip & 1) {   // development: keep S alive and P defined without doing the work
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int k = 0; k < 4; ++k) asm volatile("" : "+v"(pf[i].w[k]) : "v"(s[0]), "v"(s[1]));
-            return;
-        }
         if (blk * 64 + 64 > N) {
             const int kbase = blk * 64 + hh * 8;
 #pragma unroll
@@ -447,7 +419,7 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
         // sums say that some logit rose more than 13 binades above the reference (or no reference exists
         // yet): then the reference moves to the true maximum and the block is redone.
         float psum = 0.f;
-        bool redo = (sel && !have_ref) || (skip & 256);
+        bool redo = sel && !have_ref;
         if (!redo) {
             psum = exp_pack();
             redo = __any(!(psum <= 8192.f)) && sel;
@@ -487,12 +459,11 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
     // Block b lives in slot b % NK of the K ring and b % NV of the V ring.
     // The fetch of block j+PD is issued from each group's vector phase, where its address arithmetic
     // runs under the other group's MFMAs; the slots it goes to were last read in iteration j-1.
-    STAMP(1);
     int v_last = 0;                         // V-ring slot of the last block: the only tile still read after the loop
     if (n > 0) {
 #pragma unroll
         for (int b = 0; b < PD; ++b)
-            if (b < n && !(skip & 8)) fetch((int)(entry(b) & BLKMASK), b, b);
+            if (b < n) fetch((int)(entry(b) & BLKMASK), b, b);
         uint32_t e_prev = 0u;
         uint32_t eq[PD];                          // eq[i] = entry j + i
 #pragma unroll
@@ -503,61 +474,42 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
             {
                 int newer = n - 1 - j;
                 if (newer > PD - 1) newer = PD - 1;
-                if (skip & 8) newer = 0;
                 if (newer >= 3) WAIT_VM(12);
                 else if (newer == 2) WAIT_VM(8);
                 else if (newer == 1) WAIT_VM(4);
                 else WAIT_VM(0);
             }
-            if (!(skip & 512)) __builtin_amdgcn_s_barrier();   // (timing experiment only: results are wrong without it)
+            __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
-            TSTAMP(0);
             const int jf = j + PD;
             uint32_t e_f = 0u;
             if (jf < n) {
                 if ((jf & 63) == 0) ev = blist[jf + lane];
                 e_f = entry(jf);
             }
-            const bool do_fetch = jf < n && !(skip & 8);
+            const bool do_fetch = jf < n;
             int kslot_f = kslot + PD; if (kslot_f >= NK) kslot_f -= NK;
             int vslot_f = vslot + PD; if (vslot_f >= NV) vslot_f -= NV;
             int vslot_prev = vslot - 1; if (vslot_prev < 0) vslot_prev += NV;
             const uint32_t e_cur = eq[0];
             const bool kS = (e_cur & mybit) != 0, kP = (j >= 1) && (e_prev & mybit);
-            const bool dS = kS && !(skip & 2), dP = kP && !(skip & 4), dM0 = kS, dM1 = kP;
             const u16 *Kt = Kb + kslot * TILE;
             const u16 *Vt = Vb + vslot_prev * TILE;
             const u16 *Vc = Vb + vslot * TILE;         // V tile of block j (already landed with K(j))
             if (group == 0) {
-                if (skip & 128) __builtin_amdgcn_s_setprio(2);
-                if (dP && dS) stage_PV_S(Vt, Kt);
-                else { if (dP) stage_PV(Vt); if (dS) stage_S(Kt); }
-                if (skip & 128) __builtin_amdgcn_s_setprio(0);
-                TSTAMP(1);
-                if (skip & 16) __builtin_amdgcn_s_barrier();
+                if (kP && kS) stage_PV_S(Vt, Kt);
+                else { if (kP) stage_PV(Vt); if (kS) stage_S(Kt); }
                 asm volatile("" ::: "memory");
-                TSTAMP(2);
-                if (skip & 64) __builtin_amdgcn_s_setprio(3);
-                if (dS) preload_V(Vc);                  // for PV(j) in the next iteration; lands under the softmax
-                if (dM0) stage_softmax(e_cur);
-                TSTAMP(3);
+                if (kS) preload_V(Vc);                  // for PV(j) in the next iteration; lands under the softmax
+                if (kS) stage_softmax(e_cur);
                 if (do_fetch) fetch((int)(e_f & BLKMASK), kslot_f, vslot_f);
-                if (skip & 64) __builtin_amdgcn_s_setprio(0);
             } else {
-                if (skip & 64) __builtin_amdgcn_s_setprio(3);
-                if (dP) preload_V(Vt);                  // for PV(j-1) right after the barrier; lands under the softmax
-                if (dM1) stage_softmax(e_prev);
-                TSTAMP(1);
+                if (kP) preload_V(Vt);                  // for PV(j-1) right after the barrier; lands under the softmax
+                if (kP) stage_softmax(e_prev);
                 if (do_fetch) fetch((int)(e_f & BLKMASK), kslot_f, vslot_f);
-                if (skip & 64) __builtin_amdgcn_s_setprio(0);
-                if (skip & 16) __builtin_amdgcn_s_barrier();
                 asm volatile("" ::: "memory");
-                TSTAMP(2);
-                if (skip & 128) __builtin_amdgcn_s_setprio(2);
-                if (dP && dS) stage_PV_S(Vt, Kt);
-                else { if (dP) stage_PV(Vt); if (dS) stage_S(Kt); }
-                if (skip & 128) __builtin_amdgcn_s_setprio(0);
-                TSTAMP(3);
+                if (kP && kS) stage_PV_S(Vt, Kt);
+                else { if (kP) stage_PV(Vt); if (kS) stage_S(Kt); }
             }
             e_prev = e_cur;
 #pragma unroll
@@ -578,11 +530,10 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
             const u16 *Vt = Vb + vslot_prev * TILE;
             const bool kP = (e_prev & mybit) != 0;
             if (group == 1 && kP) { preload_V(Vt); stage_softmax(e_prev); }
-            if (kP && !(skip & 4)) stage_PV(Vt);
+            if (kP) stage_PV(Vt);
         }
     }
 
-    STAMP(2);
     // ---- epilogue ---------------------------------------------------------------------------------
     float l_tot = l_run + __shfl_xor(l_run, 32);
     const float inv_l = l_tot > 0.f ? 1.f / l_tot : 0.f;
@@ -621,7 +572,7 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
             }
         }
     }
-    if (!DBG && !(skip & 16384)) {
+    if (!DBG) {
         // bf16 results leave through LDS so that every global store is a run of full 256-byte rows: accumulator
         // layout (lane = query l32; 4 consecutive columns per (dt, g4, hh)) -> a wave-private 8 KB of the V ring
         // (the four slots that do not hold the last block: nobody reads them any more), 16-byte chunk c of row r at
@@ -685,22 +636,9 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
         }
     }
     }
-    if (DIAG && trace != nullptr && (int)blockIdx.x == trace_block) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) trace[64 + (wave * 4 + i) * 64 + lane] = tv[i];
-    }
-    if (DIAG && trace != nullptr && (int)blockIdx.x == trace_block && lane == 0) {
-        STAMP(3);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) trace[wave * 4 + i] = stamp[i];
-        trace[40 + wave] = (long long)__builtin_amdgcn_s_memrealtime() - real0;
-        trace[32 + wave] = __builtin_amdgcn_s_getreg((16 - 1) << 11 | 0 << 6 | 4);   // HW_ID[15:0]: wave, SIMD, pipe, CU, SH, SE
-    }
-#undef STAMP
-#undef TSTAMP
 }
 
-template <int PD, bool DBG, int SKIP, int MODE = 0>
+template <int PD, bool DBG, int MODE = 0>
 static hipError_t launch_v5(const AttnArgs &a, hipStream_t st)
 {
     const int ntiles = (a.nb + 3) / 4;
@@ -711,29 +649,19 @@ static hipError_t launch_v5(const AttnArgs &a, hipStream_t st)
     static_assert(PD + 1 >= 4, "the epilogue stages 64 KB of state fragments in the K ring");
     constexpr int kMaxDyn = 160 * 1024 - 2048;   // the static part is rounded up to its 1 KB alignment
     if (lds > (size_t)kMaxDyn) return hipErrorInvalidValue;
-    auto kern = sparse_attn_v5_kernel<PD, DBG, SKIP, MODE>;
+    auto kern = sparse_attn_v5_kernel<PD, DBG, MODE>;
     static bool attr_done[16] = {};
     if (hipError_t e = dyn_lds_attr_once(reinterpret_cast<const void *>(kern), kMaxDyn, attr_done); e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(512), lds, st, a, ntiles, total, per_xcd, list_cap, g_trace_ptr, g_trace_block);
+    hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(512), lds, st, a, ntiles, total, per_xcd, list_cap);
     return hipGetLastError();
 }
 
 hipError_t launch_sparse_attn_v5(const AttnArgs &a, hipStream_t st)
 {
     const bool dbg = a.o_sparse_dbg || a.o_linear_dbg;
-    if (a.g_desc) return launch_v5<3, false, 0, 2>(a, st);
-    if (a.topk_mask) return dbg ? launch_v5<3, true, 0, 1>(a, st) : launch_v5<3, false, 0, 1>(a, st);
-#ifdef SALAD_DIAG
-    switch (g_attn_variant >> 4) {
-    case 0: break;
-#define SALAD_DIAG_CASE(k) case k: return launch_v5<3, false, k>(a, st);
-    SALAD_DIAG_CASE(1) SALAD_DIAG_CASE(6) SALAD_DIAG_CASE(7) SALAD_DIAG_CASE(8) SALAD_DIAG_CASE(9) SALAD_DIAG_CASE(14)
-    SALAD_DIAG_CASE(15) SALAD_DIAG_CASE(16) SALAD_DIAG_CASE(32) SALAD_DIAG_CASE(33) SALAD_DIAG_CASE(47) SALAD_DIAG_CASE(64) SALAD_DIAG_CASE(96) SALAD_DIAG_CASE(192) SALAD_DIAG_CASE(224) SALAD_DIAG_CASE(256) SALAD_DIAG_CASE(80) SALAD_DIAG_CASE(512) SALAD_DIAG_CASE(520) SALAD_DIAG_CASE(513) SALAD_DIAG_CASE(1024) SALAD_DIAG_CASE(2048) SALAD_DIAG_CASE(16384) SALAD_DIAG_CASE(4096) SALAD_DIAG_CASE(8192) SALAD_DIAG_CASE(12288) SALAD_DIAG_CASE(4160) SALAD_DIAG_CASE(12352)
-#undef SALAD_DIAG_CASE
-    default: return hipErrorInvalidValue;
-    }
-#endif
-    return dbg ? launch_v5<3, true, 0>(a, st) : launch_v5<3, false, 0>(a, st);
+    if (a.g_desc) return launch_v5<3, false, 2>(a, st);
+    if (a.topk_mask) return dbg ? launch_v5<3, true, 1>(a, st) : launch_v5<3, false, 1>(a, st);
+    return dbg ? launch_v5<3, true>(a, st) : launch_v5<3, false>(a, st);
 }
 
 }  // namespace salad

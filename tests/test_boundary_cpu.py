@@ -111,6 +111,10 @@ def _params(**over):
     (dict(topk=4, topk_key_block=0, d=128), sb.SALAD_EINVAL, "multiple of 64"),
     (dict(topk=4, topk_key_block=64, d=128, N=8192, T=32), sb.SALAD_ENOTSUP, "key blocks"),   # 128 key blocks
     (dict(topk=4, topk_key_block=128, d=128, workspace_bytes=1 << 16), sb.SALAD_ENOSPC, "workspace"),
+    (dict(rope_cos=0xa000, d=128), sb.SALAD_EINVAL, "together"),                          # cosine table without the sine table
+    (dict(rope_sin=0xa000, d=128), sb.SALAD_EINVAL, "together"),
+    (dict(rope_cos=0xa000, rope_sin=0xb000), sb.SALAD_ENOTSUP, "rotary"),                # d = 64
+    (dict(rope_cos=0xa000, rope_sin=0xb000, d=128, dtype=sb.SALAD_F32), sb.SALAD_ENOTSUP, "rotary"),
 ])
 def test_fwd_argument_errors(lib, over, status, needle):
     p = _params(**over)
@@ -158,6 +162,34 @@ def test_step_entry_points_reject_bad_arguments(lib):
     assert lib.salad_timing_enable(3) == sb.SALAD_EINVAL and lib.salad_timing_enable(-1) == sb.SALAD_EINVAL
     assert lib.salad_timing_enable(0) == sb.SALAD_OK
     assert lib.salad_tune(b"no_such_knob", 1) == sb.SALAD_EINVAL
+    assert lib.salad_tune(None, 1) == sb.SALAD_EINVAL
+
+
+def test_tune_keys_are_the_declared_ones_and_range_checked(lib):
+    """Every key the header documents is accepted inside its range and refused outside; keys of earlier builds that the
+    header does not declare are refused."""
+    text = open(os.path.join(ROOT, "include", "salad.h")).read()
+    declared = set(re.findall(r'^ \*\s+"([a-z_]+)"', text, flags=re.M))
+    assert declared == {"state_wgs", "attn_variant", "topk_variant"}
+    for key, ok, bad in ((b"state_wgs", (1, 512, 65536), (0, -3, 65537)), (b"attn_variant", (0, 1, 2), (-1, 3, 7, 5 + 16)),
+                         (b"topk_variant", (0, 1), (-1, 2))):
+        for v in bad:
+            assert lib.salad_tune(key, v) == sb.SALAD_EINVAL, (key, v)
+            assert "outside" in _err(lib)
+        for v in ok:
+            assert lib.salad_tune(key, v) == sb.SALAD_OK, (key, v)
+    assert lib.salad_tune(b"state_wgs", 512) == sb.SALAD_OK and lib.salad_tune(b"attn_variant", 0) == sb.SALAD_OK
+    assert lib.salad_tune(b"topk_variant", 0) == sb.SALAD_OK
+    for key in (b"gate_parts", b"gate_tok"):
+        assert lib.salad_tune(key, 1) == sb.SALAD_EINVAL
+
+
+def test_static_scratch_gate_argument_errors(lib):
+    fake = 0x1000
+    assert lib.salad_gate_fwd_static(None, fake, 0.0, 1, 64, 128, sb.SALAD_BF16, fake, None) == sb.SALAD_EINVAL
+    assert lib.salad_gate_fwd_static(fake, fake, 0.0, 1, 64, 12, sb.SALAD_BF16, fake, None) == sb.SALAD_EINVAL
+    assert lib.salad_gate_fwd_static(fake, fake, 0.0, 64, 32760, 128, sb.SALAD_BF16, fake, None) == sb.SALAD_ENOSPC
+    assert "static" in _err(lib)
 
 
 def test_binding_refuses_to_run_without_library(monkeypatch, tmp_path):
