@@ -15,15 +15,19 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "salad_oracle.c")
-_LIB = os.path.join(_HERE, "libsalad_oracle.so")
+# SALAD_ORACLE_SANITIZE=1 selects a second build of the same source with the host AddressSanitizer and
+# UndefinedBehaviorSanitizer (CPU only; the process must have libasan preloaded, see tests/test_oracle_sanitized.py)
+_SANITIZE = os.environ.get("SALAD_ORACLE_SANITIZE", "") == "1"
+_LIB = os.path.join(_HERE, "libsalad_oracle_asan.so" if _SANITIZE else "libsalad_oracle.so")
 _lib: Optional[C.CDLL] = None
 
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (plain C + OpenMP).  Returns the library path."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-O2", "-march=native", "-fopenmp", "-fPIC", "-shared", "-Wall",
-               "-o", _LIB, _SRC, "-lm"]
+        opt = ["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined"] \
+            if _SANITIZE else ["-O2", "-march=native"]
+        cmd = ["gcc"] + opt + ["-fopenmp", "-fPIC", "-shared", "-Wall", "-o", _LIB, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
