@@ -87,16 +87,21 @@ def run_layer(w, inp, dev, kept, kinds, *, lam=None, dbg=True, flags=0, s=None, 
 def compare_layer(res, ref, *, check_linear=True, tol_abs=MAX_ABS, tol_rel=REL_L2, label=""):
     """Compare a run_layer result with an oracle salad_forward result on the oracle's row set."""
     rows = ref["rows"]
-    report = {}
+    report, peak = {}, {}
     for name in ("out", "o_sparse", "o_linear"):
         if name not in res or (name == "o_linear" and not check_linear):
             continue
         got, ok = gather_rows(res[name], rows)
         assert np.isfinite(got[ok]).all(), f"{label}{name}: non-finite values on valid rows"
         report[name] = errors(got[ok], ref[name][ok])
+        peak[name] = float(np.abs(ref[name][ok]).max()) if ok.any() else 0.0
     say(f"  {label} " + " ".join(f"{k}: max_abs={a:.3e} rel_l2={r:.3e}" for k, (a, r) in report.items()))
     for name, (a, r) in report.items():
         assert r <= tol_rel, f"{label}{name}: rel_l2 {r:.3e} > {tol_rel}"
         if name == "out":
             assert a <= tol_abs, f"{label}{name}: max_abs {a:.3e} > {tol_abs}"
+        else:
+            # per-branch outputs: the same max-abs bar, taken relative to the branch's own largest magnitude (the
+            # unscaled linear branch is much smaller than 1, so an absolute bar would say nothing about it)
+            assert a <= tol_abs * max(peak[name], 1e-30), f"{label}{name}: max_abs {a:.3e} > {tol_abs} x peak {peak[name]:.3e}"
     return report
