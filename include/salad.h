@@ -75,6 +75,19 @@ salad_status salad_block_mask(int32_t T, int32_t Hh, int32_t W, int32_t block, i
                               int32_t *row_ptr_dev, int32_t *col_idx_dev, int64_t col_capacity,
                               void *hip_stream);
 
+/* Visit lists of the large-tile attention kernel (bf16, d = 128) for a CSR: for every head and every tile of 4
+ * consecutive query blocks the union of the 4 rows' kept KV blocks, each entry tagged with the rows that keep it.  Like
+ * the mask they depend on no activation (App. A.1.1: the sliding-window mask is static), so they can be built once per
+ * CSR and passed to every layer call as salad_fwd_params.tile_lists; without them the layer call rebuilds them in its
+ * workspace each time (a few microseconds).  Works for any CSR with ascending unique block ids per row.
+ *   salad_tile_lists_bytes   size of the buffer for H heads and nb = ceil(N/64) blocks; 0 if the shape is invalid or the
+ *                            lists of this nb do not fit the kernel (nb > 6144: the layer call then uses another kernel
+ *                            and ignores tile_lists)
+ *   lists_dev                device, 256-byte aligned, >= salad_tile_lists_bytes (written); SALAD_ENOSPC if smaller */
+size_t salad_tile_lists_bytes(int32_t H, int32_t nb);
+salad_status salad_tile_lists(const int32_t *row_ptr_dev, const int32_t *col_idx_dev, int32_t H, int32_t nb,
+                              void *lists_dev, size_t lists_bytes, void *hip_stream);
+
 /* ---- whole layer --------------------------------------------------------------------------- */
 
 typedef struct salad_fwd_params {
@@ -118,6 +131,9 @@ typedef struct salad_fwd_params {
     const float *rope_sin;    /*   position embedding inside the linear branch (Sec. 4.1): cosine and sine of the angle
                                    of channel pair (2p, 2p+1) of token n at [n*d/2 + p].  Needs dtype bf16, d = 128,
                                    w_proj == NULL                                                                    */
+    const void *tile_lists;   /* optional device buffer filled by salad_tile_lists for exactly this row_ptr / col_idx (same H, N):
+                                 the bf16 d = 128 kernel then skips its per-call list pre-pass.  NULL: the lists are built
+                                 in the workspace on every call.  Ignored with topk > 0 and by the other kernels            */
 } salad_fwd_params;
 
 /* Run the linear apply and the scale-and-sum as a separate streaming kernel after the sparse

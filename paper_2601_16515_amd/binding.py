@@ -24,7 +24,7 @@ SALAD_PHI_RELU = 0
 SALAD_FLAG_UNFUSED_EPILOGUE = 1
 
 EXPORTS = ["salad_last_error", "salad_kept_from_sparsity", "salad_block_mask_nnz", "salad_block_mask",
-           "salad_fwd_workspace_bytes", "salad_sparse_linear_attn_fwd", "salad_linear_state_fwd",
+           "salad_tile_lists_bytes", "salad_tile_lists", "salad_fwd_workspace_bytes", "salad_sparse_linear_attn_fwd", "salad_linear_state_fwd",
            "salad_gate_fwd", "salad_gate_fwd_static", "salad_timing_enable", "salad_timing_read", "salad_tune"]
 
 
@@ -67,6 +67,7 @@ class FwdParams(C.Structure):
         ("topk_mask_out", C.c_void_p),
         ("rope_cos", C.c_void_p),
         ("rope_sin", C.c_void_p),
+        ("tile_lists", C.c_void_p),
     ]
 
 
@@ -125,6 +126,10 @@ def lib() -> C.CDLL:
         L.salad_block_mask_nnz.argtypes = [C.c_int32] * 5 + [C.c_void_p]
         L.salad_block_mask.restype = C.c_int
         L.salad_block_mask.argtypes = [C.c_int32] * 5 + [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+        L.salad_tile_lists_bytes.restype = C.c_size_t
+        L.salad_tile_lists_bytes.argtypes = [C.c_int32, C.c_int32]
+        L.salad_tile_lists.restype = C.c_int
+        L.salad_tile_lists.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
         L.salad_fwd_workspace_bytes.restype = C.c_size_t
         L.salad_fwd_workspace_bytes.argtypes = [C.POINTER(FwdParams)]
         L.salad_sparse_linear_attn_fwd.restype = C.c_int
@@ -199,6 +204,20 @@ def salad_block_mask(T: int, Hh: int, W: int, block: int, kept: Sequence[int], d
     return row_ptr, col_idx[:nnz]
 
 
+def salad_tile_lists(row_ptr, col_idx, H: int, nb: int):
+    """Visit lists of the large-tile kernel for a CSR, built once; returns a 256-byte aligned uint8 device tensor to pass
+    as tile_lists (None when the shape does not use them)."""
+    import torch
+    need = int(lib().salad_tile_lists_bytes(H, nb))
+    if need == 0:
+        return None
+    buf = torch.empty(need + 256, dtype=torch.uint8, device=row_ptr.device)
+    off = (-buf.data_ptr()) % 256
+    view = buf[off:off + need]
+    _check(lib().salad_tile_lists(row_ptr.data_ptr(), col_idx.data_ptr(), H, nb, view.data_ptr(), need, _stream()))
+    return view
+
+
 def salad_fwd_workspace_bytes(B: int, H: int, N: int, d: int, dtype: int, full_proj: bool = False,
                               topk: int = 0, rope: bool = False) -> int:
     p = FwdParams()
@@ -225,7 +244,7 @@ def make_fwd_params(q, k, v, out, grid: Tuple[int, int, int], row_ptr, col_idx, 
                     eps: float = 1e-6, softmax_scale: float = 0.0, s_out=None, o_sparse_dbg=None,
                     o_linear_dbg=None, workspace: Optional[Workspace] = None, flags: int = 0, block: int = 64,
                     drop_threshold: float = 0.0, dropped_out=None, w_proj=None, topk: int = 0,
-                    topk_key_block: int = 0, topk_mask_out=None, rope_cos=None, rope_sin=None):
+                    topk_key_block: int = 0, topk_mask_out=None, rope_cos=None, rope_sin=None, tile_lists=None):
     """Fill a salad_fwd_params from torch tensors.  Returns (params, keepalive)."""
     B, H, N, d = q.shape
     p = FwdParams()
@@ -261,7 +280,8 @@ def make_fwd_params(q, k, v, out, grid: Tuple[int, int, int], row_ptr, col_idx, 
     p.w_proj = _ptr(w_proj)
     p.topk, p.topk_key_block, p.topk_mask_out = int(topk), int(topk_key_block), _ptr(topk_mask_out)
     p.rope_cos, p.rope_sin = _ptr(rope_cos), _ptr(rope_sin)
-    return p, (hk, workspace)
+    p.tile_lists = _ptr(tile_lists)
+    return p, (hk, workspace, tile_lists)
 
 
 def salad_sparse_linear_attn_fwd(q, k, v, grid, row_ptr, col_idx, head_kind=None, *, out=None, **kw):

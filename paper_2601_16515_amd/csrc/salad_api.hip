@@ -211,6 +211,30 @@ salad_status salad_block_mask(int32_t T, int32_t Hh, int32_t W, int32_t block, i
     return SALAD_OK;
 }
 
+size_t salad_tile_lists_bytes(int32_t H, int32_t nb)
+{
+    if (H < 1 || H > 64 || nb < 1 || (size_t)tile_list_cap(nb) * 4 > 24 * 1024) return 0;
+    const size_t ntiles = ((size_t)nb + 3) / 4;
+    return align256(sizeof(uint32_t) * (size_t)H * ntiles * tile_list_cap(nb)) + align256(sizeof(int32_t) * (size_t)H * ntiles);
+}
+
+salad_status salad_tile_lists(const int32_t *row_ptr_dev, const int32_t *col_idx_dev, int32_t H, int32_t nb,
+                              void *lists_dev, size_t lists_bytes, void *hip_stream)
+{
+    if (!row_ptr_dev || !col_idx_dev || !lists_dev) return fail(SALAD_EINVAL, "salad_tile_lists: null pointer");
+    if (H < 1 || H > 64 || nb < 1) return fail(SALAD_EINVAL, "salad_tile_lists: H=%d nb=%d", (int)H, (int)nb);
+    const size_t need = salad_tile_lists_bytes(H, nb);
+    if (!need) return fail(SALAD_ENOTSUP, "salad_tile_lists: %d blocks per head are more than the large-tile kernel's list holds", (int)nb);
+    if ((uintptr_t)lists_dev & 255) return fail(SALAD_EINVAL, "salad_tile_lists: buffer not 256-byte aligned");
+    if (lists_bytes < need) return fail(SALAD_ENOSPC, "salad_tile_lists: buffer %zu < %zu bytes", lists_bytes, need);
+    const size_t ntiles = ((size_t)nb + 3) / 4;
+    char *b = (char *)lists_dev;
+    hipError_t e = launch_tile_lists(row_ptr_dev, col_idx_dev, H, nb, (uint32_t *)b,
+                                     (int32_t *)(b + align256(sizeof(uint32_t) * (size_t)H * ntiles * tile_list_cap(nb))), (hipStream_t)hip_stream);
+    if (e != hipSuccess) return hip_fail(e, "tile list launch");
+    return SALAD_OK;
+}
+
 size_t salad_fwd_workspace_bytes(const salad_fwd_params *p)
 {
     if (!p || !shape_ok(p->B, p->H, p->N, p->d, p->dtype)) return 0;
@@ -332,6 +356,7 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
         if ((size_t)tile_list_cap((p->N + 63) / 64) * 4 > 24 * 1024 || (unsigned long long)p->N * 256ull >= (1ull << 32))
             return fail(SALAD_ENOTSUP, "fwd: topk: N = %d too long for the large-tile kernel", p->N);
     }
+    if (p->tile_lists && ((uintptr_t)p->tile_lists & 255)) return fail(SALAD_EINVAL, "fwd: tile_lists not 256-byte aligned");
     if (p->phi != SALAD_PHI_RELU) return fail(SALAD_ENOTSUP, "fwd: feature map %d not supported (ReLU only)", p->phi);
     if (!(p->eps >= 0.f)) return fail(SALAD_EINVAL, "fwd: eps must be >= 0");
     if (!(p->softmax_scale >= 0.f) || !std::isfinite(p->softmax_scale)) return fail(SALAD_EINVAL, "fwd: softmax_scale must be finite and >= 0");
@@ -507,11 +532,17 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
         mark(7);
     } else if (need_lists) {
         mark(7);
-        a.tile_lists = (const uint32_t *)(ws + w.tile_lists);
-        a.tile_counts = (const int32_t *)(ws + w.tile_counts);
         a.list_cap = tile_list_cap(a.nb);
-        e = launch_tile_lists(p->row_ptr, p->col_idx, p->H, a.nb, (uint32_t *)(ws + w.tile_lists), (int32_t *)(ws + w.tile_counts), st);
-        if (e != hipSuccess) return give_back(), hip_fail(e, "tile list launch");
+        if (p->tile_lists) {      // built once for this CSR by salad_tile_lists
+            const size_t ntiles = ((size_t)a.nb + 3) / 4;
+            a.tile_lists = (const uint32_t *)p->tile_lists;
+            a.tile_counts = (const int32_t *)((const char *)p->tile_lists + align256(sizeof(uint32_t) * (size_t)p->H * ntiles * a.list_cap));
+        } else {
+            a.tile_lists = (const uint32_t *)(ws + w.tile_lists);
+            a.tile_counts = (const int32_t *)(ws + w.tile_counts);
+            e = launch_tile_lists(p->row_ptr, p->col_idx, p->H, a.nb, (uint32_t *)(ws + w.tile_lists), (int32_t *)(ws + w.tile_counts), st);
+            if (e != hipSuccess) return give_back(), hip_fail(e, "tile list launch");
+        }
     }
     if (!topk && !need_lists) mark(7);
     a.t_magic = ((uint64_t)p->N * (uint64_t)p->T < (1ull << 32) && p->T > 1) ? (unsigned)((1ull << 32) / (uint64_t)p->T + 1) : 0u;

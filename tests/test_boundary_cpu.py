@@ -184,6 +184,19 @@ def test_tune_keys_are_the_declared_ones_and_range_checked(lib):
         assert lib.salad_tune(key, 1) == sb.SALAD_EINVAL
 
 
+def test_tile_lists_argument_errors(lib):
+    fake = 0x1000
+    need = lib.salad_tile_lists_bytes(12, 512)
+    assert need == 12 * 128 * 512 * 4 + 12 * 128 * 4 and need % 256 == 0
+    assert lib.salad_tile_lists_bytes(12, 6145) == 0 and lib.salad_tile_lists_bytes(0, 8) == 0 and lib.salad_tile_lists_bytes(65, 8) == 0
+    assert lib.salad_tile_lists(None, fake, 12, 512, 0x4000, need, None) == sb.SALAD_EINVAL
+    assert lib.salad_tile_lists(fake, fake, 12, 512, 0x4001, need, None) == sb.SALAD_EINVAL
+    assert lib.salad_tile_lists(fake, fake, 12, 512, 0x4000, need - 1, None) == sb.SALAD_ENOSPC
+    assert lib.salad_tile_lists(fake, fake, 12, 7000, 0x4000, 1 << 30, None) == sb.SALAD_ENOTSUP
+    p = _params(tile_lists=0x4010, d=128)
+    assert lib.salad_sparse_linear_attn_fwd(C.byref(p)) == sb.SALAD_EINVAL and "tile_lists" in _err(lib)
+
+
 def test_static_scratch_gate_argument_errors(lib):
     fake = 0x1000
     assert lib.salad_gate_fwd_static(None, fake, 0.0, 1, 64, 128, sb.SALAD_BF16, fake, None) == sb.SALAD_EINVAL

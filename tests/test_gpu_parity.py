@@ -325,6 +325,28 @@ def test_unfused_epilogue_matches(oracle):
     compare_layer(res, ref, label="unfused")
 
 
+def test_prebuilt_tile_lists_give_the_same_bits(oracle):
+    """salad_tile_lists builds the large-tile kernel's visit lists once per CSR; a layer call that is handed them skips
+    its own pre-pass and must produce the bits of a call that builds them itself (window mask and an arbitrary CSR)."""
+    w = SMALL[7]
+    inp = wl.make_inputs(w)
+    dev = upload(w, inp)
+    kinds = wl.head_kinds(w)
+    kept = [4, 5, 4]
+    a = run_layer(w, inp, dev, kept, kinds, dbg=False)
+    b = run_layer(w, inp, dev, kept, kinds, dbg=False, prebuilt_lists=True)
+    assert np.array_equal(a["out"], b["out"])
+    ref = _oracle_layer(oracle, w, inp, kept, kinds)
+    compare_layer(b, ref, label="prebuilt lists")
+    rng = np.random.default_rng(5)
+    rows = [np.sort(rng.choice(w.nb, size=int(rng.integers(1, 7)), replace=False)) for _ in range(w.H * w.nb)]
+    row_ptr = np.concatenate([[0], np.cumsum([len(r) for r in rows])]).astype(np.int32)
+    col_idx = np.concatenate(rows).astype(np.int32)
+    a = run_layer(w, inp, dev, kept, kinds, dbg=False, csr=(row_ptr, col_idx))
+    b = run_layer(w, inp, dev, kept, kinds, dbg=False, csr=(row_ptr, col_idx), prebuilt_lists=True)
+    assert np.array_equal(a["out"], b["out"])
+
+
 @pytest.mark.parametrize("variant", [1, 2], ids=["128-row-fallback", "first-generation"])
 def test_fallback_attention_kernels(oracle, variant):
     """The d=128 kernels that serve as fallbacks (block list too long for LDS, huge N, inexact division)
