@@ -185,7 +185,9 @@ salad_status salad_linear_state_fwd(const void *k, const void *v, int32_t B, int
                                     int32_t d, int32_t dtype, float *Hs_out, float *Z_out,
                                     void *workspace, size_t workspace_bytes, void *hip_stream);
 
-/* Alg. 1 Level 2: s[b] = mean_n sigmoid(x_t[b,n,:].w_gate + b_gate); x_t [B,N,D], s fp32 [B]. */
+/* Alg. 1 Level 2: s[b] = mean_n sigmoid(x_t[b,n,:].w_gate + b_gate); x_t [B,N,D], s fp32 [B].  D a multiple of 8 up to
+ * 8192 (the widest row of the layer: 64 heads of 128 channels).  workspace: 256-byte aligned, at least
+ * 4 * B * min(ceil(N/16), 512) + 4 * B bytes with each of the two parts rounded up to 256 bytes. */
 salad_status salad_gate_fwd(const void *x_t, const float *w_gate, float b_gate, int32_t B, int32_t N,
                             int32_t D, int32_t dtype, float *s_out,
                             void *workspace, size_t workspace_bytes, void *hip_stream);
@@ -226,7 +228,7 @@ salad_status salad_timing_read(salad_kernel_times *out, int32_t reset);
  * (any other key, or a value out of range: SALAD_EINVAL).  The values are process-wide atomics; an entry point reads
  * each once at its start, so a concurrent salad_tune cannot change a call half way through.  A thread that changes
  * "state_wgs" between salad_fwd_workspace_bytes and the call gets SALAD_ENOSPC from the call's own size check.
- *   "state_wgs"     1..65536 (default 512): target workgroup count of the linear-state kernel (changes the workspace
+ *   "state_wgs"     1..65536 (default 256): target workgroup count of the linear-state kernel (changes the workspace
  *                   size: query salad_fwd_workspace_bytes again after setting it).
  *   "attn_variant"  0 (default): the d = 128 bf16 attention kernel is chosen by shape (256-query tiles, falling back
  *                   to 128-query tiles when the block list does not fit); 1: always 128-query tiles; 2: the

@@ -155,6 +155,65 @@ __global__ __launch_bounds__(256) void gate_partial_kernel(const void *x_t, cons
         partial[(size_t)b * nparts + blockIdx.x] = (wave_sum[0] + wave_sum[1]) + (wave_sum[2] + wave_sum[3]);
 }
 
+// Rows wider than the register-resident weights allow (5120 < D <= 8192, e.g. 64 heads of 128 channels): the gate
+// weights live in LDS (32 KB) and every lane reads the 8 weights of a chunk from there; one token per wave step, the
+// next token's chunks are requested before the current one is reduced.  Same partial sums, same reduce afterwards.
+constexpr int GATE_WIDE_MAX_CHUNKS = 16;   // D <= 8*64*16 = 8192
+template <bool BF16>
+__global__ __launch_bounds__(256) void gate_partial_wide_kernel(const void *x_t, const float *__restrict__ w, float bias, int N, int D,
+                                                                float *__restrict__ partial, int nparts)
+{
+    __shared__ __attribute__((aligned(16))) float wsh[GATE_WIDE_MAX_CHUNKS * 64 * 8];
+    __shared__ float wave_sum[4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int b = blockIdx.y;
+    const int nch = D >> 3;
+    for (int i = threadIdx.x; i < GATE_WIDE_MAX_CHUNKS * 64 * 8; i += 256) wsh[i] = i < D ? w[i] : 0.f;
+    __syncthreads();
+    const size_t esz = BF16 ? 2 : 4;
+    const char *xb = reinterpret_cast<const char *>(x_t) + (size_t)b * N * D * esz;
+    const int stride = nparts * 4;
+    float acc = 0.f;
+    Chunk8<BF16> bufA[GATE_WIDE_MAX_CHUNKS], bufB[GATE_WIDE_MAX_CHUNKS];
+    auto issue = [&](Chunk8<BF16> (&buf)[GATE_WIDE_MAX_CHUNKS], int n) __attribute__((always_inline)) {
+        const void *row = xb + (size_t)n * D * esz;
+#pragma unroll
+        for (int j = 0; j < GATE_WIDE_MAX_CHUNKS; ++j) {
+            const int c = lane + 64 * j;
+            if (c < nch) buf[j].load(row, c);
+            else buf[j].zero();
+        }
+    };
+    auto consume = [&](const Chunk8<BF16> (&buf)[GATE_WIDE_MAX_CHUNKS]) __attribute__((always_inline)) {
+        float dot = 0.f;
+#pragma unroll
+        for (int j = 0; j < GATE_WIDE_MAX_CHUNKS; ++j) {
+            const float4 w0 = *reinterpret_cast<const float4 *>(wsh + (lane + 64 * j) * 8);
+            const float4 w1 = *reinterpret_cast<const float4 *>(wsh + (lane + 64 * j) * 8 + 4);
+            const float wr[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
+            dot = buf[j].dot(wr, dot);
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) dot += __shfl_xor(dot, o);
+        acc += 1.f / (1.f + __expf(-(dot + bias)));   // identical in every lane
+    };
+    int n = blockIdx.x * 4 + wave;
+    if (n < N) issue(bufA, n);
+    while (n < N) {
+        if (n + stride < N) issue(bufB, n + stride);
+        consume(bufA);
+        n += stride;
+        if (n >= N) break;
+        if (n + stride < N) issue(bufA, n + stride);
+        consume(bufB);
+        n += stride;
+    }
+    if (lane == 0) wave_sum[wave] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0)
+        partial[(size_t)b * nparts + blockIdx.x] = (wave_sum[0] + wave_sum[1]) + (wave_sum[2] + wave_sum[3]);
+}
+
 constexpr int GATE_MAX_PARTS = 512;
 
 int gate_num_parts(int N)
@@ -171,7 +230,8 @@ static void gate_dispatch_bf16(dim3 grid, dim3 block, hipStream_t st, const void
     else if (nch <= 2) hipLaunchKernelGGL((gate_partial_kernel<true, 2, 4>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
     else if (nch <= 3) hipLaunchKernelGGL((gate_partial_kernel<true, 3, 2>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
     else if (nch <= 5) hipLaunchKernelGGL((gate_partial_kernel<true, 5, 2>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
-    else hipLaunchKernelGGL((gate_partial_kernel<true, GATE_MAX_CHUNKS, 1>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
+    else if (nch <= GATE_MAX_CHUNKS) hipLaunchKernelGGL((gate_partial_kernel<true, GATE_MAX_CHUNKS, 1>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
+    else hipLaunchKernelGGL((gate_partial_wide_kernel<true>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
 }
 
 // fp32 inputs are the small-shape path: one token per wave step
@@ -181,7 +241,8 @@ static void gate_dispatch_f32(dim3 grid, dim3 block, hipStream_t st, const void 
     const int nch = (D / 8 + 63) / 64;
     if (nch <= 2) hipLaunchKernelGGL((gate_partial_kernel<false, 2, 1>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
     else if (nch <= 5) hipLaunchKernelGGL((gate_partial_kernel<false, 5, 1>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
-    else hipLaunchKernelGGL((gate_partial_kernel<false, GATE_MAX_CHUNKS, 1>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
+    else if (nch <= GATE_MAX_CHUNKS) hipLaunchKernelGGL((gate_partial_kernel<false, GATE_MAX_CHUNKS, 1>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
+    else hipLaunchKernelGGL((gate_partial_wide_kernel<false>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
 }
 
 hipError_t launch_gate_partial(const void *x_t, const float *w, float bias, int B, int N, int D,

@@ -156,7 +156,7 @@ def test_step_entry_points_reject_bad_arguments(lib):
     assert lib.salad_linear_state_fwd(fake, fake, 1, 2, 64, 48, sb.SALAD_BF16, fake, fake, 0x4000, 1 << 30, None) == sb.SALAD_EINVAL
     assert lib.salad_linear_state_fwd(fake, fake, 1, 2, 64, 64, sb.SALAD_BF16, fake, fake, 0x4000, 8, None) == sb.SALAD_ENOSPC
     assert lib.salad_gate_fwd(fake, fake, 0.0, 1, 64, 12, sb.SALAD_BF16, fake, 0x4000, 1 << 20, None) == sb.SALAD_EINVAL
-    assert lib.salad_gate_fwd(fake, fake, 0.0, 1, 64, 8192, sb.SALAD_BF16, fake, 0x4000, 1 << 20, None) == sb.SALAD_ENOTSUP
+    assert lib.salad_gate_fwd(fake, fake, 0.0, 1, 64, 8200, sb.SALAD_BF16, fake, 0x4000, 1 << 20, None) == sb.SALAD_ENOTSUP
     assert lib.salad_gate_fwd(fake, None, 0.0, 1, 64, 128, sb.SALAD_BF16, fake, 0x4000, 1 << 20, None) == sb.SALAD_EINVAL
     assert lib.salad_timing_read(None, 0) == sb.SALAD_EINVAL
     assert lib.salad_timing_enable(3) == sb.SALAD_EINVAL and lib.salad_timing_enable(-1) == sb.SALAD_EINVAL
@@ -178,7 +178,7 @@ def test_tune_keys_are_the_declared_ones_and_range_checked(lib):
             assert "outside" in _err(lib)
         for v in ok:
             assert lib.salad_tune(key, v) == sb.SALAD_OK, (key, v)
-    assert lib.salad_tune(b"state_wgs", 512) == sb.SALAD_OK and lib.salad_tune(b"attn_variant", 0) == sb.SALAD_OK
+    assert lib.salad_tune(b"state_wgs", 256) == sb.SALAD_OK and lib.salad_tune(b"attn_variant", 0) == sb.SALAD_OK
     assert lib.salad_tune(b"topk_variant", 0) == sb.SALAD_OK
     for key in (b"gate_parts", b"gate_tok"):
         assert lib.salad_tune(key, 1) == sb.SALAD_EINVAL
