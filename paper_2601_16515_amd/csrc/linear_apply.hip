@@ -1,7 +1,7 @@
 // Unfused form of the linear apply (Eq. (3) quotient) plus scale-and-sum (Alg. 1 residual
 // integration) as one streaming kernel:  out <- out + coef[b,h] * relu(Q) Hs / (relu(Q).Z + eps),
 // where `out` holds the sparse branch (bf16) on entry.  HBM-bound: reads Q and O_s, writes O
-// (6*N*d bytes per head); the d x d product runs on bf16 MFMA with Hs split into hi + lo parts.
+// (6*N*d bytes per head); the d x d product runs on bf16 MFMA with Hs rounded to bf16.
 // One wave owns 32 stored rows at a time; the state fragments are staged in LDS once per workgroup.
 // d = 128 (linear_apply128_kernel): every global access is a full 128-byte line segment (8 rows x 128 bytes
 // per wave instruction); rows change between that layout and the MFMA operand / accumulator layouts
@@ -28,14 +28,14 @@ template <int D>
 __global__ __launch_bounds__(256) void linear_apply_kernel(ApplyArgs a, int rows_per_wg)
 {
     constexpr int NS = D / 16, NDT = D / 32;
-    __shared__ __attribute__((aligned(1024))) u16 hf_lds[2 * D * D];
+    __shared__ __attribute__((aligned(1024))) u16 hf_lds[D * D];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hh = lane >> 5;
     const int bh = blockIdx.y;
     if (a.drop && a.drop[bh / a.H]) return;            // pruned sample (Sec. 4.3): out already holds O_s
     {   // fragments are lane-linear in memory: copy as is (16 bytes per lane per load)
-        const u16 *hf = a.hfrag + (size_t)bh * 2 * D * D;
-        constexpr int LOADS = 2 * D * D / 8 / 256;
+        const u16 *hf = a.hfrag + (size_t)bh * D * D;
+        constexpr int LOADS = D * D / 8 / 256;
 #pragma unroll
         for (int i = 0; i < LOADS; ++i)
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(hf + (size_t)(i * 256 + tid) * 8),
@@ -89,8 +89,6 @@ __global__ __launch_bounds__(256) void linear_apply_kernel(ApplyArgs a, int rows
             for (int st = 0; st < NS; ++st) {
                 const int idx = ((dt * NS + st) * 64 + lane) * 8;
                 bf16x8 hi = *reinterpret_cast<const bf16x8 *>(hf_lds + idx);
-                bf16x8 lo = *reinterpret_cast<const bf16x8 *>(hf_lds + D * D + idx);
-                num = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo, qf[st].v, num, 0, 0, 0);
                 num = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hi, qf[st].v, num, 0, 0, 0);
             }
             if (valid) {
@@ -134,18 +132,18 @@ __global__ __launch_bounds__(512) void linear_apply128_kernel(ApplyArgs a, int r
 {
     constexpr int D = 128, NS = 8;
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
-    u16 *hf_lds = reinterpret_cast<u16 *>(smem);                                  // [2][D*D] hi, lo fragments
-    float *z_lds = reinterpret_cast<float *>(smem + 2 * D * D * 2);               // [D]
+    u16 *hf_lds = reinterpret_cast<u16 *>(smem);                                  // [D*D] state fragments
+    float *z_lds = reinterpret_cast<float *>(smem + D * D * 2);                   // [D]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    unsigned char *stage = smem + 2 * D * D * 2 + 1024 + wave * 8192;             // wave-private, 8 KB
+    unsigned char *stage = smem + D * D * 2 + 1024 + wave * 8192;                 // wave-private, 8 KB
     const int l32 = lane & 31, hh = lane >> 5;
     // ROPE: sample-head index fastest (neighbours in the grid share the angle-table rows)
     const int bh = ROPE ? blockIdx.x : blockIdx.y, rblk = ROPE ? blockIdx.y : blockIdx.x;
     if (a.drop && a.drop[bh / a.H]) return;            // pruned sample (Sec. 4.3): out already holds O_s
     {   // fragments are lane-linear in memory: copy as is (16 bytes per lane per load)
-        const u16 *hf = a.hfrag + (size_t)bh * 2 * D * D;
+        const u16 *hf = a.hfrag + (size_t)bh * D * D;
 #pragma unroll
-        for (int i = 0; i < 2 * D * D / 8 / 512; ++i)
+        for (int i = 0; i < D * D / 8 / 512; ++i)
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(hf + (size_t)(i * 512 + tid) * 8),
                                              (__attribute__((address_space(3))) void *)(hf_lds + (i * 512 + wave * 64) * 8), 16, 0, 0);
         if (tid < D) z_lds[tid] = a.Z[(size_t)bh * D + tid];
@@ -245,8 +243,6 @@ __global__ __launch_bounds__(512) void linear_apply128_kernel(ApplyArgs a, int r
                 for (int st = 0; st < NS; ++st) {
                     const int idx = ((dt * NS + st) * 64 + lane) * 8;
                     bf16x8 hi = *reinterpret_cast<const bf16x8 *>(hf_lds + idx);
-                    bf16x8 lo = *reinterpret_cast<const bf16x8 *>(hf_lds + D * D + idx);
-                    num[dl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo, qf[st].v, num[dl], 0, 0, 0);
                     num[dl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hi, qf[st].v, num[dl], 0, 0, 0);
                 }
             }
@@ -306,7 +302,7 @@ hipError_t launch_linear_apply_bf16(const ApplyArgs &a, hipStream_t st)
         int rows_per_wg = (int)((rows + 255) / 256) * 256;
         if (rows_per_wg < 256) rows_per_wg = 256;
         dim3 grid((a.N + rows_per_wg - 1) / rows_per_wg, a.BH), block(512);
-        constexpr int lds = 2 * 128 * 128 * 2 + 1024 + 8 * 8192;
+        constexpr int lds = 128 * 128 * 2 + 1024 + 8 * 8192;
         static bool done[6][16] = {};
         // variant: 0 plain, 1 debug output, 2 emit; + 3 with the rotary tables
         const int var = (a.emit ? 2 : a.o_linear_dbg ? 1 : 0) + (a.rope_tab ? 3 : 0);

@@ -256,7 +256,7 @@ hipError_t launch_gate_partial(const void *x_t, const float *w, float bias, int 
 
 // ------------------------------------------------------------------------------------------------
 // Finalize.  Workgroups [0, BH*ceil((D*D+D)/64)) add up the P partial states of one head in chunk
-// order (fp32) and emit Hs, Z and the bf16 hi/lo split of Hs laid out as MFMA A-operand fragments
+// order (fp32) and emit Hs, Z and Hs rounded to bf16 laid out as MFMA A-operand fragments
 // of Hs^T:  element (a, c) -> ((c/32 * (D/16) + a/16) * 64 + ((a%16)/8)*32 + c%32) * 8 + a%8.
 // The last workgroup reduces the gate partial sums (or takes the caller's s), writes s and the
 // per-(b, h) coefficient lambda * a_h * s_b of the residual sum (Alg. 1, Sec. 4.2).
@@ -294,12 +294,8 @@ __global__ __launch_bounds__(256) void finalize_kernel(FinalizeArgs a, int state
             a.Hs[(size_t)bh * D * D + e] = s;
             if (a.hfrag) {
                 int row = e / D, col = e - row * D;   // Hs[row = a][col = c]
-                u16 hi = f32_to_bf16_rne(s);
-                float rem = s - __uint_as_float((uint32_t)hi << 16);
-                u16 lo = f32_to_bf16_rne(rem);
                 int idx = ((col / 32 * (D / 16) + row / 16) * 64 + ((row % 16) / 8) * 32 + col % 32) * 8 + row % 8;
-                a.hfrag[(size_t)bh * 2 * D * D + idx] = hi;
-                a.hfrag[(size_t)bh * 2 * D * D + D * D + idx] = lo;
+                a.hfrag[(size_t)bh * D * D + idx] = f32_to_bf16_rne(s);
             }
         } else {
             a.Z[(size_t)bh * D + (e - D * D)] = s;

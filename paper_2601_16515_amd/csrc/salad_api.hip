@@ -58,7 +58,7 @@ WsLayout ws_layout(int B, int H, int N, int d, int dtype, int state_wgs, bool fu
     w.state_partial = off; off = align256(off + sizeof(float) * BH * (size_t)w.P * ((size_t)d * d + d));
     w.Hs = off; off = align256(off + sizeof(float) * BH * d * d);
     w.Z = off; off = align256(off + sizeof(float) * BH * d);
-    w.hfrag = off; off = align256(off + (dtype == SALAD_BF16 ? sizeof(u16) * BH * 2 * d * d : 0));
+    w.hfrag = off; off = align256(off + (dtype == SALAD_BF16 ? sizeof(u16) * BH * d * d : 0));
     w.s = off; off = align256(off + sizeof(float) * B);
     w.coef = off; off = align256(off + sizeof(float) * BH);
     w.drop = off; off = align256(off + sizeof(int32_t) * B);

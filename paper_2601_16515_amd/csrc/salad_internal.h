@@ -44,7 +44,7 @@ struct FinalizeArgs {
     // state (bf16 path only; P == 0 skips the state part)
     const float *state_partial; int P;
     float *Hs, *Z;       // [BH, D, D], [BH, D] fp32
-    u16 *hfrag;          // [BH][2][D*D] bf16 hi / lo parts of Hs in MFMA A-operand order (may be null)
+    u16 *hfrag;          // [BH][D*D] Hs rounded to bf16, in MFMA A-operand fragment order of Hs^T (may be null)
     // gate
     const float *gate_partial; int nparts; int N;   // nparts == 0: take s from s_dev
     const float *s_dev;

@@ -266,8 +266,8 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_kernel(AttnArgs a, in
         const float den = dpart + __shfl_xor(dpart, 32) + a.eps;
         inv_den = 1.f / den;
         lin_scale = a.coef[bh] * inv_den;
-        // num^T = Hs^T phi(Q)^T with Hs split into bf16 hi + lo parts
-        const u16 *hf = a.hfrag + (size_t)bh * 2 * D * D;
+        // num^T = Hs^T phi(Q)^T with Hs rounded to bf16 (MFMA operand)
+        const u16 *hf = a.hfrag + (size_t)bh * D * D;
 #pragma unroll
         for (int dt = 0; dt < NDT; ++dt) {
 #pragma unroll
@@ -276,8 +276,6 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_kernel(AttnArgs a, in
             for (int st = 0; st < NS; ++st) {
                 size_t idx = ((size_t)(dt * NS + st) * 64 + lane) * 8;
                 bf16x8 hi = *reinterpret_cast<const bf16x8 *>(hf + idx);
-                bf16x8 lo = *reinterpret_cast<const bf16x8 *>(hf + D * D + idx);
-                num[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo, qf[st].v, num[dt], 0, 0, 0);
                 num[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hi, qf[st].v, num[dt], 0, 0, 0);
             }
         }

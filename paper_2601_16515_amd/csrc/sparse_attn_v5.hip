@@ -22,7 +22,7 @@
 //     element); row sums are taken from the bf16-rounded probabilities with v_dot2c_f32_bf16; the block
 //     maximum is not computed unless a block's sums show that some logit exceeds the running reference
 //     by more than 13 binades (the reference then moves to the true maximum and the block is redone).
-//   * Epilogue: the hi/lo bf16 fragments of the linear state are staged once per workgroup in LDS.
+//   * Epilogue: the bf16 fragments of the linear state are staged once per workgroup in LDS.
 #include "salad_internal.h"
 
 namespace salad {
@@ -448,11 +448,11 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
     };
 
     const bool lin = !GATHER && a.use_linear && !a.write_sparse_only && !(a.drop && a.drop[bh / a.H]);   // pruned sample (Sec. 4.3): out = O_s
-    const u16 *hf = a.hfrag + (size_t)bh * 2 * D * D;
-    // 64 KB of linear-state fragments (hi, lo) for the epilogue, staged into the K ring once it is idle
+    const u16 *hf = a.hfrag + (size_t)bh * D * D;
+    // 32 KB of linear-state fragments for the epilogue, staged into the K ring once it is idle
     auto stage_state = [&]() INL {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) lds_dma16(hf + (size_t)(i * 512 + tid) * 8, lds_addr_of(Kb + (i * 512 + wave * 64) * 8));
+        for (int i = 0; i < 4; ++i) lds_dma16(hf + (size_t)(i * 512 + tid) * 8, lds_addr_of(Kb + (i * 512 + wave * 64) * 8));
     };
 
     // ---- main loop over the union list.  Iteration j: S(j) and softmax(j), PV(j-1); fetch block j+PD.
@@ -566,8 +566,6 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
             for (int st = 0; st < NS; ++st) {
                 const int idx = ((dt * NS + st) * 64 + lane) * 8;
                 bf16x8 hi = *reinterpret_cast<const bf16x8 *>(Kb + idx);
-                bf16x8 lo = *reinterpret_cast<const bf16x8 *>(Kb + D * D + idx);
-                num[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo, qf[st].v, num[dt], 0, 0, 0);
                 num[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hi, qf[st].v, num[dt], 0, 0, 0);
             }
         }
