@@ -373,15 +373,24 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
     // linear branch follows in its own kernel as well
     const int state_wgs = g_state_target_wgs.load(), attn_variant = g_attn_variant.load();
     const bool topk_regroup = p->topk > 0 && g_topk_variant.load() == 0;
-    // rotary linear branch (Sec. 4.1): the rotation lives in the state kernel and the separate apply kernel
+    // rotary linear branch (Sec. 4.1): the rotation lives in the state kernel and in whichever kernel applies the linear
+    // branch: the large-tile attention kernel's epilogue, or the separate apply kernel
     const bool rope = p->rope_cos != nullptr || p->rope_sin != nullptr;
     if (rope) {
         if (!p->rope_cos || !p->rope_sin) return fail(SALAD_EINVAL, "fwd: rope_cos and rope_sin must be given together");
         if (p->dtype != SALAD_BF16 || p->d != 128) return fail(SALAD_ENOTSUP, "fwd: the rotary linear branch needs dtype bf16 and d = 128");
         if (p->w_proj) return fail(SALAD_ENOTSUP, "fwd: the rotary linear branch and w_proj are not combined");
     }
+    // will the sparse branch run on the large-tile kernel?  (the same conditions as the dispatcher's: see attn_takes_large_tile)
+    bool temporal_any = false;
+    if (p->head_kind_host && p->T > 1)
+        for (int h = 0; h < p->H; ++h) temporal_any |= p->head_kind_host[h] == SALAD_HEAD_TEMPORAL;
+    const bool large_tile = p->dtype == SALAD_BF16 && p->d == 128 && attn_variant == 0 &&
+                            (size_t)tile_list_cap((p->N + 63) / 64) * 4 <= 24 * 1024 && (unsigned long long)p->N * 256ull < (1ull << 32) &&
+                            (!temporal_any || (unsigned long long)p->N * (unsigned long long)p->T < (1ull << 32));
+    const bool rope_fused = rope && large_tile && !topk && !p->w_proj && !(p->flags & SALAD_FLAG_UNFUSED_EPILOGUE);
     const bool unfused = (p->flags & SALAD_FLAG_UNFUSED_EPILOGUE) != 0 || (p->w_proj != nullptr && p->lambda != 0.f) ||
-                         (topk_regroup && p->lambda != 0.f) || (rope && p->lambda != 0.f);
+                         (topk_regroup && p->lambda != 0.f) || (rope && !rope_fused && p->lambda != 0.f);
     if (unfused && p->dtype != SALAD_BF16) return fail(SALAD_ENOTSUP, "fwd: unfused epilogue is bf16 only");
     if (p->flags & ~SALAD_FLAG_UNFUSED_EPILOGUE) return fail(SALAD_EINVAL, "fwd: unknown flags 0x%x", p->flags);
     const bool full_proj = p->w_proj != nullptr && p->lambda != 0.f;
@@ -500,6 +509,7 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
     a.write_sparse_only = unfused;
     a.drop = drop;
     a.variant = attn_variant;
+    a.rope_tab = rope_fused && use_linear ? (const uint32_t *)(ws + w.rope_tab) : nullptr;
     if (topk) {
         // App. A.1.2: key-block means -> per-query selection -> per-tile visit lists; the mask never leaves the device
         float *means = (float *)(ws + w.kmeans);

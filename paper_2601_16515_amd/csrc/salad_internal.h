@@ -95,9 +95,14 @@ struct AttnArgs {
     const int32_t *g_idx;
     u16 *g_po; float *g_lse;
     int g_kk, g_bpb, g_max_tiles;
+    const uint32_t *rope_tab;       // large-tile kernel, fused epilogue only: [N, 64] angle words (fp16 cos | fp16 sin << 16) of the
+                                    // rotary linear branch (the state fragments then hold the rotated state), or null
     int variant;                    // 0: automatic choice of the d = 128 kernel; 1: 128-query tiles; 2: first-generation kernel
 };
 hipError_t launch_sparse_attn_bf16(const AttnArgs &a, hipStream_t st);
+// whether launch_sparse_attn_bf16 will take the large-tile kernel for these arguments (the only one whose fused epilogue
+// knows the rotary linear branch)
+bool attn_takes_large_tile(const AttnArgs &a);
 // union lists of the CSR rows of every 4-query-block tile (input of the large-tile attention kernel)
 int tile_list_cap(int nb);
 hipError_t launch_tile_lists(const int32_t *row_ptr, const int32_t *col_idx, int H, int nb, uint32_t *lists,

@@ -311,6 +311,15 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_kernel(AttnArgs a, in
     }
 }
 
+bool attn_takes_large_tile(const AttnArgs &a)
+{
+    if (a.D != 128 || !a.tile_lists) return false;
+    if (a.topk_mask) return true;
+    const bool temporal = a.kind_mask != 0 && a.T > 1;
+    return a.variant == 0 && (size_t)tile_list_cap(a.nb) * 4 <= 24 * 1024 && (unsigned long long)a.N * 256ull < (1ull << 32) &&
+           (!temporal || a.t_magic != 0);
+}
+
 hipError_t launch_sparse_attn_bf16(const AttnArgs &a, hipStream_t st)
 {
     // d = 128: the large-tile ping-pong kernel unless its block list does not fit in LDS or a variant is

@@ -33,6 +33,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef short s16x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 
 #define LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 #define GLB_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
@@ -191,7 +192,11 @@ hipError_t launch_tile_lists(const int32_t *row_ptr, const int32_t *col_idx, int
 // MODE 2: Top-K regrouped by key block.  A query tile is a run of up to 256 gathered queries that all keep the same
 //   key block; the list is that key block's 64-token blocks; the normalised partial result and its log-sum-exp go
 //   to a.g_po / a.g_lse (one slot per kept (query, key block) pair) for the merge kernel.
-template <int PD, bool DBG, int MODE = 0>
+// ROPE (MODE 0 only): rotary position embedding inside the linear branch (Sec. 4.1).  The state fragments then hold
+//   sum_j (R_j relu(K_j))^T V_j, and the epilogue rotates this tile's relu(Q) fragments in registers (channel pair
+//   (2p, 2p+1) of the query's stored row n by the angle word a.rope_tab[n * 64 + p] = fp16 cos | fp16 sin << 16) after
+//   the normaliser has been taken from the unrotated features.
+template <int PD, bool DBG, int MODE = 0, bool ROPE = false>
 __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int ntiles, int total, int per_xcd, int list_cap)
 {
     constexpr int D = 128, NS = 8, NDT = 4;
@@ -455,6 +460,17 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
         for (int i = 0; i < 4; ++i) lds_dma16(hf + (size_t)(i * 512 + tid) * 8, lds_addr_of(Kb + (i * 512 + wave * 64) * 8));
     };
 
+    // ROPE: this lane's 32 angle words (its query's row of the table: pairs 8 st + 4 hh + j), fetched under the last
+    // PV product of the tile
+    uint4 ang[ROPE ? NS : 1];
+    auto load_angles = [&]() INL {
+        if (ROPE) {
+            const uint32_t *tr = a.rope_tab + (size_t)qrow * (D / 2) + hh * 4;
+#pragma unroll
+            for (int st = 0; st < NS; ++st) ang[st] = *reinterpret_cast<const uint4 *>(tr + st * 8);
+        }
+    };
+
     // ---- main loop over the union list.  Iteration j: S(j) and softmax(j), PV(j-1); fetch block j+PD.
     // Block b lives in slot b % NK of the K ring and b % NV of the V ring.
     // The fetch of block j+PD is issued from each group's vector phase, where its address arithmetic
@@ -524,6 +540,7 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
         if (lin) stage_state();
+        if (ROPE && lin) load_angles();
         {
             int vslot_prev = vslot - 1; if (vslot_prev < 0) vslot_prev += NV;
             v_last = vslot_prev;
@@ -540,7 +557,7 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
     f32x16 num[NDT];
     float lin_scale = 0.f, inv_den = 0.f;
     if (lin) {
-        if (n == 0) stage_state();
+        if (n == 0) { stage_state(); if (ROPE) load_angles(); }
         float dpart = 0.f;
         const float *Zh = a.Z + (size_t)bh * D;
 #pragma unroll
@@ -557,6 +574,22 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
         inv_den = 1.f / den;
         lin_scale = a.coef[bh] * inv_den;
         WAIT_VM(0);
+        if (ROPE) {
+            // numerator operand: R_i relu(Q_i), rounded to bf16 like every MFMA operand (the normaliser above keeps the
+            // unrotated features)
+#pragma unroll
+            for (int st = 0; st < NS; ++st) {
+                const uint32_t cw[4] = {ang[st].x, ang[st].y, ang[st].z, ang[st].w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t w = qf[st].w[j];
+                    const float x = __uint_as_float(w << 16), y = __uint_as_float(w & 0xffff0000u);
+                    const f16x2 hcs = __builtin_bit_cast(f16x2, cw[j]);
+                    const float cc = (float)hcs[0], ss = (float)hcs[1];
+                    qf[st].w[j] = pack2e(x * cc - y * ss, x * ss + y * cc);
+                }
+            }
+        }
         __syncthreads();   // the staged fragments have landed in every wave's view
 #pragma unroll
         for (int dt = 0; dt < NDT; ++dt) {
@@ -636,7 +669,7 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
     }
 }
 
-template <int PD, bool DBG, int MODE = 0>
+template <int PD, bool DBG, int MODE = 0, bool ROPE = false>
 static hipError_t launch_v5(const AttnArgs &a, hipStream_t st)
 {
     const int ntiles = (a.nb + 3) / 4;
@@ -647,7 +680,7 @@ static hipError_t launch_v5(const AttnArgs &a, hipStream_t st)
     static_assert(PD + 1 >= 4, "the epilogue stages 64 KB of state fragments in the K ring");
     constexpr int kMaxDyn = 160 * 1024 - 2048;   // the static part is rounded up to its 1 KB alignment
     if (lds > (size_t)kMaxDyn) return hipErrorInvalidValue;
-    auto kern = sparse_attn_v5_kernel<PD, DBG, MODE>;
+    auto kern = sparse_attn_v5_kernel<PD, DBG, MODE, ROPE>;
     static bool attr_done[16] = {};
     if (hipError_t e = dyn_lds_attr_once(reinterpret_cast<const void *>(kern), kMaxDyn, attr_done); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(512), lds, st, a, ntiles, total, per_xcd, list_cap);
@@ -659,6 +692,7 @@ hipError_t launch_sparse_attn_v5(const AttnArgs &a, hipStream_t st)
     const bool dbg = a.o_sparse_dbg || a.o_linear_dbg;
     if (a.g_desc) return launch_v5<3, false, 2>(a, st);
     if (a.topk_mask) return dbg ? launch_v5<3, true, 1>(a, st) : launch_v5<3, false, 1>(a, st);
+    if (a.rope_tab) return dbg ? launch_v5<3, true, 0, true>(a, st) : launch_v5<3, false, 0, true>(a, st);
     return dbg ? launch_v5<3, true>(a, st) : launch_v5<3, false>(a, st);
 }
 

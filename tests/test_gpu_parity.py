@@ -480,10 +480,12 @@ def test_topk_mask_layer(oracle, topk_variant, wi, key_block, topk, variant):
         assert errors(res["out"], dense["out"])[1] < 5e-3   # two independently rounded bf16 results
 
 
+@pytest.mark.parametrize("flags", [0, sb.SALAD_FLAG_UNFUSED_EPILOGUE], ids=["fused", "unfused"])
 @pytest.mark.parametrize("wi", [1, 7, 0, 4], ids=["N693-B2", "N1170", "N270-tail14", "N512"])
-def test_rotary_linear_branch(oracle, wi):
+def test_rotary_linear_branch(oracle, wi, flags):
     """RoPE inside the linear branch (Sec. 4.1; numerator rotated, normaliser not): the layer against the oracle,
-    with a static scale large enough that the linear branch carries weight; zero angles reproduce the plain layer."""
+    with a static scale large enough that the linear branch carries weight; zero angles reproduce the plain layer.
+    fused: the attention kernel's epilogue rotates relu(Q) in registers; unfused: the separate apply kernel does."""
     w = SMALL[wi]
     inp = wl.make_inputs(w)
     dev = upload(w, inp)
@@ -493,13 +495,15 @@ def test_rotary_linear_branch(oracle, wi):
     rope_dev = (torch.from_numpy(cs).cuda(), torch.from_numpy(sn).cuda())
     ref = _oracle_layer(oracle, w, inp, kept, kinds, lam=20.0, rope=(cs, sn))
     ref_plain = _oracle_layer(oracle, w, inp, kept, kinds, lam=20.0)
-    res = run_layer(w, inp, dev, kept, kinds, lam=20.0, rope=rope_dev)
+    res = run_layer(w, inp, dev, kept, kinds, lam=20.0, rope=rope_dev, flags=flags)
     compare_layer(res, ref, label=f"rope-{w.name}")
+    fast = run_layer(w, inp, dev, kept, kinds, lam=20.0, rope=rope_dev, flags=flags, dbg=False)
+    assert np.array_equal(fast["out"], res["out"])
     if w.N > 1:
         assert errors(ref["o_linear"], ref_plain["o_linear"])[1] > 0.05          # the rotation is not a small effect
     one = torch.ones_like(rope_dev[0]); zero = torch.zeros_like(rope_dev[0])
-    res0 = run_layer(w, inp, dev, kept, kinds, lam=20.0, rope=(one, zero))
-    plain = run_layer(w, inp, dev, kept, kinds, lam=20.0, flags=sb.SALAD_FLAG_UNFUSED_EPILOGUE)
+    res0 = run_layer(w, inp, dev, kept, kinds, lam=20.0, rope=(one, zero), flags=flags)
+    plain = run_layer(w, inp, dev, kept, kinds, lam=20.0, flags=flags)
     assert torch.equal(res0["out_t"], plain["out_t"])                            # identity rotation: the same bits
 
 
