@@ -536,6 +536,47 @@ int salad_oracle_combine_proj(const float *q, const double *Hs, const double *Z,
     return SO_OK;
 }
 
+/* The same residual integration when the linear branch carries the rotary position embedding (Sec. 4.1 together with
+ * Alg. 1 "Proj"): O_l of every head at row n is (R_n relu(Q_n)) Hr / (relu(Q_n).Z + eps) with the rotated state Hr
+ * (the numerator is rotated, the normaliser is not), then projected across heads as above.  cs, sn: [N, d/2]. */
+int salad_oracle_combine_proj_rope(const float *q, const double *Hr, const double *Z, const float *cs, const float *sn,
+                                   int B, int H, int64_t N, int d, double eps, const double *o_s, const int64_t *rows,
+                                   int64_t nrows, const double *Wp, double lambda, const double *s, double *out)
+{
+    if (d % 2) return SO_EINVAL;
+    const int64_t total = (int64_t)B * H * nrows;
+    const int64_t D = (int64_t)H * d;
+#pragma omp parallel
+    {
+        double *qr = (double *)malloc(sizeof(double) * (size_t)d);
+#pragma omp for schedule(static)
+        for (int64_t idx = 0; idx < total; ++idx) {
+            const int64_t bh = idx / nrows;
+            const int b = (int)(bh / H), ho = (int)(bh % H);
+            const int64_t n = rows[idx];
+            double *o = out + idx * d;
+            for (int c = 0; c < d; ++c) o[c] = o_s[idx * d + c];
+            if (n < 0 || n >= N) continue;
+            for (int hi = 0; hi < H; ++hi) {
+                const int64_t bhi = (int64_t)b * H + hi;
+                const float *qi = q + (bhi * N + n) * d;
+                rope_rotate(qi, cs + n * (d / 2), sn + n * (d / 2), d, qr);
+                double den = eps;
+                for (int a = 0; a < d; ++a) den += relu((double)qi[a]) * Z[bhi * d + a];
+                for (int a2 = 0; a2 < d; ++a2) {
+                    double num = 0.0;
+                    for (int a = 0; a < d; ++a) num += qr[a] * Hr[(bhi * d + a) * d + a2];
+                    const double ol = num / den;
+                    const double *wrow = Wp + ((int64_t)hi * d + a2) * D + (int64_t)ho * d;
+                    for (int c = 0; c < d; ++c) o[c] += lambda * s[b] * ol * wrow[c];
+                }
+            }
+        }
+        free(qr);
+    }
+    return SO_OK;
+}
+
 /* Post-tuning branch dropping, Sec. 4.3: dropped[b] = 1 when the sample's dynamic scale is below the
  * threshold.  The comparison is made on the float32 value of s, the precision the device holds it in. */
 int salad_oracle_branch_drop(const double *s, int B, double tau, int *dropped)

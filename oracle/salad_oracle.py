@@ -200,9 +200,10 @@ def combine(o_s, o_l, lam: float, head_scale, s) -> np.ndarray:
     return out
 
 
-def combine_proj(q, Hs, Z, eps: float, o_s, rows, w_proj, lam: float, s) -> np.ndarray:
+def combine_proj(q, Hs, Z, eps: float, o_s, rows, w_proj, lam: float, s, rope=None) -> np.ndarray:
     """Alg. 1 residual integration with the full projection: O_s + lambda s_b (O_l W_p), W_p [D,D] over the
-    concatenated heads; evaluated on the compact rows of each (b, h) (`rows`: their stored row indices)."""
+    concatenated heads; evaluated on the compact rows of each (b, h) (`rows`: their stored row indices).
+    rope = (cos, sin) [N, d/2]: the linear branch carries the rotary embedding of Sec. 4.1 (Hs is then the rotated state)."""
     q = _f32(q)
     B, H, N, d = q.shape
     o_s = np.ascontiguousarray(o_s, dtype=np.float64)
@@ -214,6 +215,15 @@ def combine_proj(q, Hs, Z, eps: float, o_s, rows, w_proj, lam: float, s) -> np.n
     assert wp.shape == (H * d, H * d)
     s = np.ascontiguousarray(s, dtype=np.float64)
     out = np.zeros_like(o_s)
+    if rope is not None:
+        cs, sn = _f32(rope[0]), _f32(rope[1])
+        assert cs.shape == (N, d // 2) and sn.shape == (N, d // 2)
+        rc = _load().salad_oracle_combine_proj_rope(_p(q), _p(Hs), _p(Z), _p(cs), _p(sn), C.c_int(B), C.c_int(H), C.c_int64(N),
+                                                    C.c_int(d), C.c_double(eps), _p(o_s), _p(rows), C.c_int64(nrows), _p(wp),
+                                                    C.c_double(lam), _p(s), _p(out))
+        if rc != 0:
+            raise ValueError("salad_oracle_combine_proj_rope: invalid arguments")
+        return out
     _load().salad_oracle_combine_proj(_p(q), _p(Hs), _p(Z), C.c_int(B), C.c_int(H), C.c_int64(N), C.c_int(d),
                                       C.c_double(eps), _p(o_s), _p(rows), C.c_int64(nrows), _p(wp),
                                       C.c_double(lam), _p(s), _p(out))
@@ -291,10 +301,8 @@ def salad_forward(q, k, v, x_t, w_gate, head_scale, grid, block, head_kind, kept
     dropped = branch_drop(s, drop_threshold)
     # a pruned branch contributes exactly nothing: its samples are combined with a zero dynamic scale
     s_eff = np.where(dropped != 0, 0.0, s)
-    if w_proj is not None and rope is not None:
-        raise ValueError("the full projection and the rotary linear branch are not combined here")
     if w_proj is not None:       # full Level-1 projection across heads instead of the per-head scalars
-        out = combine_proj(q, Hs, Z, eps, o_s, rows, w_proj, lam, s_eff)
+        out = combine_proj(q, Hs, Z, eps, o_s, rows, w_proj, lam, s_eff, rope=rope)
     else:
         out = combine(o_s, o_l, lam, head_scale, s_eff)
     return {"o_sparse": o_s, "o_linear": o_l, "out": out, "rows": rows, "Hs": Hs, "Z": Z, "s": s,

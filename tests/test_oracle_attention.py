@@ -548,3 +548,43 @@ def test_rope_layer(oracle):
     assert np.array_equal(r["o_linear"], want)
     coef = 1.5 * inp["head_scale"].astype(np.float64)[None, :, None, None] * r["s"][:, None, None, None]
     assert np.abs(r["out"] - (r["o_sparse"] + coef * r["o_linear"])).max() < 1e-12
+
+
+def test_full_projection_with_rotary_linear_branch(oracle):
+    """Alg. 1 "Proj" across heads applied to the rotary linear branch of Sec. 4.1.  Pins: the block-diagonal projection
+    diag(a_h) x I reproduces the per-head rotary layer; zero angles reproduce the plain full projection; one non-zero
+    entry of W_p moves exactly one output column by lambda s_b times the named channel of the rotary O_l; a transposed
+    W_p fails."""
+    w = wl.small("proj-rope", 2, 3, 16, 2, 6, 7, "f32", 0.5, seed=45, block=16)     # D = 48
+    inp = wl.make_inputs(w)
+    D = w.H * w.d
+    cs, sn, _ = _rope_tables(w.N, w.d)
+    kw = dict(grid=(w.T, w.Hh, w.W), block=w.block, head_kind=[0, 1, 0], kept=[3, 3, 2], eps=1e-6)
+    args = (inp["q"], inp["k"], inp["v"], inp["x_t"], inp["w_gate"])
+    a = inp["head_scale"].astype(np.float64)
+    per_head = oracle.salad_forward(*args, inp["head_scale"], lam=0.8, rope=(cs, sn), **kw)
+    ok = per_head["rows"] >= 0
+    wp = np.kron(np.diag(a), np.eye(w.d))
+    full = oracle.salad_forward(*args, None, lam=0.8, w_proj=wp, rope=(cs, sn), **kw)
+    assert np.abs(full["out"] - per_head["out"])[ok].max() < 1e-12
+    plain_rope = oracle.salad_forward(*args, inp["head_scale"], lam=0.8, **kw)
+    assert np.abs(per_head["out"] - plain_rope["out"])[ok].max() > 1e-3          # the rotation matters on these inputs
+    # identity rotation: the plain full projection
+    w1 = wl.normal(45, "w1", (D, D)).astype(np.float64) * 0.1
+    one, zero = np.ones((w.N, w.d // 2), np.float32), np.zeros((w.N, w.d // 2), np.float32)
+    r0 = oracle.salad_forward(*args, None, lam=0.8, w_proj=w1, rope=(one, zero), **kw)["out"]
+    p0 = oracle.salad_forward(*args, None, lam=0.8, w_proj=w1, **kw)["out"]
+    assert np.abs(r0 - p0)[ok].max() < 1e-12
+    # a single entry W_p[(h1, aa), (h2, cc)] (two spatial heads: same compact rows)
+    h1, aa, h2, cc = 2, 5, 0, 9
+    e = np.zeros((D, D)); e[h1 * w.d + aa, h2 * w.d + cc] = 1.0
+    oe = oracle.salad_forward(*args, None, lam=0.8, w_proj=e, rope=(cs, sn), **kw)
+    delta = oe["out"] - oe["o_sparse"]
+    assert np.array_equal(oe["rows"][:, h1], oe["rows"][:, h2])
+    want = 0.8 * oe["s"][:, None] * per_head["o_linear"][:, h1, :, aa]
+    okr = oe["rows"][:, h2] >= 0
+    assert np.abs(delta[:, h2, :, cc] - want)[okr].max() < 1e-12
+    mask = np.ones_like(delta, dtype=bool); mask[:, h2, :, cc] = False
+    assert np.abs(delta[mask]).max() == 0.0
+    et = oracle.salad_forward(*args, None, lam=0.8, w_proj=e.T.copy(), rope=(cs, sn), **kw)
+    assert np.abs(et["out"] - oe["out"])[ok].max() > 1e-6
