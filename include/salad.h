@@ -129,8 +129,8 @@ typedef struct salad_fwd_params {
     uint64_t *topk_mask_out;  /* optional device uint64 [B,H,N]: bit J set = the query keeps key block J            */
     const float *rope_cos;    /* optional device fp32 [N, d/2] (shared by all samples and heads), with rope_sin: rotary  */
     const float *rope_sin;    /*   position embedding inside the linear branch (Sec. 4.1): cosine and sine of the angle
-                                   of channel pair (2p, 2p+1) of token n at [n*d/2 + p].  Needs dtype bf16, d = 128,
-                                   w_proj == NULL                                                                    */
+                                   of channel pair (2p, 2p+1) of token n at [n*d/2 + p].  Needs dtype bf16, d = 128;
+                                   may be combined with w_proj (the rotated O_l is what gets projected)             */
     const void *tile_lists;   /* optional device buffer filled by salad_tile_lists for exactly this row_ptr / col_idx (same H, N):
                                  the bf16 d = 128 kernel then skips its per-call list pre-pass.  NULL: the lists are built
                                  in the workspace on every call.  Ignored with topk > 0 and by the other kernels            */
@@ -167,8 +167,9 @@ size_t salad_fwd_workspace_bytes(const salad_fwd_params *p);
  * the normaliser keeps the unrotated features:
  *   O_l[i] = sum_j (R_i phi(Q_i)).(R_j phi(K_j)) V_j / (phi(Q_i).Z + eps) = (R_i phi(Q_i)) Hr / (phi(Q_i).Z + eps),
  *   Hr = sum_j (R_j phi(K_j))^T V_j.  The caller owns the split of the pairs over the t, y, x axes and the frequencies
- * (they are in the tables; the kernels read them as fp16 pairs packed once per call).  Runs with the separate
- * linear-apply kernel.
+ * (they are in the tables; the kernels read them as fp16 pairs packed once per call).  The rotation of phi(Q) happens
+ * in the attention kernel's epilogue (bf16 d = 128 large-tile kernel) or in the separate linear-apply kernel (unfused
+ * epilogue, Top-K, w_proj: there the rotated O_l is what the projection multiplies).
  * Post-tuning branch dropping (Sec. 4.3, App. A.3): with drop_threshold = tau > 0, a sample whose dynamic
  * scale s_b < tau (strict, compared in fp32) loses its linear branch: out[b] = O_s[b], exactly as with
  * lambda == 0.  The decision is taken on the device (no host synchronisation): the gate is reduced first,

@@ -379,7 +379,6 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
     if (rope) {
         if (!p->rope_cos || !p->rope_sin) return fail(SALAD_EINVAL, "fwd: rope_cos and rope_sin must be given together");
         if (p->dtype != SALAD_BF16 || p->d != 128) return fail(SALAD_ENOTSUP, "fwd: the rotary linear branch needs dtype bf16 and d = 128");
-        if (p->w_proj) return fail(SALAD_ENOTSUP, "fwd: the rotary linear branch and w_proj are not combined");
     }
     // will the sparse branch run on the large-tile kernel?  (the same conditions as the dispatcher's: see attn_takes_large_tile)
     bool temporal_any = false;

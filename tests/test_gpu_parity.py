@@ -507,6 +507,26 @@ def test_rotary_linear_branch(oracle, wi, flags):
     assert torch.equal(res0["out_t"], plain["out_t"])                            # identity rotation: the same bits
 
 
+def test_full_projection_with_rotary_linear_branch(oracle):
+    """Alg. 1 "Proj" as a full matrix over the rotary linear branch (the paper's layer has both): the emit pass writes the
+    rotated O_l, the GEMM projects it; small shape with B = 2 and a ragged tail, against the oracle."""
+    w = SMALL[1]                                      # N = 693, B = 2, H = 3
+    inp = wl.make_inputs(w)
+    dev = upload(w, inp)
+    kinds = wl.head_kinds(w)
+    kept = [3, 4, 3]
+    D = w.H * w.d
+    wp = wl.round_to_bf16((wl.normal(w.seed, "w_proj", (D, D)) / np.sqrt(D) * 8.0).astype(np.float32))
+    wp_dev = torch.from_numpy(wp).cuda().to(torch.bfloat16)
+    cs, sn = wl.rope_tables(w.T, w.Hh, w.W, w.d)
+    rope_dev = (torch.from_numpy(cs).cuda(), torch.from_numpy(sn).cuda())
+    res = run_layer(w, inp, dev, kept, kinds, head_scale=None, w_proj=wp_dev, rope=rope_dev, dbg=False)
+    ref = _oracle_layer(oracle, w, inp, kept, kinds, w_proj=wp.astype(np.float64), rope=(cs, sn))
+    ref_plain = _oracle_layer(oracle, w, inp, kept, kinds, w_proj=wp.astype(np.float64))
+    assert errors(ref["out"], ref_plain["out"])[1] > 1e-2             # the rotation changes the projected branch
+    compare_layer(res, ref, check_linear=False, label="proj+rope")
+
+
 def test_wan13_480p_rotary_sampled(oracle):
     """The rotary linear branch at the headline size: full rotated state and sampled rows against the oracle."""
     w = wl.WAN13_480P
