@@ -206,10 +206,12 @@ int salad_oracle_sparse_attn(const float *q, const float *k, const float *v,
 
 /* ---- Top-K block-sparse attention, Sec. 3 "Top-K attention", App. A.1.2 ---------------- */
 
-/* Steps 1 and 2 of App. A.1.2: the keys are cut into blocks of key_block consecutive tokens of the stored
- * order, each block is reduced to the mean of its keys, and every query token keeps the topk blocks whose
- * mean has the largest dot product with the query.  mask[(b*H + h)*N + n] has bit J set when query n keeps
- * block J (nbk = ceil(N / key_block) <= 64 blocks; topk >= nbk keeps all of them).
+/* Steps 1 and 2 of App. A.1.2: the keys are cut into blocks of key_block consecutive tokens of the head's own
+ * token order (App. A.1.1: the stored order for a spatial head, tokens grouped by location for a temporal one;
+ * head_kind == NULL: every head spatial), each block is reduced to the mean of its keys, and every query token
+ * keeps the topk blocks whose mean has the largest dot product with the query.  mask[(b*H + h)*N + n] (n = the
+ * query's stored row) has bit J set when query n keeps block J (nbk = ceil(N / key_block) <= 64 blocks;
+ * topk >= nbk keeps all of them).  Block J holds positions J key_block .. (J+1) key_block - 1 of the order.
  *
  * Here floating point decides an integer, so the decision is taken in the arithmetic the device uses for it,
  * written out step by step: float32 throughout; a block's sum is accumulated token by token in ascending order
@@ -217,9 +219,11 @@ int salad_oracle_sparse_attn(const float *q, const float *k, const float *v,
  * multiply-add; a block replaces a kept one only on a strictly larger score, so ties go to the lower index.
  * (tests pin the outcome to the float64 definition wherever the float64 scores leave a clear margin). */
 int salad_oracle_topk_select(const float *q, const float *k, int B, int H, int64_t N, int d,
-                             int key_block, int topk, uint64_t *mask)
+                             int key_block, int topk, const uint8_t *head_kind, int T, int Hh, int W, uint64_t *mask)
 {
     if (key_block <= 0 || topk <= 0 || N <= 0 || d <= 0) return SO_EINVAL;
+    if (head_kind && (T < 1 || Hh < 1 || W < 1 || (int64_t)T * Hh * W != N)) return SO_EINVAL;
+    const int64_t HW = (int64_t)Hh * W;
     const int64_t nbk = (N + key_block - 1) / key_block;
     if (nbk > 64) return SO_EINVAL;
     const int kk = topk < nbk ? topk : (int)nbk;
@@ -229,10 +233,11 @@ int salad_oracle_topk_select(const float *q, const float *k, int B, int H, int64
 #pragma omp parallel for schedule(static)
     for (int64_t e = 0; e < BH * nbk; ++e) {
         const int64_t bh = e / nbk, J = e % nbk;
+        const int kind = head_kind ? (int)head_kind[bh % H] : 0;
         const int64_t t0 = J * key_block, t1 = (t0 + key_block < N) ? t0 + key_block : N;
         for (int c = 0; c < d; ++c) {
-            volatile float sum = 0.0f;           /* volatile: one rounding per addition, in this order */
-            for (int64_t t = t0; t < t1; ++t) sum = sum + k[(bh * N + t) * d + c];
+            volatile float sum = 0.0f;           /* volatile: one rounding per addition, in this order (ascending position) */
+            for (int64_t t = t0; t < t1; ++t) sum = sum + k[(bh * N + row_of_position(kind, t, T, HW)) * d + c];
             mean[e * d + c] = sum / (float)(t1 - t0);
         }
     }
@@ -269,10 +274,12 @@ int salad_oracle_topk_select(const float *q, const float *k, int B, int H, int64
  * token-level mask: two-pass softmax in double precision over exactly those keys, logits q.k*scale.
  * rows [B, H, nrows]: stored rows to evaluate (< 0: skipped, output left zero); out [B, H, nrows, d]. */
 int salad_oracle_topk_attn(const float *q, const float *k, const float *v, int B, int H, int64_t N, int d,
-                           int key_block, const uint64_t *mask, double scale,
+                           int key_block, const uint64_t *mask, double scale, const uint8_t *head_kind, int T, int Hh, int W,
                            const int64_t *rows, int64_t nrows, double *out)
 {
     if (key_block <= 0 || N <= 0 || d <= 0) return SO_EINVAL;
+    if (head_kind && (T < 1 || Hh < 1 || W < 1 || (int64_t)T * Hh * W != N)) return SO_EINVAL;
+    const int64_t HW = (int64_t)Hh * W;
     const int64_t nbk = (N + key_block - 1) / key_block;
     if (nbk > 64) return SO_EINVAL;
     const int64_t total = (int64_t)B * H * nrows;
@@ -289,12 +296,14 @@ int salad_oracle_topk_attn(const float *q, const float *k, const float *v, int B
             if (n < 0 || n >= N) continue;
             const float *qi = q + (bh * N + n) * d;
             const uint64_t m = mask[bh * N + n];
+            const int kind = head_kind ? (int)head_kind[bh % H] : 0;
             int64_t cnt = 0;
             double mx = -INFINITY;
             for (int64_t J = 0; J < nbk; ++J) {
                 if (!((m >> J) & 1)) continue;
                 const int64_t t1 = ((J + 1) * key_block < N) ? (J + 1) * key_block : N;
-                for (int64_t t = J * key_block; t < t1; ++t) {
+                for (int64_t p = J * key_block; p < t1; ++p) {       /* positions of block J in the head's order */
+                    const int64_t t = row_of_position(kind, p, T, HW);
                     const float *kj = k + (bh * N + t) * d;
                     double acc = 0.0;
                     for (int x = 0; x < d; ++x) acc += (double)qi[x] * (double)kj[x];

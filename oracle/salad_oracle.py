@@ -230,21 +230,32 @@ def combine_proj(q, Hs, Z, eps: float, o_s, rows, w_proj, lam: float, s, rope=No
     return out
 
 
-def topk_select(q, k, key_block: int, topk: int) -> np.ndarray:
-    """App. A.1.2 steps 1-2: per query token the `topk` key blocks (runs of `key_block` stored tokens) whose mean
-    key has the largest dot product with the query, as a uint64 bit mask [B,H,N] (bit J = block J kept)."""
+def _kind_args(head_kind, grid, H):
+    """(head_kind pointer or None, T, Hh, W) for the Top-K entry points: None = every head in the stored order."""
+    if head_kind is None:
+        return None, None, 1, 1, 1
+    hk = np.ascontiguousarray(head_kind, dtype=np.uint8)
+    assert hk.shape == (H,) and grid is not None
+    return hk, _p(hk), int(grid[0]), int(grid[1]), int(grid[2])
+
+
+def topk_select(q, k, key_block: int, topk: int, head_kind=None, grid=None) -> np.ndarray:
+    """App. A.1.2 steps 1-2: per query token the `topk` key blocks (runs of `key_block` tokens of the head's own order:
+    stored order, or grouped by location for a temporal head, App. A.1.1) whose mean key has the largest dot product
+    with the query, as a uint64 bit mask [B,H,N] indexed by the query's stored row (bit J = block J kept)."""
     q, k = _f32(q), _f32(k)
     B, H, N, d = q.shape
     mask = np.zeros((B, H, N), dtype=np.uint64)
+    keep, hkp, T, Hh, W = _kind_args(head_kind, grid, H)
     rc = _load().salad_oracle_topk_select(_p(q), _p(k), C.c_int(B), C.c_int(H), C.c_int64(N), C.c_int(d),
-                                          C.c_int(key_block), C.c_int(topk), _p(mask))
+                                          C.c_int(key_block), C.c_int(topk), hkp, C.c_int(T), C.c_int(Hh), C.c_int(W), _p(mask))
     if rc != 0:
         raise ValueError("salad_oracle_topk_select: invalid arguments (more than 64 key blocks?)")
     return mask
 
 
 def topk_attn(q, k, v, key_block: int, mask, scale: Optional[float] = None,
-              rows: Optional[np.ndarray] = None) -> np.ndarray:
+              rows: Optional[np.ndarray] = None, head_kind=None, grid=None) -> np.ndarray:
     """App. A.1.2 step 3: Eq. (2) with the token-level mask of `topk_select`, on stored rows `rows` [B,H,nrows]
     (default: every row).  Returns [B,H,nrows,d] float64."""
     q, k, v = _f32(q), _f32(k), _f32(v)
@@ -255,9 +266,10 @@ def topk_attn(q, k, v, key_block: int, mask, scale: Optional[float] = None,
     mask = np.ascontiguousarray(mask, dtype=np.uint64)
     out = np.zeros((B, H, rows.shape[-1], d), dtype=np.float64)
     sc = (1.0 / np.sqrt(d)) if scale is None else float(scale)
+    keep, hkp, T, Hh, W = _kind_args(head_kind, grid, H)
     rc = _load().salad_oracle_topk_attn(_p(q), _p(k), _p(v), C.c_int(B), C.c_int(H), C.c_int64(N), C.c_int(d),
-                                        C.c_int(key_block), _p(mask), C.c_double(sc), _p(rows),
-                                        C.c_int64(rows.shape[-1]), _p(out))
+                                        C.c_int(key_block), _p(mask), C.c_double(sc), hkp, C.c_int(T), C.c_int(Hh), C.c_int(W),
+                                        _p(rows), C.c_int64(rows.shape[-1]), _p(out))
     if rc != 0:
         raise ValueError("salad_oracle_topk_attn: invalid arguments")
     return out
@@ -281,14 +293,14 @@ def salad_forward(q, k, v, x_t, w_gate, head_scale, grid, block, head_kind, kept
     T, Hh, W = grid
     row_ptr, col_idx = block_mask(T, Hh, W, block, kept)
     topk_mask = None
-    if topk > 0:   # Top-K dynamic mask (App. A.1.2) instead of the sliding window; stored token order only
+    if topk > 0:   # Top-K dynamic mask (App. A.1.2) instead of the sliding window; key blocks in each head's own order
         N = q.shape[2]
         nb = (N + block - 1) // block
         sel_b = np.arange(nb) if sel is None else np.asarray(sel)
         pos = (sel_b[:, None] * block + np.arange(block)[None, :]).reshape(-1)
         rows = np.broadcast_to(np.where(pos < N, pos, -1).astype(np.int64), q.shape[:2] + (pos.size,)).copy()
-        topk_mask = topk_select(q, k, key_block, topk)
-        o_s = topk_attn(q, k, v, key_block, topk_mask, scale, rows)
+        topk_mask = topk_select(q, k, key_block, topk, head_kind, grid)
+        o_s = topk_attn(q, k, v, key_block, topk_mask, scale, rows, head_kind, grid)
     else:
         o_s, rows = sparse_attn(q, k, v, grid, block, head_kind, row_ptr, col_idx, scale, sel)
     Hs, Z = linear_state(k, v)

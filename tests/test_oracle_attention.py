@@ -588,3 +588,40 @@ def test_full_projection_with_rotary_linear_branch(oracle):
     assert np.abs(delta[mask]).max() == 0.0
     et = oracle.salad_forward(*args, None, lam=0.8, w_proj=e.T.copy(), rope=(cs, sn), **kw)
     assert np.abs(et["out"] - oe["out"])[ok].max() > 1e-6
+
+
+def test_topk_over_the_temporal_token_order(oracle):
+    """Top-K key blocks of a temporal head are runs of its own order (App. A.1.1: tokens grouped by location).  Pin:
+    selecting and attending over keys and values that were permuted into that order by hand, with the stored-order
+    routine, gives the same mask and the same output (queries keep their stored rows); T = 1 makes both orders equal;
+    a spatial head next to a temporal one is untouched."""
+    T, Hh, W, d, kb, topk = 5, 4, 6, 8, 16, 3
+    N = T * Hh * W
+    B, H = 1, 2
+    q, k, v = _qkv(61, B, H, N, d)
+    kinds = np.array([0, 1], dtype=np.uint8)
+    mask = oracle.topk_select(q, k, kb, topk, kinds, (T, Hh, W))
+    out = oracle.topk_attn(q, k, v, kb, mask, head_kind=kinds, grid=(T, Hh, W))
+    # position p of the temporal order holds stored row (p mod T) * Hh * W + p div T
+    p = np.arange(N)
+    perm = (p % T) * (Hh * W) + p // T
+    assert sorted(perm.tolist()) == list(range(N))
+    kp, vp = k.copy(), v.copy()
+    kp[:, 1], vp[:, 1] = k[:, 1][:, perm], v[:, 1][:, perm]
+    mask_p = oracle.topk_select(q, kp, kb, topk)
+    out_p = oracle.topk_attn(q, kp, vp, kb, mask_p)
+    assert np.array_equal(mask, mask_p)
+    assert np.abs(out - out_p).max() < 1e-12
+    # the spatial head is what the stored-order routine gives on the untouched tensors
+    plain = oracle.topk_select(q, k, kb, topk)
+    assert np.array_equal(mask[:, 0], plain[:, 0]) and not np.array_equal(mask[:, 1], plain[:, 1])
+    # T = 1: the two orders coincide
+    q1, k1, v1 = _qkv(62, 1, 2, 40, d)
+    assert np.array_equal(oracle.topk_select(q1, k1, 8, 2, kinds, (1, 5, 8)), oracle.topk_select(q1, k1, 8, 2))
+    # the layer: temporal Top-K head inside salad_forward
+    w = wl.small("topk-temporal", 1, 2, 16, T, Hh, W, "f32", 0.5, seed=63)
+    inp = wl.make_inputs(w)
+    r = oracle.salad_forward(inp["q"], inp["k"], inp["v"], inp["x_t"], inp["w_gate"], inp["head_scale"], grid=(T, Hh, W),
+                             block=w.block, head_kind=kinds, kept=[1, 1], topk=topk, key_block=64)
+    want = oracle.topk_select(inp["q"], inp["k"], 64, topk, kinds, (T, Hh, W))
+    assert np.array_equal(r["topk_mask"], want)
