@@ -124,8 +124,9 @@ typedef struct salad_fwd_params {
     int32_t topk;             /* > 0: Top-K dynamic block mask (Sec. 3 "Top-K attention", App. A.1.2) instead of the
                                  CSR: every query token keeps the topk (<= 8) key blocks whose mean key has the
                                  largest dot product with it; row_ptr / col_idx are ignored (may be NULL).  Needs
-                                 dtype bf16, d = 128, all heads SPATIAL (blocks are runs of the stored order)    */
-    int32_t topk_key_block;   /* tokens per key block: a multiple of 64 with ceil(N / topk_key_block) <= 64         */
+                                 dtype bf16, d = 128.  Key blocks are runs of the head's own token order           */
+    int32_t topk_key_block;   /* tokens (positions of the head's order) per key block: a multiple of 64 with
+                                 ceil(N / topk_key_block) <= 64                                                       */
     uint64_t *topk_mask_out;  /* optional device uint64 [B,H,N]: bit J set = the query keeps key block J            */
     const float *rope_cos;    /* optional device fp32 [N, d/2] (shared by all samples and heads), with rope_sin: rotary  */
     const float *rope_sin;    /*   position embedding inside the linear branch (Sec. 4.1): cosine and sine of the angle
@@ -158,7 +159,9 @@ size_t salad_fwd_workspace_bytes(const salad_fwd_params *p);
  * to the workspace (bf16), W_p is rearranged into MFMA fragment order, and one bf16 MFMA GEMM adds lambda s_b O_l W_p
  * to O_s (fp32 accumulation, one rounding of the sum).  o_linear_dbg is not written in this mode.
  * With topk > 0 the sparse branch uses the Top-K block mask of App. A.1.2 in place of the CSR: the keys are cut into
- * blocks of topk_key_block consecutive stored tokens, each block is reduced to its mean key, every query token
+ * blocks of topk_key_block consecutive tokens of the head's own order (App. A.1.1: the stored order for a SPATIAL head,
+ * tokens grouped by location for a TEMPORAL one; the token-mask variant of salad_tune("topk_variant", 1) takes SPATIAL
+ * heads only), each block is reduced to its mean key, every query token
  * keeps the topk blocks with the largest q.mean and attends to exactly their tokens.  The selection runs on the
  * device in a fixed float32 order (block sums token by token, scores channel by channel with fused multiply-adds,
  * ties to the lower block index), so that it can be reproduced bit for bit.

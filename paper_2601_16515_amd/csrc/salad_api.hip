@@ -350,9 +350,13 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
         if (p->topk_key_block < 64 || p->topk_key_block % 64) return fail(SALAD_EINVAL, "fwd: topk_key_block = %d must be a positive multiple of 64", p->topk_key_block);
         nbk = (p->N + p->topk_key_block - 1) / p->topk_key_block;
         if (nbk > 64) return fail(SALAD_ENOTSUP, "fwd: %d key blocks above 64 (raise topk_key_block)", nbk);
-        if (p->head_kind_host)
+        if (p->head_kind_host && p->T > 1)
             for (int h = 0; h < p->H; ++h)
-                if (p->head_kind_host[h] != SALAD_HEAD_SPATIAL) return fail(SALAD_ENOTSUP, "fwd: topk works on the stored token order (head %d is not SPATIAL)", h);
+                if (p->head_kind_host[h] == SALAD_HEAD_TEMPORAL) {
+                    // key blocks of a temporal head are runs of its own order; only the regrouped path gathers them
+                    if (g_topk_variant.load() != 0) return fail(SALAD_ENOTSUP, "fwd: topk_variant 1 works on the stored token order (head %d is TEMPORAL)", h);
+                    if ((unsigned long long)p->N * (unsigned long long)p->T >= (1ull << 32)) return fail(SALAD_ENOTSUP, "fwd: topk: N * T too large for a TEMPORAL head");
+                }
         if ((size_t)tile_list_cap((p->N + 63) / 64) * 4 > 24 * 1024 || (unsigned long long)p->N * 256ull >= (1ull << 32))
             return fail(SALAD_ENOTSUP, "fwd: topk: N = %d too long for the large-tile kernel", p->N);
     }
@@ -513,7 +517,7 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
         // App. A.1.2: key-block means -> per-query selection -> per-tile visit lists; the mask never leaves the device
         float *means = (float *)(ws + w.kmeans);
         unsigned long long *mask = (unsigned long long *)(ws + w.topk_mask);
-        e = launch_kblock_mean((const u16 *)p->k, BH, p->N, p->topk_key_block, nbk, means, st);
+        e = launch_kblock_mean((const u16 *)p->k, BH, p->N, p->topk_key_block, nbk, means, kind_mask, p->H, p->T, p->Hh * p->W, st);
         if (e != hipSuccess) return give_back(), hip_fail(e, "key-block mean launch");
         e = launch_topk_select((const u16 *)p->q, means, BH, p->N, nbk, p->topk, mask, st);
         if (e != hipSuccess) return give_back(), hip_fail(e, "top-k selection launch");

@@ -112,8 +112,10 @@ hipError_t launch_sparse_attn_v2(const AttnArgs &a, hipStream_t st);   // d = 12
 hipError_t launch_sparse_attn_v5(const AttnArgs &a, hipStream_t st);   // d = 128 only
 
 // ---- Top-K dynamic mask (App. A.1.2), d = 128 bf16 ---------------------------------------------------------
-// means [BH][nbk][128] fp32: mean key of each run of key_block stored tokens (sequential fp32 sum / count)
-hipError_t launch_kblock_mean(const u16 *k, int BH, int N, int key_block, int nbk, float *means, hipStream_t st);
+// means [BH][nbk][128] fp32: mean key of each run of key_block positions of the head's own order (bit h of kind_mask:
+// temporal; sequential fp32 sum in position order / count)
+hipError_t launch_kblock_mean(const u16 *k, int BH, int N, int key_block, int nbk, float *means, unsigned long long kind_mask,
+                              int H, int T, int HW, hipStream_t st);
 // mask [BH][N]: bit J set for the topk key blocks with the largest q.mean (fp32, channels in ascending order,
 // fused multiply-add; ties to the lower index)
 hipError_t launch_topk_select(const u16 *q, const float *means, int BH, int N, int nbk, int topk,

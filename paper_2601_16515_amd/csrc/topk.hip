@@ -1,5 +1,5 @@
 // Top-K dynamic block mask (Sec. 3 "Top-K attention", App. A.1.2), d = 128, bf16.
-//   step 1  kblock_mean_kernel      mean key of every run of key_block consecutive stored tokens
+//   step 1  kblock_mean_kernel      mean key of every run of key_block consecutive tokens of the head's own order
 //   step 2  topk_select_kernel      per query token: the topk key blocks with the largest q . mean, as a 64-bit mask
 //           topk_tile_lists_kernel  per tile of 256 queries: the 64-token blocks the attention kernel has to visit
 //   step 3  the large-tile attention kernel in its token-mask mode
@@ -16,33 +16,34 @@ constexpr int D = 128;
 __device__ inline float bf16_to_f32(u16 x) { return __uint_as_float((uint32_t)x << 16); }
 }  // namespace
 
-// grid (nbk, BH), 128 threads: thread c sums channel c of the block's keys in token order.
+// grid (nbk, BH), 128 threads: thread c sums channel c of the block's keys in the order of the head's positions
+// (App. A.1.1: position p of a temporal head is stored row (p mod T) HW + p div T; a spatial head's is row p).
 __global__ __launch_bounds__(128) void kblock_mean_kernel(const u16 *__restrict__ k, int N, int key_block, int nbk,
-                                                          float *__restrict__ means)
+                                                          float *__restrict__ means, unsigned long long kind_mask, int H,
+                                                          int T, int HW)
 {
     const int J = blockIdx.x, bh = blockIdx.y, c = threadIdx.x;
     const int t0 = J * key_block, t1 = min(N, t0 + key_block);
-    const u16 *src = k + ((size_t)bh * N + t0) * D + c;
+    const bool temporal = T > 1 && ((kind_mask >> (bh % H)) & 1ull);
+    const u16 *base = k + (size_t)bh * N * D + c;
+    auto row_of = [&](int p) { return temporal ? (p % T) * HW + p / T : p; };
     float sum = 0.f;
     int t = t0;
-    for (; t + 16 <= t1; t += 16) {           // 16 independent loads in flight, added in token order
+    for (; t + 16 <= t1; t += 16) {           // 16 independent loads in flight, added in position order
         u16 x[16];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) x[i] = src[(size_t)i * D];
+        for (int i = 0; i < 16; ++i) x[i] = base[(size_t)row_of(t + i) * D];
 #pragma unroll
         for (int i = 0; i < 16; ++i) sum = __fadd_rn(sum, bf16_to_f32(x[i]));
-        src += 16 * D;
     }
-    for (; t < t1; ++t) {
-        sum = __fadd_rn(sum, bf16_to_f32(*src));
-        src += D;
-    }
+    for (; t < t1; ++t) sum = __fadd_rn(sum, bf16_to_f32(base[(size_t)row_of(t) * D]));
     means[((size_t)bh * nbk + J) * D + c] = __fdiv_rn(sum, (float)(t1 - t0));
 }
 
-hipError_t launch_kblock_mean(const u16 *k, int BH, int N, int key_block, int nbk, float *means, hipStream_t st)
+hipError_t launch_kblock_mean(const u16 *k, int BH, int N, int key_block, int nbk, float *means, unsigned long long kind_mask,
+                              int H, int T, int HW, hipStream_t st)
 {
-    hipLaunchKernelGGL(kblock_mean_kernel, dim3(nbk, BH), dim3(128), 0, st, k, N, key_block, nbk, means);
+    hipLaunchKernelGGL(kblock_mean_kernel, dim3(nbk, BH), dim3(128), 0, st, k, N, key_block, nbk, means, kind_mask, H, T, HW);
     return hipGetLastError();
 }
 

@@ -130,11 +130,19 @@ def test_fwd_null_params_and_head_kind(lib):
     assert "head_kind" in _err(lib)
 
 
-def test_topk_rejects_temporal_heads_and_ignores_csr(lib):
+def test_topk_temporal_heads_and_csr_pointers(lib):
     hk = (C.c_uint8 * 2)(0, 1)
-    p = _params(topk=2, topk_key_block=128, d=128, head_kind_host=C.cast(hk, C.c_void_p))
-    assert lib.salad_sparse_linear_attn_fwd(C.byref(p)) == sb.SALAD_ENOTSUP
-    assert "stored token order" in _err(lib)
+    # temporal heads are taken by the default (regrouped) Top-K path: the next check that fails is the workspace size
+    p = _params(topk=2, topk_key_block=128, d=128, head_kind_host=C.cast(hk, C.c_void_p), workspace_bytes=256)
+    assert lib.salad_sparse_linear_attn_fwd(C.byref(p)) == sb.SALAD_ENOSPC
+    # the token-mask variant works on the stored order only
+    assert lib.salad_tune(b"topk_variant", 1) == sb.SALAD_OK
+    try:
+        p = _params(topk=2, topk_key_block=128, d=128, head_kind_host=C.cast(hk, C.c_void_p))
+        assert lib.salad_sparse_linear_attn_fwd(C.byref(p)) == sb.SALAD_ENOTSUP
+        assert "stored token order" in _err(lib)
+    finally:
+        assert lib.salad_tune(b"topk_variant", 0) == sb.SALAD_OK
     # the CSR pointers may be null with topk: the next check that fails is a different one (workspace size)
     p = _params(topk=2, topk_key_block=128, d=128, row_ptr=None, col_idx=None, workspace_bytes=256)
     assert lib.salad_sparse_linear_attn_fwd(C.byref(p)) == sb.SALAD_ENOSPC

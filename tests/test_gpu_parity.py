@@ -480,6 +480,28 @@ def test_topk_mask_layer(oracle, topk_variant, wi, key_block, topk, variant):
         assert errors(res["out"], dense["out"])[1] < 5e-3   # two independently rounded bf16 results
 
 
+@pytest.mark.parametrize("wi,key_block,topk", [(1, 64, 4), (7, 128, 2), (5, 64, 3), (0, 64, 2)],
+                         ids=["N693-B2-kb64-k4", "N1170-kb128-k2", "T70-gt-block-k3", "N270-tail14-k2"])
+def test_topk_mask_temporal_heads(oracle, wi, key_block, topk):
+    """Top-K with temporal heads (App. A.1.1 order inside App. A.1.2): the key blocks of an odd head are runs of its
+    location-major order, so its block means, its selection and the keys it attends to differ from the stored-order
+    ones; mask bit for bit, output to the bf16 bar, ragged last key block included."""
+    w = SMALL[wi]
+    inp = wl.make_inputs(w)
+    dev = upload(w, inp)
+    kinds = wl.head_kinds(w)
+    assert kinds.any() and w.T > 1
+    kept = [1] * w.H
+    ref = _oracle_layer(oracle, w, inp, kept, kinds, topk=topk, key_block=key_block)
+    ref_stored = _oracle_layer(oracle, w, inp, kept, np.zeros(w.H, dtype=np.uint8), topk=topk, key_block=key_block)
+    assert not np.array_equal(ref["topk_mask"], ref_stored["topk_mask"])          # the order matters on these inputs
+    res = run_layer(w, inp, dev, kept, kinds, topk=topk, topk_key_block=key_block)
+    assert np.array_equal(res["topk_mask"], ref["topk_mask"])
+    compare_layer(res, ref, label=f"topk-temporal-{w.name}")
+    fast = run_layer(w, inp, dev, kept, kinds, topk=topk, topk_key_block=key_block, dbg=False)
+    compare_layer(fast, ref, label=f"topk-temporal-{w.name}-fast")
+
+
 @pytest.mark.parametrize("flags", [0, sb.SALAD_FLAG_UNFUSED_EPILOGUE], ids=["fused", "unfused"])
 @pytest.mark.parametrize("wi", [1, 7, 0, 4], ids=["N693-B2", "N1170", "N270-tail14", "N512"])
 def test_rotary_linear_branch(oracle, wi, flags):
