@@ -21,9 +21,6 @@
 // microseconds for 4.7 MB) so that the GEMM's LDS reads are lane-linear.
 #include "salad_internal.h"
 #include <type_traits>
-#ifdef SALAD_DIAG
-#include <stdlib.h>
-#endif
 
 namespace salad {
 
@@ -93,10 +90,8 @@ __device__ __forceinline__ void static_for(F &&f)
     }
 }
 
-template <int SKIP>
 __global__ __launch_bounds__(256, 2) void proj_apply_kernel(ProjArgs a)
 {
-    // SKIP (development builds only): 1 no loads in the loop, 2 no barrier, 4 no MFMA, 8 no epilogue, 16 no operand reads
     constexpr int D = 128;
     constexpr int NSTAGE = 4, PDIST = 3;              // stages; stages in flight ahead of the one in use
     constexpr int STAGE_B = 8 * 1024;                  // LDS per stage: 8 W_p fragments of 1 KB
@@ -139,12 +134,10 @@ __global__ __launch_bounds__(256, 2) void proj_apply_kernel(ProjArgs a)
     auto stage_load = [&](int kk, int i, u32x4 (&bq)[2][2]) __attribute__((always_inline)) {
         const int hi = kk >> 2, q4 = kk & 3;           // input head, quarter of its 128 channels
         if (i < 2) {
-            if (SKIP & 32) return;
             const unsigned buf = lds0 + (unsigned)(kk % NSTAGE) * STAGE_B + wave_u * 2048u;
             const size_t woff = (size_t)hi * H * (BLK * 2) + q4 * 2048;
             proj_dma16(wsrc + woff + i * 1024, lane16, buf + i * 1024u);
         } else {
-            if (SKIP & 64) return;
             const int rt = (i - 2) >> 1;
             const unsigned char *src = olb[rt] + ((size_t)hi << 13) + q4 * 2048;
             if (i & 1) asm volatile("global_load_dwordx4 %0, %1, %2 offset:1024" : "=v"(bq[rt][1]) : "v"(lane16), "s"(src) : "memory");
@@ -176,37 +169,30 @@ __global__ __launch_bounds__(256, 2) void proj_apply_kernel(ProjArgs a)
             const int kk = kk0 + u;
             // stage kk must have landed; up to PDIST - 1 newer stages (6 loads each) may stay in flight
             // (nk is a multiple of NSTAGE: only the last two steps of the last group have fewer behind them)
-            constexpr int LPS = 6 - ((SKIP & 32) ? 2 : 0) - ((SKIP & 64) ? 4 : 0);   // loads per stage (6 in the product)
-            if (SKIP & 128) { if (kk + 1 == nk) __builtin_amdgcn_s_waitcnt(0x0F70); }
-            else if (u <= 1 || kk0 + NSTAGE < nk) __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * LPS));
+            constexpr int LPS = 6;                     // loads per stage
+            if (u <= 1 || kk0 + NSTAGE < nk) __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * LPS));
             else if (u == 2) __builtin_amdgcn_s_waitcnt(0x0F70 | LPS);
             else __builtin_amdgcn_s_waitcnt(0x0F70);
             // the fragment registers are defined from here on (the loads above complete asynchronously)
             asm volatile("" : "+v"(bq[u][0][0]), "+v"(bq[u][0][1]), "+v"(bq[u][1][0]), "+v"(bq[u][1][1]));
-            if (!(SKIP & 2)) __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
             // 8 x (W_p fragment from LDS, one ahead; 2 MFMAs); the 6 loads of stage kk + PDIST (its LDS buffer was
             // read in step kk - 1, its registers too) go out one at a time between them, so that a full memory
             // queue never holds up a wave that has MFMAs to issue
-            const bool more = !(SKIP & 1) && kk + PDIST < nk;
+            const bool more = kk + PDIST < nk;
             const unsigned char *buf = smem + u * STAGE_B + aoff;
             FragP af[2];
             auto read_a = [&](int i) __attribute__((always_inline)) {      // i = sp * 4 + ct
-                if (!(SKIP & 16)) af[i & 1].u = *reinterpret_cast<const uint4 *>(buf + ((i & 3) * 2 + (i >> 2)) * 1024);
-                else { af[i & 1].u = make_uint4(kk, i, 0, 0); asm volatile("" : "+v"(af[i & 1].u.x), "+v"(af[i & 1].u.y), "+v"(af[i & 1].u.z), "+v"(af[i & 1].u.w)); }
+                af[i & 1].u = *reinterpret_cast<const uint4 *>(buf + ((i & 3) * 2 + (i >> 2)) * 1024);
             };
             read_a(0);
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 const int sp = i >> 2, ct = i & 3;
                 if (i + 1 < 8) read_a(i + 1);
-                if (!(SKIP & 4)) {
-                    acc[0][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i & 1].v, __builtin_bit_cast(bf16x8, bq[u][0][sp]), acc[0][ct], 0, 0, 0);
-                    acc[1][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i & 1].v, __builtin_bit_cast(bf16x8, bq[u][1][sp]), acc[1][ct], 0, 0, 0);
-                } else {
-                    asm volatile("" :: "v"(af[i & 1].u.x), "v"(af[i & 1].u.y), "v"(af[i & 1].u.z), "v"(af[i & 1].u.w));
-                    asm volatile("" :: "v"(bq[u][0][sp]), "v"(bq[u][1][sp]));
-                }
+                acc[0][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i & 1].v, __builtin_bit_cast(bf16x8, bq[u][0][sp]), acc[0][ct], 0, 0, 0);
+                acc[1][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i & 1].v, __builtin_bit_cast(bf16x8, bq[u][1][sp]), acc[1][ct], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
                 if (more && i < 6) stage_load(kk + PDIST, i, bq[(u + PDIST) % NSTAGE]);
                 __builtin_amdgcn_sched_barrier(0);
@@ -215,17 +201,6 @@ __global__ __launch_bounds__(256, 2) void proj_apply_kernel(ProjArgs a)
     }
     __builtin_amdgcn_s_barrier();                      // every wave is done with the stages: they become staging space
     asm volatile("" ::: "memory");
-    if (SKIP & 8) {
-        float t = 0.f;
-#pragma unroll
-        for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-            for (int ct = 0; ct < 4; ++ct)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) t += acc[rt][ct][r];
-        if (t == 12345.678f) a.out[tid] = 1;
-        return;
-    }
     // ---- out = O_s + coef * C, one rounding.  Accumulator layout (lane = row l32; register 4 g4 + t = column
     // 32 ct + 8 g4 + 4 hh + t) -> wave-private 8 KB of LDS (fp32, rows of 64 columns = 16 chunks of 16 bytes,
     // chunk ^ (row & 15)) -> row layout (8 rows x 8 chunks of 8 columns per instruction), so that O_s is read
@@ -283,20 +258,8 @@ hipError_t launch_proj_apply(const ProjArgs &a, hipStream_t st)
     static bool done[16] = {};
     const int ny = a.H, ngrp = ((a.N + 255) / 256 + 7) / 8;
     dim3 grid(8 * ny * ngrp * a.B), block(256);
-#ifdef SALAD_DIAG
-    // development builds: SALAD_PROJ_SKIP selects a stage-skipping instantiation (timing only, wrong results)
-    static bool done_v[256][16] = {};
-    const char *ev = getenv("SALAD_PROJ_SKIP");
-    const int skip = ev ? atoi(ev) : 0;
-#define PROJ_CASE(S) case S: if (hipError_t e = dyn_lds_attr_once(reinterpret_cast<const void *>(proj_apply_kernel<S>), lds, done_v[S]); e != hipSuccess) return e; \
-        hipLaunchKernelGGL(proj_apply_kernel<S>, grid, block, lds, st, a); return hipGetLastError();
-    switch (skip) {
-        PROJ_CASE(1) PROJ_CASE(2) PROJ_CASE(4) PROJ_CASE(8) PROJ_CASE(9) PROJ_CASE(11) PROJ_CASE(27) PROJ_CASE(12) PROJ_CASE(5) PROJ_CASE(40) PROJ_CASE(72) PROJ_CASE(44) PROJ_CASE(76) PROJ_CASE(24) PROJ_CASE(28) PROJ_CASE(92) PROJ_CASE(60) PROJ_CASE(128) PROJ_CASE(136) PROJ_CASE(140) PROJ_CASE(156)
-        default: break;
-    }
-#endif
-    if (hipError_t e = dyn_lds_attr_once(reinterpret_cast<const void *>(proj_apply_kernel<0>), lds, done); e != hipSuccess) return e;
-    hipLaunchKernelGGL(proj_apply_kernel<0>, grid, block, lds, st, a);
+    if (hipError_t e = dyn_lds_attr_once(reinterpret_cast<const void *>(proj_apply_kernel), lds, done); e != hipSuccess) return e;
+    hipLaunchKernelGGL(proj_apply_kernel, grid, block, lds, st, a);
     return hipGetLastError();
 }
 

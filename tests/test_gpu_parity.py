@@ -422,10 +422,16 @@ def test_branch_dropping_fp32(oracle):
     compare_layer(res, ref, check_linear=False, tol_abs=1e-4, tol_rel=1e-5, label="drop-f32")
 
 
-def test_full_projection(oracle):
+PROJ_SHAPES = [
+    SMALL[1],                                                                    # B = 2, H = 3 (odd: one output head per workgroup), N = 693
+    wl.small("proj-even-heads", 2, 4, 128, 7, 9, 11, "bf16", 0.6, seed=112),     # H = 4: two output heads per workgroup, 3 row tiles, tail
+]
+
+
+@pytest.mark.parametrize("w", PROJ_SHAPES, ids=lambda w: w.name)
+def test_full_projection(oracle, w):
     """Alg. 1 "Proj" as a full D x D matrix across heads: O_s + lambda s_b (O_l W_p), against the oracle; the
     block-diagonal W_p reproduces the per-head form; pruned samples stay the sparse branch."""
-    w = SMALL[1]                                      # B = 2, H = 3 (odd: one output-head pair is half empty), N = 693
     inp = wl.make_inputs(w)
     dev = upload(w, inp)
     kinds = wl.head_kinds(w)
@@ -529,14 +535,14 @@ def test_rotary_linear_branch(oracle, wi, flags):
     assert torch.equal(res0["out_t"], plain["out_t"])                            # identity rotation: the same bits
 
 
-def test_full_projection_with_rotary_linear_branch(oracle):
+@pytest.mark.parametrize("w", PROJ_SHAPES, ids=lambda w: w.name)
+def test_full_projection_with_rotary_linear_branch(oracle, w):
     """Alg. 1 "Proj" as a full matrix over the rotary linear branch (the paper's layer has both): the emit pass writes the
-    rotated O_l, the GEMM projects it; small shape with B = 2 and a ragged tail, against the oracle."""
-    w = SMALL[1]                                      # N = 693, B = 2, H = 3
+    rotated O_l, the GEMM projects it; small shapes with B = 2 and a ragged tail, against the oracle."""
     inp = wl.make_inputs(w)
     dev = upload(w, inp)
     kinds = wl.head_kinds(w)
-    kept = [3, 4, 3]
+    kept = [3, 4, 3, 4][:w.H]
     D = w.H * w.d
     wp = wl.round_to_bf16((wl.normal(w.seed, "w_proj", (D, D)) / np.sqrt(D) * 8.0).astype(np.float32))
     wp_dev = torch.from_numpy(wp).cuda().to(torch.bfloat16)
