@@ -122,6 +122,30 @@ int64_t salad_oracle_block_mask(int T, int Hh, int W, int block, int H,
     return nnz;
 }
 
+/* The same sliding window without the inward shift at the sequence ends: query block i of head h keeps
+ * the blocks of [i - kept/2, i - kept/2 + kept) that exist, so rows near either end are shorter.  The paper gives
+ * no formula for the window (Sec. 3 "Sliding-window attention", App. A.1.1); this is the second plain reading next
+ * to the constant-count one above.  col_idx needs at most sum_h nb*kept[h] entries.  Returns nnz, or -1. */
+int64_t salad_oracle_block_mask_truncated(int T, int Hh, int W, int block, int H,
+                                          const int32_t *kept, int32_t *row_ptr, int32_t *col_idx)
+{
+    int64_t N = (int64_t)T * Hh * W;
+    if (N <= 0 || block <= 0 || H <= 0) return -1;
+    int64_t nb = (N + block - 1) / block;
+    int64_t nnz = 0;
+    for (int h = 0; h < H; ++h) {
+        int64_t k = kept[h];
+        if (k < 1 || k > nb) return -1;
+        for (int64_t i = 0; i < nb; ++i) {
+            row_ptr[h * nb + i] = (int32_t)nnz;
+            for (int64_t j = i - k / 2; j < i - k / 2 + k; ++j)
+                if (j >= 0 && j < nb) col_idx[nnz++] = (int32_t)j;
+        }
+    }
+    row_ptr[(int64_t)H * nb] = (int32_t)nnz;
+    return nnz;
+}
+
 /* ---- sparse attention, Eq. (2) ------------------------------------------------------ */
 
 /* For the selected query blocks sel[0..nsel) of every (b, h): softmax over exactly the keys of

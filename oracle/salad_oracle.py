@@ -37,6 +37,7 @@ def _load() -> C.CDLL:
     if _lib is None:
         _lib = C.CDLL(build())
         _lib.salad_oracle_block_mask.restype = C.c_int64
+        _lib.salad_oracle_block_mask_truncated.restype = C.c_int64
         _lib.salad_oracle_row_of_position.restype = C.c_int64
         _lib.salad_oracle_kept_from_sparsity.restype = C.c_int32
     return _lib
@@ -63,16 +64,19 @@ def row_of_position(kind: int, p: int, T: int, Hh: int, W: int) -> int:
                                                     C.c_int(Hh), C.c_int(W)))
 
 
-def block_mask(T: int, Hh: int, W: int, block: int, kept: Sequence[int]) -> Tuple[np.ndarray, np.ndarray]:
-    """CSR (row_ptr [H*nb+1], col_idx [nnz]) of kept KV blocks per (head, query block)."""
+def block_mask(T: int, Hh: int, W: int, block: int, kept: Sequence[int], truncated: bool = False
+               ) -> Tuple[np.ndarray, np.ndarray]:
+    """CSR (row_ptr [H*nb+1], col_idx [nnz]) of kept KV blocks per (head, query block).  truncated: the window is
+    cut at the sequence ends instead of shifted inward."""
     kept = np.ascontiguousarray(kept, dtype=np.int32)
     H = kept.shape[0]
     N = T * Hh * W
     nb = (N + block - 1) // block
     row_ptr = np.zeros(H * nb + 1, dtype=np.int32)
     col_idx = np.zeros(int(nb * np.clip(kept, 0, nb).astype(np.int64).sum()) + 1, dtype=np.int32)
-    nnz = _load().salad_oracle_block_mask(C.c_int(T), C.c_int(Hh), C.c_int(W), C.c_int(block),
-                                          C.c_int(H), _p(kept), _p(row_ptr), _p(col_idx))
+    fn = _load().salad_oracle_block_mask_truncated if truncated else _load().salad_oracle_block_mask
+    nnz = fn(C.c_int(T), C.c_int(Hh), C.c_int(W), C.c_int(block),
+             C.c_int(H), _p(kept), _p(row_ptr), _p(col_idx))
     if nnz < 0:
         raise ValueError("invalid mask arguments")
     return row_ptr, col_idx[:nnz].copy()

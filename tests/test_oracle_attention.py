@@ -62,17 +62,18 @@ def test_dense_window_equals_library_softmax_attention(oracle, grid, block, d):
     assert np.abs(got - ref).max() < 1e-12
 
 
+@pytest.mark.parametrize("truncated", [False, True], ids=["shifted", "truncated"])
 @pytest.mark.parametrize("grid,block,kept", [((3, 5, 7), 16, [2, 3]), ((4, 6, 5), 16, [1, 4]),
                                               ((2, 9, 9), 64, [2, 1])])
-def test_sparse_equals_library_attention_with_token_mask(oracle, grid, block, kept):
+def test_sparse_equals_library_attention_with_token_mask(oracle, grid, block, kept, truncated):
     """Eq. (2): masked softmax.  The token-level boolean mask is expanded from the CSR and handed
-    to torch SDPA (float64); ragged last block and both head orders included."""
+    to torch SDPA (float64); ragged last block, both head orders and both window shapes at the sequence ends."""
     T, Hh, W = grid
     N = T * Hh * W
     nb = (N + block - 1) // block
     d = 32
     q, k, v = _qkv(12, 1, 2, N, d, scale=1.5)
-    row_ptr, col_idx = oracle.block_mask(T, Hh, W, block, kept)
+    row_ptr, col_idx = oracle.block_mask(T, Hh, W, block, kept, truncated=truncated)
     out, rows = oracle.sparse_attn(q, k, v, grid, block, [0, 1], row_ptr, col_idx)
     got = _scatter(out, rows, N)
     for h, kind in enumerate([0, 1]):

@@ -75,6 +75,56 @@ def test_window_structure(oracle, grid, kept):
         assert s[0] == 0 and s[-1] == nb - k
 
 
+@pytest.mark.parametrize("grid,kept", [((4, 16, 16), [4, 5]), ((3, 5, 7), [1, 2]), ((5, 9, 11), [3, 8]),
+                                        ((2, 8, 8), [2, 2]), ((7, 6, 10), [7, 6])])
+def test_truncated_window(oracle, grid, kept):
+    """The window cut at the sequence ends instead of shifted inward: written here as a set intersection; interior
+    rows are those of the constant-count window; the end rows lose exactly the blocks that do not exist; the number
+    of kept pairs has a closed form; and the mask is symmetric for odd window sizes (block j in the window of i exactly
+    when i is in the window of j)."""
+    T, Hh, W = grid
+    block = 64 if T * Hh * W >= 512 else 16
+    nb = (T * Hh * W + block - 1) // block
+    kept = [min(k, nb) for k in kept]
+    row_ptr, col_idx = oracle.block_mask(T, Hh, W, block, kept, truncated=True)
+    rp_c, ci_c = oracle.block_mask(T, Hh, W, block, kept)
+    assert row_ptr[0] == 0 and row_ptr[-1] == len(col_idx)
+    nnz = 0
+    for h, k in enumerate(kept):
+        member = np.zeros((nb, nb), dtype=bool)
+        for i in range(nb):
+            cols = list(col_idx[row_ptr[h * nb + i]:row_ptr[h * nb + i + 1]])
+            want = sorted(set(range(i - k // 2, i - k // 2 + k)) & set(range(nb)))
+            assert cols == want
+            assert i in cols                                   # a block always sees itself
+            member[i, cols] = True
+            if i - k // 2 >= 0 and i - k // 2 + k <= nb:       # interior: the two readings agree
+                assert cols == list(ci_c[rp_c[h * nb + i]:rp_c[h * nb + i + 1]])
+            else:
+                assert len(cols) < k
+            nnz += len(cols)
+        left, right = k // 2, k - 1 - k // 2                   # blocks on either side of the query block
+        lost = sum(range(1, left + 1)) + sum(range(1, right + 1))    # 1 + 2 + ... missing at each end
+        assert member.sum() == nb * k - lost                         # closed form: 1 + 2 + ... blocks missing at each end
+        if k % 2 == 1:
+            assert np.array_equal(member, member.T)
+    assert nnz == len(col_idx)
+
+
+def test_truncated_full_window_and_bad_arguments(oracle):
+    # kept = nb does not make the truncated window dense (its left part sticks out at the start); kept = 1 is the diagonal
+    nb = 12
+    row_ptr, col_idx = oracle.block_mask(3, 8, 8, 16, [nb], truncated=True)
+    assert list(col_idx[row_ptr[0]:row_ptr[1]]) == list(range(0, nb - nb // 2))
+    assert list(col_idx[row_ptr[nb - 1]:row_ptr[nb]]) == list(range(nb - 1 - nb // 2, nb))
+    row_ptr, col_idx = oracle.block_mask(3, 8, 8, 16, [1], truncated=True)
+    assert list(col_idx) == list(range(nb)) and list(row_ptr) == list(range(nb + 1))
+    with pytest.raises(ValueError):
+        oracle.block_mask(2, 4, 4, 16, [0], truncated=True)
+    with pytest.raises(ValueError):
+        oracle.block_mask(2, 4, 4, 16, [3], truncated=True)   # nb = 2
+
+
 def test_full_window_is_dense(oracle):
     row_ptr, col_idx = oracle.block_mask(3, 8, 8, 16, [12, 12])
     nb = 12
