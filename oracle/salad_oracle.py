@@ -289,13 +289,13 @@ def branch_drop(s, tau: float) -> np.ndarray:
 
 def salad_forward(q, k, v, x_t, w_gate, head_scale, grid, block, head_kind, kept, lam=1.0, eps=1e-6,
                   b_gate=0.0, scale=None, sel=None, s_override=None, drop_threshold=0.0,
-                  w_proj=None, topk: int = 0, key_block: int = 0, rope=None) -> Dict[str, np.ndarray]:
+                  w_proj=None, topk: int = 0, key_block: int = 0, rope=None, truncated: bool = False) -> Dict[str, np.ndarray]:
     """Whole layer (Alg. 1 from SparseAttn to the residual sum) on the selected query blocks.
 
     Returns compact row sets [B,H,nsel*block,d] for o_sparse, o_linear and out, the stored row
     index of each compact row (`rows`, -1 = beyond N), the full state (Hs, Z) and s [B]."""
     T, Hh, W = grid
-    row_ptr, col_idx = block_mask(T, Hh, W, block, kept)
+    row_ptr, col_idx = block_mask(T, Hh, W, block, kept, truncated=truncated)
     topk_mask = None
     if topk > 0:   # Top-K dynamic mask (App. A.1.2) instead of the sliding window; key blocks in each head's own order
         N = q.shape[2]
