@@ -75,6 +75,21 @@ salad_status salad_block_mask(int32_t T, int32_t Hh, int32_t W, int32_t block, i
                               int32_t *row_ptr_dev, int32_t *col_idx_dev, int64_t col_capacity,
                               void *hip_stream);
 
+/* The same mask with the other plain reading of the window at the sequence ends (the paper gives no formula, Sec. 3
+ * "Sliding-window attention", App. A.1.1): SALAD_WINDOW_SHIFTED is salad_block_mask above (every row has exactly
+ * kept[h] entries); SALAD_WINDOW_TRUNCATED keeps the blocks of [i - kept[h]/2, i - kept[h]/2 + kept[h]) that exist, so
+ * the first kept[h]/2 and the last kept[h] - 1 - kept[h]/2 rows of a head are shorter and
+ * nnz = sum_h (nb*kept[h] - l(l+1)/2 - r(r+1)/2), l = kept[h]/2, r = kept[h] - 1 - l.  The layer call takes either CSR.
+ * Arguments, ownership and errors as for salad_block_mask / salad_block_mask_nnz; an unknown window_mode is
+ * SALAD_EINVAL (-1 from the nnz function). */
+typedef enum { SALAD_WINDOW_SHIFTED = 0, SALAD_WINDOW_TRUNCATED = 1 } salad_window_mode;
+int64_t salad_block_mask_nnz_mode(int32_t T, int32_t Hh, int32_t W, int32_t block, int32_t H,
+                                  const int32_t *kept_host, int32_t window_mode);
+salad_status salad_block_mask_mode(int32_t T, int32_t Hh, int32_t W, int32_t block, int32_t H,
+                                   const int32_t *kept_host, int32_t window_mode,
+                                   int32_t *row_ptr_dev, int32_t *col_idx_dev, int64_t col_capacity,
+                                   void *hip_stream);
+
 /* Visit lists of the large-tile attention kernel (bf16, d = 128) for a CSR: for every head and every tile of 4
  * consecutive query blocks the union of the 4 rows' kept KV blocks, each entry tagged with the rows that keep it.  Like
  * the mask they depend on no activation (App. A.1.1: the sliding-window mask is static), so they can be built once per

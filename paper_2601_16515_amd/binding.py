@@ -24,6 +24,7 @@ SALAD_PHI_RELU = 0
 SALAD_FLAG_UNFUSED_EPILOGUE = 1
 
 EXPORTS = ["salad_last_error", "salad_kept_from_sparsity", "salad_block_mask_nnz", "salad_block_mask",
+           "salad_block_mask_nnz_mode", "salad_block_mask_mode",
            "salad_tile_lists_bytes", "salad_tile_lists", "salad_fwd_workspace_bytes", "salad_sparse_linear_attn_fwd", "salad_linear_state_fwd",
            "salad_gate_fwd", "salad_gate_fwd_static", "salad_timing_enable", "salad_timing_read", "salad_tune"]
 
@@ -126,6 +127,10 @@ def lib() -> C.CDLL:
         L.salad_block_mask_nnz.argtypes = [C.c_int32] * 5 + [C.c_void_p]
         L.salad_block_mask.restype = C.c_int
         L.salad_block_mask.argtypes = [C.c_int32] * 5 + [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+        L.salad_block_mask_nnz_mode.restype = C.c_int64
+        L.salad_block_mask_nnz_mode.argtypes = [C.c_int32] * 5 + [C.c_void_p, C.c_int32]
+        L.salad_block_mask_mode.restype = C.c_int
+        L.salad_block_mask_mode.argtypes = [C.c_int32] * 5 + [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
         L.salad_tile_lists_bytes.restype = C.c_size_t
         L.salad_tile_lists_bytes.argtypes = [C.c_int32, C.c_int32]
         L.salad_tile_lists.restype = C.c_int
@@ -184,9 +189,17 @@ def salad_kept_from_sparsity(nb: int, sparsity: float) -> int:
     return int(lib().salad_kept_from_sparsity(nb, sparsity))
 
 
+SALAD_WINDOW_SHIFTED, SALAD_WINDOW_TRUNCATED = 0, 1
+
+
 def salad_block_mask_nnz(T: int, Hh: int, W: int, block: int, kept: Sequence[int]) -> int:
     arr = (C.c_int32 * len(kept))(*kept)
     return int(lib().salad_block_mask_nnz(T, Hh, W, block, len(kept), arr))
+
+
+def salad_block_mask_nnz_mode(T: int, Hh: int, W: int, block: int, kept: Sequence[int], window_mode: int) -> int:
+    arr = (C.c_int32 * len(kept))(*kept)
+    return int(lib().salad_block_mask_nnz_mode(T, Hh, W, block, len(kept), arr, window_mode))
 
 
 def salad_block_mask(T: int, Hh: int, W: int, block: int, kept: Sequence[int], device="cuda"):
@@ -201,6 +214,21 @@ def salad_block_mask(T: int, Hh: int, W: int, block: int, kept: Sequence[int], d
     row_ptr = torch.empty(H * nb + 1, dtype=torch.int32, device=device)
     col_idx = torch.empty(max(nnz, 1), dtype=torch.int32, device=device)
     _check(lib().salad_block_mask(T, Hh, W, block, H, arr, row_ptr.data_ptr(), col_idx.data_ptr(), nnz, _stream()))
+    return row_ptr, col_idx[:nnz]
+
+
+def salad_block_mask_mode(T: int, Hh: int, W: int, block: int, kept: Sequence[int], window_mode: int, device="cuda"):
+    """Returns (row_ptr, col_idx) int32 device tensors for the given window shape at the sequence ends."""
+    import torch
+    H = len(kept)
+    arr = (C.c_int32 * H)(*kept)
+    nnz = lib().salad_block_mask_nnz_mode(T, Hh, W, block, H, arr, window_mode)
+    if nnz < 0:
+        raise SaladError(SALAD_EINVAL, "salad_block_mask_nnz_mode rejected the arguments")
+    nb = (T * Hh * W + block - 1) // block
+    row_ptr = torch.empty(H * nb + 1, dtype=torch.int32, device=device)
+    col_idx = torch.empty(max(nnz, 1), dtype=torch.int32, device=device)
+    _check(lib().salad_block_mask_mode(T, Hh, W, block, H, arr, window_mode, row_ptr.data_ptr(), col_idx.data_ptr(), nnz, _stream()))
     return row_ptr, col_idx[:nnz]
 
 

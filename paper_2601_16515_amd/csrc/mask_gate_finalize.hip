@@ -15,13 +15,23 @@ __global__ __launch_bounds__(256) void block_mask_kernel(MaskArgs a)
     int rows = a.H * a.nb;
     if (row > rows) return;
     if (row == rows) {
-        int h = a.H - 1;
-        a.row_ptr[rows] = (int32_t)(a.base[h] + (int64_t)a.nb * a.kept[h]);
+        a.row_ptr[rows] = (int32_t)a.total;
         return;
     }
     int h = row / a.nb;
     int i = row - h * a.nb;
     int k = a.kept[h];
+    if (a.truncated) {
+        // the blocks of [i - l, i - l + k) that exist; rows before l miss l - r' blocks (r' the row), rows after
+        // nb - 1 - r miss 1, 2, ... : the row's first entry follows in closed form
+        const int l = k / 2, r = k - 1 - l;
+        const int lo = i - l < 0 ? 0 : i - l, hi = i - l + k > a.nb ? a.nb : i - l + k;
+        const int64_t m = i < l ? i : l, t = i - (a.nb - r) > 0 ? i - (a.nb - r) : 0;
+        const int64_t off = a.base[h] + (int64_t)i * k - (m * l - m * (m - 1) / 2) - t * (t + 1) / 2;
+        a.row_ptr[row] = (int32_t)off;
+        for (int j = lo; j < hi; ++j) a.col_idx[off + (j - lo)] = j;
+        return;
+    }
     int start = i - k / 2;
     start = start < 0 ? 0 : start;
     start = start > a.nb - k ? a.nb - k : start;

@@ -168,47 +168,70 @@ int32_t salad_kept_from_sparsity(int32_t nb, double sparsity)
     return (int32_t)k;
 }
 
-int64_t salad_block_mask_nnz(int32_t T, int32_t Hh, int32_t W, int32_t block, int32_t H, const int32_t *kept_host)
+int64_t salad_block_mask_nnz_mode(int32_t T, int32_t Hh, int32_t W, int32_t block, int32_t H, const int32_t *kept_host,
+                                  int32_t window_mode)
 {
     if (T < 1 || Hh < 1 || W < 1 || block < 1 || H < 1 || !kept_host) return -1;
+    if (window_mode != SALAD_WINDOW_SHIFTED && window_mode != SALAD_WINDOW_TRUNCATED) return -1;
     const int64_t N = (int64_t)T * Hh * W;
     const int64_t nb = (N + block - 1) / block;
     int64_t nnz = 0;
     for (int h = 0; h < H; ++h) {
-        if (kept_host[h] < 1 || kept_host[h] > nb) return -1;
-        nnz += nb * kept_host[h];
+        const int64_t k = kept_host[h];
+        if (k < 1 || k > nb) return -1;
+        nnz += nb * k;
+        if (window_mode == SALAD_WINDOW_TRUNCATED) {
+            const int64_t l = k / 2, r = k - 1 - l;
+            nnz -= l * (l + 1) / 2 + r * (r + 1) / 2;
+        }
     }
     return nnz;
 }
 
-salad_status salad_block_mask(int32_t T, int32_t Hh, int32_t W, int32_t block, int32_t H,
-                              const int32_t *kept_host, int32_t *row_ptr_dev, int32_t *col_idx_dev,
-                              int64_t col_capacity, void *hip_stream)
+int64_t salad_block_mask_nnz(int32_t T, int32_t Hh, int32_t W, int32_t block, int32_t H, const int32_t *kept_host)
+{
+    return salad_block_mask_nnz_mode(T, Hh, W, block, H, kept_host, SALAD_WINDOW_SHIFTED);
+}
+
+salad_status salad_block_mask_mode(int32_t T, int32_t Hh, int32_t W, int32_t block, int32_t H,
+                                   const int32_t *kept_host, int32_t window_mode, int32_t *row_ptr_dev, int32_t *col_idx_dev,
+                                   int64_t col_capacity, void *hip_stream)
 {
     if (T < 1 || Hh < 1 || W < 1) return fail(SALAD_EINVAL, "salad_block_mask: grid (%d,%d,%d) must be positive", T, Hh, W);
     if (block != 64) return fail(SALAD_ENOTSUP, "salad_block_mask: block %d not supported (64 only)", block);
     if (H < 1 || H > 64) return fail(SALAD_ENOTSUP, "salad_block_mask: H=%d outside 1..64", H);
+    if (window_mode != SALAD_WINDOW_SHIFTED && window_mode != SALAD_WINDOW_TRUNCATED)
+        return fail(SALAD_EINVAL, "salad_block_mask: window_mode %d is neither SALAD_WINDOW_SHIFTED nor SALAD_WINDOW_TRUNCATED", (int)window_mode);
     if (!kept_host || !row_ptr_dev || !col_idx_dev) return fail(SALAD_EINVAL, "salad_block_mask: null pointer");
     const int64_t N = (int64_t)T * Hh * W;
     if (N > (1ll << 30)) return fail(SALAD_EINVAL, "salad_block_mask: N=%lld too large", (long long)N);
-    const int64_t nnz = salad_block_mask_nnz(T, Hh, W, block, H, kept_host);
+    const int64_t nnz = salad_block_mask_nnz_mode(T, Hh, W, block, H, kept_host, window_mode);
     if (nnz < 0) return fail(SALAD_EINVAL, "salad_block_mask: kept[h] must lie in 1..nb");
     if (nnz > 0x7fffffffll) return fail(SALAD_ENOTSUP, "salad_block_mask: nnz=%lld exceeds int32", (long long)nnz);
     if (col_capacity < nnz) return fail(SALAD_ENOSPC, "salad_block_mask: col_capacity %lld < nnz %lld", (long long)col_capacity, (long long)nnz);
     MaskArgs a{};
     a.nb = (int32_t)((N + block - 1) / block);
     a.H = H;
+    a.truncated = window_mode == SALAD_WINDOW_TRUNCATED;
     int64_t base = 0;
     for (int h = 0; h < H; ++h) {
         a.kept[h] = kept_host[h];
         a.base[h] = base;
-        base += (int64_t)a.nb * kept_host[h];
+        base += salad_block_mask_nnz_mode(T, Hh, W, block, 1, kept_host + h, window_mode);
     }
+    a.total = base;
     a.row_ptr = row_ptr_dev;
     a.col_idx = col_idx_dev;
     hipError_t e = launch_block_mask(a, (hipStream_t)hip_stream);
     if (e != hipSuccess) return hip_fail(e, "salad_block_mask launch");
     return SALAD_OK;
+}
+
+salad_status salad_block_mask(int32_t T, int32_t Hh, int32_t W, int32_t block, int32_t H,
+                              const int32_t *kept_host, int32_t *row_ptr_dev, int32_t *col_idx_dev,
+                              int64_t col_capacity, void *hip_stream)
+{
+    return salad_block_mask_mode(T, Hh, W, block, H, kept_host, SALAD_WINDOW_SHIFTED, row_ptr_dev, col_idx_dev, col_capacity, hip_stream);
 }
 
 size_t salad_tile_lists_bytes(int32_t H, int32_t nb)

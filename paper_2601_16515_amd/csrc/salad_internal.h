@@ -11,8 +11,10 @@ typedef unsigned short u16;
 // ---- block mask -------------------------------------------------------------------------------
 struct MaskArgs {
     int32_t nb, H;
+    int32_t truncated;  // window cut at the sequence ends instead of shifted inward
     int32_t kept[64];
     int64_t base[64];   // first col_idx entry of head h
+    int64_t total;      // number of col_idx entries
     int32_t *row_ptr, *col_idx;
 };
 hipError_t launch_block_mask(const MaskArgs &a, hipStream_t st);

@@ -47,6 +47,22 @@ def test_mask_nnz(lib):
     assert sb.salad_block_mask_nnz(0, 16, 16, 64, [1]) == -1
 
 
+def test_mask_nnz_of_the_truncated_window(lib, oracle):
+    # the closed form of the header against the oracle's count, and the mode argument's range
+    for grid, kept in (((21, 30, 52), [51] * 12), ((4, 16, 16), [4, 5]), ((5, 6, 9), [1, 5, 3]), ((3, 8, 8), [3, 3])):
+        _, ci = oracle.block_mask(*grid, 64, kept, truncated=True)
+        assert sb.salad_block_mask_nnz_mode(*grid, 64, kept, sb.SALAD_WINDOW_TRUNCATED) == len(ci)
+        assert sb.salad_block_mask_nnz_mode(*grid, 64, kept, sb.SALAD_WINDOW_SHIFTED) == sb.salad_block_mask_nnz(*grid, 64, kept)
+    assert sb.salad_block_mask_nnz_mode(4, 16, 16, 64, [4, 4], 2) == -1
+    assert sb.salad_block_mask_nnz_mode(4, 16, 16, 64, [4, 17], sb.SALAD_WINDOW_TRUNCATED) == -1
+    kept = (C.c_int32 * 2)(4, 4)
+    fake = 0x1000   # never dereferenced
+    assert lib.salad_block_mask_mode(4, 16, 16, 64, 2, kept, 7, fake, fake, 128, None) == sb.SALAD_EINVAL
+    assert "window_mode" in lib.salad_last_error().decode()
+    assert lib.salad_block_mask_mode(4, 16, 16, 64, 2, kept, sb.SALAD_WINDOW_TRUNCATED, fake, fake, 119, None) == sb.SALAD_ENOSPC    # nnz = 120
+    assert lib.salad_block_mask_mode(4, 16, 16, 64, 2, kept, sb.SALAD_WINDOW_TRUNCATED, None, fake, 128, None) == sb.SALAD_EINVAL
+
+
 def _err(lib):
     return lib.salad_last_error().decode()
 

@@ -33,6 +33,42 @@ def test_block_mask_bit_exact(oracle, grid, kept):
     assert np.array_equal(col_idx.cpu().numpy(), ci)
 
 
+@pytest.mark.parametrize("grid,kept", [
+    ((4, 16, 16), [4, 5]), ((5, 6, 9), [1, 5, 3]), ((21, 30, 52), [51] * 12), ((21, 30, 52), [512, 1, 26, 255]),
+    ((1, 1, 1), [1]), ((21, 45, 80), [118] * 40),
+])
+def test_block_mask_truncated_bit_exact(oracle, grid, kept):
+    """The window cut at the sequence ends (rows of different lengths, first entries in closed form) against the oracle."""
+    say(f"truncated mask grid={grid} kept[0]={kept[0]} H={len(kept)}")
+    row_ptr, col_idx = sb.salad_block_mask_mode(*grid, 64, kept, sb.SALAD_WINDOW_TRUNCATED)
+    torch.cuda.synchronize()
+    rp, ci = oracle.block_mask(*grid, 64, kept, truncated=True)
+    assert np.array_equal(row_ptr.cpu().numpy(), rp)
+    assert np.array_equal(col_idx.cpu().numpy(), ci)
+    assert sb.salad_block_mask_nnz_mode(*grid, 64, kept, sb.SALAD_WINDOW_TRUNCATED) == len(ci)
+    same = sb.salad_block_mask_mode(*grid, 64, kept, sb.SALAD_WINDOW_SHIFTED)
+    ref = sb.salad_block_mask(*grid, 64, kept)
+    assert torch.equal(same[0], ref[0]) and torch.equal(same[1], ref[1])
+
+
+def test_layer_with_truncated_window(oracle):
+    """The layer on the truncated-window mask built on the device (short rows at both ends of every head, both head
+    orders, prebuilt visit lists) against the oracle on its own truncated mask."""
+    w = SMALL[7]                                      # N = 1170: 19 blocks, 3 heads
+    inp = wl.make_inputs(w)
+    dev = upload(w, inp)
+    kinds = wl.head_kinds(w)
+    kept = [4, 7, 5]
+    row_ptr, col_idx = sb.salad_block_mask_mode(w.T, w.Hh, w.W, 64, kept, sb.SALAD_WINDOW_TRUNCATED)
+    csr = (row_ptr.cpu().numpy(), col_idx.cpu().numpy())
+    ref = _oracle_layer(oracle, w, inp, kept, kinds, truncated=True)
+    assert np.array_equal(csr[0], ref["row_ptr"]) and np.array_equal(csr[1], ref["col_idx"])
+    res = run_layer(w, inp, dev, kept, kinds, csr=csr)
+    compare_layer(res, ref, label="truncated window")
+    fast = run_layer(w, inp, dev, kept, kinds, csr=csr, dbg=False, prebuilt_lists=True)
+    assert np.array_equal(fast["out"], res["out"])
+
+
 # --------------------------------------------------------------------------------------------- gate
 
 @pytest.mark.parametrize("B,N,D,dtype", [(1, 1024, 128, "f32"), (2, 270, 1536, "bf16"), (1, 4099, 5120, "bf16"),
