@@ -249,9 +249,10 @@ salad_status salad_timing_read(salad_kernel_times *out, int32_t reset);
  * "state_wgs" between salad_fwd_workspace_bytes and the call gets SALAD_ENOSPC from the call's own size check.
  *   "state_wgs"     1..65536 (default 256): target workgroup count of the linear-state kernel (changes the workspace
  *                   size: query salad_fwd_workspace_bytes again after setting it).
- *   "attn_variant"  0 (default): the d = 128 bf16 attention kernel is chosen by shape (256-query tiles, falling back
- *                   to 128-query tiles when the block list does not fit); 1: always 128-query tiles; 2: the
- *                   first-generation kernel (the one d = 64 uses).  Same results within the parity bar.
+ *   "attn_variant"  0 (default): the bf16 attention kernel is chosen by shape (256-query tiles for d = 128 and
+ *                   d = 64, falling back to 128-query tiles at d = 128, to the first-generation kernel at d = 64,
+ *                   when the block list does not fit); 1: never 256-query tiles; 2: the first-generation kernel.
+ *                   Same results within the parity bar.
  *   "topk_variant"  0 (default): Top-K attention regrouped by key block (queries that keep a block are gathered,
  *                   partial results merged); 1: token mask applied on ordinary query tiles. */
 salad_status salad_tune(const char *key, int32_t value);

@@ -64,7 +64,7 @@ WsLayout ws_layout(int B, int H, int N, int d, int dtype, int state_wgs, bool fu
     w.drop = off; off = align256(off + sizeof(int32_t) * B);
     {   // union lists per (head, 4-block tile) for the large-tile attention kernel
         const int nb = (N + 63) / 64, ntiles = (nb + 3) / 4;
-        const bool need = dtype == SALAD_BF16 && d == 128 && (size_t)tile_list_cap(nb) * 4 <= 24 * 1024;
+        const bool need = dtype == SALAD_BF16 && (d == 128 || (d == 64 && !topk)) && (size_t)tile_list_cap(nb) * 4 <= 24 * 1024;
         const size_t nl = topk ? BH : (size_t)H;       // Top-K masks differ between samples
         w.tile_lists = off; off = align256(off + (need ? sizeof(uint32_t) * nl * ntiles * tile_list_cap(nb) : 0));
         w.tile_counts = off; off = align256(off + (need ? sizeof(int32_t) * nl * ntiles : 0));
@@ -411,7 +411,7 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
     bool temporal_any = false;
     if (p->head_kind_host && p->T > 1)
         for (int h = 0; h < p->H; ++h) temporal_any |= p->head_kind_host[h] == SALAD_HEAD_TEMPORAL;
-    const bool large_tile = p->dtype == SALAD_BF16 && p->d == 128 && attn_variant == 0 &&
+    const bool large_tile = p->dtype == SALAD_BF16 && (p->d == 128 || p->d == 64) && attn_variant == 0 &&
                             (size_t)tile_list_cap((p->N + 63) / 64) * 4 <= 24 * 1024 && (unsigned long long)p->N * 256ull < (1ull << 32) &&
                             (!temporal_any || (unsigned long long)p->N * (unsigned long long)p->T < (1ull << 32));
     const bool rope_fused = rope && large_tile && !topk && !p->w_proj && !(p->flags & SALAD_FLAG_UNFUSED_EPILOGUE);
@@ -425,7 +425,7 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
         if (p->head_scale) return fail(SALAD_EINVAL, "fwd: w_proj and head_scale exclude each other");
     }
     const WsLayout w = ws_layout(p->B, p->H, p->N, p->d, p->dtype, state_wgs, p->w_proj != nullptr, topk ? p->topk : 0, p->rope_cos != nullptr);
-    const bool need_lists = p->dtype == SALAD_BF16 && p->d == 128 && (size_t)tile_list_cap((p->N + 63) / 64) * 4 <= 24 * 1024;
+    const bool need_lists = p->dtype == SALAD_BF16 && (p->d == 128 || p->d == 64) && (size_t)tile_list_cap((p->N + 63) / 64) * 4 <= 24 * 1024;
     if (use_linear || need_lists) {
         if (!p->workspace || ((uintptr_t)p->workspace & 255)) return fail(SALAD_EINVAL, "fwd: workspace null or not 256-byte aligned");
         if (p->workspace_bytes < w.total) return fail(SALAD_ENOSPC, "fwd: workspace %zu < %zu bytes", p->workspace_bytes, w.total);

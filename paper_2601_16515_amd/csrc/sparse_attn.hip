@@ -313,8 +313,8 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_bf16_kernel(AttnArgs a, in
 
 bool attn_takes_large_tile(const AttnArgs &a)
 {
-    if (a.D != 128 || !a.tile_lists) return false;
-    if (a.topk_mask) return true;
+    if ((a.D != 128 && a.D != 64) || !a.tile_lists) return false;
+    if (a.topk_mask) return a.D == 128;
     const bool temporal = a.kind_mask != 0 && a.T > 1;
     return a.variant == 0 && (size_t)tile_list_cap(a.nb) * 4 <= 24 * 1024 && (unsigned long long)a.N * 256ull < (1ull << 32) &&
            (!temporal || a.t_magic != 0);
@@ -329,14 +329,14 @@ hipError_t launch_sparse_attn_bf16(const AttnArgs &a, hipStream_t st)
         if (a.D != 128 || !a.tile_lists) return hipErrorInvalidValue;
         return launch_sparse_attn_v5(a, st);
     }
-    if (a.D == 128 && variant != 2) {
+    if (variant != 2) {
         // the large-tile kernel addresses rows with 32-bit byte offsets and divides by T with a
         // multiply (t_magic); a T = 1 grid makes the temporal order the identity
         const bool temporal = a.kind_mask != 0 && a.T > 1;
         const bool fits = (size_t)tile_list_cap(a.nb) * 4 <= 24 * 1024 && (unsigned long long)a.N * 256ull < (1ull << 32) &&
                           (!temporal || a.t_magic != 0);
         if (variant == 0 && fits && a.tile_lists) return launch_sparse_attn_v5(a, st);
-        return launch_sparse_attn_v2(a, st);
+        if (a.D == 128) return launch_sparse_attn_v2(a, st);
     }
     const int ntiles = (a.nb + 1) / 2;
     const int total = a.B * a.H * ntiles;

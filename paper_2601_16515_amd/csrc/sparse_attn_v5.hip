@@ -1,8 +1,8 @@
 // Block-sparse softmax attention (Eq. (2)) with the fused linear apply / scale / sum epilogue,
-// d = 128.  Large tile, deep LDS prefetch, ping-pong wave groups.
+// d = 128 (and d = 64 on half-size tiles).  Large tile, deep LDS prefetch, ping-pong wave groups.
 //
 //   * One workgroup = 8 waves = 256 query positions = 4 CSR rows of one (batch, head); one workgroup
-//     per CU (LDS: 4 K + 5 V tiles of 16 KB plus the block list).
+//     per CU (LDS: 4 K + 5 V tiles of 16 KB plus the block list; registers at d = 64, where the tiles are 8 KB).
 //   * The ascending union of the 4 rows' kept-block lists is built once per workgroup in LDS (bitmap +
 //     ballot compaction), each entry carrying a 4-bit "kept by query block i" mask.  The main loop
 //     reads one entry per iteration from LDS; no global or scalar load sits on its critical path.
@@ -196,10 +196,16 @@ hipError_t launch_tile_lists(const int32_t *row_ptr, const int32_t *col_idx, int
 //   sum_j (R_j relu(K_j))^T V_j, and the epilogue rotates this tile's relu(Q) fragments in registers (channel pair
 //   (2p, 2p+1) of the query's stored row n by the angle word a.rope_tab[n * 64 + p] = fp16 cos | fp16 sin << 16) after
 //   the normaliser has been taken from the unrotated features.
-template <int PD, bool DBG, int MODE = 0, bool ROPE = false>
+// D = 64 (MODE 0 without ROPE only): the same kernel on half-size tiles.  A row is 8 chunks of 16 bytes instead of 16,
+// so one pass of the 512 threads fetches a whole 64-row tile, the swizzles below take the row pair instead of the row
+// (rows 128 bytes apart alternate between the two halves of the banks), and every fragment count halves.
+template <int D, int PD, bool DBG, int MODE = 0, bool ROPE = false>
 __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int ntiles, int total, int per_xcd, int list_cap)
 {
-    constexpr int D = 128, NS = 8, NDT = 4;
+    static_assert(D == 128 || (D == 64 && MODE == 0 && !ROPE), "d = 64 has the CSR mode only");
+    constexpr int NS = D / 16, NDT = D / 32;     // 16-channel steps of S, 32-channel tiles of O^T
+    constexpr int CH = D / 8;                    // 16-byte chunks per row
+    constexpr int RPP = 512 / CH, NPASS = 64 / RPP;   // rows per pass of the 512 threads over a tile, passes per tile
     constexpr int TILE = 64 * D;                 // elements
     constexpr int NK = PD + 1, NV = PD + 2;
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
@@ -208,6 +214,9 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
     uint32_t *blist = reinterpret_cast<uint32_t *>(Vb + NV * TILE);      // [list_cap] union list: blk | mask << 24
 
     constexpr bool TOPK = MODE == 1, GATHER = MODE == 2;
+    // chunk swizzles of the K tile, the V tile and the output staging as functions of the row
+    auto kswz = [](int row) INL -> int { return D == 128 ? (row & 15) : ((row >> 1) & 7); };
+    auto vswz = [](int row) INL -> int { return D == 128 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2); };
     const int g = blockIdx.x;
     const int L = (g & 7) * per_xcd + (g >> 3);
     if (L >= total) return;
@@ -281,11 +290,11 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
 
     const float c2 = a.scale * 1.44269504088896340736f;   // logits are handled in the log2 domain
 
-    // ---- global -> LDS: thread owns LDS slots (row 32 i + tid/16, chunk tid%16), i = 0, 1, of a tile.
+    // ---- global -> LDS: thread owns LDS slots (row RPP i + tid/CH, chunk tid%CH), i < NPASS, of a tile.
     // LDS destinations are wave-uniform scalars; global sources are a uniform base plus a 32-bit offset.
-    const int lr = tid >> 4, pc = tid & 15;
-    const unsigned kchunk_b = (unsigned)((pc ^ (lr & 15)) * 16);
-    const unsigned vchunk_b = (unsigned)((pc ^ ((lr & 3) << 2)) * 16);
+    const int lr = tid / CH, pc = tid % CH;
+    const unsigned kchunk_b = (unsigned)((pc ^ kswz(lr)) * 16);
+    const unsigned vchunk_b = (unsigned)((pc ^ vswz(lr)) * 16);
     const unsigned wave_u = (unsigned)__builtin_amdgcn_readfirstlane(wave);
     const unsigned k_lds0 = lds_addr_of(Kb) + wave_u * 1024u;
     const unsigned v_lds0 = lds_addr_of(Vb) + wave_u * 1024u;
@@ -293,8 +302,8 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
         const unsigned kl = k_lds0 + (unsigned)kslot * (unsigned)(TILE * 2);
         const unsigned vl = v_lds0 + (unsigned)vslot * (unsigned)(TILE * 2);
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            int p = blk * 64 + i * 32 + lr;
+        for (int i = 0; i < NPASS; ++i) {
+            int p = blk * 64 + i * RPP + lr;
             p = p < N ? p : N - 1;
             const unsigned row_b = (unsigned)row_of_position5(kind, p, T, HW, magic) * (unsigned)(D * 2);
             lds_dma16_base(kb, row_b + kchunk_b, kl + i * 8192u);
@@ -310,13 +319,13 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
     const int kappa = (l32 & 0x13) | ((l32 & 4) << 1) | ((l32 & 8) >> 1);
     int koff[NS];
 #pragma unroll
-    for (int st = 0; st < NS; ++st) koff[st] = kappa * D + (((2 * st + hh) ^ (kappa & 15)) << 3);
+    for (int st = 0; st < NS; ++st) koff[st] = kappa * D + (((2 * st + hh) ^ kswz(kappa)) << 3);
     const int vr = 8 * hh + ((l32 >> 2) & 3);
     int voff[NDT];
 #pragma unroll
     for (int dt = 0; dt < NDT; ++dt) {
         int chunk = 4 * dt + 2 * (l32 >> 4) + ((l32 & 3) >> 1);
-        voff[dt] = vr * D + ((chunk ^ ((vr & 3) << 2)) << 3) + 4 * (l32 & 1);
+        voff[dt] = vr * D + ((chunk ^ vswz(vr)) << 3) + 4 * (l32 & 1);
     }
 
     f32x16 o[NDT];
@@ -338,21 +347,22 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
     // phase, once the V tile they come from is known to have landed.
     constexpr int RING = 7;
     Frag5 ring[RING];
+    constexpr int NPV = 4 * NDT, NSTEP = NPV + 2 * NS;     // PV steps (4 key groups x NDT), all steps of a block
     auto read_frag = [&](int i, const u16 *Vt, const u16 *Kt, Frag5 &f) INL {
-        if (i < 16) {
-            const u16 *vp = Vt + (i >> 2) * 16 * D + voff[i & 3];
+        if (i < NPV) {
+            const u16 *vp = Vt + (i / NDT) * 16 * D + voff[i % NDT];
             f.h[0] = TR_READ(vp);
             f.h[1] = TR_READ(vp + 4 * D);
         } else {
-            const int t = i - 16;
+            const int t = i - NPV;
             f.v = *reinterpret_cast<const bf16x8 *>(Kt + (t & 1) * 32 * D + koff[t >> 1]);
         }
     };
     auto mfma_step = [&](int i, const Frag5 &f) INL {
-        if (i < 16) {
-            o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.v, pf[i >> 2].v, o[i & 3], 0, 0, 0);
+        if (i < NPV) {
+            o[i % NDT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.v, pf[i / NDT].v, o[i % NDT], 0, 0, 0);
         } else {
-            const int t = i - 16, kt = t & 1, st = t >> 1;
+            const int t = i - NPV, kt = t & 1, st = t >> 1;
             if (st == 0) {
                 f32x16 z;
 #pragma unroll
@@ -376,12 +386,12 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
             __builtin_amdgcn_sched_barrier(0);
         }
     };
-    auto stage_PV_S = [&](const u16 *Vt, const u16 *Kt) INL { run_steps(Vt, Kt, 0, 32); };
-    auto stage_PV = [&](const u16 *Vt) INL { run_steps(Vt, nullptr, 0, 16); };
+    auto stage_PV_S = [&](const u16 *Vt, const u16 *Kt) INL { run_steps(Vt, Kt, 0, NSTEP); };
+    auto stage_PV = [&](const u16 *Vt) INL { run_steps(Vt, nullptr, 0, NPV); };
     auto stage_S = [&](const u16 *Kt) INL {          // rare (first block of a row, blocks another row's mask drops)
 #pragma unroll
-        for (int i = 0; i < RING; ++i) read_frag(16 + i, nullptr, Kt, ring[(16 + i) % RING]);
-        run_steps(nullptr, Kt, 16, 32);
+        for (int i = 0; i < RING; ++i) read_frag(NPV + i, nullptr, Kt, ring[(NPV + i) % RING]);
+        run_steps(nullptr, Kt, NPV, NSTEP);
     };
     auto stage_softmax = [&](uint32_t e) INL {
         const int blk = (int)(e & BLKMASK);
@@ -454,10 +464,10 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
 
     const bool lin = !GATHER && a.use_linear && !a.write_sparse_only && !(a.drop && a.drop[bh / a.H]);   // pruned sample (Sec. 4.3): out = O_s
     const u16 *hf = a.hfrag + (size_t)bh * D * D;
-    // 32 KB of linear-state fragments for the epilogue, staged into the K ring once it is idle
+    // the D x D linear-state fragments (32 KB at d = 128) for the epilogue, staged into the K ring once it is idle
     auto stage_state = [&]() INL {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) lds_dma16(hf + (size_t)(i * 512 + tid) * 8, lds_addr_of(Kb + (i * 512 + wave * 64) * 8));
+        for (int i = 0; i < D * D / (512 * 8); ++i) lds_dma16(hf + (size_t)(i * 512 + tid) * 8, lds_addr_of(Kb + (i * 512 + wave * 64) * 8));
     };
 
     // ROPE: this lane's 32 angle words (its query's row of the table: pairs 8 st + 4 hh + j), fetched under the last
@@ -490,9 +500,10 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
             {
                 int newer = n - 1 - j;
                 if (newer > PD - 1) newer = PD - 1;
-                if (newer >= 3) WAIT_VM(12);
-                else if (newer == 2) WAIT_VM(8);
-                else if (newer == 1) WAIT_VM(4);
+                constexpr int LPB = 2 * NPASS;          // loads per lane and block (K and V, NPASS each)
+                if (newer >= 3) WAIT_VM(3 * LPB);
+                else if (newer == 2) WAIT_VM(2 * LPB);
+                else if (newer == 1) WAIT_VM(LPB);
                 else WAIT_VM(0);
             }
             __builtin_amdgcn_s_barrier();
@@ -610,7 +621,8 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
         // r * 256 + ((c ^ (r & 15)) << 4) -> row layout (4 rows x 16 chunks per instruction).
         int vs = v_last + 1 + (wave >> 1);
         if (vs >= NV) vs -= NV;
-        unsigned char *stg = reinterpret_cast<unsigned char *>(Vb + vs * TILE) + (wave & 1) * 8192;
+        constexpr int ROWB = D * 2;          // bytes of a row
+        unsigned char *stg = reinterpret_cast<unsigned char *>(Vb + vs * TILE) + (wave & 1) * (32 * ROWB);
 #pragma unroll
         for (int dt = 0; dt < NDT; ++dt)
 #pragma unroll
@@ -624,17 +636,18 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
                 uint2 pk;
                 pk.x = pack2e(ov[0], ov[1]);
                 pk.y = pack2e(ov[2], ov[3]);
-                *reinterpret_cast<uint2 *>(stg + l32 * 256 + (((dt * 4 + g4) ^ (l32 & 15)) << 4) + hh * 8) = pk;
+                *reinterpret_cast<uint2 *>(stg + l32 * ROWB + (((dt * 4 + g4) ^ kswz(l32)) << 4) + hh * 8) = pk;
             }
         asm volatile("" ::: "memory");       // the wave's LDS operations execute in order
         // destination of row r: the stored row (or the pair slot) of the lane that owns query r
         const int dest_mine = !qvalid ? -1 : GATHER ? g_slot0 + wave * 32 + l32 : qrow;
-        const int r4 = lane >> 4, c16 = lane & 15;
+        constexpr int RPI = 64 / CH;          // rows per store instruction (4 rows x 16 chunks, or 8 x 8)
+        const int r4 = lane / CH, c16 = lane % CH;
         u16 *dbase = GATHER ? a.g_po + (size_t)bh * N * a.g_kk * D : reinterpret_cast<u16 *>(a.out) + (size_t)bh * N * D;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int r = 4 * i + r4;
-            const uint4 v = *reinterpret_cast<const uint4 *>(stg + r * 256 + ((c16 ^ (r & 15)) << 4));
+        for (int i = 0; i < 32 / RPI; ++i) {
+            const int r = RPI * i + r4;
+            const uint4 v = *reinterpret_cast<const uint4 *>(stg + r * ROWB + ((c16 ^ kswz(r)) << 4));
             const int dest = __shfl(dest_mine, r);
             if (dest >= 0) *reinterpret_cast<uint4 *>(dbase + (size_t)dest * D + c16 * 8) = v;
         }
@@ -669,18 +682,18 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
     }
 }
 
-template <int PD, bool DBG, int MODE = 0, bool ROPE = false>
+template <int PD, bool DBG, int MODE = 0, bool ROPE = false, int D = 128>
 static hipError_t launch_v5(const AttnArgs &a, hipStream_t st)
 {
     const int ntiles = (a.nb + 3) / 4;
     const int total = MODE == 2 ? a.g_max_tiles : a.B * a.H * ntiles;
     const int per_xcd = (total + 7) / 8;
     const int list_cap = (a.nb + 63) & ~63;
-    const size_t lds = (size_t)(2 * PD + 3) * 64 * 128 * 2 + (size_t)list_cap * 4;
-    static_assert(PD + 1 >= 4, "the epilogue stages 64 KB of state fragments in the K ring");
+    const size_t lds = (size_t)(2 * PD + 3) * 64 * D * 2 + (size_t)list_cap * 4;
+    static_assert(PD + 1 >= 2, "the epilogue stages the state fragments (two tiles' worth) in the K ring");
     constexpr int kMaxDyn = 160 * 1024 - 2048;   // the static part is rounded up to its 1 KB alignment
     if (lds > (size_t)kMaxDyn) return hipErrorInvalidValue;
-    auto kern = sparse_attn_v5_kernel<PD, DBG, MODE, ROPE>;
+    auto kern = sparse_attn_v5_kernel<D, PD, DBG, MODE, ROPE>;
     static bool attr_done[16] = {};
     if (hipError_t e = dyn_lds_attr_once(reinterpret_cast<const void *>(kern), kMaxDyn, attr_done); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(512), lds, st, a, ntiles, total, per_xcd, list_cap);
@@ -690,6 +703,10 @@ static hipError_t launch_v5(const AttnArgs &a, hipStream_t st)
 hipError_t launch_sparse_attn_v5(const AttnArgs &a, hipStream_t st)
 {
     const bool dbg = a.o_sparse_dbg || a.o_linear_dbg;
+    if (a.D == 64) {
+        if (a.g_desc || a.topk_mask || a.rope_tab) return hipErrorInvalidValue;
+        return dbg ? launch_v5<3, true, 0, false, 64>(a, st) : launch_v5<3, false, 0, false, 64>(a, st);
+    }
     if (a.g_desc) return launch_v5<3, false, 2>(a, st);
     if (a.topk_mask) return dbg ? launch_v5<3, true, 1>(a, st) : launch_v5<3, false, 1>(a, st);
     if (a.rope_tab) return dbg ? launch_v5<3, true, 0, true>(a, st) : launch_v5<3, false, 0, true>(a, st);

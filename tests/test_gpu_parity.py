@@ -747,6 +747,23 @@ def test_mid_config_sampled(oracle):
     _sampled_parity(oracle, wl.MID, 12, "mid")
 
 
+def test_d64_large_tile_kernel_sampled(oracle):
+    """bf16 d = 64 on the large-tile kernel at a size that fills the chip (N = 12480: 195 blocks, tail 0, 24 heads,
+    odd heads temporal): sampled query blocks against the oracle, the benchmark launch bit-equal to the call with
+    per-branch outputs, prebuilt visit lists bit-equal too, and the first-generation d = 64 kernel (the fallback,
+    selected through the knob) within the same bars."""
+    w = wl.small("d64-mid", 1, 24, 64, 8, 30, 52, "bf16", 0.75, seed=113)
+    res, ref, inp, dev, kinds, kept = _sampled_parity(oracle, w, 10, "d64-mid")
+    pre = run_layer(w, inp, dev, kept, kinds, dbg=False, prebuilt_lists=True)
+    assert np.array_equal(pre["out"], res["out"])
+    sb.salad_tune("attn_variant", 2)
+    try:
+        old = run_layer(w, inp, dev, kept, kinds)
+    finally:
+        sb.salad_tune("attn_variant", 0)
+    compare_layer(old, ref, label="d64-mid/first-generation")
+
+
 @pytest.mark.timeout(600)
 def test_wan13_480p_90_sampled(oracle):
     """The headline configuration at full size, in the launch configuration the benchmark times; the oracle
