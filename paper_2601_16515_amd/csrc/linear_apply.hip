@@ -315,14 +315,14 @@ hipError_t launch_linear_apply_bf16(const ApplyArgs &a, hipStream_t st)
         if (hipError_t e = dyn_lds_attr_once(kerns[var], lds, done[var]); e != hipSuccess) return e;
         const dim3 grid_r(grid.y, grid.x);     // rotary variants: sample-head index fastest
         switch (var) {
-        case 0: hipLaunchKernelGGL((linear_apply128_kernel<false, false, false>), grid, block, lds, st, a, rows_per_wg); break;
-        case 1: hipLaunchKernelGGL((linear_apply128_kernel<true, false, false>), grid, block, lds, st, a, rows_per_wg); break;
-        case 2: hipLaunchKernelGGL((linear_apply128_kernel<false, true, false>), grid, block, lds, st, a, rows_per_wg); break;
-        case 3: hipLaunchKernelGGL((linear_apply128_kernel<false, false, true>), grid_r, block, lds, st, a, rows_per_wg); break;
-        case 4: hipLaunchKernelGGL((linear_apply128_kernel<true, false, true>), grid_r, block, lds, st, a, rows_per_wg); break;
-        default: hipLaunchKernelGGL((linear_apply128_kernel<false, true, true>), grid_r, block, lds, st, a, rows_per_wg); break;
+        case 0: launch_kernel((linear_apply128_kernel<false, false, false>), grid, block, lds, st, a, rows_per_wg); break;
+        case 1: launch_kernel((linear_apply128_kernel<true, false, false>), grid, block, lds, st, a, rows_per_wg); break;
+        case 2: launch_kernel((linear_apply128_kernel<false, true, false>), grid, block, lds, st, a, rows_per_wg); break;
+        case 3: launch_kernel((linear_apply128_kernel<false, false, true>), grid_r, block, lds, st, a, rows_per_wg); break;
+        case 4: launch_kernel((linear_apply128_kernel<true, false, true>), grid_r, block, lds, st, a, rows_per_wg); break;
+        default: launch_kernel((linear_apply128_kernel<false, true, true>), grid_r, block, lds, st, a, rows_per_wg); break;
         }
-        return hipGetLastError();
+        return take_launch_status();
     }
     // rows per workgroup (a multiple of 128): about two workgroups per CU, so that the 2*d*d*2 bytes of
     // state fragments staged in LDS are reused over many rows
@@ -330,8 +330,8 @@ hipError_t launch_linear_apply_bf16(const ApplyArgs &a, hipStream_t st)
     int rows_per_wg = (int)((rows + 127) / 128) * 128;
     if (rows_per_wg < 128) rows_per_wg = 128;
     dim3 grid((a.N + rows_per_wg - 1) / rows_per_wg, a.BH), block(256);
-    hipLaunchKernelGGL(linear_apply_kernel<64>, grid, block, 0, st, a, rows_per_wg);
-    return hipGetLastError();
+    launch_kernel(linear_apply_kernel<64>, grid, block, 0, st, a, rows_per_wg);
+    return take_launch_status();
 }
 
 }  // namespace salad

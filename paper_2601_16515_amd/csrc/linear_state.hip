@@ -232,14 +232,14 @@ hipError_t launch_state_partial_bf16(const u16 *k, const u16 *v, int BH, int N, 
     dim3 grid(P, BH), block(256);
     if (rope_tab) {
         if (D != 128) return hipErrorInvalidValue;
-        hipLaunchKernelGGL((state_partial_kernel<128, true>), dim3(BH, P), block, 0, st, k, v, N, tpc, P, partial, drop, H, rope_tab);
-        return hipGetLastError();
+        launch_kernel((state_partial_kernel<128, true>), dim3(BH, P), block, 0, st, k, v, N, tpc, P, partial, drop, H, rope_tab);
+        return take_launch_status();
     }
     if (D == 128)
-        hipLaunchKernelGGL((state_partial_kernel<128, false>), grid, block, 0, st, k, v, N, tpc, P, partial, drop, H, nullptr);
+        launch_kernel((state_partial_kernel<128, false>), grid, block, 0, st, k, v, N, tpc, P, partial, drop, H, nullptr);
     else
-        hipLaunchKernelGGL((state_partial_kernel<64, false>), grid, block, 0, st, k, v, N, tpc, P, partial, drop, H, nullptr);
-    return hipGetLastError();
+        launch_kernel((state_partial_kernel<64, false>), grid, block, 0, st, k, v, N, tpc, P, partial, drop, H, nullptr);
+    return take_launch_status();
 }
 
 // (cos, sin) tables of the rotary linear branch, fp32 [n] each -> one word per angle: fp16 cos | fp16 sin << 16
@@ -254,8 +254,8 @@ __global__ __launch_bounds__(256) void rope_pack_kernel(const float *__restrict_
 
 hipError_t launch_rope_pack(const float *rope_cos, const float *rope_sin, size_t n, uint32_t *tab, hipStream_t st)
 {
-    hipLaunchKernelGGL(rope_pack_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, rope_cos, rope_sin, n, tab);
-    return hipGetLastError();
+    launch_kernel(rope_pack_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, rope_cos, rope_sin, n, tab);
+    return take_launch_status();
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -288,8 +288,8 @@ hipError_t launch_state_f32(const float *k, const float *v, int BH, int N, int D
                             const int32_t *drop, int H, hipStream_t st)
 {
     dim3 grid((D * D + D + 255) / 256, BH), block(256);
-    hipLaunchKernelGGL(state_f32_kernel, grid, block, 0, st, k, v, N, D, Hs, Z, drop, H);
-    return hipGetLastError();
+    launch_kernel(state_f32_kernel, grid, block, 0, st, k, v, N, D, Hs, Z, drop, H);
+    return take_launch_status();
 }
 
 }  // namespace salad

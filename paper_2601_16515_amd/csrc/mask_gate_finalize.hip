@@ -43,8 +43,8 @@ __global__ __launch_bounds__(256) void block_mask_kernel(MaskArgs a)
 hipError_t launch_block_mask(const MaskArgs &a, hipStream_t st)
 {
     int rows = a.H * a.nb + 1;
-    hipLaunchKernelGGL(block_mask_kernel, dim3((rows + 255) / 256), dim3(256), 0, st, a);
-    return hipGetLastError();
+    launch_kernel(block_mask_kernel, dim3((rows + 255) / 256), dim3(256), 0, st, a);
+    return take_launch_status();
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -236,12 +236,12 @@ static void gate_dispatch_bf16(dim3 grid, dim3 block, hipStream_t st, const void
                                float *partial, int nparts)
 {
     const int nch = (D / 8 + 63) / 64;
-    if (nch <= 1) hipLaunchKernelGGL((gate_partial_kernel<true, 1, 4>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
-    else if (nch <= 2) hipLaunchKernelGGL((gate_partial_kernel<true, 2, 4>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
-    else if (nch <= 3) hipLaunchKernelGGL((gate_partial_kernel<true, 3, 2>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
-    else if (nch <= 5) hipLaunchKernelGGL((gate_partial_kernel<true, 5, 2>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
-    else if (nch <= GATE_MAX_CHUNKS) hipLaunchKernelGGL((gate_partial_kernel<true, GATE_MAX_CHUNKS, 1>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
-    else hipLaunchKernelGGL((gate_partial_wide_kernel<true>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
+    if (nch <= 1) launch_kernel((gate_partial_kernel<true, 1, 4>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
+    else if (nch <= 2) launch_kernel((gate_partial_kernel<true, 2, 4>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
+    else if (nch <= 3) launch_kernel((gate_partial_kernel<true, 3, 2>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
+    else if (nch <= 5) launch_kernel((gate_partial_kernel<true, 5, 2>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
+    else if (nch <= GATE_MAX_CHUNKS) launch_kernel((gate_partial_kernel<true, GATE_MAX_CHUNKS, 1>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
+    else launch_kernel((gate_partial_wide_kernel<true>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
 }
 
 // fp32 inputs are the small-shape path: one token per wave step
@@ -249,10 +249,10 @@ static void gate_dispatch_f32(dim3 grid, dim3 block, hipStream_t st, const void 
                               float *partial, int nparts)
 {
     const int nch = (D / 8 + 63) / 64;
-    if (nch <= 2) hipLaunchKernelGGL((gate_partial_kernel<false, 2, 1>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
-    else if (nch <= 5) hipLaunchKernelGGL((gate_partial_kernel<false, 5, 1>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
-    else if (nch <= GATE_MAX_CHUNKS) hipLaunchKernelGGL((gate_partial_kernel<false, GATE_MAX_CHUNKS, 1>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
-    else hipLaunchKernelGGL((gate_partial_wide_kernel<false>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
+    if (nch <= 2) launch_kernel((gate_partial_kernel<false, 2, 1>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
+    else if (nch <= 5) launch_kernel((gate_partial_kernel<false, 5, 1>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
+    else if (nch <= GATE_MAX_CHUNKS) launch_kernel((gate_partial_kernel<false, GATE_MAX_CHUNKS, 1>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
+    else launch_kernel((gate_partial_wide_kernel<false>), grid, block, 0, st, x_t, w, bias, N, D, partial, nparts);
 }
 
 hipError_t launch_gate_partial(const void *x_t, const float *w, float bias, int B, int N, int D,
@@ -261,7 +261,7 @@ hipError_t launch_gate_partial(const void *x_t, const float *w, float bias, int 
     dim3 grid(nparts, B), block(256);
     if (is_bf16) gate_dispatch_bf16(grid, block, st, x_t, w, bias, N, D, partial, nparts);
     else gate_dispatch_f32(grid, block, st, x_t, w, bias, N, D, partial, nparts);
-    return hipGetLastError();
+    return take_launch_status();
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -351,8 +351,8 @@ hipError_t launch_finalize(const FinalizeArgs &a, hipStream_t st)
     int per = a.D * a.D + a.D;
     int blocks_per_head = (per + 63) / 64;
     int state_blocks = a.P > 0 ? a.B * a.H * blocks_per_head : 0;
-    hipLaunchKernelGGL(finalize_kernel, dim3(state_blocks + (a.do_gate ? 1 : 0)), dim3(256), 0, st, a, state_blocks, blocks_per_head);
-    return hipGetLastError();
+    launch_kernel(finalize_kernel, dim3(state_blocks + (a.do_gate ? 1 : 0)), dim3(256), 0, st, a, state_blocks, blocks_per_head);
+    return take_launch_status();
 }
 
 }  // namespace salad

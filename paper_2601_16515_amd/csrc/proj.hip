@@ -70,8 +70,8 @@ __global__ __launch_bounds__(256) void proj_pack_kernel(const u16 *__restrict__ 
 
 hipError_t launch_proj_pack(const u16 *w_proj, int H, u16 *wfrag, hipStream_t st)
 {
-    hipLaunchKernelGGL(proj_pack_kernel, dim3(H, H, 4), dim3(256), 0, st, w_proj, H, wfrag);
-    return hipGetLastError();
+    launch_kernel(proj_pack_kernel, dim3(H, H, 4), dim3(256), 0, st, w_proj, H, wfrag);
+    return take_launch_status();
 }
 
 // One 16-byte-per-lane global -> LDS load (lane i lands at lds_addr + 16 i), issued through inline assembly so
@@ -259,8 +259,8 @@ hipError_t launch_proj_apply(const ProjArgs &a, hipStream_t st)
     const int ny = a.H, ngrp = ((a.N + 255) / 256 + 7) / 8;
     dim3 grid(8 * ny * ngrp * a.B), block(256);
     if (hipError_t e = dyn_lds_attr_once(reinterpret_cast<const void *>(proj_apply_kernel), lds, done); e != hipSuccess) return e;
-    hipLaunchKernelGGL(proj_apply_kernel, grid, block, lds, st, a);
-    return hipGetLastError();
+    launch_kernel(proj_apply_kernel, grid, block, lds, st, a);
+    return take_launch_status();
 }
 
 }  // namespace salad

@@ -2,6 +2,9 @@
 // Not installed; the public interface is include/salad.h.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <tuple>
+#include <type_traits>
+#include <utility>
 #include <stdint.h>
 
 namespace salad {
@@ -157,6 +160,35 @@ struct ProjArgs {
 };
 hipError_t launch_proj_pack(const u16 *w_proj, int H, u16 *wfrag, hipStream_t st);
 hipError_t launch_proj_apply(const ProjArgs &a, hipStream_t st);
+
+// Kernel launch whose status is this launch's own.  The <<<>>> form reports a failed launch only through the thread's
+// "last error" slot, which an earlier, unrelated call may have set; hipLaunchKernel returns the launch's status.
+// A launcher issues its launches through launch_kernel and returns take_launch_status(): the first failure among them.
+inline hipError_t &launch_status_slot()
+{
+    static thread_local hipError_t e = hipSuccess;
+    return e;
+}
+inline hipError_t take_launch_status()
+{
+    const hipError_t e = launch_status_slot();
+    launch_status_slot() = hipSuccess;
+    return e;
+}
+template <class Tuple, size_t... I>
+inline hipError_t launch_with(const void *kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st, Tuple &vals, std::index_sequence<I...>)
+{
+    void *ptrs[] = {static_cast<void *>(&std::get<I>(vals))...};
+    return hipLaunchKernel(kernel, grid, block, ptrs, lds, st);
+}
+template <class... P, class... A>
+inline void launch_kernel(void (*kernel)(P...), dim3 grid, dim3 block, size_t lds, hipStream_t st, A &&...args)
+{
+    static_assert(sizeof...(P) == sizeof...(A), "every kernel parameter needs its argument");
+    std::tuple<std::remove_cv_t<P>...> vals(static_cast<P>(std::forward<A>(args))...);   // copies in the parameter types
+    const hipError_t e = launch_with(reinterpret_cast<const void *>(kernel), grid, block, lds, st, vals, std::index_sequence_for<P...>{});
+    if (e != hipSuccess && launch_status_slot() == hipSuccess) launch_status_slot() = e;
+}
 
 // Raises a kernel's dynamic-LDS limit once per device (`done` is the caller's per-kernel flag array).
 inline hipError_t dyn_lds_attr_once(const void *kernel, int bytes, bool (&done)[16])

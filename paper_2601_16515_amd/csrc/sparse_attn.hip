@@ -344,13 +344,13 @@ hipError_t launch_sparse_attn_bf16(const AttnArgs &a, hipStream_t st)
     dim3 grid(per_xcd * 8), block(256);
     const bool dbg = a.o_sparse_dbg || a.o_linear_dbg;
     if (a.D == 128) {
-        if (dbg) hipLaunchKernelGGL((sparse_attn_bf16_kernel<128, true>), grid, block, 0, st, a, ntiles, total, per_xcd);
-        else hipLaunchKernelGGL((sparse_attn_bf16_kernel<128, false>), grid, block, 0, st, a, ntiles, total, per_xcd);
+        if (dbg) launch_kernel((sparse_attn_bf16_kernel<128, true>), grid, block, 0, st, a, ntiles, total, per_xcd);
+        else launch_kernel((sparse_attn_bf16_kernel<128, false>), grid, block, 0, st, a, ntiles, total, per_xcd);
     } else {
-        if (dbg) hipLaunchKernelGGL((sparse_attn_bf16_kernel<64, true>), grid, block, 0, st, a, ntiles, total, per_xcd);
-        else hipLaunchKernelGGL((sparse_attn_bf16_kernel<64, false>), grid, block, 0, st, a, ntiles, total, per_xcd);
+        if (dbg) launch_kernel((sparse_attn_bf16_kernel<64, true>), grid, block, 0, st, a, ntiles, total, per_xcd);
+        else launch_kernel((sparse_attn_bf16_kernel<64, false>), grid, block, 0, st, a, ntiles, total, per_xcd);
     }
-    return hipGetLastError();
+    return take_launch_status();
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -429,8 +429,8 @@ hipError_t launch_sparse_attn_f32(const AttnArgs &a, hipStream_t st)
 {
     long long totalq = (long long)a.B * a.H * a.N;
     dim3 grid((unsigned)((totalq + 3) / 4)), block(256);
-    hipLaunchKernelGGL(sparse_attn_f32_kernel, grid, block, 0, st, a);
-    return hipGetLastError();
+    launch_kernel(sparse_attn_f32_kernel, grid, block, 0, st, a);
+    return take_launch_status();
 }
 
 }  // namespace salad

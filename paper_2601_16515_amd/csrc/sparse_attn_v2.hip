@@ -327,9 +327,9 @@ hipError_t launch_sparse_attn_v2(const AttnArgs &a, hipStream_t st)
     const int per_xcd = (total + 7) / 8;
     dim3 grid(per_xcd * 8), block(256);
     const bool dbg = a.o_sparse_dbg || a.o_linear_dbg;
-    if (dbg) hipLaunchKernelGGL((sparse_attn_v2_kernel<true>), grid, block, 0, st, a, ntiles, total, per_xcd);
-    else hipLaunchKernelGGL((sparse_attn_v2_kernel<false>), grid, block, 0, st, a, ntiles, total, per_xcd);
-    return hipGetLastError();
+    if (dbg) launch_kernel((sparse_attn_v2_kernel<true>), grid, block, 0, st, a, ntiles, total, per_xcd);
+    else launch_kernel((sparse_attn_v2_kernel<false>), grid, block, 0, st, a, ntiles, total, per_xcd);
+    return take_launch_status();
 }
 
 }  // namespace salad

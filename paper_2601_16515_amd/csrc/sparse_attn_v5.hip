@@ -179,8 +179,8 @@ hipError_t launch_tile_lists(const int32_t *row_ptr, const int32_t *col_idx, int
 {
     const int ntiles = (nb + 3) / 4;
     const int cap = tile_list_cap(nb);
-    hipLaunchKernelGGL(tile_lists_kernel, dim3(ntiles, H), dim3(64), (size_t)cap * 8, st, row_ptr, col_idx, nb, ntiles, cap, lists, counts);
-    return hipGetLastError();
+    launch_kernel(tile_lists_kernel, dim3(ntiles, H), dim3(64), (size_t)cap * 8, st, row_ptr, col_idx, nb, ntiles, cap, lists, counts);
+    return take_launch_status();
 }
 
 // PD: prefetch distance in KV blocks.  K(b) is read in iteration b only, V(b) also in iteration b+1: the K ring
@@ -696,8 +696,8 @@ static hipError_t launch_v5(const AttnArgs &a, hipStream_t st)
     auto kern = sparse_attn_v5_kernel<D, PD, DBG, MODE, ROPE>;
     static bool attr_done[16] = {};
     if (hipError_t e = dyn_lds_attr_once(reinterpret_cast<const void *>(kern), kMaxDyn, attr_done); e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(512), lds, st, a, ntiles, total, per_xcd, list_cap);
-    return hipGetLastError();
+    launch_kernel(kern, dim3(per_xcd * 8), dim3(512), lds, st, a, ntiles, total, per_xcd, list_cap);
+    return take_launch_status();
 }
 
 hipError_t launch_sparse_attn_v5(const AttnArgs &a, hipStream_t st)

@@ -43,8 +43,8 @@ __global__ __launch_bounds__(128) void kblock_mean_kernel(const u16 *__restrict_
 hipError_t launch_kblock_mean(const u16 *k, int BH, int N, int key_block, int nbk, float *means, unsigned long long kind_mask,
                               int H, int T, int HW, hipStream_t st)
 {
-    hipLaunchKernelGGL(kblock_mean_kernel, dim3(nbk, BH), dim3(128), 0, st, k, N, key_block, nbk, means, kind_mask, H, T, HW);
-    return hipGetLastError();
+    launch_kernel(kblock_mean_kernel, dim3(nbk, BH), dim3(128), 0, st, k, N, key_block, nbk, means, kind_mask, H, T, HW);
+    return take_launch_status();
 }
 
 // grid (ceil(N / 256), BH), 256 threads: a thread owns one query and keeps one score accumulator per key block
@@ -133,8 +133,8 @@ hipError_t launch_topk_select(const u16 *q, const float *means, int BH, int N, i
     const dim3 grid((N + 255) / 256, BH), block(256);
 #define SALAD_TOPK_SELECT(NBK_)                                                                                              \
     do {                                                                                                                     \
-        if (topk <= 4) hipLaunchKernelGGL((topk_select_kernel<NBK_, 4>), grid, block, 0, st, q, means, N, nbk, topk, mask);  \
-        else hipLaunchKernelGGL((topk_select_kernel<NBK_, 8>), grid, block, 0, st, q, means, N, nbk, topk, mask);            \
+        if (topk <= 4) launch_kernel((topk_select_kernel<NBK_, 4>), grid, block, 0, st, q, means, N, nbk, topk, mask);  \
+        else launch_kernel((topk_select_kernel<NBK_, 8>), grid, block, 0, st, q, means, N, nbk, topk, mask);            \
     } while (0)
     if (nbk <= 8) SALAD_TOPK_SELECT(8);
     else if (nbk <= 16) SALAD_TOPK_SELECT(16);
@@ -145,7 +145,7 @@ hipError_t launch_topk_select(const u16 *q, const float *means, int BH, int N, i
     else if (nbk <= 56) SALAD_TOPK_SELECT(56);
     else SALAD_TOPK_SELECT(64);
 #undef SALAD_TOPK_SELECT
-    return hipGetLastError();
+    return take_launch_status();
 }
 
 // grid (ntiles, BH), 256 threads: thread t holds the mask of query 256 tile + t; attention wave w of the tile owns
@@ -202,9 +202,9 @@ hipError_t launch_topk_tile_lists(const unsigned long long *mask, int BH, int N,
                                   uint32_t *lists, int32_t *counts, hipStream_t st)
 {
     const int ntiles = (nb + 3) / 4;
-    hipLaunchKernelGGL(topk_tile_lists_kernel, dim3(ntiles, BH), dim3(256), 0, st, mask, N, nb, key_block / 64, nbk,
+    launch_kernel(topk_tile_lists_kernel, dim3(ntiles, BH), dim3(256), 0, st, mask, N, nb, key_block / 64, nbk,
                        ntiles, tile_list_cap(nb), lists, counts);
-    return hipGetLastError();
+    return take_launch_status();
 }
 
 // ---- regrouping by key block -----------------------------------------------------------------------------------
@@ -402,18 +402,18 @@ hipError_t launch_topk_group(const unsigned long long *mask, int BH, int N, int 
                              int32_t *cbase, uint4 *desc, int32_t *gidx, int32_t *slot_of, hipStream_t st)
 {
     const int nch = (N + 1023) / 1024;
-    hipLaunchKernelGGL(topk_count_kernel, dim3(nch, BH), dim3(1024), 0, st, mask, N, nbk, nch, ccnt);
-    hipLaunchKernelGGL(topk_plan_kernel, dim3(BH), dim3(64), 0, st, ccnt, nbk, nch, cbase, desc, topk_tiles_per_head(N, kk, nbk));
-    hipLaunchKernelGGL(topk_group_kernel, dim3(nch, BH), dim3(1024), 0, st, mask, N, nbk, kk, nch, cbase, gidx, slot_of);
-    return hipGetLastError();
+    launch_kernel(topk_count_kernel, dim3(nch, BH), dim3(1024), 0, st, mask, N, nbk, nch, ccnt);
+    launch_kernel(topk_plan_kernel, dim3(BH), dim3(64), 0, st, ccnt, nbk, nch, cbase, desc, topk_tiles_per_head(N, kk, nbk));
+    launch_kernel(topk_group_kernel, dim3(nch, BH), dim3(1024), 0, st, mask, N, nbk, kk, nch, cbase, gidx, slot_of);
+    return take_launch_status();
 }
 
 hipError_t launch_topk_merge(const u16 *po, const float *lse, const int32_t *slot_of, const unsigned long long *mask,
                              int BH, int N, int kk, u16 *out, float *o_dbg, hipStream_t st)
 {
     const size_t nq = (size_t)BH * N;
-    hipLaunchKernelGGL(topk_merge_kernel, dim3((unsigned)((nq + 31) / 32)), dim3(256), 0, st, po, lse, slot_of, mask, BH, N, kk, out, o_dbg);
-    return hipGetLastError();
+    launch_kernel(topk_merge_kernel, dim3((unsigned)((nq + 31) / 32)), dim3(256), 0, st, po, lse, slot_of, mask, BH, N, kk, out, o_dbg);
+    return take_launch_status();
 }
 
 }  // namespace salad
