@@ -26,17 +26,34 @@ __global__ __launch_bounds__(128) void kblock_mean_kernel(const u16 *__restrict_
     const int t0 = J * key_block, t1 = min(N, t0 + key_block);
     const bool temporal = T > 1 && ((kind_mask >> (bh % H)) & 1ull);
     const u16 *base = k + (size_t)bh * N * D + c;
-    auto row_of = [&](int p) { return temporal ? (p % T) * HW + p / T : p; };
     float sum = 0.f;
     int t = t0;
-    for (; t + 16 <= t1; t += 16) {           // 16 independent loads in flight, added in position order
-        u16 x[16];
+    if (!temporal) {
+        for (; t + 16 <= t1; t += 16) {           // 16 independent loads in flight, added in position order
+            u16 x[16];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) x[i] = base[(size_t)row_of(t + i) * D];
+            for (int i = 0; i < 16; ++i) x[i] = base[(size_t)(t + i) * D];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) sum = __fadd_rn(sum, bf16_to_f32(x[i]));
+            for (int i = 0; i < 16; ++i) sum = __fadd_rn(sum, bf16_to_f32(x[i]));
+        }
+        for (; t < t1; ++t) sum = __fadd_rn(sum, bf16_to_f32(base[(size_t)t * D]));
+    } else {
+        // position p = loc T + f (location loc, frame f) is stored row f HW + loc; the pair is stepped, not divided
+        int loc = t0 / T, f = t0 - loc * T;
+        auto next_row = [&]() {
+            const int row = f * HW + loc;
+            if (++f == T) { f = 0; ++loc; }
+            return row;
+        };
+        for (; t + 16 <= t1; t += 16) {
+            u16 x[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) x[i] = base[(size_t)next_row() * D];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) sum = __fadd_rn(sum, bf16_to_f32(x[i]));
+        }
+        for (; t < t1; ++t) sum = __fadd_rn(sum, bf16_to_f32(base[(size_t)next_row() * D]));
     }
-    for (; t < t1; ++t) sum = __fadd_rn(sum, bf16_to_f32(base[(size_t)row_of(t) * D]));
     means[((size_t)bh * nbk + J) * D + c] = __fdiv_rn(sum, (float)(t1 - t0));
 }
 
