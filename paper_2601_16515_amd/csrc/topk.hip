@@ -29,14 +29,19 @@ __global__ __launch_bounds__(128) void kblock_mean_kernel(const u16 *__restrict_
     float sum = 0.f;
     int t = t0;
     if (!temporal) {
+        const u16 *src = base + (size_t)t0 * D;   // one running address, the 16 rows at constant offsets from it
         for (; t + 16 <= t1; t += 16) {           // 16 independent loads in flight, added in position order
             u16 x[16];
 #pragma unroll
-            for (int i = 0; i < 16; ++i) x[i] = base[(size_t)(t + i) * D];
+            for (int i = 0; i < 16; ++i) x[i] = src[(size_t)i * D];
 #pragma unroll
             for (int i = 0; i < 16; ++i) sum = __fadd_rn(sum, bf16_to_f32(x[i]));
+            src += 16 * D;
         }
-        for (; t < t1; ++t) sum = __fadd_rn(sum, bf16_to_f32(base[(size_t)t * D]));
+        for (; t < t1; ++t) {
+            sum = __fadd_rn(sum, bf16_to_f32(*src));
+            src += D;
+        }
     } else {
         // position p = loc T + f (location loc, frame f) is stored row f HW + loc; the pair is stepped, not divided
         int loc = t0 / T, f = t0 - loc * T;
