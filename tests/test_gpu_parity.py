@@ -141,6 +141,9 @@ SMALL = [
     wl.small("single-token", 1, 1, 128, 1, 1, 1, "bf16", 0.0, seed=109),      # N=1
     wl.small("five-tiles-d128", 1, 3, 128, 9, 10, 13, "bf16", 0.8, seed=110), # N=1170: 19 blocks = 5 tiles of 4, tail 18
     wl.small("d64-ragged", 2, 2, 64, 3, 11, 13, "bf16", 0.5, seed=111),       # N=429, d=64, B=2
+    wl.small("d64-one-block", 1, 3, 64, 2, 3, 5, "bf16", 0.0, seed=114),      # N=30 < one block, d=64
+    wl.small("d64-single-token", 2, 1, 64, 1, 1, 1, "bf16", 0.0, seed=115),   # N=1, d=64, B=2
+    wl.small("d64-T-gt-block", 1, 2, 64, 70, 3, 3, "bf16", 0.5, seed=116),    # d=64, T=70 > 64: temporal rows far apart
 ]
 
 
