@@ -103,6 +103,16 @@ size_t salad_tile_lists_bytes(int32_t H, int32_t nb);
 salad_status salad_tile_lists(const int32_t *row_ptr_dev, const int32_t *col_idx_dev, int32_t H, int32_t nb,
                               void *lists_dev, size_t lists_bytes, void *hip_stream);
 
+/* W_p of the full Level-1 projection (Alg. 1 "Proj"; see salad_fwd_params.w_proj) rearranged once into the order the
+ * projection GEMM reads it in (MFMA operand fragments of its [H x H] blocks of d x d).  The weights are static per layer,
+ * so this runs once per layer, not per call; pass the result as salad_fwd_params.w_proj_packed.
+ *   salad_proj_pack_bytes   size of the packed buffer (2 (H d)^2 bytes); 0 unless 1 <= H <= 64 and d == 128
+ *   w_proj_dev              device bf16 [H*d, H*d], row-major (read)
+ *   packed_dev              device, 256-byte aligned, >= salad_proj_pack_bytes (written); SALAD_ENOSPC if smaller */
+size_t salad_proj_pack_bytes(int32_t H, int32_t d);
+salad_status salad_proj_pack(const void *w_proj_dev, int32_t H, int32_t d, void *packed_dev, size_t packed_bytes,
+                             void *hip_stream);
+
 /* ---- whole layer --------------------------------------------------------------------------- */
 
 typedef struct salad_fwd_params {
@@ -150,6 +160,9 @@ typedef struct salad_fwd_params {
     const void *tile_lists;   /* optional device buffer filled by salad_tile_lists for exactly this row_ptr / col_idx (same H, N):
                                  the bf16 d = 128 kernel then skips its per-call list pre-pass.  NULL: the lists are built
                                  in the workspace on every call.  Ignored with topk > 0 and by the other kernels            */
+    const void *w_proj_packed; /* optional device buffer filled by salad_proj_pack from the layer's W_p (static per layer): the
+                                 full projection then skips its per-call rearrangement of w_proj, which may be NULL.
+                                 Same conditions as w_proj (dtype bf16, d = 128, head_scale == NULL)                          */
 } salad_fwd_params;
 
 /* Run the linear apply and the scale-and-sum as a separate streaming kernel after the sparse

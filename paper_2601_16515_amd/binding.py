@@ -25,7 +25,7 @@ SALAD_FLAG_UNFUSED_EPILOGUE = 1
 
 EXPORTS = ["salad_last_error", "salad_kept_from_sparsity", "salad_block_mask_nnz", "salad_block_mask",
            "salad_block_mask_nnz_mode", "salad_block_mask_mode",
-           "salad_tile_lists_bytes", "salad_tile_lists", "salad_fwd_workspace_bytes", "salad_sparse_linear_attn_fwd", "salad_linear_state_fwd",
+           "salad_tile_lists_bytes", "salad_tile_lists", "salad_proj_pack_bytes", "salad_proj_pack", "salad_fwd_workspace_bytes", "salad_sparse_linear_attn_fwd", "salad_linear_state_fwd",
            "salad_gate_fwd", "salad_gate_fwd_static", "salad_timing_enable", "salad_timing_read", "salad_tune"]
 
 
@@ -69,6 +69,7 @@ class FwdParams(C.Structure):
         ("rope_cos", C.c_void_p),
         ("rope_sin", C.c_void_p),
         ("tile_lists", C.c_void_p),
+        ("w_proj_packed", C.c_void_p),
     ]
 
 
@@ -135,6 +136,10 @@ def lib() -> C.CDLL:
         L.salad_tile_lists_bytes.argtypes = [C.c_int32, C.c_int32]
         L.salad_tile_lists.restype = C.c_int
         L.salad_tile_lists.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.salad_proj_pack_bytes.restype = C.c_size_t
+        L.salad_proj_pack_bytes.argtypes = [C.c_int32, C.c_int32]
+        L.salad_proj_pack.restype = C.c_int
+        L.salad_proj_pack.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
         L.salad_fwd_workspace_bytes.restype = C.c_size_t
         L.salad_fwd_workspace_bytes.argtypes = [C.POINTER(FwdParams)]
         L.salad_sparse_linear_attn_fwd.restype = C.c_int
@@ -232,6 +237,20 @@ def salad_block_mask_mode(T: int, Hh: int, W: int, block: int, kept: Sequence[in
     return row_ptr, col_idx[:nnz]
 
 
+def salad_proj_pack(w_proj, H: int, d: int):
+    """W_p [H*d, H*d] (bf16 device tensor) rearranged once for the projection GEMM; returns a 256-byte aligned uint8
+    device tensor to pass as w_proj_packed."""
+    import torch
+    need = int(lib().salad_proj_pack_bytes(H, d))
+    if need == 0:
+        raise SaladError(SALAD_ENOTSUP, "salad_proj_pack_bytes: shape outside the projection's envelope")
+    buf = torch.empty(need + 256, dtype=torch.uint8, device=w_proj.device)
+    off = (-buf.data_ptr()) % 256
+    view = buf[off:off + need]
+    _check(lib().salad_proj_pack(w_proj.data_ptr(), H, d, view.data_ptr(), need, _stream()))
+    return view
+
+
 def salad_tile_lists(row_ptr, col_idx, H: int, nb: int):
     """Visit lists of the large-tile kernel for a CSR, built once; returns a 256-byte aligned uint8 device tensor to pass
     as tile_lists (None when the shape does not use them)."""
@@ -272,7 +291,7 @@ def make_fwd_params(q, k, v, out, grid: Tuple[int, int, int], row_ptr, col_idx, 
                     eps: float = 1e-6, softmax_scale: float = 0.0, s_out=None, o_sparse_dbg=None,
                     o_linear_dbg=None, workspace: Optional[Workspace] = None, flags: int = 0, block: int = 64,
                     drop_threshold: float = 0.0, dropped_out=None, w_proj=None, topk: int = 0,
-                    topk_key_block: int = 0, topk_mask_out=None, rope_cos=None, rope_sin=None, tile_lists=None):
+                    topk_key_block: int = 0, topk_mask_out=None, rope_cos=None, rope_sin=None, tile_lists=None, w_proj_packed=None):
     """Fill a salad_fwd_params from torch tensors.  Returns (params, keepalive)."""
     B, H, N, d = q.shape
     p = FwdParams()
@@ -309,7 +328,8 @@ def make_fwd_params(q, k, v, out, grid: Tuple[int, int, int], row_ptr, col_idx, 
     p.topk, p.topk_key_block, p.topk_mask_out = int(topk), int(topk_key_block), _ptr(topk_mask_out)
     p.rope_cos, p.rope_sin = _ptr(rope_cos), _ptr(rope_sin)
     p.tile_lists = _ptr(tile_lists)
-    return p, (hk, workspace, tile_lists)
+    p.w_proj_packed = _ptr(w_proj_packed)
+    return p, (hk, workspace, tile_lists, w_proj_packed)
 
 
 def salad_sparse_linear_attn_fwd(q, k, v, grid, row_ptr, col_idx, head_kind=None, *, out=None, **kw):
@@ -322,7 +342,7 @@ def salad_sparse_linear_attn_fwd(q, k, v, grid, row_ptr, col_idx, head_kind=None
     if out is None:
         out = torch.empty_like(q)
     if kw.get("workspace") is None:
-        kw["workspace"] = Workspace(B, H, N, d, _dtype_code(q), q.device, full_proj=kw.get("w_proj") is not None,
+        kw["workspace"] = Workspace(B, H, N, d, _dtype_code(q), q.device, full_proj=kw.get("w_proj") is not None or kw.get("w_proj_packed") is not None,
                                     topk=kw.get("topk", 0), rope=kw.get("rope_cos") is not None)
     p, keep = make_fwd_params(q, k, v, out, grid, row_ptr, col_idx, head_kind, **kw)
     _check(lib().salad_sparse_linear_attn_fwd(C.byref(p)))

@@ -258,10 +258,28 @@ salad_status salad_tile_lists(const int32_t *row_ptr_dev, const int32_t *col_idx
     return SALAD_OK;
 }
 
+size_t salad_proj_pack_bytes(int32_t H, int32_t d)
+{
+    if (H < 1 || H > 64 || d != 128) return 0;
+    return align256(sizeof(u16) * (size_t)H * d * H * d);
+}
+
+salad_status salad_proj_pack(const void *w_proj_dev, int32_t H, int32_t d, void *packed_dev, size_t packed_bytes, void *hip_stream)
+{
+    if (!w_proj_dev || !packed_dev) return fail(SALAD_EINVAL, "salad_proj_pack: null pointer");
+    const size_t need = salad_proj_pack_bytes(H, d);
+    if (!need) return fail(SALAD_ENOTSUP, "salad_proj_pack: needs 1 <= H <= 64 and d = 128 (H=%d d=%d)", (int)H, (int)d);
+    if ((uintptr_t)packed_dev & 255) return fail(SALAD_EINVAL, "salad_proj_pack: buffer not 256-byte aligned");
+    if (packed_bytes < need) return fail(SALAD_ENOSPC, "salad_proj_pack: buffer %zu < %zu bytes", packed_bytes, need);
+    hipError_t e = launch_proj_pack((const u16 *)w_proj_dev, H, (u16 *)packed_dev, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return hip_fail(e, "projection pack launch");
+    return SALAD_OK;
+}
+
 size_t salad_fwd_workspace_bytes(const salad_fwd_params *p)
 {
     if (!p || !shape_ok(p->B, p->H, p->N, p->d, p->dtype)) return 0;
-    return ws_layout(p->B, p->H, p->N, p->d, p->dtype, g_state_target_wgs.load(), p->w_proj != nullptr, p->topk > 0 ? p->topk : 0, p->rope_cos != nullptr).total;
+    return ws_layout(p->B, p->H, p->N, p->d, p->dtype, g_state_target_wgs.load(), p->w_proj != nullptr || p->w_proj_packed != nullptr, p->topk > 0 ? p->topk : 0, p->rope_cos != nullptr).total;
 }
 
 salad_status salad_linear_state_fwd(const void *k, const void *v, int32_t B, int32_t H, int32_t N, int32_t d,
@@ -414,17 +432,19 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
     const bool large_tile = p->dtype == SALAD_BF16 && (p->d == 128 || p->d == 64) && attn_variant == 0 &&
                             (size_t)tile_list_cap((p->N + 63) / 64) * 4 <= 24 * 1024 && (unsigned long long)p->N * 256ull < (1ull << 32) &&
                             (!temporal_any || (unsigned long long)p->N * (unsigned long long)p->T < (1ull << 32));
-    const bool rope_fused = rope && large_tile && !topk && !p->w_proj && !(p->flags & SALAD_FLAG_UNFUSED_EPILOGUE);
-    const bool unfused = (p->flags & SALAD_FLAG_UNFUSED_EPILOGUE) != 0 || (p->w_proj != nullptr && p->lambda != 0.f) ||
+    const bool has_proj = p->w_proj != nullptr || p->w_proj_packed != nullptr;
+    const bool rope_fused = rope && large_tile && !topk && !has_proj && !(p->flags & SALAD_FLAG_UNFUSED_EPILOGUE);
+    const bool unfused = (p->flags & SALAD_FLAG_UNFUSED_EPILOGUE) != 0 || (has_proj && p->lambda != 0.f) ||
                          (topk_regroup && p->lambda != 0.f) || (rope && !rope_fused && p->lambda != 0.f);
     if (unfused && p->dtype != SALAD_BF16) return fail(SALAD_ENOTSUP, "fwd: unfused epilogue is bf16 only");
     if (p->flags & ~SALAD_FLAG_UNFUSED_EPILOGUE) return fail(SALAD_EINVAL, "fwd: unknown flags 0x%x", p->flags);
-    const bool full_proj = p->w_proj != nullptr && p->lambda != 0.f;
-    if (p->w_proj) {
+    const bool full_proj = has_proj && p->lambda != 0.f;
+    if (p->w_proj_packed && ((uintptr_t)p->w_proj_packed & 255)) return fail(SALAD_EINVAL, "fwd: w_proj_packed not 256-byte aligned");
+    if (has_proj) {
         if (p->dtype != SALAD_BF16 || p->d != 128) return fail(SALAD_ENOTSUP, "fwd: w_proj needs dtype bf16 and d = 128");
         if (p->head_scale) return fail(SALAD_EINVAL, "fwd: w_proj and head_scale exclude each other");
     }
-    const WsLayout w = ws_layout(p->B, p->H, p->N, p->d, p->dtype, state_wgs, p->w_proj != nullptr, topk ? p->topk : 0, p->rope_cos != nullptr);
+    const WsLayout w = ws_layout(p->B, p->H, p->N, p->d, p->dtype, state_wgs, has_proj, topk ? p->topk : 0, p->rope_cos != nullptr);
     const bool need_lists = p->dtype == SALAD_BF16 && (p->d == 128 || p->d == 64) && (size_t)tile_list_cap((p->N + 63) / 64) * 4 <= 24 * 1024;
     if (use_linear || need_lists) {
         if (!p->workspace || ((uintptr_t)p->workspace & 255)) return fail(SALAD_EINVAL, "fwd: workspace null or not 256-byte aligned");
@@ -602,10 +622,13 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
         mark(5);
         if (full_proj) {
             // Alg. 1 "Proj" as one GEMM over the concatenated heads, fused with the residual sum
-            e = launch_proj_pack((const u16 *)p->w_proj, p->H, (u16 *)(ws + w.wfrag), st);
-            if (e != hipSuccess) return give_back(), hip_fail(e, "projection pack launch");
+            if (!p->w_proj_packed) {      // W_p in fragment order: built here unless the caller did it once for the layer
+                e = launch_proj_pack((const u16 *)p->w_proj, p->H, (u16 *)(ws + w.wfrag), st);
+                if (e != hipSuccess) return give_back(), hip_fail(e, "projection pack launch");
+            }
             ProjArgs pa{};
-            pa.ol = (const u16 *)(ws + w.ol); pa.out = (u16 *)p->out; pa.wfrag = (const u16 *)(ws + w.wfrag);
+            pa.ol = (const u16 *)(ws + w.ol); pa.out = (u16 *)p->out;
+            pa.wfrag = p->w_proj_packed ? (const u16 *)p->w_proj_packed : (const u16 *)(ws + w.wfrag);
             pa.coef = (const float *)(ws + w.coef); pa.drop = drop; pa.B = p->B; pa.H = p->H; pa.N = p->N;
             e = launch_proj_apply(pa, st);
             if (e != hipSuccess) return give_back(), hip_fail(e, "projection launch");

@@ -50,7 +50,7 @@ def gather_rows(full, rows):
 
 def run_layer(w, inp, dev, kept, kinds, *, lam=None, dbg=True, flags=0, s=None, head_scale="default",
               b_gate=0.0, csr=None, softmax_scale=0.0, eps=None, drop_threshold=0.0, w_proj=None,
-              topk=0, topk_key_block=0, rope=None, prebuilt_lists=False):
+              topk=0, topk_key_block=0, rope=None, prebuilt_lists=False, w_proj_packed=None):
     """One layer call; returns dict of numpy float64 arrays (out, o_sparse, o_linear, s)."""
     grid = (w.T, w.Hh, w.W)
     if csr is None:
@@ -72,7 +72,7 @@ def run_layer(w, inp, dev, kept, kinds, *, lam=None, dbg=True, flags=0, s=None, 
         b_gate=b_gate, eps=w.eps if eps is None else eps, softmax_scale=softmax_scale, s_out=s_out,
         o_sparse_dbg=o_s, o_linear_dbg=o_l, flags=flags, drop_threshold=drop_threshold, dropped_out=dropped, w_proj=w_proj,
         topk=topk, topk_key_block=topk_key_block, topk_mask_out=tmask,
-        rope_cos=None if rope is None else rope[0], rope_sin=None if rope is None else rope[1], tile_lists=lists)
+        rope_cos=None if rope is None else rope[0], rope_sin=None if rope is None else rope[1], tile_lists=lists, w_proj_packed=w_proj_packed)
     torch.cuda.synchronize()
     res = {"out": out.float().cpu().numpy().astype(np.float64), "s": s_out.cpu().numpy().astype(np.float64),
            "row_ptr": row_ptr.cpu().numpy(), "col_idx": col_idx.cpu().numpy(), "out_t": out,

@@ -63,6 +63,18 @@ def test_mask_nnz_of_the_truncated_window(lib, oracle):
     assert lib.salad_block_mask_mode(4, 16, 16, 64, 2, kept, sb.SALAD_WINDOW_TRUNCATED, None, fake, 128, None) == sb.SALAD_EINVAL
 
 
+def test_proj_pack_argument_errors(lib):
+    assert lib.salad_proj_pack_bytes(12, 128) == 2 * (12 * 128) ** 2
+    assert lib.salad_proj_pack_bytes(12, 64) == 0 and lib.salad_proj_pack_bytes(0, 128) == 0 and lib.salad_proj_pack_bytes(65, 128) == 0
+    fake = 0x1000   # never dereferenced
+    need = lib.salad_proj_pack_bytes(3, 128)
+    assert lib.salad_proj_pack(None, 3, 128, fake, need, None) == sb.SALAD_EINVAL
+    assert lib.salad_proj_pack(fake, 3, 64, fake, need, None) == sb.SALAD_ENOTSUP
+    assert lib.salad_proj_pack(fake, 3, 128, fake + 16, need, None) == sb.SALAD_EINVAL
+    assert "aligned" in lib.salad_last_error().decode()
+    assert lib.salad_proj_pack(fake, 3, 128, fake, need - 1, None) == sb.SALAD_ENOSPC
+
+
 def _err(lib):
     return lib.salad_last_error().decode()
 
@@ -120,6 +132,9 @@ def _params(**over):
     (dict(drop_threshold=float("nan")), sb.SALAD_EINVAL, "drop_threshold"),
     (dict(w_proj=0x8000), sb.SALAD_ENOTSUP, "w_proj"),                                   # d = 64
     (dict(w_proj=0x8000, d=128, head_scale=0x9000), sb.SALAD_EINVAL, "exclude"),
+    (dict(w_proj_packed=0x8000), sb.SALAD_ENOTSUP, "w_proj"),                            # packed W_p alone, d = 64
+    (dict(w_proj_packed=0x8000, d=128, head_scale=0x9000), sb.SALAD_EINVAL, "exclude"),
+    (dict(w_proj_packed=0x8010, d=128), sb.SALAD_EINVAL, "w_proj_packed not 256-byte aligned"),
     (dict(topk=-1), sb.SALAD_EINVAL, "topk"),
     (dict(topk=4, topk_key_block=128), sb.SALAD_ENOTSUP, "d = 128"),                     # d = 64
     (dict(topk=9, topk_key_block=128, d=128), sb.SALAD_ENOTSUP, "above 8"),

@@ -483,6 +483,10 @@ def test_full_projection(oracle, w):
     assert errors(ref["out"], ref_ps["out"])[1] > 0.05                 # the projection is not a small effect here
     res = run_layer(w, inp, dev, kept, kinds, lam=25.0, head_scale=None, w_proj=wp_dev)
     compare_layer(res, ref, check_linear=False, label="full-proj")
+    # W_p rearranged once for the layer (salad_proj_pack) and handed in instead of w_proj: the same bits
+    packed = sb.salad_proj_pack(wp_dev, w.H, w.d)
+    res_p = run_layer(w, inp, dev, kept, kinds, lam=25.0, head_scale=None, w_proj_packed=packed)
+    assert np.array_equal(res_p["out"], res["out"])
     # block-diagonal projection = per-head scalars (a_h representable in bf16)
     a = wl.round_to_bf16(inp["head_scale"])
     wd = torch.from_numpy(np.kron(np.diag(a), np.eye(w.d, dtype=np.float32)).astype(np.float32)).cuda().to(torch.bfloat16)
