@@ -444,6 +444,43 @@ def test_branch_dropping(oracle, flags):
     assert every["dropped"].tolist() == [1, 1] and torch.equal(every["out_t"], sparse_only)
 
 
+def test_d64_large_tile_modes(oracle):
+    """bf16 d = 64 on the large-tile kernel through the modes of the layer call: lambda = 0 (sparse branch alone, bit
+    equal to what a pruned sample gets), branch dropping with B = 2, the unfused epilogue, a precomputed s, and an
+    arbitrary CSR with an empty row."""
+    w = SMALL[8]                                      # d64-ragged: N = 429, B = 2, 2 heads
+    inp = wl.make_inputs(w)
+    wg = inp["w_gate"]
+    inp["x_t"] = inp["x_t"].copy()
+    inp["x_t"][1] = wl.round_to_bf16(inp["x_t"][1] + (2.0 * wg / float(np.dot(wg, wg))).astype(np.float32))
+    dev = upload(w, inp)
+    kinds = wl.head_kinds(w)
+    kept = [3, 4]
+    base = _oracle_layer(oracle, w, inp, kept, kinds, lam=20.0)
+    tau = float(0.5 * (base["s"][0] + base["s"][1]))
+    ref = _oracle_layer(oracle, w, inp, kept, kinds, lam=20.0, drop_threshold=tau)
+    assert ref["dropped"].tolist() == [1, 0]
+    sparse_only = run_layer(w, inp, dev, kept, kinds, lam=0.0)
+    compare_layer(sparse_only, _oracle_layer(oracle, w, inp, kept, kinds, lam=0.0), check_linear=False, label="d64 lambda=0")
+    for flags in (0, sb.SALAD_FLAG_UNFUSED_EPILOGUE):
+        res = run_layer(w, inp, dev, kept, kinds, lam=20.0, flags=flags, drop_threshold=tau)
+        assert res["dropped"].tolist() == [1, 0]
+        compare_layer(res, ref, check_linear=False, label=f"d64 drop flags={flags}")
+        assert torch.equal(res["out_t"][0], sparse_only["out_t"][0])
+        full = run_layer(w, inp, dev, kept, kinds, lam=20.0, flags=flags)
+        compare_layer(full, base, label=f"d64 flags={flags}")
+    s_fixed = np.array([0.25, 0.75], dtype=np.float32)
+    res_s = run_layer(w, inp, dev, kept, kinds, lam=3.0, s=torch.from_numpy(s_fixed).cuda())
+    compare_layer(res_s, _oracle_layer(oracle, w, inp, kept, kinds, lam=3.0, s_override=s_fixed.astype(np.float64)), label="d64 s_dev")
+    rng = np.random.default_rng(9)
+    rows = [np.sort(rng.choice(w.nb, size=int(rng.integers(0 if r == 2 else 1, 5)), replace=False)) for r in range(w.H * w.nb)]
+    csr = (np.concatenate([[0], np.cumsum([len(r) for r in rows])]).astype(np.int32), np.concatenate(rows).astype(np.int32))
+    res_c = run_layer(w, inp, dev, None, kinds, csr=csr)
+    o_s, rws = oracle.sparse_attn(inp["q"], inp["k"], inp["v"], (w.T, w.Hh, w.W), 64, kinds, *csr)
+    got, ok = gather_rows(res_c["o_sparse"], rws)
+    assert errors(got[ok], o_s[ok])[1] <= REL_L2
+
+
 def test_branch_dropping_fp32(oracle):
     w = wl.small("drop-f32", 2, 2, 64, 3, 6, 8, "f32", 0.5, seed=112)       # N = 144
     inp = wl.make_inputs(w)
