@@ -361,6 +361,38 @@ def test_unfused_epilogue_matches(oracle):
     compare_layer(res, ref, label="unfused")
 
 
+@pytest.mark.parametrize("grid,kept,truncated", [((9, 10, 13), [4, 7, 5], False), ((9, 10, 13), [4, 7, 5], True),
+                                                 ((21, 30, 52), [51] * 3, False), ((5, 6, 9), [1, 5], True)])
+def test_tile_lists_layout(oracle, grid, kept, truncated):
+    """salad_tile_lists against the documented layout, rebuilt here from the oracle's CSR: per (head, tile of 4 query
+    blocks) the ascending union of the rows' kept blocks, each entry block | (kept-by-row bits << 24), rotated to start at
+    the entry whose block id is smallest modulo the list length; counts after the lists at the next 256-byte boundary."""
+    T, Hh, W = grid
+    H, nb = len(kept), (T * Hh * W + 63) // 64
+    rp, ci = oracle.block_mask(T, Hh, W, 64, kept, truncated=truncated)
+    row_ptr, col_idx = torch.from_numpy(rp).cuda(), torch.from_numpy(ci).cuda()
+    buf = sb.salad_tile_lists(row_ptr, col_idx, H, nb)
+    torch.cuda.synchronize()
+    raw = buf.cpu().numpy()
+    ntiles, cap = (nb + 3) // 4, (nb + 63) // 64 * 64
+    nlist = H * ntiles * cap * 4
+    lists = raw[:nlist].view(np.uint32).reshape(H, ntiles, cap)
+    counts = raw[(nlist + 255) // 256 * 256:][:H * ntiles * 4].view(np.int32).reshape(H, ntiles)
+    for h in range(H):
+        for t in range(ntiles):
+            bits = {}
+            for i in range(4):
+                r = 4 * t + i
+                if r < nb:
+                    for c in ci[rp[h * nb + r]:rp[h * nb + r + 1]]:
+                        bits[int(c)] = bits.get(int(c), 0) | (1 << (24 + i))
+            asc = [b | m for b, m in sorted(bits.items())]
+            n = len(asc)
+            assert counts[h, t] == n
+            rot = min(range(n), key=lambda i: ((asc[i] & 0xffffff) % n, i)) if n else 0
+            assert lists[h, t, :n].tolist() == asc[rot:] + asc[:rot]
+
+
 def test_prebuilt_tile_lists_give_the_same_bits(oracle):
     """salad_tile_lists builds the large-tile kernel's visit lists once per CSR; a layer call that is handed them skips
     its own pre-pass and must produce the bits of a call that builds them itself (window mask and an arbitrary CSR)."""
