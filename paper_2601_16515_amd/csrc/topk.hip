@@ -270,9 +270,17 @@ __global__ __launch_bounds__(64) void topk_plan_kernel(const int32_t *__restrict
                                                        int32_t *__restrict__ cbase, uint4 *__restrict__ desc, int mt)
 {
     const int bh = blockIdx.x, J = threadIdx.x;
+    // the per-chunk counts of this key block, 32 chunks' loads in flight at a time (the loop is latency-bound)
+    const int32_t *cc = ccnt + (size_t)bh * nch * 64 + J;
     int c = 0;
     if (J < nbk)
-        for (int ch = 0; ch < nch; ++ch) c += ccnt[((size_t)bh * nch + ch) * 64 + J];
+        for (int ch0 = 0; ch0 < nch; ch0 += 32) {
+            int x[32];
+#pragma unroll
+            for (int i = 0; i < 32; ++i) x[i] = ch0 + i < nch ? cc[(size_t)(ch0 + i) * 64] : 0;
+#pragma unroll
+            for (int i = 0; i < 32; ++i) c += x[i];
+        }
     // exclusive prefix sums over the key blocks: slots and tiles
     const int tl = (c + 255) >> 8;
     int s_incl = c, t_incl = tl;
@@ -285,10 +293,16 @@ __global__ __launch_bounds__(64) void topk_plan_kernel(const int32_t *__restrict
     const int used = __shfl(t_incl, 63);
     if (J < nbk) {
         int run = s0;
-        for (int ch = 0; ch < nch; ++ch) {
-            const size_t i = ((size_t)bh * nch + ch) * 64 + J;
-            cbase[i] = run;
-            run += ccnt[i];
+        int32_t *cb = cbase + (size_t)bh * nch * 64 + J;
+        for (int ch0 = 0; ch0 < nch; ch0 += 32) {
+            int x[32];
+#pragma unroll
+            for (int i = 0; i < 32; ++i) x[i] = ch0 + i < nch ? cc[(size_t)(ch0 + i) * 64] : 0;
+#pragma unroll
+            for (int i = 0; i < 32; ++i) {
+                if (ch0 + i < nch) cb[(size_t)(ch0 + i) * 64] = run;
+                run += x[i];
+            }
         }
         for (int i = 0; i < tl; ++i)
             if (t0 + i < mt)
