@@ -476,6 +476,34 @@ def test_branch_dropping(oracle, flags):
     assert every["dropped"].tolist() == [1, 1] and torch.equal(every["out_t"], sparse_only)
 
 
+def _random_shapes(count, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(count):
+        T, Hh, W = int(rng.integers(1, 9)), int(rng.integers(1, 13)), int(rng.integers(1, 13))
+        H, B, d = int(rng.integers(1, 5)), int(rng.integers(1, 3)), int(rng.choice([64, 128]))
+        out.append(wl.small(f"rand{i}-T{T}x{Hh}x{W}-H{H}-B{B}-d{d}", B, H, d, T, Hh, W, "bf16", 0.5, seed=1000 + seed * 100 + i))
+    return out
+
+
+@pytest.mark.parametrize("w", _random_shapes(16, 1), ids=lambda w: w.name)
+def test_layer_parity_random_shapes(oracle, w):
+    """Seeded random small grids (1 to 1152 tokens), head counts, batch sizes, both head widths, random window sizes and
+    head orders: the whole layer against the oracle, and the benchmark launch bit-equal to the call with per-branch outputs."""
+    rng = np.random.default_rng(w.seed)
+    inp = wl.make_inputs(w)
+    dev = upload(w, inp)
+    kinds = rng.integers(0, 2, size=w.H).astype(np.uint8)
+    kept = [int(rng.integers(1, w.nb + 1)) for _ in range(w.H)]
+    res = run_layer(w, inp, dev, kept, kinds)
+    ref = _oracle_layer(oracle, w, inp, kept, kinds)
+    assert np.array_equal(res["row_ptr"], ref["row_ptr"]) and np.array_equal(res["col_idx"], ref["col_idx"])
+    assert np.abs(res["s"] - ref["s"]).max() < 2e-6
+    compare_layer(res, ref, label=w.name)
+    fast = run_layer(w, inp, dev, kept, kinds, dbg=False, prebuilt_lists=True)
+    assert np.array_equal(fast["out"], res["out"])
+
+
 def test_d64_large_tile_modes(oracle):
     """bf16 d = 64 on the large-tile kernel through the modes of the layer call: lambda = 0 (sparse branch alone, bit
     equal to what a pruned sample gets), branch dropping with B = 2, the unfused epilogue, a precomputed s, and an
