@@ -504,6 +504,48 @@ def test_layer_parity_random_shapes(oracle, w):
     assert np.array_equal(fast["out"], res["out"])
 
 
+def _random_shapes_d128(count, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(count):
+        T, Hh, W = int(rng.integers(1, 9)), int(rng.integers(2, 13)), int(rng.integers(2, 13))
+        H, B = int(rng.integers(1, 5)), int(rng.integers(1, 3))
+        out.append(wl.small(f"randw{i}-T{T}x{Hh}x{W}-H{H}-B{B}", B, H, 128, T, Hh, W, "bf16", 0.5, seed=2000 + seed * 100 + i))
+    return out
+
+
+@pytest.mark.parametrize("w", _random_shapes_d128(12, 2), ids=lambda w: w.name)
+def test_widened_rows_random_shapes(oracle, w):
+    """Seeded random small shapes through the widened rows and their combinations: rotary linear branch (fused and with
+    the separate apply pass), full projection with and without the rotation, Top-K masks (mixed head orders; mask bit for
+    bit), each against the oracle."""
+    rng = np.random.default_rng(w.seed)
+    inp = wl.make_inputs(w)
+    dev = upload(w, inp)
+    kinds = rng.integers(0, 2, size=w.H).astype(np.uint8)
+    kept = [int(rng.integers(1, w.nb + 1)) for _ in range(w.H)]
+    cs, sn = wl.rope_tables(w.T, w.Hh, w.W, w.d)
+    rope_dev = (torch.from_numpy(cs).cuda(), torch.from_numpy(sn).cuda())
+    flags = sb.SALAD_FLAG_UNFUSED_EPILOGUE if rng.integers(0, 2) else 0
+    ref = _oracle_layer(oracle, w, inp, kept, kinds, lam=10.0, rope=(cs, sn))
+    res = run_layer(w, inp, dev, kept, kinds, lam=10.0, rope=rope_dev, flags=flags)
+    compare_layer(res, ref, label=f"{w.name} rope flags={flags}")
+    D = w.H * w.d
+    wp = wl.round_to_bf16((wl.normal(w.seed, "w_proj", (D, D)) / np.sqrt(D) * 4.0).astype(np.float32))
+    wp_dev = torch.from_numpy(wp).cuda().to(torch.bfloat16)
+    with_rope = bool(rng.integers(0, 2))
+    ref = _oracle_layer(oracle, w, inp, kept, kinds, w_proj=wp.astype(np.float64), rope=(cs, sn) if with_rope else None)
+    res = run_layer(w, inp, dev, kept, kinds, head_scale=None, w_proj=wp_dev, rope=rope_dev if with_rope else None, dbg=False)
+    compare_layer(res, ref, check_linear=False, label=f"{w.name} proj rope={with_rope}")
+    key_block = int(rng.choice([64, 128]))
+    nbk = -(-w.N // key_block)
+    topk = int(rng.integers(1, min(8, nbk) + 1))
+    ref = _oracle_layer(oracle, w, inp, kept, kinds, lam=5.0, topk=topk, key_block=key_block)
+    res = run_layer(w, inp, dev, kept, kinds, lam=5.0, topk=topk, topk_key_block=key_block)
+    assert np.array_equal(res["topk_mask"], ref["topk_mask"])
+    compare_layer(res, ref, label=f"{w.name} topk={topk}/{key_block}")
+
+
 def test_d64_large_tile_modes(oracle):
     """bf16 d = 64 on the large-tile kernel through the modes of the layer call: lambda = 0 (sparse branch alone, bit
     equal to what a pruned sample gets), branch dropping with B = 2, the unfused epilogue, a precomputed s, and an
