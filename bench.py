@@ -314,7 +314,10 @@ def main():
             bw = torch.nn.functional.pad(bits, (0, 0, 0, pad)).reshape(w.B, w.H, -1, 32, nbk).amax(3)   # per wave
             fl_wave = float((bw.double() * sizes).sum()) * 32 * 4.0 * w.d
             attn_t = kt_t.attn_ms / max(kt_t.calls, 1)
+            # attention_ms: the attention kernel on the regrouped queries alone; the k partial results of a query are
+            # merged by the linear-apply pass (merge_and_linear_apply_ms), which adds the linear branch in the same pass
             return {"ms_per_call": ms_t, "mask_steps_ms": kt_t.topk_ms / max(kt_t.calls, 1), "attention_ms": attn_t,
+                    "merge_and_linear_apply_ms": kt_t.epilogue_ms / max(kt_t.calls, 1),
                     "kept_gflop_token_level": fl_tok * 1e-9,
                     "attention_TFLOP/s_on_kept": fl_tok / (attn_t * 1e-3) * 1e-12,
                     # what a kernel that keeps queries in stored order would have to compute (a wave of 32 neighbouring

@@ -192,7 +192,10 @@ size_t salad_fwd_workspace_bytes(const salad_fwd_params *p);
  * heads only), each block is reduced to its mean key, every query token
  * keeps the topk blocks with the largest q.mean and attends to exactly their tokens.  The selection runs on the
  * device in a fixed float32 order (block sums token by token, scores channel by channel with fused multiply-adds,
- * ties to the lower block index), so that it can be reproduced bit for bit.
+ * ties to the lower block index), so that it can be reproduced bit for bit.  The default Top-K path computes one
+ * partial result per kept key block and query (normalised, rounded to bf16, with its log-sum-exp in fp32) and merges
+ * them; with topk <= 4, lambda != 0 and none of w_proj, rope_*, o_sparse_dbg, o_linear_dbg the merge happens inside
+ * the linear-apply pass in fp32 (one rounding of the sum), otherwise a merge kernel writes O_s in bf16 first.
  * With rope_cos / rope_sin the linear branch carries a rotary position embedding (the paper states that it does and
  * gives no formula; the reading implemented): phi(Q), phi(K) are rotated pairwise by the given angles in the numerator,
  * the normaliser keeps the unrotated features:
@@ -246,7 +249,8 @@ typedef struct salad_kernel_times {
 
 /* on = 1: the layer call brackets each of its stages with HIP events on its stream (eight records per call; every
  * record is a dependency between two kernels that would otherwise start back to back, so the call itself gets some
- * 5 % slower).  on = 2: only the attention stage (pre-pass + attention kernel, Top-K: + merge) is bracketed, two
+ * 5 % slower).  on = 2: only the attention stage (pre-pass + attention kernel, Top-K: + the merge kernel when the
+ * linear-apply pass does not merge) is bracketed, two
  * records per call; salad_timing_read then fills attn_ms and calls only.  on = 0: no events.  Other values:
  * SALAD_EINVAL. */
 salad_status salad_timing_enable(int32_t on);

@@ -127,9 +127,15 @@ __global__ __launch_bounds__(256) void linear_apply_kernel(ApplyArgs a, int rows
 // (cos, sin) words (two fp16 values per channel pair, [N, 64] words: 256 bytes per row, the same geometry as a bf16
 // Q row) go through the same LDS staging as Q, and channel pair (2p, 2p+1) of relu(Q) is rotated before it becomes
 // the numerator's MFMA operand (the state fragments then hold the rotated state).
-template <bool DBG, bool EMIT, bool ROPE = false>
+// MERGE: the regrouped Top-K path (App. A.1.2) leaves O_s as up to four partial results per query (normalised per
+// key block, bf16, with a log2-domain log-sum-exp each).  Instead of reading a merged O_s back, every thread gathers
+// the 16-byte pieces of the partial rows it adds to, weighs them by 2^(lse - max lse) / sum and keeps the merged
+// piece in fp32: one pass over Q and the partial results, one rounding.  The slot numbers and the selection word
+// of a pass are loaded one pass ahead, the pieces of the second half row while the first half's MFMAs run.
+template <bool DBG, bool EMIT, bool ROPE = false, bool MERGE = false>
 __global__ __launch_bounds__(512) void linear_apply128_kernel(ApplyArgs a, int rows_per_wg)
 {
+    static_assert(!MERGE || (!DBG && !EMIT && !ROPE), "the merging variant exists for the plain sum only");
     constexpr int D = 128, NS = 8;
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     u16 *hf_lds = reinterpret_cast<u16 *>(smem);                                  // [D*D] state fragments
@@ -139,7 +145,8 @@ __global__ __launch_bounds__(512) void linear_apply128_kernel(ApplyArgs a, int r
     const int l32 = lane & 31, hh = lane >> 5;
     // ROPE: sample-head index fastest (neighbours in the grid share the angle-table rows)
     const int bh = ROPE ? blockIdx.x : blockIdx.y, rblk = ROPE ? blockIdx.y : blockIdx.x;
-    if (a.drop && a.drop[bh / a.H]) return;            // pruned sample (Sec. 4.3): out already holds O_s
+    const bool pruned = a.drop && a.drop[bh / a.H];    // pruned sample (Sec. 4.3): out = O_s
+    if (pruned && !MERGE) return;                      // out already holds O_s
     {   // fragments are lane-linear in memory: copy as is (16 bytes per lane per load)
         const u16 *hf = a.hfrag + (size_t)bh * D * D;
 #pragma unroll
@@ -148,7 +155,7 @@ __global__ __launch_bounds__(512) void linear_apply128_kernel(ApplyArgs a, int r
                                              (__attribute__((address_space(3))) void *)(hf_lds + (i * 512 + wave * 64) * 8), 16, 0, 0);
         if (tid < D) z_lds[tid] = a.Z[(size_t)bh * D + tid];
     }
-    const float coef = a.coef[bh];
+    const float coef = pruned ? 0.f : a.coef[bh];
     __syncthreads();
     const int N = a.N;
     const u16 *qh = a.q + (size_t)bh * N * D;
@@ -156,7 +163,73 @@ __global__ __launch_bounds__(512) void linear_apply128_kernel(ApplyArgs a, int r
     const int r8 = lane >> 3, c8 = lane & 7;          // row layout of a half: 8 rows x 8 chunks of 16 bytes per instruction
     const int r4 = lane >> 4, c16 = lane & 15;        // row layout of full rows: 4 rows x 16 chunks
     const int row_end = min(N, (rblk + 1) * rows_per_wg);
+    // MERGE: per row 8 k + r8 of the pass (k < 4) the number of partial results and their slots, loaded a pass ahead
+    const size_t mslots = MERGE ? (size_t)N * a.m_kk : 0;
+    int mcnt[4] = {0, 0, 0, 0}, msl[4][4] = {};
+    auto merge_slots = [&](int rb0) __attribute__((always_inline)) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int row = rb0 + 8 * k + r8;
+            const bool ok = row < N;
+            const size_t qi = (size_t)bh * N + (ok ? row : N - 1);
+            const int pc = (int)__popcll(a.m_mask[qi]);
+            mcnt[k] = ok ? min(a.m_kk, pc) : 0;        // only the ranks the regrouping pass filled in
+#pragma unroll
+            for (int r = 0; r < 4; ++r) msl[k][r] = r < a.m_kk ? a.m_slot_of[qi * a.m_kk + r] : 0;
+        }
+    };
+    if (MERGE && rblk * rows_per_wg + wave * 32 < row_end) merge_slots(rblk * rows_per_wg + wave * 32);
     for (int rb = rblk * rows_per_wg + wave * 32; rb < row_end; rb += 256) {
+        float mw[4][4], minv[4];                       // weight of partial result r of row k; 1 / their sum
+        uint4 mx4[4][4];                               // the pieces of the half row in flight
+        auto merge_issue = [&](int h) __attribute__((always_inline)) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (r < mcnt[k])
+                        mx4[k][r] = *reinterpret_cast<const uint4 *>(a.m_po + ((size_t)bh * mslots + msl[k][r]) * D + h * 64 + c8 * 8);
+        };
+        if (MERGE) {
+            float ml[4][4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) ml[k][r] = r < mcnt[k] ? a.m_lse[(size_t)bh * mslots + msl[k][r]] : -INFINITY;
+            merge_issue(0);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float mx = fmaxf(fmaxf(ml[k][0], ml[k][1]), fmaxf(ml[k][2], ml[k][3]));
+                float den = 0.f;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    mw[k][r] = r < mcnt[k] ? __builtin_amdgcn_exp2f(ml[k][r] - mx) : 0.f;
+                    den += mw[k][r];
+                }
+                minv[k] = den > 0.f ? 1.f / den : 0.f;
+            }
+        }
+        // merged O_s pieces of the half row in flight (fp32): acc[k][j] = (sum_r mw[k][r] * piece r) * minv[k], in the
+        // order of topk_merge_kernel, so that a pruned sample gets the bits that kernel would write
+        auto merge_take = [&](float (&acc)[4][8]) __attribute__((always_inline)) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[k][j] = 0.f;
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (r < mcnt[k]) {
+                        const uint32_t w4[4] = {mx4[k][r].x, mx4[k][r].y, mx4[k][r].z, mx4[k][r].w};
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            acc[k][2 * j] = fmaf(mw[k][r], __uint_as_float(w4[j] << 16), acc[k][2 * j]);
+                            acc[k][2 * j + 1] = fmaf(mw[k][r], __uint_as_float(w4[j] & 0xffff0000u), acc[k][2 * j + 1]);
+                        }
+                    }
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[k][j] *= minv[k];
+            }
+        };
         // ---- Q: 8 coalesced loads, swizzled into LDS (chunk ^ (row & 15)), read back as B-operand fragments
         uint4 qc[8];
 #pragma unroll
@@ -171,7 +244,7 @@ __global__ __launch_bounds__(512) void linear_apply128_kernel(ApplyArgs a, int r
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const int row = min(rb + 8 * k + r8, N - 1);
-                os[h][k] = EMIT ? make_uint4(0, 0, 0, 0) : *reinterpret_cast<const uint4 *>(oh + (size_t)row * D + h * 64 + c8 * 8);
+                os[h][k] = (EMIT || MERGE) ? make_uint4(0, 0, 0, 0) : *reinterpret_cast<const uint4 *>(oh + (size_t)row * D + h * 64 + c8 * 8);
             }
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
@@ -263,6 +336,12 @@ __global__ __launch_bounds__(512) void linear_apply128_kernel(ApplyArgs a, int r
                     }
                 }
             asm volatile("" ::: "memory");
+            float macc[4][8];
+            if (MERGE) {
+                merge_take(macc);
+                if (h == 0) merge_issue(1);            // lands under the second half's MFMAs
+                else if (rb + 256 < row_end) merge_slots(rb + 256);
+            }
             // row layout: 8 rows x 8 chunks of 8 columns per instruction; out = O_s + scaled numerator, one rounding
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
@@ -272,10 +351,23 @@ __global__ __launch_bounds__(512) void linear_apply128_kernel(ApplyArgs a, int r
                 const uint4 o4 = os[h][k];
                 uint4 pk;
                 {
-                    f32x2 x0 = {__uint_as_float(o4.x << 16) + n0.x, __uint_as_float(o4.x & 0xffff0000u) + n0.y};
-                    f32x2 x1 = {__uint_as_float(o4.y << 16) + n0.z, __uint_as_float(o4.y & 0xffff0000u) + n0.w};
-                    f32x2 x2 = {__uint_as_float(o4.z << 16) + n1.x, __uint_as_float(o4.z & 0xffff0000u) + n1.y};
-                    f32x2 x3 = {__uint_as_float(o4.w << 16) + n1.z, __uint_as_float(o4.w & 0xffff0000u) + n1.w};
+                    f32x2 x0, x1, x2, x3;
+                    if (MERGE && pruned) {             // no state was computed for this sample: O_s alone
+                        x0 = (f32x2){macc[k][0], macc[k][1]};
+                        x1 = (f32x2){macc[k][2], macc[k][3]};
+                        x2 = (f32x2){macc[k][4], macc[k][5]};
+                        x3 = (f32x2){macc[k][6], macc[k][7]};
+                    } else if (MERGE) {
+                        x0 = (f32x2){macc[k][0] + n0.x, macc[k][1] + n0.y};
+                        x1 = (f32x2){macc[k][2] + n0.z, macc[k][3] + n0.w};
+                        x2 = (f32x2){macc[k][4] + n1.x, macc[k][5] + n1.y};
+                        x3 = (f32x2){macc[k][6] + n1.z, macc[k][7] + n1.w};
+                    } else {
+                        x0 = (f32x2){__uint_as_float(o4.x << 16) + n0.x, __uint_as_float(o4.x & 0xffff0000u) + n0.y};
+                        x1 = (f32x2){__uint_as_float(o4.y << 16) + n0.z, __uint_as_float(o4.y & 0xffff0000u) + n0.w};
+                        x2 = (f32x2){__uint_as_float(o4.z << 16) + n1.x, __uint_as_float(o4.z & 0xffff0000u) + n1.y};
+                        x3 = (f32x2){__uint_as_float(o4.w << 16) + n1.z, __uint_as_float(o4.w & 0xffff0000u) + n1.w};
+                    }
                     pk.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(x0, bf16x2));
                     pk.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(x1, bf16x2));
                     pk.z = __builtin_bit_cast(uint32_t, __builtin_convertvector(x2, bf16x2));
@@ -303,6 +395,13 @@ hipError_t launch_linear_apply_bf16(const ApplyArgs &a, hipStream_t st)
         if (rows_per_wg < 256) rows_per_wg = 256;
         dim3 grid((a.N + rows_per_wg - 1) / rows_per_wg, a.BH), block(512);
         constexpr int lds = 128 * 128 * 2 + 1024 + 8 * 8192;
+        if (a.m_po) {                                  // O_s still lies in partial results: merge them in the same pass
+            if (a.emit || a.o_linear_dbg || a.rope_tab || a.m_kk < 1 || a.m_kk > 4) return hipErrorInvalidValue;
+            static bool done_m[16] = {};
+            if (hipError_t e = dyn_lds_attr_once(reinterpret_cast<const void *>(linear_apply128_kernel<false, false, false, true>), lds, done_m); e != hipSuccess) return e;
+            launch_kernel((linear_apply128_kernel<false, false, false, true>), grid, block, lds, st, a, rows_per_wg);
+            return take_launch_status();
+        }
         static bool done[6][16] = {};
         // variant: 0 plain, 1 debug output, 2 emit; + 3 with the rotary tables
         const int var = (a.emit ? 2 : a.o_linear_dbg ? 1 : 0) + (a.rope_tab ? 3 : 0);

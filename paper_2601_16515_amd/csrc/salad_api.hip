@@ -603,7 +603,11 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
     a.t_magic = ((uint64_t)p->N * (uint64_t)p->T < (1ull << 32) && p->T > 1) ? (unsigned)((1ull << 32) / (uint64_t)p->T + 1) : 0u;
     e = bf16 ? launch_sparse_attn_bf16(a, st) : launch_sparse_attn_f32(a, st);
     if (e != hipSuccess) return give_back(), hip_fail(e, "sparse attention launch");
-    if (a.g_desc) {
+    // regrouped Top-K: the partial results of a query are merged by the linear-apply pass itself when that pass is the
+    // plain sum (no debug outputs, no projection, no rotation, at most 4 partial results), else by a kernel of their own
+    const bool merge_in_apply = a.g_desc && unfused && use_linear && !full_proj && !rope && !p->o_sparse_dbg &&
+                                !p->o_linear_dbg && a.g_kk <= 4 && p->d == 128;
+    if (a.g_desc && !merge_in_apply) {
         e = launch_topk_merge(a.g_po, a.g_lse, (const int32_t *)(ws + w.g_slot), a.topk_mask, BH, p->N, a.g_kk,
                               (u16 *)p->out, p->o_sparse_dbg, st);
         if (e != hipSuccess) return give_back(), hip_fail(e, "top-k merge launch");
@@ -617,6 +621,10 @@ salad_status salad_sparse_linear_attn_fwd(const salad_fwd_params *p)
         ap.drop = drop; ap.H = p->H;
         ap.emit = full_proj ? (u16 *)(ws + w.ol) : nullptr;
         ap.rope_tab = rope ? (const uint32_t *)(ws + w.rope_tab) : nullptr;
+        if (merge_in_apply) {
+            ap.m_po = a.g_po; ap.m_lse = a.g_lse; ap.m_slot_of = (const int32_t *)(ws + w.g_slot);
+            ap.m_mask = a.topk_mask; ap.m_kk = a.g_kk;
+        }
         e = launch_linear_apply_bf16(ap, st);
         if (e != hipSuccess) return give_back(), hip_fail(e, "linear apply launch");
         mark(5);

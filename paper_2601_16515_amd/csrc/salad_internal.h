@@ -146,6 +146,9 @@ struct ApplyArgs {
     const int32_t *drop; int H;     // [B] or null: pruned samples are left as they are (out = O_s)
     const uint32_t *rope_tab;       // d = 128: [N, 64] words (fp16 cos | fp16 sin << 16) of the rotary linear branch, or null
     u16 *emit;                      // d = 128: non-null -> write the unscaled O_l (bf16, [B][ceil(N/32)][H] fragment blocks) here, leave out alone
+    // d = 128, non-null m_po: out does not hold O_s yet; O_s of a row is the merge of its m_kk <= 4 partial results
+    // (regrouped Top-K path, App. A.1.2), taken here in fp32 instead of by topk_merge_kernel.  Arguments as there.
+    const u16 *m_po; const float *m_lse; const int32_t *m_slot_of; const unsigned long long *m_mask; int m_kk;
 };
 hipError_t launch_linear_apply_bf16(const ApplyArgs &a, hipStream_t st);
 

@@ -802,6 +802,38 @@ def test_topk_rotary_dropping_together(oracle):
     assert torch.equal(fast["out_t"][b_drop], sparse_only[b_drop])
 
 
+@pytest.mark.parametrize("topk,key_block", [(4, 64), (2, 128), (1, 64)], ids=["k4", "k2", "k1"])
+def test_topk_merge_inside_the_apply_pass(oracle, topk, key_block):
+    """Regrouped Top-K path without debug outputs, projection or rotation: the partial results of a query are merged
+    by the linear-apply pass itself (fp32, one rounding of the sum).  Against the oracle, with one of the two samples
+    pruned (Sec. 4.3): that sample must come out as the merge kernel writes it for lambda = 0, bit for bit, and the
+    call with debug outputs (merge kernel, then the apply pass) must agree with the oracle as well."""
+    w = SMALL[1]                                        # B = 2, H = 3, N = 693: three passes of 256 rows, ragged
+    inp = wl.make_inputs(w)
+    dev = upload(w, inp)
+    kinds = np.zeros(w.H, dtype=np.uint8)
+    kept = [1] * w.H
+    s = oracle.gate(inp["x_t"], inp["w_gate"], 0.0)
+    tau = float(0.5 * (s.min() + s.max()))
+    ref = _oracle_layer(oracle, w, inp, kept, kinds, lam=10.0, topk=topk, key_block=key_block, drop_threshold=tau)
+    ref_all = _oracle_layer(oracle, w, inp, kept, kinds, lam=10.0, topk=topk, key_block=key_block)
+    fast = run_layer(w, inp, dev, kept, kinds, lam=10.0, topk=topk, topk_key_block=key_block, drop_threshold=tau, dbg=False)
+    assert fast["dropped"].tolist() == ref["dropped"].tolist() and sorted(fast["dropped"].tolist()) == [0, 1]
+    assert np.array_equal(fast["topk_mask"], ref["topk_mask"])
+    compare_layer(fast, ref, check_linear=False, label="topk-merge-in-apply+drop")
+    b_drop = int(np.argmax(ref["dropped"]))
+    sparse_only = run_layer(w, inp, dev, kept, kinds, lam=0.0, topk=topk, topk_key_block=key_block, dbg=False)["out_t"]
+    assert torch.equal(fast["out_t"][b_drop], sparse_only[b_drop])
+    assert not torch.equal(fast["out_t"][1 - b_drop], sparse_only[1 - b_drop])
+    # nobody pruned: both ways of merging against the oracle, and against each other (they differ by one bf16 rounding of O_s)
+    fast_all = run_layer(w, inp, dev, kept, kinds, lam=10.0, topk=topk, topk_key_block=key_block, dbg=False)
+    slow_all = run_layer(w, inp, dev, kept, kinds, lam=10.0, topk=topk, topk_key_block=key_block)
+    e_fast = compare_layer(fast_all, ref_all, check_linear=False, label="topk-merge-in-apply")["out"]
+    e_slow = compare_layer(slow_all, ref_all, label="topk-merge-kernel")["out"]
+    assert e_fast[1] <= e_slow[1] * 1.05               # one rounding less cannot be less accurate
+    assert errors(fast_all["out"], slow_all["out"])[1] < 5e-3
+
+
 @pytest.fixture
 def topk_variant():
     yield lambda v: sb.salad_tune("topk_variant", v)
