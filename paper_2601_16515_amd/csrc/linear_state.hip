@@ -259,35 +259,55 @@ hipError_t launch_rope_pack(const float *rope_cos, const float *rope_sin, size_t
 }
 
 // ------------------------------------------------------------------------------------------------
-// fp32 state for small shapes: one thread per element of Hs, one extra row of threads for Z.
+// fp32 state for small shapes.  A workgroup owns 64 consecutive elements of [Hs | Z] of one head (for d = 64: one
+// row a of Hs, so relu(K[n][a]) is one broadcast load and V[n][c] a coalesced one) and splits the tokens over 16
+// thread groups (token n goes to group n mod 16); every thread adds its tokens in ascending order with 8 loads in
+// flight, the 16 sums are added in group order through LDS: the same result whatever the launch looks like.
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void state_f32_kernel(const float *__restrict__ k, const float *__restrict__ v,
-                                                        int N, int D, float *__restrict__ Hs, float *__restrict__ Z,
-                                                        const int32_t *__restrict__ drop, int H)
+__global__ __launch_bounds__(1024) void state_f32_kernel(const float *__restrict__ k, const float *__restrict__ v,
+                                                         int N, int D, float *__restrict__ Hs, float *__restrict__ Z,
+                                                         const int32_t *__restrict__ drop, int H)
 {
-    int bh = blockIdx.y;
+    __shared__ float part[16][64];
+    const int bh = blockIdx.y;
     if (drop && drop[bh / H]) return;                  // pruned sample (Sec. 4.3)
-    int e = blockIdx.x * 256 + threadIdx.x;
-    if (e >= D * D + D) return;
-    const float *kb = k + (size_t)bh * N * D;
-    const float *vb = v + (size_t)bh * N * D;
-    if (e < D * D) {
-        int a = e / D, c = e - a * D;
-        float s = 0.f;
-        for (int n = 0; n < N; ++n) s = fmaf(fmaxf(kb[(size_t)n * D + a], 0.f), vb[(size_t)n * D + c], s);
-        Hs[(size_t)bh * D * D + e] = s;
-    } else {
-        int a = e - D * D;
-        float s = 0.f;
-        for (int n = 0; n < N; ++n) s += fmaxf(kb[(size_t)n * D + a], 0.f);
-        Z[(size_t)bh * D + a] = s;
+    const int le = threadIdx.x & 63, g = threadIdx.x >> 6;
+    const int e = blockIdx.x * 64 + le;
+    const bool live = e < D * D + D;
+    const bool is_z = e >= D * D;
+    const int a = is_z ? e - D * D : e / D, c = is_z ? 0 : e - a * D;
+    const float *kb = k + (size_t)bh * N * D + (live ? a : 0);
+    const float *vb = v + (size_t)bh * N * D + c;
+    float s = 0.f;
+    if (live) {
+        int n = g;
+        for (; n + 7 * 16 < N; n += 8 * 16) {
+            float kk[8], vv[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                kk[u] = kb[(size_t)(n + 16 * u) * D];
+                vv[u] = is_z ? 1.f : vb[(size_t)(n + 16 * u) * D];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s = fmaf(fmaxf(kk[u], 0.f), vv[u], s);
+        }
+        for (; n < N; n += 16) s = fmaf(fmaxf(kb[(size_t)n * D], 0.f), is_z ? 1.f : vb[(size_t)n * D], s);
+    }
+    part[g][le] = s;
+    __syncthreads();
+    if (g == 0 && live) {
+        float t = part[0][le];
+#pragma unroll
+        for (int i = 1; i < 16; ++i) t += part[i][le];
+        if (is_z) Z[(size_t)bh * D + a] = t;
+        else Hs[(size_t)bh * D * D + e] = t;
     }
 }
 
 hipError_t launch_state_f32(const float *k, const float *v, int BH, int N, int D, float *Hs, float *Z,
                             const int32_t *drop, int H, hipStream_t st)
 {
-    dim3 grid((D * D + D + 255) / 256, BH), block(256);
+    dim3 grid((D * D + D + 63) / 64, BH), block(1024);
     launch_kernel(state_f32_kernel, grid, block, 0, st, k, v, N, D, Hs, Z, drop, H);
     return take_launch_status();
 }

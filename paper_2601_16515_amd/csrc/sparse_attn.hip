@@ -354,16 +354,19 @@ hipError_t launch_sparse_attn_bf16(const AttnArgs &a, hipStream_t st)
 }
 
 // ------------------------------------------------------------------------------------------------
-// fp32 path for small shapes: one wave per query position, lanes across the head dimension
-// (d <= 128: two elements per lane), online softmax in fp32, same fused epilogue.  Not tuned.
+// fp32 path for small shapes: one wave per query position, online softmax in fp32, same fused epilogue.
+// Per kept block the lanes are the block's 64 keys for the logits (every lane takes the whole dot product of its key
+// with the query, which sits in LDS: independent row loads, one maximum and one sum across the wave per block) and
+// the head dimension for the output (lane c owns channels c and c + 64; the key's weight comes from its lane).
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void sparse_attn_f32_kernel(AttnArgs a)
 {
+    __shared__ __attribute__((aligned(16))) float qs[4][128];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int D = a.D, N = a.N, nb = a.nb;
     const long long gw = (long long)blockIdx.x * 4 + wave;     // (bh, position)
     const long long totalq = (long long)a.B * a.H * N;
-    if (gw >= totalq) return;
+    if (gw >= totalq) return;                          // whole waves leave; nothing below synchronises across waves
     const int bh = (int)(gw / N), p = (int)(gw - (long long)bh * N);
     const int h = bh % a.H;
     const int kind = (int)((a.kind_mask >> h) & 1ull);
@@ -374,25 +377,55 @@ __global__ __launch_bounds__(256) void sparse_attn_f32_kernel(AttnArgs a)
     const int c0 = lane, c1 = lane + 64;
     const bool h1 = c1 < D, h0 = c0 < D;
     const float q0 = h0 ? qb[(size_t)n * D + c0] : 0.f, q1 = h1 ? qb[(size_t)n * D + c1] : 0.f;
+    qs[wave][c0] = q0;
+    qs[wave][c1] = q1;
+    __builtin_amdgcn_wave_barrier();                   // the wave's own LDS writes, read back by its own lanes
     float m = -1e30f, l = 0.f, o0 = 0.f, o1 = 0.f;
     const int row = h * nb + p / 64;
     for (int e = a.row_ptr[row]; e < a.row_ptr[row + 1]; ++e) {
         const int j = a.col_idx[e];
-        for (int c = 0; c < 64; ++c) {
-            int pk = j * 64 + c;
-            if (pk >= N) break;
-            int nk = row_of_position(kind, pk, a.T, a.HW);
-            const float *kr = kb + (size_t)nk * D, *vr = vb + (size_t)nk * D;
-            float part = (h0 ? q0 * kr[c0] : 0.f) + (h1 ? q1 * kr[c1] : 0.f);
+        const int pk = j * 64 + lane;                  // this lane's key
+        const bool kvalid = pk < N;
+        const int nk = row_of_position(kind, kvalid ? pk : N - 1, a.T, a.HW);
+        const float4 *kr = reinterpret_cast<const float4 *>(kb + (size_t)nk * D);
+        float part = 0.f;
+        for (int d4 = 0; d4 < D / 4; d4 += 8) {        // D is 64 or 128: 8 row loads in flight
+            float4 kv[8];
 #pragma unroll
-            for (int x = 32; x > 0; x >>= 1) part += __shfl_xor(part, x);
-            float logit = part * a.scale;
-            float mn = fmaxf(m, logit);
-            float alpha = __expf(m - mn), pw = __expf(logit - mn);
-            l = l * alpha + pw;
-            o0 = o0 * alpha + (h0 ? pw * vr[c0] : 0.f);
-            o1 = o1 * alpha + (h1 ? pw * vr[c1] : 0.f);
-            m = mn;
+            for (int u = 0; u < 8; ++u) kv[u] = kr[d4 + u];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const float4 qv = *reinterpret_cast<const float4 *>(&qs[wave][(d4 + u) * 4]);
+                part = fmaf(qv.x, kv[u].x, part); part = fmaf(qv.y, kv[u].y, part);
+                part = fmaf(qv.z, kv[u].z, part); part = fmaf(qv.w, kv[u].w, part);
+            }
+        }
+        const float logit = kvalid ? part * a.scale : -INFINITY;
+        float mb = logit;
+#pragma unroll
+        for (int x = 32; x > 0; x >>= 1) mb = fmaxf(mb, __shfl_xor(mb, x));
+        const float mn = fmaxf(m, mb);
+        const float alpha = __expf(m - mn), pw = kvalid ? __expf(logit - mn) : 0.f;
+        float ps = pw;
+#pragma unroll
+        for (int x = 32; x > 0; x >>= 1) ps += __shfl_xor(ps, x);
+        l = l * alpha + ps;
+        o0 *= alpha; o1 *= alpha;
+        m = mn;
+        const int cmax = min(64, N - j * 64);
+        for (int c = 0; c < cmax; c += 16) {           // 16 value rows in flight; weights and rows past the block are zero / clamped
+            float v0[16], v1[16], wc[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int cc = c + u < cmax ? c + u : cmax - 1;
+                const int nv = __shfl(nk, cc);
+                wc[u] = c + u < cmax ? __shfl(pw, cc) : 0.f;
+                const float *vr = vb + (size_t)nv * D;
+                v0[u] = h0 ? vr[c0] : 0.f;
+                v1[u] = h1 ? vr[c1] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < 16; ++u) { o0 = fmaf(wc[u], v0[u], o0); o1 = fmaf(wc[u], v1[u], o1); }
         }
     }
     const float inv_l = l > 0.f ? 1.f / l : 0.f;
@@ -408,10 +441,19 @@ __global__ __launch_bounds__(256) void sparse_attn_f32_kernel(AttnArgs a)
         for (int x = 32; x > 0; x >>= 1) dpart += __shfl_xor(dpart, x);
         const float inv_den = 1.f / (dpart + a.eps);
         float n0 = 0.f, n1 = 0.f;
-        for (int aa = 0; aa < D; ++aa) {
-            float qa = aa < 64 ? __shfl(f0, aa) : __shfl(f1, aa - 64);
-            n0 = fmaf(qa, h0 ? Hh[(size_t)aa * D + c0] : 0.f, n0);
-            n1 = fmaf(qa, h1 ? Hh[(size_t)aa * D + c1] : 0.f, n1);
+        for (int aa = 0; aa < D; aa += 8) {            // D is a multiple of 8: 8 state rows in flight
+            float x0[8], x1[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                x0[u] = h0 ? Hh[(size_t)(aa + u) * D + c0] : 0.f;
+                x1[u] = h1 ? Hh[(size_t)(aa + u) * D + c1] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const float qa = fmaxf(qs[wave][aa + u], 0.f);
+                n0 = fmaf(qa, x0[u], n0);
+                n1 = fmaf(qa, x1[u], n1);
+            }
         }
         ol0 = n0 * inv_den; ol1 = n1 * inv_den;
         const float cf = a.coef[bh];
