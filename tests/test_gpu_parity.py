@@ -544,6 +544,10 @@ def test_widened_rows_random_shapes(oracle, w):
     res = run_layer(w, inp, dev, kept, kinds, lam=5.0, topk=topk, topk_key_block=key_block)
     assert np.array_equal(res["topk_mask"], ref["topk_mask"])
     compare_layer(res, ref, label=f"{w.name} topk={topk}/{key_block}")
+    # without the debug outputs (topk <= 4: the partial results are merged inside the linear-apply pass)
+    fast = run_layer(w, inp, dev, kept, kinds, lam=5.0, topk=topk, topk_key_block=key_block, dbg=False)
+    assert np.array_equal(fast["topk_mask"], ref["topk_mask"])
+    compare_layer(fast, ref, check_linear=False, label=f"{w.name} topk={topk}/{key_block} fast")
 
 
 def test_d64_large_tile_modes(oracle):
