@@ -339,7 +339,8 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
     Frag5 pf[4];
 
     // Matrix phase = 32 MFMAs per wave: 16 for O^T += V^T P^T (A = V^T fragment: two transposing 8-byte reads),
-    // then 16 for S^T = K Q^T (A = K fragment: one 16-byte read).  Operand fragments move through a ring of
+    // then 16 for S^T = K Q^T (A = K fragment: one 16-byte read; the NS products of the block's first 32 keys, then
+    // those of the other 32, so that the softmax finds its first logits finished).  Operand fragments move through a ring of
     // RING register quads: MFMA i takes ring[i % RING] and the read of fragment i + RING is issued right after
     // it, so LDS requests are spread evenly over the phase (the LDS has to deliver 1 KB per MFMA per wave,
     // about three quarters of what it can sustain, and bursts of reads stall the matrix pipe) and at most
@@ -355,14 +356,14 @@ __global__ __launch_bounds__(512, 2) void sparse_attn_v5_kernel(AttnArgs a, int 
             f.h[1] = TR_READ(vp + 4 * D);
         } else {
             const int t = i - NPV;
-            f.v = *reinterpret_cast<const bf16x8 *>(Kt + (t & 1) * 32 * D + koff[t >> 1]);
+            f.v = *reinterpret_cast<const bf16x8 *>(Kt + (t / NS) * 32 * D + koff[t % NS]);
         }
     };
     auto mfma_step = [&](int i, const Frag5 &f) INL {
         if (i < NPV) {
             o[i % NDT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.v, pf[i / NDT].v, o[i % NDT], 0, 0, 0);
         } else {
-            const int t = i - NPV, kt = t & 1, st = t >> 1;
+            const int t = i - NPV, kt = t / NS, st = t % NS;   // the first 32 keys' logits are complete NS MFMAs before the phase ends
             if (st == 0) {
                 f32x16 z;
 #pragma unroll
