@@ -149,133 +149,9 @@ __global__ __launch_bounds__(256) void topk_select_kernel(const u16 *__restrict_
     if (n < N) mask[(size_t)bh * N + n] = m;
 }
 
-// More than 32 key blocks: the same scores on the matrix pipe.  v_mfma_f32_32x32x1_2b_f32 is two independent 32 x 32
-// outer products with one fused multiply-add per element (K = 1: D[i][j] = fma(A[i], B[j], D[i][j]), the IEEE operation,
-// checked bit for bit against fmaf chains), so a chain of them over the channels in ascending order is exactly the
-// accumulation the selection fixes.  Rows are key blocks (A = the block means from LDS: lane J supplies block J, lanes
-// 0-31 to the first product, lanes 32-63 to the second), columns are queries (B = the lane's query value; both halves
-// of the wave take the same 32 queries), so one instruction gives 64 key blocks x 32 queries for one channel.
-// A lane then holds, for query lane % 32, the scores of blocks 32 b + 8 g + 4 (lane / 32) + t (b = r / 16,
-// g = (r % 16) / 4, t = r % 4 for accumulator register r): half of the query's blocks, ascending in r.  Each lane
-// collects its best SLOTS in the usual way and the two lanes of a query merge their lists (larger score first, ties
-// to the lower block index: the order the sequential insertion produces for finite scores).
-// The 32 query rows of a wave come in with coalesced loads (four rows per instruction) and go through LDS to the
-// lanes that own them.  grid (ceil(N / 128), BH), 256 threads: a wave takes 32 queries.
-typedef float f32x32 __attribute__((ext_vector_type(32)));
-template <int SLOTS>
-__global__ __launch_bounds__(256) void topk_select_mfma_kernel(const u16 *__restrict__ q, const float *__restrict__ means,
-                                                               int N, int nbk, int topk,
-                                                               unsigned long long *__restrict__ mask)
-{
-    constexpr int MP = D + 4;                          // row pitch of the means in LDS (floats): 16-byte reads of 64 rows without bank conflicts
-    constexpr int QP = D / 8 + 1;                      // row pitch of the staged query rows (16-byte chunks)
-    __shared__ __attribute__((aligned(16))) float sm[64 * MP];
-    __shared__ uint4 qs[4][32 * QP];
-    const int bh = blockIdx.y;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int i = threadIdx.x; i < 64 * D; i += 256) {
-        const int J = i / D, c = i - J * D;
-        sm[J * MP + c] = J < nbk ? means[((size_t)bh * nbk + J) * D + c] : 0.f;
-    }
-    __syncthreads();
-    const float *ar = sm + lane * MP;                  // this lane's key block (A operand)
-    const int half = lane >> 5;
-    const int n0 = blockIdx.x * 128 + wave * 32;
-    if (n0 >= N) return;                               // wave-uniform; no workgroup barrier follows
-    {
-        const uint4 *src = reinterpret_cast<const uint4 *>(q + (size_t)bh * N * D);
-        uint4 t[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            int row = n0 + 4 * i + (lane >> 4);
-            row = row < N ? row : N - 1;
-            t[i] = src[(size_t)row * (D / 8) + (lane & 15)];
-        }
-#pragma unroll
-        for (int i = 0; i < 8; ++i) qs[wave][(4 * i + (lane >> 4)) * QP + (lane & 15)] = t[i];
-    }
-    asm volatile("" ::: "memory");                     // the wave's LDS operations execute in order
-    const int n = n0 + (lane & 31);
-    const uint4 *qrow = &qs[wave][(lane & 31) * QP];
-    f32x32 acc;
-#pragma unroll
-    for (int r = 0; r < 32; ++r) acc[r] = 0.f;
-#pragma unroll
-    for (int c8 = 0; c8 < D / 8; ++c8) {
-        const float4 m0 = *reinterpret_cast<const float4 *>(ar + c8 * 8);
-        const float4 m1 = *reinterpret_cast<const float4 *>(ar + c8 * 8 + 4);
-        const float mv[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
-        const uint4 u = qrow[c8];
-        const uint32_t w[4] = {u.x, u.y, u.z, u.w};
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            acc = __builtin_amdgcn_mfma_f32_32x32x1f32(mv[2 * j], __uint_as_float(w[j] << 16), acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x1f32(mv[2 * j + 1], __uint_as_float(w[j] & 0xffff0000u), acc, 0, 0, 0);
-        }
-    }
-    float best[SLOTS];
-    int bidx[SLOTS];
-#pragma unroll
-    for (int i = 0; i < SLOTS; ++i) { best[i] = -INFINITY; bidx[i] = -1; }
-#pragma unroll
-    for (int r = 0; r < 32; ++r) {
-        const int J = 32 * (r >> 4) + 8 * ((r & 15) >> 2) + 4 * half + (r & 3);
-        if (32 * (r >> 4) + 8 * ((r & 15) >> 2) >= nbk) continue;      // wave-uniform: no lane has this block
-        if (J < nbk) {
-            float v = acc[r];
-            int id = J;
-            bool carry = false;
-#pragma unroll
-            for (int i = 0; i < SLOTS; ++i) {
-                const bool take = (id >= 0) && (carry || bidx[i] < 0 || v > best[i]);
-                carry = carry || take;
-                const float tv = best[i];
-                const int ti = bidx[i];
-                best[i] = take ? v : tv;
-                bidx[i] = take ? id : ti;
-                v = take ? tv : v;
-                id = take ? ti : id;
-            }
-        }
-    }
-    // the other half of the query's blocks sits in lane ^ 32
-    float pv[SLOTS];
-    int pi[SLOTS];
-#pragma unroll
-    for (int i = 0; i < SLOTS; ++i) { pv[i] = __shfl_xor(best[i], 32); pi[i] = __shfl_xor(bidx[i], 32); }
-#pragma unroll
-    for (int e = 0; e < SLOTS; ++e) {
-        float v = pv[e];
-        int id = pi[e];
-        bool carry = false;
-#pragma unroll
-        for (int i = 0; i < SLOTS; ++i) {
-            const bool take = (id >= 0) && (carry || bidx[i] < 0 || v > best[i] || (v == best[i] && id < bidx[i]));
-            carry = carry || take;
-            const float tv = best[i];
-            const int ti = bidx[i];
-            best[i] = take ? v : tv;
-            bidx[i] = take ? id : ti;
-            v = take ? tv : v;
-            id = take ? ti : id;
-        }
-    }
-    unsigned long long m = 0ull;
-#pragma unroll
-    for (int i = 0; i < SLOTS; ++i)
-        if (i < topk && bidx[i] >= 0) m |= 1ull << bidx[i];
-    if (half == 0 && n < N) mask[(size_t)bh * N + n] = m;
-}
-
 hipError_t launch_topk_select(const u16 *q, const float *means, int BH, int N, int nbk, int topk,
                               unsigned long long *mask, hipStream_t st)
 {
-    if (nbk > 32) {
-        const dim3 grid_m((N + 127) / 128, BH);
-        if (topk <= 4) launch_kernel((topk_select_mfma_kernel<4>), grid_m, dim3(256), 0, st, q, means, N, nbk, topk, mask);
-        else launch_kernel((topk_select_mfma_kernel<8>), grid_m, dim3(256), 0, st, q, means, N, nbk, topk, mask);
-        return take_launch_status();
-    }
     const dim3 grid((N + 255) / 256, BH), block(256);
 #define SALAD_TOPK_SELECT(NBK_)                                                                                              \
     do {                                                                                                                     \
